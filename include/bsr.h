@@ -1,0 +1,195 @@
+/*
+ * bsr.h — C ABI of the MI355X (gfx950) library for one Block Selective Reprogramming (BSR)
+ * fine-tuning step of a Vision Transformer (arxiv 2405.10951).
+ *
+ * One step is:  bsr_forward_frozen  ->  bsr_train_blocks_fwd_bwd  ->  bsr_sgd_step.
+ *
+ * Conventions for every entry point
+ *   - Plain C.  Every function returns a bsr status (0 = BSR_OK, negative = error); nothing throws
+ *     or aborts.  bsr_last_error() gives a text for the last failure on a context.
+ *   - "device" pointers are HIP device memory owned by the caller; "host" pointers are ordinary
+ *     host memory.  The library never allocates or frees device memory and never synchronises the
+ *     device: all kernels are enqueued on the `stream` argument (a hipStream_t passed as void*;
+ *     NULL is the default stream) and the call returns.  The only thing the library owns is the
+ *     small host-side context, released by bsr_destroy().
+ *   - Device pointers must be 16-byte aligned.  A NULL or misaligned required pointer gives
+ *     BSR_ERR_INVALID_ARG before anything is launched.
+ *   - Activations ("act" below) have the configured compute dtype: bf16 (2 bytes) or fp32.
+ *     Parameters, gradients and momenta are always fp32.  Linear weights are row-major [in, out].
+ *   - Block and drop indices are 0-based.  Token tensors are row-major [B, T, D], token 0 = CLS.
+ *   - Calls on one context are not thread-safe and must be issued on one stream (or be ordered by
+ *     the caller); different contexts are independent.
+ */
+#ifndef BSR_H_
+#define BSR_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define BSR_MAX_BLOCKS 16
+
+enum {
+  BSR_OK = 0,
+  BSR_ERR_INVALID_ARG = -1,         /* NULL / misaligned pointer, B out of range, ...            */
+  BSR_ERR_BAD_CONFIG = -2,          /* inconsistent bsr_config                                    */
+  BSR_ERR_WORKSPACE_TOO_SMALL = -3, /* workspace_bytes < bsr_workspace_bytes()                    */
+  BSR_ERR_UNSUPPORTED_ARCH = -4,    /* current device is not gfx950                               */
+  BSR_ERR_HIP = -5                  /* a HIP call failed; text in bsr_last_error()                */
+};
+
+enum { BSR_BF16 = 0, BSR_FP32 = 1 };          /* activation / compute dtype                       */
+enum { BSR_LOSS_CE = 0, BSR_LOSS_MEAN_SQ = 1 }; /* cross-entropy on the head, or mean of squared
+                                                   outputs of the last block (no head)            */
+
+typedef struct bsr_ctx bsr_ctx;
+
+/* The model and the BSR layout (Fig. 2; Sec. 4.3 Discussion 3): which blocks drop tokens, how many
+ * patch tokens survive each drop, and from which block on weights are trained. */
+typedef struct {
+  int32_t image_size, patch_size, in_chans; /* 224, 16, 3.  image_size == 0: no stem, the input of
+                                               bsr_forward_frozen already is tokens [B,tokens_in,D] */
+  int32_t tokens_in;                        /* T of a token input; ignored when image_size > 0     */
+  int32_t dim, heads, mlp_hidden, depth;    /* L (=D), H, D_ffn, number of encoder blocks          */
+  int32_t num_classes;                      /* 0: no head (use BSR_LOSS_MEAN_SQ)                   */
+  int32_t max_batch;                        /* workspace is sized for this many images             */
+  int32_t n_drop;                           /* number of token drop locations                      */
+  int32_t drop_blocks[BSR_MAX_BLOCKS];      /* strictly ascending block indices                    */
+  int32_t keep_k[BSR_MAX_BLOCKS];           /* patch tokens kept at each drop (CLS is kept on top).
+                                               If all entries are 0 they are derived from
+                                               keep_ratio as floor(keep_ratio * n + 1e-9) on the
+                                               current patch count n (Sec. 4.1: "K determined by
+                                               the token drop rate"; keep_ratio = 1 - drop rate)   */
+  float keep_ratio;                         /* 0 < r <= 1; only read when keep_k is all 0          */
+  int32_t first_trainable_block;            /* blocks [first, depth), the final LayerNorm and the
+                                               head are trained; blocks before it are frozen and
+                                               keep no activations (Fig. 2, Eq. 8)                 */
+  int32_t dtype;                            /* BSR_BF16 or BSR_FP32                                */
+  int32_t loss;                             /* BSR_LOSS_CE or BSR_LOSS_MEAN_SQ                     */
+  float ln_eps;                             /* LayerNorm epsilon; 0 means 1e-6                     */
+} bsr_config;
+
+/* Tables of device pointers, one per tensor (fp32).  The same struct describes parameters,
+ * gradients and momenta.  Shapes: ln*_g, ln*_b, b_proj, b_fc2 [D]; w_qkv [D,3D] with columns
+ * [q|k|v], each split into H heads of D/H; b_qkv [3D]; w_proj [D,D]; w_fc1 [D,F]; b_fc1 [F];
+ * w_fc2 [F,D]; w_patch [C*P*P, D] with rows in (channel, row, column) order of a patch;
+ * b_patch, cls [D]; pos [T,D]; lnf_g, lnf_b [D]; w_head [D,classes]; b_head [classes]. */
+typedef struct {
+  void *ln1_g, *ln1_b, *w_qkv, *b_qkv, *w_proj, *b_proj, *ln2_g, *ln2_b, *w_fc1, *b_fc1, *w_fc2, *b_fc2;
+} bsr_block_params;
+
+typedef struct {
+  void *w_patch, *b_patch, *cls, *pos;
+  bsr_block_params blocks[BSR_MAX_BLOCKS];
+  void *lnf_g, *lnf_b, *w_head, *b_head;
+} bsr_params;
+
+/*
+ * Token schedule of a configuration (host only, touches no GPU).  Sec. 4.1 / Sec. 4.3
+ * Discussion 3: a drop location ranks all incoming tokens in its MHSA and hands K of them to its
+ * FFN, e.g. N/2, N/4, N/8 at drop rate 0.5.
+ *   keep_k_out   host [n_drop]  patch tokens kept at each drop, may be NULL
+ *   tokens_attn  host [depth]   tokens (CLS included) seen by the MHSA of each block, may be NULL
+ *   tokens_mlp   host [depth]   tokens seen by the FFN of each block, may be NULL
+ * Errors: BSR_ERR_INVALID_ARG (cfg NULL), BSR_ERR_BAD_CONFIG.
+ */
+int32_t bsr_token_schedule(const bsr_config* cfg, int32_t* keep_k_out, int32_t* tokens_attn,
+                           int32_t* tokens_mlp);
+
+/* Bytes of device workspace bsr_init needs for this configuration (host only). */
+int32_t bsr_workspace_bytes(const bsr_config* cfg, size_t* bytes_out);
+
+/*
+ * Create a context (the problem statement of Sec. 4.1: a pre-trained ViT, drop locations, drop
+ * rate, trainable set).
+ *   params     host struct of device fp32 pointers: the master weights.  The struct is copied; the
+ *              tensors stay owned by the caller, must outlive the context and are updated in place
+ *              by bsr_sgd_step.  Entries for parts the configuration lacks (stem, head) may be NULL.
+ *   workspace  device, 256-byte aligned, workspace_bytes >= bsr_workspace_bytes(); owned by the
+ *              caller, used by the context until bsr_destroy.
+ * In bf16 mode this enqueues the kernels that build bf16 copies of the weight matrices.
+ * Errors: INVALID_ARG, BAD_CONFIG, WORKSPACE_TOO_SMALL, UNSUPPORTED_ARCH, HIP.
+ */
+int32_t bsr_init(const bsr_config* cfg, const bsr_params* params, void* workspace,
+                 size_t workspace_bytes, void* stream, bsr_ctx** ctx_out);
+
+/* After the caller has overwritten master weights by other means than bsr_sgd_step (loading a
+ * checkpoint), rebuild the bf16 copies. */
+int32_t bsr_refresh_weights(bsr_ctx* ctx, void* stream);
+
+/*
+ * Frozen prefix (Fig. 2; Sec. 4.1): stem (Sec. 3.1) and blocks [0, first_trainable_block), forward
+ * only, nothing kept for backward.  Drop locations inside the prefix rank patch tokens by the
+ * head-averaged CLS row of the softmax attention map (Eq. 6) and pass CLS + the K best on to the
+ * FFN of that block.
+ *   input        device act: images [B,C,S,S], or tokens [B,tokens_in,D] when image_size == 0
+ *   x_out        device act [B,T_f,D]: tokens entering block first_trainable_block
+ *   kept_idx_out device int32, may be NULL: kept patch indices (ascending) of the prefix's drops,
+ *                concatenated, drop i holding [B,keep_k[i]]
+ *   scores_out   device fp32, may be NULL: importance scores of the prefix's drops, concatenated,
+ *                drop i holding [B,n_i]
+ *   forced_idx   device int32, may be NULL: use these indices (layout of kept_idx_out) instead of
+ *                ranking — for parity tests against a reference that took the same decisions
+ * Errors: INVALID_ARG (NULL input/x_out, B < 1 or > max_batch), HIP.
+ */
+int32_t bsr_forward_frozen(bsr_ctx* ctx, const void* input, int32_t B, void* x_out,
+                           int32_t* kept_idx_out, float* scores_out, const int32_t* forced_idx,
+                           void* stream);
+
+/*
+ * Token selection on its own (Sec. 4.1): the K largest of each row of cls_attn, ties to the lower
+ * index, indices emitted ascending; then x_out[b,0] = x_in[b,0], x_out[b,1+i] = x_in[b,1+idx[b,i]].
+ *   cls_attn device fp32 [B,n]   importance of the n patch tokens
+ *   x_in     device act [B,n+1,D], may be NULL together with x_out (indices only)
+ *   idx_out  device int32 [B,k]
+ *   x_out    device act [B,k+1,D]
+ * Limits: 0 <= k <= n <= 1024.  Errors: INVALID_ARG, HIP.
+ */
+int32_t bsr_select_tokens(bsr_ctx* ctx, const float* cls_attn, const void* x_in, int32_t B,
+                          int32_t n, int32_t k, int32_t* idx_out, void* x_out, void* stream);
+
+/*
+ * Trainable blocks [first_trainable_block, depth) and the head: forward keeping what Eq. 2-5 need
+ * (Sec. 3.2), loss, and backward down to the parameters of block first_trainable_block; the
+ * gradient is not propagated into the frozen prefix (Fig. 2, Eq. 8).  Drop locations inside the
+ * trainable range behave as in the prefix; kept indices are constants of the backward pass.
+ *   x_in         device act [B,T_f,D] (output of bsr_forward_frozen); not modified
+ *   labels       device int32 [B]; may be NULL with BSR_LOSS_MEAN_SQ
+ *   loss_out     device fp32 scalar
+ *   logits_out   device fp32 [B,classes], may be NULL
+ *   x_final_out  device act [B,T_last,D], may be NULL: output of the last block
+ *   grads        host struct of device fp32 pointers; every tensor of the trainable blocks, lnf_*
+ *                and *_head must be non-NULL; each is overwritten with dLoss/dTensor
+ *   kept_idx_out, scores_out, forced_idx: as in bsr_forward_frozen, for the drops in this range
+ * Errors: INVALID_ARG, HIP.
+ */
+int32_t bsr_train_blocks_fwd_bwd(bsr_ctx* ctx, const void* x_in, const int32_t* labels, int32_t B,
+                                 float* loss_out, float* logits_out, void* x_final_out,
+                                 const bsr_params* grads, int32_t* kept_idx_out, float* scores_out,
+                                 const int32_t* forced_idx, void* stream);
+
+/*
+ * SGD update of the trainable tensors (Sec. 5, "SGD optimizer"), in place on the master weights
+ * given to bsr_init:  g' = g + weight_decay * w;  momentum > 0: m = momentum * m + g', w -= lr * m;
+ * otherwise w -= lr * g'.  Also refreshes the bf16 copies the kernels read.
+ *   grads     host struct of device fp32 pointers, as produced by bsr_train_blocks_fwd_bwd
+ *   momenta   same layout, or NULL when momentum == 0; updated in place
+ * Errors: INVALID_ARG, HIP.
+ */
+int32_t bsr_sgd_step(bsr_ctx* ctx, const bsr_params* grads, const bsr_params* momenta, float lr,
+                     float momentum, float weight_decay, void* stream);
+
+/* Release the host-side context (no device memory is touched). */
+int32_t bsr_destroy(bsr_ctx* ctx);
+
+/* Text of the last error on this context ("" if none); valid until the next call on it.
+ * With ctx == NULL: the text of the last failed bsr_init / bsr_workspace_bytes on this thread. */
+const char* bsr_last_error(const bsr_ctx* ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BSR_H_ */

@@ -1,0 +1,246 @@
+"""ctypes binding of include/bsr.h.  Argument marshalling only: tensors are torch CUDA tensors used
+as device memory, the stream is torch's current HIP stream.  Same names as the C entry points."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+MAX_BLOCKS = 16
+BSR_BF16, BSR_FP32 = 0, 1
+BSR_LOSS_CE, BSR_LOSS_MEAN_SQ = 0, 1
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+
+BLOCK_FIELDS = ("ln1_g", "ln1_b", "w_qkv", "b_qkv", "w_proj", "b_proj",
+                "ln2_g", "ln2_b", "w_fc1", "b_fc1", "w_fc2", "b_fc2")
+STEM_FIELDS = ("w_patch", "b_patch", "cls", "pos")
+HEAD_FIELDS = ("lnf_g", "lnf_b", "w_head", "b_head")
+
+
+class BsrError(RuntimeError):
+    def __init__(self, code, text):
+        super().__init__(f"bsr error {code}: {text}")
+        self.code = code
+
+
+class bsr_config(C.Structure):
+    _fields_ = [("image_size", C.c_int32), ("patch_size", C.c_int32), ("in_chans", C.c_int32),
+                ("tokens_in", C.c_int32), ("dim", C.c_int32), ("heads", C.c_int32),
+                ("mlp_hidden", C.c_int32), ("depth", C.c_int32), ("num_classes", C.c_int32),
+                ("max_batch", C.c_int32), ("n_drop", C.c_int32),
+                ("drop_blocks", C.c_int32 * MAX_BLOCKS), ("keep_k", C.c_int32 * MAX_BLOCKS),
+                ("keep_ratio", C.c_float), ("first_trainable_block", C.c_int32),
+                ("dtype", C.c_int32), ("loss", C.c_int32), ("ln_eps", C.c_float)]
+
+
+class bsr_block_params(C.Structure):
+    _fields_ = [(f, C.c_void_p) for f in BLOCK_FIELDS]
+
+
+class bsr_params(C.Structure):
+    _fields_ = ([(f, C.c_void_p) for f in STEM_FIELDS] + [("blocks", bsr_block_params * MAX_BLOCKS)]
+                + [(f, C.c_void_p) for f in HEAD_FIELDS])
+
+
+def lib_path() -> str:
+    return os.path.join(_HERE, "libbsr_hip.so")
+
+
+_lib = None
+
+
+def load_library():
+    """Load libbsr_hip.so.  Fails loudly when it has not been built (there is no fallback)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    path = lib_path()
+    if not os.path.exists(path):
+        raise FileNotFoundError(f"{path} is missing: run `python -m paper_2405_10951_amd.build` "
+                                "(or __graft_entry__.build()) first")
+    lib = C.CDLL(path)
+    lib.bsr_last_error.restype = C.c_char_p
+    lib.bsr_last_error.argtypes = [C.c_void_p]
+    for name in ("bsr_token_schedule", "bsr_workspace_bytes", "bsr_init", "bsr_refresh_weights",
+                 "bsr_forward_frozen", "bsr_select_tokens", "bsr_train_blocks_fwd_bwd",
+                 "bsr_sgd_step", "bsr_destroy"):
+        getattr(lib, name).restype = C.c_int32
+    lib.bsr_token_schedule.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.bsr_workspace_bytes.argtypes = [C.c_void_p, C.POINTER(C.c_size_t)]
+    lib.bsr_init.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p, C.POINTER(C.c_void_p)]
+    lib.bsr_refresh_weights.argtypes = [C.c_void_p, C.c_void_p]
+    lib.bsr_forward_frozen.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p,
+                                       C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.bsr_select_tokens.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32,
+                                      C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.bsr_train_blocks_fwd_bwd.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p,
+                                             C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                             C.c_void_p, C.c_void_p]
+    lib.bsr_sgd_step.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_float, C.c_float, C.c_float, C.c_void_p]
+    lib.bsr_destroy.argtypes = [C.c_void_p]
+    _lib = lib
+    return lib
+
+
+def make_config(cfg: dict, max_batch: int, keep_k=None) -> bsr_config:
+    """Fill a bsr_config from a plain dict (the keys of the C struct; `first_trainable` is accepted
+    for first_trainable_block, dtype may be "bf16"/"fp32")."""
+    c = bsr_config()
+    for f in ("image_size", "patch_size", "in_chans", "tokens_in", "dim", "heads", "mlp_hidden",
+              "depth", "num_classes", "loss"):
+        setattr(c, f, int(cfg.get(f, 0)))
+    c.max_batch = int(max_batch)
+    c.first_trainable_block = int(cfg.get("first_trainable_block", cfg.get("first_trainable", 0)))
+    dt = cfg.get("dtype", "bf16")
+    c.dtype = {"bf16": BSR_BF16, "fp32": BSR_FP32}.get(dt, dt)
+    c.keep_ratio = float(cfg.get("keep_ratio", 1.0))
+    c.ln_eps = float(cfg.get("ln_eps", 1e-6))
+    drops = list(cfg.get("drop_blocks", []))
+    c.n_drop = len(drops)
+    for i, b in enumerate(drops):
+        c.drop_blocks[i] = int(b)
+    if keep_k is None:
+        keep_k = cfg.get("keep_k")
+    if keep_k:
+        for i, k in enumerate(keep_k):
+            c.keep_k[i] = int(k)
+    return c
+
+
+def _check(rc, ctx=None):
+    if rc != 0:
+        raise BsrError(rc, load_library().bsr_last_error(ctx).decode())
+
+
+def bsr_token_schedule(cfg: bsr_config):
+    """-> (keep_k per drop, tokens seen by MHSA per block, tokens seen by the FFN per block)."""
+    lib = load_library()
+    kk = (C.c_int32 * MAX_BLOCKS)()
+    ta = (C.c_int32 * MAX_BLOCKS)()
+    tm = (C.c_int32 * MAX_BLOCKS)()
+    _check(lib.bsr_token_schedule(C.byref(cfg), kk, ta, tm))
+    return list(kk[:cfg.n_drop]), list(ta[:cfg.depth]), list(tm[:cfg.depth])
+
+
+def bsr_workspace_bytes(cfg: bsr_config) -> int:
+    n = C.c_size_t(0)
+    _check(load_library().bsr_workspace_bytes(C.byref(cfg), C.byref(n)))
+    return int(n.value)
+
+
+def _params_struct(tensors: dict) -> bsr_params:
+    p = bsr_params()
+    for name, t in tensors.items():
+        if t is None:
+            continue
+        ptr = t.data_ptr()
+        if name.startswith("blocks."):
+            _, i, leaf = name.split(".")
+            setattr(p.blocks[int(i)], leaf, ptr)
+        else:
+            setattr(p, name, ptr)
+    return p
+
+
+def _dp(t):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+class Context:
+    """Owns a bsr_ctx and the torch tensors (device memory) it points into.  Methods carry the
+    names of the C entry points and forward to them one to one."""
+
+    def __init__(self, cfg: dict, params: dict, max_batch: int, keep_k=None, device="cuda:0"):
+        import torch
+        self.torch = torch
+        self.lib = load_library()
+        self.device = torch.device(device)
+        self.c = make_config(cfg, max_batch, keep_k)
+        self.act_dtype = torch.float32 if self.c.dtype == BSR_FP32 else torch.bfloat16
+        self.keep_k, self.tokens_attn, self.tokens_mlp = bsr_token_schedule(self.c)
+        # master weights: fp32 device tensors owned here, updated in place by bsr_sgd_step
+        self.params = {k: torch.as_tensor(v, dtype=torch.float32).to(self.device).contiguous()
+                       for k, v in params.items()}
+        self._pstruct = _params_struct(self.params)
+        nbytes = bsr_workspace_bytes(self.c)
+        self.workspace = torch.empty(nbytes + 256, dtype=torch.uint8, device=self.device)
+        base = (self.workspace.data_ptr() + 255) & ~255
+        self.ctx = C.c_void_p()
+        _check(self.lib.bsr_init(C.byref(self.c), C.byref(self._pstruct), C.c_void_p(base),
+                                 C.c_size_t(nbytes), self._stream(), C.byref(self.ctx)))
+        ft, L = self.c.first_trainable_block, self.c.depth
+        self.T_f = self.tokens_attn[ft] if ft < L else self.tokens_mlp[L - 1]
+        self.T_last = self.tokens_mlp[L - 1]
+        self.frozen_drops = [i for i in range(self.c.n_drop) if self.c.drop_blocks[i] < ft]
+        self.train_drops = [i for i in range(self.c.n_drop) if self.c.drop_blocks[i] >= ft]
+        self.trainable_names = [n for n in self.params if n in HEAD_FIELDS or
+                                (n.startswith("blocks.") and int(n.split(".")[1]) >= ft)]
+
+    def _stream(self):
+        return C.c_void_p(self.torch.cuda.current_stream(self.device).cuda_stream)
+
+    def _chk(self, rc):
+        _check(rc, self.ctx)
+
+    def n_in(self, drop_i: int) -> int:
+        """patch tokens entering drop location drop_i"""
+        return self.tokens_attn[self.c.drop_blocks[drop_i]] - 1
+
+    def new_grads(self) -> dict:
+        return {n: self.torch.zeros_like(self.params[n]) for n in self.trainable_names}
+
+    # ---- entry points ---------------------------------------------------------------------
+    def bsr_refresh_weights(self):
+        self._chk(self.lib.bsr_refresh_weights(self.ctx, self._stream()))
+
+    def bsr_forward_frozen(self, inp, x_out=None, kept_idx_out=None, scores_out=None, forced_idx=None):
+        t = self.torch
+        B = inp.shape[0]
+        if x_out is None:
+            x_out = t.empty((B, self.T_f, self.c.dim), dtype=self.act_dtype, device=self.device)
+        self._chk(self.lib.bsr_forward_frozen(self.ctx, _dp(inp), B, _dp(x_out), _dp(kept_idx_out),
+                                              _dp(scores_out), _dp(forced_idx), self._stream()))
+        return x_out
+
+    def bsr_select_tokens(self, cls_attn, x_in, k, idx_out=None, x_out=None):
+        t = self.torch
+        B, n = cls_attn.shape
+        if idx_out is None:
+            idx_out = t.empty((B, max(k, 1)), dtype=t.int32, device=self.device)
+        if x_in is not None and x_out is None:
+            x_out = t.empty((B, k + 1, self.c.dim), dtype=self.act_dtype, device=self.device)
+        self._chk(self.lib.bsr_select_tokens(self.ctx, _dp(cls_attn), _dp(x_in), B, n, k, _dp(idx_out),
+                                             _dp(x_out), self._stream()))
+        return idx_out[:, :k], x_out
+
+    def bsr_train_blocks_fwd_bwd(self, x_in, labels, grads: dict, loss_out=None, logits_out=None,
+                                 x_final_out=None, kept_idx_out=None, scores_out=None, forced_idx=None):
+        t = self.torch
+        B = x_in.shape[0]
+        if loss_out is None:
+            loss_out = t.zeros(4, dtype=t.float32, device=self.device)
+        gs = _params_struct(grads)
+        self._chk(self.lib.bsr_train_blocks_fwd_bwd(self.ctx, _dp(x_in), _dp(labels), B, _dp(loss_out),
+                                                    _dp(logits_out), _dp(x_final_out), C.byref(gs),
+                                                    _dp(kept_idx_out), _dp(scores_out), _dp(forced_idx),
+                                                    self._stream()))
+        return loss_out
+
+    def bsr_sgd_step(self, grads: dict, momenta: dict | None, lr: float, momentum: float = 0.0,
+                     weight_decay: float = 0.0):
+        gs = _params_struct(grads)
+        ms = _params_struct(momenta) if momenta is not None else None
+        self._chk(self.lib.bsr_sgd_step(self.ctx, C.byref(gs), C.byref(ms) if ms is not None else None,
+                                        C.c_float(lr), C.c_float(momentum), C.c_float(weight_decay),
+                                        self._stream()))
+
+    def bsr_destroy(self):
+        if self.ctx:
+            self.lib.bsr_destroy(self.ctx)
+            self.ctx = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.bsr_destroy()
+        except Exception:
+            pass

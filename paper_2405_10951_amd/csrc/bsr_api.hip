@@ -1,0 +1,677 @@
+// C ABI of libbsr_hip (see include/bsr.h): context, workspace plan and the kernel sequence of one
+// Block Selective Reprogramming step.  Everything is enqueued on the caller's stream; nothing here
+// allocates device memory or waits for the device.
+#include <math.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <algorithm>
+#include <new>
+
+#include "../../include/bsr.h"
+#include "bsr_internal.h"
+
+using namespace bsr;
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+struct Schedule {
+  int T0 = 0;                       // tokens entering block 0 (CLS included)
+  int keep_k[BSR_MAX_BLOCKS] = {};  // per drop
+  int Ta[BSR_MAX_BLOCKS] = {};      // tokens seen by MHSA of block l
+  int Tm[BSR_MAX_BLOCKS] = {};      // tokens seen by FFN of block l
+  int drop_of[BSR_MAX_BLOCKS];      // drop index of block l, or -1
+  int T_last = 0;
+};
+
+struct SavedBlock {  // what a trainable block keeps for its backward pass (Sec. 3.2 of the paper)
+  float *mean1, *rstd1, *mean2, *rstd2, *lse;
+  char *h1, *qkv, *o, *xmid_full, *xmid, *h2, *u, *g, *xout;
+  int32_t* idx;
+};
+
+struct Shadow {  // bf16 copies of a block's matrices: transposed [out,in] and, if trained, straight [in,out]
+  bf16 *t_qkv, *t_proj, *t_fc1, *t_fc2;
+  bf16 *s_qkv, *s_proj, *s_fc1, *s_fc2;
+};
+
+struct Buffers {
+  bf16* t_patch = nullptr;
+  Shadow sh[BSR_MAX_BLOCKS] = {};
+  char *patches = nullptr, *x0 = nullptr, *x1 = nullptr, *h = nullptr, *qkv = nullptr, *o = nullptr, *g = nullptr;
+  float *clsp = nullptr, *scores = nullptr;
+  int32_t* idx_tmp = nullptr;
+  SavedBlock sv[BSR_MAX_BLOCKS] = {};
+  char *dxa = nullptr, *dxb = nullptr, *dgu = nullptr, *dh = nullptr, *dqkv = nullptr;
+  float *delta = nullptr, *partial = nullptr;
+  float *xc = nullptr, *z = nullptr, *dz = nullptr, *dxc = nullptr, *meanf = nullptr, *rstdf = nullptr;
+  float *logits = nullptr, *dlogits = nullptr, *loss_rows = nullptr;
+};
+
+}  // namespace
+
+struct bsr_ctx {
+  bsr_config cfg;
+  bsr_params p;
+  Schedule sc;
+  Buffers b;
+  bool f32;
+  size_t esz;
+  float eps;
+  char* ws;
+  size_t ws_bytes;
+  char err[512];
+};
+
+namespace {
+
+int fail(bsr_ctx* c, int code, const char* fmt, ...) {
+  char* dst = c ? c->err : g_err;
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(dst, 512, fmt, ap);
+  va_end(ap);
+  if (c) snprintf(g_err, sizeof(g_err), "%s", dst);
+  return code;
+}
+
+bool aligned16(const void* p) { return p && (((uintptr_t)p) & 15) == 0; }
+
+int check_hip(bsr_ctx* c, const char* where) {
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(c, BSR_ERR_HIP, "%s: %s", where, hipGetErrorString(e));
+  return BSR_OK;
+}
+
+// Validates the configuration and derives the token schedule: K = floor(keep_ratio * n + 1e-9)
+// on the current patch count when keep_k is not given (Sec. 4.1, Sec. 4.3 Discussion 3).
+int make_schedule(const bsr_config* c, Schedule* s, char* why, size_t whyn) {
+#define BAD(...) do { snprintf(why, whyn, __VA_ARGS__); return BSR_ERR_BAD_CONFIG; } while (0)
+  if (c->dim <= 0 || c->heads <= 0 || c->dim % c->heads) BAD("dim %d must be a positive multiple of heads %d", c->dim, c->heads);
+  if (c->dim % 8) BAD("dim %d must be a multiple of 8", c->dim);
+  if (c->dim / c->heads > 256) BAD("head size %d exceeds 256", c->dim / c->heads);
+  if (c->mlp_hidden <= 0 || c->mlp_hidden % 8) BAD("mlp_hidden %d must be a positive multiple of 8", c->mlp_hidden);
+  if (c->depth <= 0 || c->depth > BSR_MAX_BLOCKS) BAD("depth %d out of range 1..%d", c->depth, BSR_MAX_BLOCKS);
+  if (c->max_batch <= 0) BAD("max_batch %d must be positive", c->max_batch);
+  if (c->first_trainable_block < 0 || c->first_trainable_block > c->depth) BAD("first_trainable_block %d out of range", c->first_trainable_block);
+  if (c->dtype != BSR_BF16 && c->dtype != BSR_FP32) BAD("unknown dtype %d", c->dtype);
+  if (c->loss != BSR_LOSS_CE && c->loss != BSR_LOSS_MEAN_SQ) BAD("unknown loss %d", c->loss);
+  if (c->loss == BSR_LOSS_CE && c->num_classes <= 0) BAD("cross-entropy needs num_classes > 0");
+  if (c->loss == BSR_LOSS_MEAN_SQ && c->num_classes != 0) BAD("mean-square loss is defined for num_classes == 0");
+  if (c->num_classes < 0) BAD("num_classes %d is negative", c->num_classes);
+  if (c->image_size > 0) {
+    if (c->patch_size <= 0 || c->in_chans <= 0 || c->image_size % c->patch_size) BAD("image %d / patch %d / channels %d inconsistent", c->image_size, c->patch_size, c->in_chans);
+    if ((c->in_chans * c->patch_size * c->patch_size) % 8) BAD("patch vector length must be a multiple of 8");
+    int g = c->image_size / c->patch_size;
+    s->T0 = g * g + 1;
+  } else if (c->image_size == 0) {
+    if (c->tokens_in < 1) BAD("tokens_in %d must be >= 1 when image_size == 0", c->tokens_in);
+    s->T0 = c->tokens_in;
+  } else {
+    BAD("image_size %d is negative", c->image_size);
+  }
+  if (s->T0 > 1024) BAD("%d tokens exceed the limit of 1024", s->T0);
+  if (c->n_drop < 0 || c->n_drop > BSR_MAX_BLOCKS) BAD("n_drop %d out of range", c->n_drop);
+  bool given = false;
+  for (int i = 0; i < c->n_drop; ++i) given |= c->keep_k[i] != 0;
+  if (!given && c->n_drop > 0 && !(c->keep_ratio > 0.f && c->keep_ratio <= 1.f)) BAD("keep_ratio %g must lie in (0, 1]", (double)c->keep_ratio);
+  for (int l = 0; l < BSR_MAX_BLOCKS; ++l) s->drop_of[l] = -1;
+  int n = s->T0 - 1;
+  for (int i = 0; i < c->n_drop; ++i) {
+    int blk = c->drop_blocks[i];
+    if (blk < 0 || blk >= c->depth) BAD("drop_blocks[%d] = %d out of range", i, blk);
+    if (i && blk <= c->drop_blocks[i - 1]) BAD("drop_blocks must be strictly ascending");
+    int k = given ? c->keep_k[i] : (int)floor((double)c->keep_ratio * (double)n + 1e-9);
+    if (k < 0 || k > n) BAD("keep_k[%d] = %d must lie in 0..%d", i, k, n);
+    s->keep_k[i] = k;
+    s->drop_of[blk] = i;
+    n = k;
+  }
+  int T = s->T0;
+  for (int l = 0; l < c->depth; ++l) {
+    s->Ta[l] = T;
+    if (s->drop_of[l] >= 0) T = s->keep_k[s->drop_of[l]] + 1;
+    s->Tm[l] = T;
+  }
+  s->T_last = T;
+  return BSR_OK;
+#undef BAD
+}
+
+struct Carver {
+  char* base;
+  size_t off = 0;
+  template <typename T>
+  T* take(size_t count) {
+    size_t bytes = (count * sizeof(T) + 255) & ~(size_t)255;
+    T* p = base ? (T*)(base + off) : nullptr;
+    off += bytes;
+    return p;
+  }
+};
+
+// One function lays out the workspace; with base == nullptr it only measures.
+size_t carve(const bsr_config& c, const Schedule& s, char* base, Buffers* out) {
+  Carver w{base};
+  Buffers b;
+  const bool f32 = c.dtype == BSR_FP32;
+  const size_t E = f32 ? 4 : 2;
+  const size_t B = c.max_batch, D = c.dim, F = c.mlp_hidden, H = c.heads, T0 = s.T0;
+  const int ft = c.first_trainable_block, L = c.depth;
+  const size_t Kp = (size_t)c.in_chans * c.patch_size * c.patch_size;
+  if (!f32) {
+    if (c.image_size) b.t_patch = w.take<bf16>(D * Kp);
+    for (int l = 0; l < L; ++l) {
+      b.sh[l].t_qkv = w.take<bf16>(3 * D * D);
+      b.sh[l].t_proj = w.take<bf16>(D * D);
+      b.sh[l].t_fc1 = w.take<bf16>(D * F);
+      b.sh[l].t_fc2 = w.take<bf16>(D * F);
+      if (l >= ft) {
+        b.sh[l].s_qkv = w.take<bf16>(3 * D * D);
+        b.sh[l].s_proj = w.take<bf16>(D * D);
+        b.sh[l].s_fc1 = w.take<bf16>(D * F);
+        b.sh[l].s_fc2 = w.take<bf16>(D * F);
+      }
+    }
+  }
+  if (c.image_size) b.patches = w.take<char>(B * (T0 - 1) * Kp * E);
+  b.x0 = w.take<char>(B * T0 * D * E);
+  b.x1 = w.take<char>(B * T0 * D * E);
+  b.h = w.take<char>(B * T0 * D * E);
+  b.qkv = w.take<char>(B * T0 * 3 * D * E);
+  b.o = w.take<char>(B * T0 * D * E);
+  b.g = w.take<char>(B * T0 * F * E);
+  b.clsp = w.take<float>(B * H * T0);
+  b.scores = w.take<float>(B * T0);
+  b.idx_tmp = w.take<int32_t>(B * T0);
+  size_t Tmax = s.T_last;
+  for (int l = ft; l < L; ++l) {
+    const size_t Ta = s.Ta[l], Tm = s.Tm[l];
+    Tmax = std::max(Tmax, Ta);
+    SavedBlock& v = b.sv[l];
+    v.mean1 = w.take<float>(B * Ta);
+    v.rstd1 = w.take<float>(B * Ta);
+    v.mean2 = w.take<float>(B * Tm);
+    v.rstd2 = w.take<float>(B * Tm);
+    v.lse = w.take<float>(B * H * Ta);
+    v.h1 = w.take<char>(B * Ta * D * E);
+    v.qkv = w.take<char>(B * Ta * 3 * D * E);
+    v.o = w.take<char>(B * Ta * D * E);
+    v.xmid_full = w.take<char>(B * Ta * D * E);
+    v.xmid = (s.drop_of[l] >= 0) ? w.take<char>(B * Tm * D * E) : v.xmid_full;
+    v.h2 = w.take<char>(B * Tm * D * E);
+    v.u = w.take<char>(B * Tm * F * E);
+    v.g = w.take<char>(B * Tm * F * E);
+    v.xout = w.take<char>(B * Tm * D * E);
+    v.idx = w.take<int32_t>(B * Tm);
+  }
+  b.dxa = w.take<char>(B * Tmax * D * E);
+  b.dxb = w.take<char>(B * Tmax * D * E);
+  b.dgu = w.take<char>(B * Tmax * F * E);
+  b.dh = w.take<char>(B * Tmax * D * E);
+  b.dqkv = w.take<char>(B * Tmax * 3 * D * E);
+  b.delta = w.take<float>(B * H * Tmax);
+  b.partial = w.take<float>(std::max(colsum_partial_floats(0, (int)std::max(3 * D, F)), mean_sq_partial_floats()));
+  const size_t C = std::max(c.num_classes, 1);
+  b.xc = w.take<float>(B * D);
+  b.z = w.take<float>(B * D);
+  b.dz = w.take<float>(B * D);
+  b.dxc = w.take<float>(B * D);
+  b.meanf = w.take<float>(B);
+  b.rstdf = w.take<float>(B);
+  b.logits = w.take<float>(B * C);
+  b.dlogits = w.take<float>(B * C);
+  b.loss_rows = w.take<float>(B);
+  if (out) *out = b;
+  return w.off;
+}
+
+// ---- GEMM descriptions of the three uses of a linear layer ------------------------------------
+
+// y[M,out] = x[M,in] . W        (forward; W from the fp32 master [in,out] or the bf16 copy [out,in])
+GemmDesc fwd_desc(const bsr_ctx* c, const void* x, int M, int in, int out, const void* w_master,
+                  const bf16* w_t, void* y) {
+  GemmDesc g;
+  g.A = x; g.a_rs = in; g.a_cs = 1;
+  if (c->f32) { g.B = w_master; g.b_rs = out; g.b_cs = 1; }
+  else        { g.B = w_t;      g.b_rs = 1;   g.b_cs = in; }
+  g.C = y; g.ldc = out; g.M = M; g.N = out; g.K = in;
+  g.in_f32 = c->f32; g.out_f32 = c->f32;
+  return g;
+}
+
+// dx[M,in] = dy[M,out] . W^T    (Eq. 2 of the paper)
+GemmDesc dgrad_desc(const bsr_ctx* c, const void* dy, int M, int in, int out, const void* w_master,
+                    const bf16* w_s, void* dx) {
+  GemmDesc g;
+  g.A = dy; g.a_rs = out; g.a_cs = 1;
+  g.B = c->f32 ? w_master : (const void*)w_s; g.b_rs = 1; g.b_cs = out;   // B(k=o, n=i) = W[i*out + o]
+  g.C = dx; g.ldc = in; g.M = M; g.N = in; g.K = out;
+  g.in_f32 = c->f32; g.out_f32 = c->f32;
+  return g;
+}
+
+// dW[in,out] = x^T . dy  (Eq. 4), fp32 result summed over all M tokens
+GemmDesc wgrad_desc(const bsr_ctx* c, const void* x, const void* dy, int M, int in, int out, void* dw) {
+  GemmDesc g;
+  g.A = x;  g.a_rs = 1;   g.a_cs = in;    // A(m=i, k=token)
+  g.B = dy; g.b_rs = out; g.b_cs = 1;     // B(k=token, n=o)
+  g.C = dw; g.ldc = out; g.M = in; g.N = out; g.K = M;
+  g.in_f32 = c->f32; g.out_f32 = true;
+  return g;
+}
+
+void gemm(const bsr_ctx*, const GemmDesc& g, hipStream_t s) {
+  if (gemm_mfma_supported(g)) gemm_mfma(g, s);
+  else gemm_generic(g, s);
+}
+
+void attention_fwd(const bsr_ctx* c, const void* qkv, int B, int T, void* out, float* lse, float* clsp,
+                   hipStream_t s) {
+  const int H = c->cfg.heads, d = c->cfg.dim / H;
+  attn_fwd_generic(qkv, B, T, H, d, c->f32, out, lse, clsp, s);
+}
+
+void attention_bwd(const bsr_ctx* c, const void* qkv, const void* out, const void* dout, const float* lse,
+                   int B, int T, void* dqkv, hipStream_t s) {
+  const int H = c->cfg.heads, d = c->cfg.dim / H;
+  attn_bwd_generic(qkv, out, dout, lse, B, T, H, d, c->f32, c->b.delta, dqkv, s);
+}
+
+// Rank the patch tokens of a drop location and hand CLS + the K best to the FFN (Sec. 4.1).
+// Returns the device pointer holding the kept indices.
+const int32_t* drop_tokens(bsr_ctx* c, int B, int T, int k, const void* x_full, void* x_kept,
+                           int32_t* idx_own, const int32_t* forced, int32_t* idx_out, float* scores_out,
+                           hipStream_t s) {
+  const int n = T - 1, H = c->cfg.heads, D = c->cfg.dim;
+  float* scores = scores_out ? scores_out : c->b.scores;
+  const int32_t* idx = forced;
+  if (!forced || scores_out) cls_head_mean(c->b.clsp, B, H, T, scores, s);
+  if (!forced) {
+    topk_select(scores, B, n, k, idx_own, s);
+    idx = idx_own;
+  }
+  if (idx_out && k > 0)
+    (void)hipMemcpyAsync(idx_out, idx, sizeof(int32_t) * (size_t)B * k, hipMemcpyDeviceToDevice, s);
+  gather_tokens(x_full, idx, B, T, k, D, c->f32, x_kept, s);
+  return idx;
+}
+
+void build_shadows(bsr_ctx* c, int first_block, hipStream_t s) {
+  if (c->f32) return;
+  const bsr_config& cf = c->cfg;
+  const int D = cf.dim, F = cf.mlp_hidden;
+  if (first_block == 0 && cf.image_size)
+    cast_matrix((const float*)c->p.w_patch, cf.in_chans * cf.patch_size * cf.patch_size, D, nullptr, c->b.t_patch, s);
+  for (int l = first_block; l < cf.depth; ++l) {
+    const bsr_block_params& w = c->p.blocks[l];
+    Shadow& sh = c->b.sh[l];
+    cast_matrix((const float*)w.w_qkv, D, 3 * D, sh.s_qkv, sh.t_qkv, s);
+    cast_matrix((const float*)w.w_proj, D, D, sh.s_proj, sh.t_proj, s);
+    cast_matrix((const float*)w.w_fc1, D, F, sh.s_fc1, sh.t_fc1, s);
+    cast_matrix((const float*)w.w_fc2, F, D, sh.s_fc2, sh.t_fc2, s);
+  }
+}
+
+int check_params(const bsr_config& cf, const bsr_params* p, int first_block, bool need_stem, const char** which) {
+#define NEED(ptr, name) if (!aligned16(ptr)) { *which = name; return BSR_ERR_INVALID_ARG; }
+  if (need_stem && cf.image_size) { NEED(p->w_patch, "w_patch"); NEED(p->b_patch, "b_patch"); NEED(p->cls, "cls"); NEED(p->pos, "pos"); }
+  for (int l = first_block; l < cf.depth; ++l) {
+    const bsr_block_params& w = p->blocks[l];
+    NEED(w.ln1_g, "ln1_g"); NEED(w.ln1_b, "ln1_b"); NEED(w.w_qkv, "w_qkv"); NEED(w.b_qkv, "b_qkv");
+    NEED(w.w_proj, "w_proj"); NEED(w.b_proj, "b_proj"); NEED(w.ln2_g, "ln2_g"); NEED(w.ln2_b, "ln2_b");
+    NEED(w.w_fc1, "w_fc1"); NEED(w.b_fc1, "b_fc1"); NEED(w.w_fc2, "w_fc2"); NEED(w.b_fc2, "b_fc2");
+  }
+  if (cf.num_classes > 0) { NEED(p->lnf_g, "lnf_g"); NEED(p->lnf_b, "lnf_b"); NEED(p->w_head, "w_head"); NEED(p->b_head, "b_head"); }
+#undef NEED
+  return BSR_OK;
+}
+
+}  // namespace
+
+// ================================================================================ C ABI
+
+extern "C" {
+
+int32_t bsr_token_schedule(const bsr_config* cfg, int32_t* keep_k_out, int32_t* tokens_attn,
+                           int32_t* tokens_mlp) {
+  if (!cfg) return fail(nullptr, BSR_ERR_INVALID_ARG, "cfg is NULL");
+  Schedule s;
+  char why[256];
+  int rc = make_schedule(cfg, &s, why, sizeof(why));
+  if (rc != BSR_OK) return fail(nullptr, rc, "%s", why);
+  for (int i = 0; i < cfg->n_drop && keep_k_out; ++i) keep_k_out[i] = s.keep_k[i];
+  for (int l = 0; l < cfg->depth; ++l) {
+    if (tokens_attn) tokens_attn[l] = s.Ta[l];
+    if (tokens_mlp) tokens_mlp[l] = s.Tm[l];
+  }
+  return BSR_OK;
+}
+
+int32_t bsr_workspace_bytes(const bsr_config* cfg, size_t* bytes_out) {
+  if (!cfg || !bytes_out) return fail(nullptr, BSR_ERR_INVALID_ARG, "cfg or bytes_out is NULL");
+  Schedule s;
+  char why[256];
+  int rc = make_schedule(cfg, &s, why, sizeof(why));
+  if (rc != BSR_OK) return fail(nullptr, rc, "%s", why);
+  *bytes_out = carve(*cfg, s, nullptr, nullptr);
+  return BSR_OK;
+}
+
+int32_t bsr_init(const bsr_config* cfg, const bsr_params* params, void* workspace,
+                 size_t workspace_bytes, void* stream, bsr_ctx** ctx_out) {
+  if (!cfg || !params || !ctx_out) return fail(nullptr, BSR_ERR_INVALID_ARG, "cfg, params or ctx_out is NULL");
+  *ctx_out = nullptr;
+  Schedule s;
+  char why[256];
+  int rc = make_schedule(cfg, &s, why, sizeof(why));
+  if (rc != BSR_OK) return fail(nullptr, rc, "%s", why);
+  if (!workspace || (((uintptr_t)workspace) & 255)) return fail(nullptr, BSR_ERR_INVALID_ARG, "workspace must be a 256-byte aligned device pointer");
+  const size_t need = carve(*cfg, s, nullptr, nullptr);
+  if (workspace_bytes < need) return fail(nullptr, BSR_ERR_WORKSPACE_TOO_SMALL, "workspace has %zu bytes, %zu needed", workspace_bytes, need);
+  const char* which = "";
+  if (check_params(*cfg, params, 0, true, &which) != BSR_OK) return fail(nullptr, BSR_ERR_INVALID_ARG, "parameter %s is NULL or not 16-byte aligned", which);
+  int dev = 0;
+  hipDeviceProp_t prop;
+  if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) {
+    (void)hipGetLastError();
+    return fail(nullptr, BSR_ERR_HIP, "no usable HIP device");
+  }
+  if (strncmp(prop.gcnArchName, "gfx950", 6) != 0) return fail(nullptr, BSR_ERR_UNSUPPORTED_ARCH, "device is %s, this library is built for gfx950", prop.gcnArchName);
+  bsr_ctx* c = new (std::nothrow) bsr_ctx();
+  if (!c) return fail(nullptr, BSR_ERR_INVALID_ARG, "out of host memory");
+  c->cfg = *cfg;
+  c->p = *params;
+  c->sc = s;
+  c->f32 = cfg->dtype == BSR_FP32;
+  c->esz = c->f32 ? 4 : 2;
+  c->eps = cfg->ln_eps > 0.f ? cfg->ln_eps : 1e-6f;
+  c->ws = (char*)workspace;
+  c->ws_bytes = workspace_bytes;
+  c->err[0] = 0;
+  carve(*cfg, s, c->ws, &c->b);
+  build_shadows(c, 0, (hipStream_t)stream);
+  rc = check_hip(c, "bsr_init");
+  if (rc != BSR_OK) { snprintf(g_err, sizeof(g_err), "%s", c->err); delete c; return rc; }
+  *ctx_out = c;
+  return BSR_OK;
+}
+
+int32_t bsr_refresh_weights(bsr_ctx* c, void* stream) {
+  if (!c) return fail(nullptr, BSR_ERR_INVALID_ARG, "ctx is NULL");
+  build_shadows(c, 0, (hipStream_t)stream);
+  return check_hip(c, "bsr_refresh_weights");
+}
+
+int32_t bsr_forward_frozen(bsr_ctx* c, const void* input, int32_t B, void* x_out,
+                           int32_t* kept_idx_out, float* scores_out, const int32_t* forced_idx,
+                           void* stream) {
+  if (!c) return fail(nullptr, BSR_ERR_INVALID_ARG, "ctx is NULL");
+  if (!aligned16(input) || !aligned16(x_out)) return fail(c, BSR_ERR_INVALID_ARG, "input / x_out is NULL or not 16-byte aligned");
+  if (B < 1 || B > c->cfg.max_batch) return fail(c, BSR_ERR_INVALID_ARG, "B = %d outside 1..max_batch (%d)", B, c->cfg.max_batch);
+  hipStream_t s = (hipStream_t)stream;
+  const bsr_config& cf = c->cfg;
+  const Schedule& sc = c->sc;
+  Buffers& b = c->b;
+  const int D = cf.dim, F = cf.mlp_hidden, ft = cf.first_trainable_block;
+  const bool f32 = c->f32;
+  const size_t E = c->esz;
+
+  // stem (Sec. 3.1): patch embedding, CLS token, positional embedding
+  char* x = (ft == 0) ? (char*)x_out : b.x0;
+  char* xalt = b.x1;
+  if (cf.image_size) {
+    const int np = sc.T0 - 1, Kp = cf.in_chans * cf.patch_size * cf.patch_size;
+    patchify(input, B, cf.in_chans, cf.image_size, cf.patch_size, f32, b.patches, s);
+    GemmDesc g = fwd_desc(c, b.patches, B * np, Kp, D, c->p.w_patch, b.t_patch, x);
+    g.bias = (const float*)c->p.b_patch;
+    g.remap_np = np;
+    g.pos = (const float*)c->p.pos;
+    gemm(c, g, s);
+    write_cls_rows((const float*)c->p.cls, (const float*)c->p.pos, B, sc.T0, D, f32, x, s);
+  } else {
+    (void)hipMemcpyAsync(x, input, (size_t)B * sc.T0 * D * E, hipMemcpyDeviceToDevice, s);
+  }
+
+  size_t idx_off = 0, sc_off = 0;
+  for (int l = 0; l < ft; ++l) {
+    const bsr_block_params& w = c->p.blocks[l];
+    const Shadow& sh = b.sh[l];
+    const int Ta = sc.Ta[l], Tm = sc.Tm[l], M = B * Ta, M2 = B * Tm;
+    const int di = sc.drop_of[l];
+    // MHSA: x <- x + proj(Attention(LN1(x)))
+    layernorm_fwd(x, M, D, (const float*)w.ln1_g, (const float*)w.ln1_b, c->eps, f32, b.h, nullptr, nullptr, s);
+    GemmDesc g1 = fwd_desc(c, b.h, M, D, 3 * D, w.w_qkv, sh.t_qkv, b.qkv);
+    g1.bias = (const float*)w.b_qkv;
+    gemm(c, g1, s);
+    attention_fwd(c, b.qkv, B, Ta, b.o, nullptr, di >= 0 ? b.clsp : nullptr, s);
+    GemmDesc g2 = fwd_desc(c, b.o, M, D, D, w.w_proj, sh.t_proj, x);
+    g2.bias = (const float*)w.b_proj;
+    g2.res = x;
+    gemm(c, g2, s);
+    if (di >= 0) {
+      const int k = sc.keep_k[di];
+      drop_tokens(c, B, Ta, k, x, xalt, b.idx_tmp, forced_idx ? forced_idx + idx_off : nullptr,
+                  kept_idx_out ? kept_idx_out + idx_off : nullptr, scores_out ? scores_out + sc_off : nullptr, s);
+      std::swap(x, xalt);
+      idx_off += (size_t)B * k;
+      sc_off += (size_t)B * (Ta - 1);
+    }
+    // FFN: x <- x + fc2(GELU(fc1(LN2(x))))
+    layernorm_fwd(x, M2, D, (const float*)w.ln2_g, (const float*)w.ln2_b, c->eps, f32, b.h, nullptr, nullptr, s);
+    GemmDesc g3 = fwd_desc(c, b.h, M2, D, F, w.w_fc1, sh.t_fc1, b.g);
+    g3.bias = (const float*)w.b_fc1;
+    g3.act = ACT_GELU;
+    gemm(c, g3, s);
+    char* dest = (l == ft - 1) ? (char*)x_out : x;
+    GemmDesc g4 = fwd_desc(c, b.g, M2, F, D, w.w_fc2, sh.t_fc2, dest);
+    g4.bias = (const float*)w.b_fc2;
+    g4.res = x;
+    gemm(c, g4, s);
+  }
+  return check_hip(c, "bsr_forward_frozen");
+}
+
+int32_t bsr_select_tokens(bsr_ctx* c, const float* cls_attn, const void* x_in, int32_t B, int32_t n,
+                          int32_t k, int32_t* idx_out, void* x_out, void* stream) {
+  if (!c) return fail(nullptr, BSR_ERR_INVALID_ARG, "ctx is NULL");
+  if (!aligned16(cls_attn) || !aligned16(idx_out)) return fail(c, BSR_ERR_INVALID_ARG, "cls_attn / idx_out is NULL or not 16-byte aligned");
+  if ((x_in == nullptr) != (x_out == nullptr)) return fail(c, BSR_ERR_INVALID_ARG, "x_in and x_out must both be given or both be NULL");
+  if (x_in && (!aligned16(x_in) || !aligned16(x_out))) return fail(c, BSR_ERR_INVALID_ARG, "x_in / x_out not 16-byte aligned");
+  if (B < 1 || n < 0 || n > 1024 || k < 0 || k > n) return fail(c, BSR_ERR_INVALID_ARG, "need B >= 1 and 0 <= k <= n <= 1024 (B=%d n=%d k=%d)", B, n, k);
+  hipStream_t s = (hipStream_t)stream;
+  topk_select(cls_attn, B, n, k, idx_out, s);
+  if (x_in) gather_tokens(x_in, idx_out, B, n + 1, k, c->cfg.dim, c->f32, x_out, s);
+  return check_hip(c, "bsr_select_tokens");
+}
+
+int32_t bsr_train_blocks_fwd_bwd(bsr_ctx* c, const void* x_in, const int32_t* labels, int32_t B,
+                                 float* loss_out, float* logits_out, void* x_final_out,
+                                 const bsr_params* grads, int32_t* kept_idx_out, float* scores_out,
+                                 const int32_t* forced_idx, void* stream) {
+  if (!c) return fail(nullptr, BSR_ERR_INVALID_ARG, "ctx is NULL");
+  const bsr_config& cf = c->cfg;
+  if (!aligned16(x_in) || !loss_out || !grads) return fail(c, BSR_ERR_INVALID_ARG, "x_in, loss_out or grads is NULL / misaligned");
+  if (cf.loss == BSR_LOSS_CE && !labels) return fail(c, BSR_ERR_INVALID_ARG, "labels are required for the cross-entropy loss");
+  if (B < 1 || B > cf.max_batch) return fail(c, BSR_ERR_INVALID_ARG, "B = %d outside 1..max_batch (%d)", B, cf.max_batch);
+  const char* which = "";
+  if (check_params(cf, grads, cf.first_trainable_block, false, &which) != BSR_OK)
+    return fail(c, BSR_ERR_INVALID_ARG, "gradient tensor %s is NULL or not 16-byte aligned", which);
+  hipStream_t s = (hipStream_t)stream;
+  const Schedule& sc = c->sc;
+  Buffers& b = c->b;
+  const int D = cf.dim, F = cf.mlp_hidden, ft = cf.first_trainable_block, L = cf.depth;
+  const bool f32 = c->f32;
+  const size_t E = c->esz;
+  const int32_t* idx_used[BSR_MAX_BLOCKS] = {};
+
+  // ---------------------------------------------------------------- forward, keeping activations
+  const char* x = (const char*)x_in;
+  size_t idx_off = 0, sc_off = 0;
+  for (int l = ft; l < L; ++l) {
+    const bsr_block_params& w = c->p.blocks[l];
+    const Shadow& sh = b.sh[l];
+    SavedBlock& v = b.sv[l];
+    const int Ta = sc.Ta[l], Tm = sc.Tm[l], M = B * Ta, M2 = B * Tm;
+    const int di = sc.drop_of[l];
+    layernorm_fwd(x, M, D, (const float*)w.ln1_g, (const float*)w.ln1_b, c->eps, f32, v.h1, v.mean1, v.rstd1, s);
+    GemmDesc g1 = fwd_desc(c, v.h1, M, D, 3 * D, w.w_qkv, sh.t_qkv, v.qkv);
+    g1.bias = (const float*)w.b_qkv;
+    gemm(c, g1, s);
+    attention_fwd(c, v.qkv, B, Ta, v.o, v.lse, di >= 0 ? b.clsp : nullptr, s);
+    GemmDesc g2 = fwd_desc(c, v.o, M, D, D, w.w_proj, sh.t_proj, v.xmid_full);
+    g2.bias = (const float*)w.b_proj;
+    g2.res = x;
+    gemm(c, g2, s);
+    if (di >= 0) {
+      const int k = sc.keep_k[di];
+      idx_used[l] = drop_tokens(c, B, Ta, k, v.xmid_full, v.xmid, v.idx, forced_idx ? forced_idx + idx_off : nullptr,
+                                kept_idx_out ? kept_idx_out + idx_off : nullptr,
+                                scores_out ? scores_out + sc_off : nullptr, s);
+      idx_off += (size_t)B * k;
+      sc_off += (size_t)B * (Ta - 1);
+    }
+    layernorm_fwd(v.xmid, M2, D, (const float*)w.ln2_g, (const float*)w.ln2_b, c->eps, f32, v.h2, v.mean2, v.rstd2, s);
+    GemmDesc g3 = fwd_desc(c, v.h2, M2, D, F, w.w_fc1, sh.t_fc1, v.g);
+    g3.bias = (const float*)w.b_fc1;
+    g3.act = ACT_GELU;
+    g3.aux = v.u;
+    gemm(c, g3, s);
+    GemmDesc g4 = fwd_desc(c, v.g, M2, F, D, w.w_fc2, sh.t_fc2, v.xout);
+    g4.bias = (const float*)w.b_fc2;
+    g4.res = v.xmid;
+    gemm(c, g4, s);
+    x = v.xout;
+  }
+  const int Tl = sc.T_last;
+  if (x_final_out) (void)hipMemcpyAsync(x_final_out, x, (size_t)B * Tl * D * E, hipMemcpyDeviceToDevice, s);
+
+  // ---------------------------------------------------------------- head, loss, dLoss/dx_last
+  char* dx = b.dxa;
+  char* dx_other = b.dxb;
+  if (cf.loss == BSR_LOSS_CE) {
+    const int C = cf.num_classes;
+    extract_cls(x, B, Tl, D, f32, b.xc, s);
+    layernorm_fwd(b.xc, B, D, (const float*)c->p.lnf_g, (const float*)c->p.lnf_b, c->eps, true, b.z, b.meanf, b.rstdf, s);
+    GemmDesc gl;   // logits = z . W_h + b_h (fp32)
+    gl.A = b.z; gl.a_rs = D; gl.a_cs = 1; gl.B = c->p.w_head; gl.b_rs = C; gl.b_cs = 1;
+    gl.C = b.logits; gl.ldc = C; gl.M = B; gl.N = C; gl.K = D; gl.in_f32 = gl.out_f32 = true;
+    gl.bias = (const float*)c->p.b_head;
+    gemm_generic(gl, s);
+    cross_entropy(b.logits, labels, B, C, b.loss_rows, b.dlogits, loss_out, s);
+    if (logits_out) (void)hipMemcpyAsync(logits_out, b.logits, sizeof(float) * (size_t)B * C, hipMemcpyDeviceToDevice, s);
+    GemmDesc gz;   // dz = dlogits . W_h^T
+    gz.A = b.dlogits; gz.a_rs = C; gz.a_cs = 1; gz.B = c->p.w_head; gz.b_rs = 1; gz.b_cs = C;
+    gz.C = b.dz; gz.ldc = D; gz.M = B; gz.N = D; gz.K = C; gz.in_f32 = gz.out_f32 = true;
+    gemm_generic(gz, s);
+    GemmDesc gw;   // dW_h = z^T . dlogits
+    gw.A = b.z; gw.a_rs = 1; gw.a_cs = D; gw.B = b.dlogits; gw.b_rs = C; gw.b_cs = 1;
+    gw.C = grads->w_head; gw.ldc = C; gw.M = D; gw.N = C; gw.K = B; gw.in_f32 = gw.out_f32 = true;
+    gemm_generic(gw, s);
+    colsum(b.dlogits, B, C, C, true, b.partial, (float*)grads->b_head, s);
+    layernorm_bwd_params(b.dz, b.xc, b.meanf, b.rstdf, B, D, true, b.partial, (float*)grads->lnf_g, (float*)grads->lnf_b, s);
+    layernorm_bwd_dx(b.dz, b.xc, b.meanf, b.rstdf, (const float*)c->p.lnf_g, nullptr, B, D, true, b.dxc, s);
+    place_cls_grad(b.dxc, B, Tl, D, f32, dx, s);
+  } else {
+    mean_sq_loss(x, (int64_t)B * Tl * D, f32, b.partial, loss_out, dx, s);
+  }
+
+  // ---------------------------------------------------------------- backward (Eq. 2-5), last block first
+  for (int l = L - 1; l >= ft; --l) {
+    const bsr_block_params& w = c->p.blocks[l];
+    const bsr_block_params& gw = grads->blocks[l];
+    const Shadow& sh = b.sh[l];
+    SavedBlock& v = b.sv[l];
+    const int Ta = sc.Ta[l], Tm = sc.Tm[l], M = B * Ta, M2 = B * Tm;
+    const int di = sc.drop_of[l];
+    const char* xin = (l == ft) ? (const char*)x_in : b.sv[l - 1].xout;
+
+    // FFN branch.  du = (dx . W2^T) * GELU'(u); dW2 = g^T dx; dh2 = du . W1^T; dW1 = h2^T du
+    GemmDesc d1 = dgrad_desc(c, dx, M2, F, D, w.w_fc2, sh.s_fc2, b.dgu);
+    d1.act = ACT_GELU_BWD;
+    d1.aux = v.u;
+    gemm(c, d1, s);
+    gemm(c, wgrad_desc(c, v.g, dx, M2, F, D, gw.w_fc2), s);
+    colsum(dx, M2, D, D, f32, b.partial, (float*)gw.b_fc2, s);
+    gemm(c, dgrad_desc(c, b.dgu, M2, D, F, w.w_fc1, sh.s_fc1, b.dh), s);
+    gemm(c, wgrad_desc(c, v.h2, b.dgu, M2, D, F, gw.w_fc1), s);
+    colsum(b.dgu, M2, F, F, f32, b.partial, (float*)gw.b_fc1, s);
+    layernorm_bwd_params(b.dh, v.xmid, v.mean2, v.rstd2, M2, D, f32, b.partial, (float*)gw.ln2_g, (float*)gw.ln2_b, s);
+    layernorm_bwd_dx(b.dh, v.xmid, v.mean2, v.rstd2, (const float*)w.ln2_g, dx, M2, D, f32, dx_other, s);
+    std::swap(dx, dx_other);   // dx: gradient at x_mid (kept tokens)
+
+    // adjoint of the token drop: dropped tokens receive nothing from the FFN side
+    if (di >= 0) {
+      scatter_tokens(dx, idx_used[l], B, Ta, sc.keep_k[di], D, f32, dx_other, s);
+      std::swap(dx, dx_other);
+    }
+
+    // MHSA branch.  dO = dx . Wproj^T; dWproj = o^T dx; attention backward; dWqkv = h1^T dqkv
+    gemm(c, dgrad_desc(c, dx, M, D, D, w.w_proj, sh.s_proj, b.dh), s);
+    gemm(c, wgrad_desc(c, v.o, dx, M, D, D, gw.w_proj), s);
+    colsum(dx, M, D, D, f32, b.partial, (float*)gw.b_proj, s);
+    attention_bwd(c, v.qkv, v.o, b.dh, v.lse, B, Ta, b.dqkv, s);
+    gemm(c, wgrad_desc(c, v.h1, b.dqkv, M, D, 3 * D, gw.w_qkv), s);
+    colsum(b.dqkv, M, 3 * D, 3 * D, f32, b.partial, (float*)gw.b_qkv, s);
+    gemm(c, dgrad_desc(c, b.dqkv, M, D, 3 * D, w.w_qkv, sh.s_qkv, b.dh), s);
+    layernorm_bwd_params(b.dh, xin, v.mean1, v.rstd1, M, D, f32, b.partial, (float*)gw.ln1_g, (float*)gw.ln1_b, s);
+    if (l > ft) {   // the gradient is not carried below the earliest trainable block (Fig. 2)
+      layernorm_bwd_dx(b.dh, xin, v.mean1, v.rstd1, (const float*)w.ln1_g, dx, M, D, f32, dx_other, s);
+      std::swap(dx, dx_other);
+    }
+  }
+  return check_hip(c, "bsr_train_blocks_fwd_bwd");
+}
+
+int32_t bsr_sgd_step(bsr_ctx* c, const bsr_params* grads, const bsr_params* momenta, float lr,
+                     float momentum, float weight_decay, void* stream) {
+  if (!c) return fail(nullptr, BSR_ERR_INVALID_ARG, "ctx is NULL");
+  if (!grads) return fail(c, BSR_ERR_INVALID_ARG, "grads is NULL");
+  if (momentum < 0.f) return fail(c, BSR_ERR_INVALID_ARG, "momentum must be >= 0");
+  if (momentum > 0.f && !momenta) return fail(c, BSR_ERR_INVALID_ARG, "momenta is NULL but momentum > 0");
+  const bsr_config& cf = c->cfg;
+  const char* which = "";
+  if (check_params(cf, grads, cf.first_trainable_block, false, &which) != BSR_OK)
+    return fail(c, BSR_ERR_INVALID_ARG, "gradient tensor %s is NULL or not 16-byte aligned", which);
+  if (momentum > 0.f && check_params(cf, momenta, cf.first_trainable_block, false, &which) != BSR_OK)
+    return fail(c, BSR_ERR_INVALID_ARG, "momentum tensor %s is NULL or not 16-byte aligned", which);
+  hipStream_t s = (hipStream_t)stream;
+  const int D = cf.dim, F = cf.mlp_hidden;
+  const bool mom = momentum > 0.f;
+#define UPD(field, rows, cols, sp, tp)                                                              \
+  sgd_update((float*)W.field, (const float*)G.field, mom ? (float*)Mo.field : nullptr, rows, cols, lr, \
+             momentum, weight_decay, sp, tp, s)
+  for (int l = cf.first_trainable_block; l < cf.depth; ++l) {
+    const bsr_block_params& W = c->p.blocks[l];
+    const bsr_block_params& G = grads->blocks[l];
+    const bsr_block_params& Mo = mom ? momenta->blocks[l] : grads->blocks[l];
+    const Shadow& sh = c->b.sh[l];
+    UPD(ln1_g, 1, D, nullptr, nullptr); UPD(ln1_b, 1, D, nullptr, nullptr);
+    UPD(w_qkv, D, 3 * D, sh.s_qkv, sh.t_qkv); UPD(b_qkv, 1, 3 * D, nullptr, nullptr);
+    UPD(w_proj, D, D, sh.s_proj, sh.t_proj); UPD(b_proj, 1, D, nullptr, nullptr);
+    UPD(ln2_g, 1, D, nullptr, nullptr); UPD(ln2_b, 1, D, nullptr, nullptr);
+    UPD(w_fc1, D, F, sh.s_fc1, sh.t_fc1); UPD(b_fc1, 1, F, nullptr, nullptr);
+    UPD(w_fc2, F, D, sh.s_fc2, sh.t_fc2); UPD(b_fc2, 1, D, nullptr, nullptr);
+  }
+  if (cf.num_classes > 0) {
+    const bsr_params& W = c->p;
+    const bsr_params& G = *grads;
+    const bsr_params& Mo = mom ? *momenta : *grads;
+    UPD(lnf_g, 1, D, nullptr, nullptr); UPD(lnf_b, 1, D, nullptr, nullptr);
+    UPD(w_head, 1, D * cf.num_classes, nullptr, nullptr); UPD(b_head, 1, cf.num_classes, nullptr, nullptr);
+  }
+#undef UPD
+  return check_hip(c, "bsr_sgd_step");
+}
+
+int32_t bsr_destroy(bsr_ctx* c) {
+  delete c;
+  return BSR_OK;
+}
+
+const char* bsr_last_error(const bsr_ctx* c) { return c ? c->err : g_err; }
+
+}  // extern "C"

@@ -1,0 +1,80 @@
+// Internal declarations shared by the translation units of libbsr_hip: kernel launchers take raw
+// device pointers and a stream, never allocate and never synchronise.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace bsr {
+
+typedef __bf16 bf16;
+
+enum Act { ACT_NONE = 0, ACT_GELU = 1, ACT_GELU_BWD = 2 };
+
+// C(m,n) = epilogue( sum_k A(m,k) * B(k,n) ), operands addressed through element strides so that
+// one description covers X.W (forward), dY.W^T (Eq. 2) and X^T.dY (Eq. 4).
+struct GemmDesc {
+  const void* A = nullptr; int64_t a_rs = 0, a_cs = 0;   // A(m,k) = A[m*a_rs + k*a_cs]
+  const void* B = nullptr; int64_t b_rs = 0, b_cs = 0;   // B(k,n) = B[k*b_rs + n*b_cs]
+  void* C = nullptr;       int64_t ldc = 0;              // C(m,n) = C[row(m)*ldc + n]
+  int M = 0, N = 0, K = 0;
+  bool in_f32 = false;                                   // A and B are fp32 (else bf16)
+  bool out_f32 = false;                                  // C is fp32 (else bf16)
+  const float* bias = nullptr;                           // [N], added before the activation
+  int act = ACT_NONE;
+  void* aux = nullptr;       // ACT_GELU: if set, receives the pre-activation u (dtype of C, ld = ldc)
+                             // ACT_GELU_BWD: the stored u; C = acc * GELU'(u)
+  const void* res = nullptr; // residual added last (dtype of C, ld = ldc, same row mapping)
+  int remap_np = 0;          // > 0 (patch embedding): row(m) = m + m / np + 1, and pos[(m % np + 1), n]
+  const float* pos = nullptr;//   is added; rows of CLS tokens are left untouched
+};
+
+// ---- generic (any shape, fp32 or bf16 storage, fp32 arithmetic) ---------------------------------
+void gemm_generic(const GemmDesc& g, hipStream_t s);
+void attn_fwd_generic(const void* qkv, int B, int T, int H, int d, bool f32, void* out, float* lse,
+                      float* cls_prob, hipStream_t s);
+void attn_bwd_generic(const void* qkv, const void* out, const void* dout, const float* lse, int B,
+                      int T, int H, int d, bool f32, float* delta, void* dqkv, hipStream_t s);
+
+// ---- bf16 MFMA paths --------------------------------------------------------------------------
+bool gemm_mfma_supported(const GemmDesc& g);
+void gemm_mfma(const GemmDesc& g, hipStream_t s);
+
+// ---- row-wise / element-wise kernels ------------------------------------------------------------
+void layernorm_fwd(const void* x, int64_t M, int D, const float* gamma, const float* beta, float eps,
+                   bool f32, void* y, float* mean, float* rstd, hipStream_t s);
+// dx = res + LN'(dy) (res may be null; dx may be null to skip it)
+void layernorm_bwd_dx(const void* dy, const void* x, const float* mean, const float* rstd,
+                      const float* gamma, const void* res, int64_t M, int D, bool f32, void* dx,
+                      hipStream_t s);
+// dgamma[j] = sum_m dy*xhat, dbeta[j] = sum_m dy ; partial is scratch of colsum_partial_floats()
+void layernorm_bwd_params(const void* dy, const void* x, const float* mean, const float* rstd,
+                          int64_t M, int D, bool f32, float* partial, float* dgamma, float* dbeta,
+                          hipStream_t s);
+// out[j] = sum_m a[m*ld + j]
+void colsum(const void* a, int64_t M, int N, int64_t ld, bool f32, float* partial, float* out,
+            hipStream_t s);
+size_t colsum_partial_floats(int64_t M, int N);
+
+void patchify(const void* img, int B, int C, int S, int P, bool f32, void* out, hipStream_t s);
+void write_cls_rows(const float* cls, const float* pos, int B, int T, int D, bool f32, void* x,
+                    hipStream_t s);
+void cls_head_mean(const float* cls_prob, int B, int H, int T, float* scores, hipStream_t s);
+void topk_select(const float* scores, int B, int n, int k, int32_t* idx, hipStream_t s);
+void gather_tokens(const void* x, const int32_t* idx, int B, int T, int k, int D, bool f32, void* y,
+                   hipStream_t s);
+void scatter_tokens(const void* dy, const int32_t* idx, int B, int T, int k, int D, bool f32,
+                    void* dx, hipStream_t s);
+void extract_cls(const void* x, int B, int T, int D, bool f32, float* out, hipStream_t s);
+void place_cls_grad(const float* dxc, int B, int T, int D, bool f32, void* dx, hipStream_t s);
+void cross_entropy(const float* logits, const int32_t* labels, int B, int C, float* loss_rows,
+                   float* dlogits, float* loss, hipStream_t s);
+void mean_sq_loss(const void* x, int64_t n, bool f32, float* partial, float* loss, void* dx,
+                  hipStream_t s);
+size_t mean_sq_partial_floats();
+
+void cast_matrix(const float* w, int rows, int cols, bf16* straight, bf16* transposed, hipStream_t s);
+// SGD on one tensor; matrices (rows > 1) also refresh their bf16 copies (either may be null)
+void sgd_update(float* w, const float* g, float* m, int rows, int cols, float lr, float mu, float wd,
+                bf16* straight, bf16* transposed, hipStream_t s);
+
+}  // namespace bsr

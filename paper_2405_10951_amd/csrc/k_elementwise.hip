@@ -1,0 +1,496 @@
+// Row-wise and element-wise kernels of the BSR step: LayerNorm forward / backward, column sums
+// (bias and LayerNorm parameter gradients), patch extraction, CLS-attention ranking (Eq. 6 of the
+// paper), token gather / scatter, losses, SGD and weight casts.  All are HBM-bound; reductions are
+// two-pass with a fixed order, so results are bit-reproducible run to run.
+#include "bsr_internal.h"
+
+namespace bsr {
+
+namespace {
+
+constexpr int WAVE = 64;
+constexpr int COLSUM_R = 64;  // row chunks of the two-pass column reductions
+
+__device__ inline float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, WAVE);
+  return v;
+}
+__device__ inline float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, WAVE));
+  return v;
+}
+
+// ---------------------------------------------------------------- LayerNorm
+// One wavefront per token row; mean and biased variance in fp32, two passes over the row.
+template <typename T>
+__global__ __launch_bounds__(256) void ln_fwd_kernel(const T* __restrict__ x, int64_t M, int D,
+                                                     const float* __restrict__ gamma,
+                                                     const float* __restrict__ beta, float eps,
+                                                     T* __restrict__ y, float* __restrict__ mean,
+                                                     float* __restrict__ rstd) {
+  const int lane = threadIdx.x % WAVE;
+  const int64_t m = (int64_t)blockIdx.x * (blockDim.x / WAVE) + threadIdx.x / WAVE;
+  if (m >= M) return;
+  const T* xr = x + m * D;
+  float s = 0.f;
+  for (int j = lane; j < D; j += WAVE) s += (float)xr[j];
+  const float mu = wave_sum(s) / (float)D;
+  float v = 0.f;
+  for (int j = lane; j < D; j += WAVE) {
+    float c = (float)xr[j] - mu;
+    v += c * c;
+  }
+  const float rs = rsqrtf(wave_sum(v) / (float)D + eps);
+  if (lane == 0) {
+    if (mean) mean[m] = mu;
+    if (rstd) rstd[m] = rs;
+  }
+  T* yr = y + m * D;
+  for (int j = lane; j < D; j += WAVE) yr[j] = (T)(((float)xr[j] - mu) * rs * gamma[j] + beta[j]);
+}
+
+// dx = res + rstd * (g - mean(g) - xhat * mean(g * xhat)),  g = dy * gamma
+template <typename T>
+__global__ __launch_bounds__(256) void ln_bwd_dx_kernel(const T* __restrict__ dy, const T* __restrict__ x,
+                                                        const float* __restrict__ mean,
+                                                        const float* __restrict__ rstd,
+                                                        const float* __restrict__ gamma,
+                                                        const T* __restrict__ res, int64_t M, int D,
+                                                        T* __restrict__ dx) {
+  const int lane = threadIdx.x % WAVE;
+  const int64_t m = (int64_t)blockIdx.x * (blockDim.x / WAVE) + threadIdx.x / WAVE;
+  if (m >= M) return;
+  const float mu = mean[m], rs = rstd[m];
+  const T* dyr = dy + m * D;
+  const T* xr = x + m * D;
+  float s1 = 0.f, s2 = 0.f;
+  for (int j = lane; j < D; j += WAVE) {
+    float g = (float)dyr[j] * gamma[j];
+    s1 += g;
+    s2 += g * ((float)xr[j] - mu) * rs;
+  }
+  const float m1 = wave_sum(s1) / (float)D, m2 = wave_sum(s2) / (float)D;
+  for (int j = lane; j < D; j += WAVE) {
+    float g = (float)dyr[j] * gamma[j];
+    float xh = ((float)xr[j] - mu) * rs;
+    float v = rs * (g - m1 - xh * m2);
+    if (res) v += (float)res[m * D + j];
+    dx[m * D + j] = (T)v;
+  }
+}
+
+// Pass 1 of a column reduction over M rows: block (cx, r) sums rows of chunk r for 64 columns.
+// WITH_XHAT: two sums, dy*xhat (slot 0) and dy (slot 1); otherwise the plain column sum (slot 0).
+template <typename T, bool WITH_XHAT>
+__global__ __launch_bounds__(256) void colsum_partial_kernel(const T* __restrict__ a, int64_t ld,
+                                                             const T* __restrict__ x,
+                                                             const float* __restrict__ mean,
+                                                             const float* __restrict__ rstd, int64_t M,
+                                                             int N, int rows_per_chunk,
+                                                             float* __restrict__ partial) {
+  __shared__ float red[2][4][WAVE];
+  const int lane = threadIdx.x % WAVE, w = threadIdx.x / WAVE;
+  const int col = blockIdx.x * WAVE + lane;
+  const int64_t r0 = (int64_t)blockIdx.y * rows_per_chunk;
+  const int64_t r1 = min(r0 + (int64_t)rows_per_chunk, M);
+  float s0 = 0.f, s1 = 0.f;
+  if (col < N) {
+    for (int64_t m = r0 + w; m < r1; m += 4) {
+      float v = (float)a[m * ld + col];
+      if (WITH_XHAT) {
+        s0 += v * ((float)x[m * ld + col] - mean[m]) * rstd[m];
+        s1 += v;
+      } else {
+        s0 += v;
+      }
+    }
+  }
+  red[0][w][lane] = s0;
+  red[1][w][lane] = s1;
+  __syncthreads();
+  if (w == 0 && col < N) {
+    partial[(int64_t)blockIdx.y * N + col] = red[0][0][lane] + red[0][1][lane] + red[0][2][lane] + red[0][3][lane];
+    if (WITH_XHAT)
+      partial[(int64_t)(COLSUM_R + blockIdx.y) * N + col] =
+          red[1][0][lane] + red[1][1][lane] + red[1][2][lane] + red[1][3][lane];
+  }
+}
+
+// Pass 2: out[col] = sum over chunks in ascending order.
+__global__ void colsum_final_kernel(const float* __restrict__ partial, int N, int chunks,
+                                    float* __restrict__ out0, float* __restrict__ out1) {
+  const int col = blockIdx.x * blockDim.x + threadIdx.x;
+  if (col >= N) return;
+  float s = 0.f;
+  for (int r = 0; r < chunks; ++r) s += partial[(int64_t)r * N + col];
+  out0[col] = s;
+  if (out1) {
+    float t = 0.f;
+    for (int r = 0; r < chunks; ++r) t += partial[(int64_t)(COLSUM_R + r) * N + col];
+    out1[col] = t;
+  }
+}
+
+// ---------------------------------------------------------------- stem helpers
+// out[(b*N + p), (c*P + r)*P + q] = img[b, c, gy*P + r, gx*P + q],  p = gy*G + gx
+template <typename T>
+__global__ void patchify_kernel(const T* __restrict__ img, int B, int C, int S, int P,
+                                T* __restrict__ out) {
+  const int G = S / P, Kp = C * P * P;
+  const int64_t total = (int64_t)B * G * G * Kp;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total;
+       i += (int64_t)gridDim.x * blockDim.x) {
+    int kk = (int)(i % Kp);
+    int64_t bp = i / Kp;
+    int p = (int)(bp % (G * G));
+    int b = (int)(bp / (G * G));
+    int q = kk % P, r = (kk / P) % P, c = kk / (P * P);
+    int gy = p / G, gx = p % G;
+    out[i] = img[(((int64_t)b * C + c) * S + gy * P + r) * S + gx * P + q];
+  }
+}
+
+template <typename T>
+__global__ void write_cls_rows_kernel(const float* __restrict__ cls, const float* __restrict__ pos,
+                                      int B, int T_, int D, T* __restrict__ x) {
+  const int b = blockIdx.x;
+  for (int j = threadIdx.x; j < D; j += blockDim.x) x[(int64_t)b * T_ * D + j] = (T)(cls[j] + pos[j]);
+}
+
+// ---------------------------------------------------------------- token importance and selection
+// scores[b, j] = (sum_h cls_prob[b, h, 1 + j]) / H, heads added in ascending order (Eq. 6 read as
+// the head mean of the post-softmax CLS row; the CLS column itself is not ranked).
+__global__ void cls_head_mean_kernel(const float* __restrict__ cls_prob, int B, int H, int T_,
+                                     float* __restrict__ scores) {
+  const int n = T_ - 1;
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= (int64_t)B * n) return;
+  const int b = (int)(i / n), j = (int)(i % n);
+  float s = 0.f;
+  for (int h = 0; h < H; ++h) s += cls_prob[((int64_t)b * H + h) * T_ + 1 + j];
+  scores[i] = s / (float)H;
+}
+
+// One wavefront per image.  Token j is kept when fewer than k tokens beat it (larger score, or the
+// same score and a lower index); kept indices are written in ascending order by a ballot prefix.
+__global__ __launch_bounds__(WAVE) void topk_select_kernel(const float* __restrict__ scores, int n,
+                                                            int k, int32_t* __restrict__ idx) {
+  __shared__ float sc[1024];
+  const int b = blockIdx.x, lane = threadIdx.x;
+  for (int j = lane; j < n; j += WAVE) sc[j] = scores[(int64_t)b * n + j];
+  __syncthreads();
+  int base = 0;
+  for (int c0 = 0; c0 < n; c0 += WAVE) {
+    const int j = c0 + lane;
+    bool keep = false;
+    if (j < n) {
+      const float mine = sc[j];
+      int ahead = 0;
+      for (int i = 0; i < n; ++i) {
+        const float o = sc[i];
+        ahead += (o > mine || (o == mine && i < j)) ? 1 : 0;
+      }
+      keep = ahead < k;
+    }
+    const unsigned long long mask = __ballot(keep);
+    if (keep) idx[(int64_t)b * k + base + __popcll(mask & ((1ull << lane) - 1ull))] = j;
+    base += __popcll(mask);
+  }
+}
+
+// y[b,0] = x[b,0]; y[b,1+i] = x[b,1+idx[b,i]].  One block per output row, 16-byte accesses.
+__global__ void gather_rows_kernel(const uint4* __restrict__ x, const int32_t* __restrict__ idx,
+                                   int T_, int k, int row_vecs, uint4* __restrict__ y) {
+  const int i = blockIdx.x, b = blockIdx.y;
+  const int src = (i == 0) ? 0 : 1 + idx[(int64_t)b * k + i - 1];
+  const uint4* s = x + ((int64_t)b * T_ + src) * row_vecs;
+  uint4* d = y + ((int64_t)b * (k + 1) + i) * row_vecs;
+  for (int v = threadIdx.x; v < row_vecs; v += blockDim.x) d[v] = s[v];
+}
+
+// Adjoint of the gather: every row of dx is written exactly once (kept rows copied, dropped rows
+// zero), found by a binary search of the ascending kept list — no atomics, no separate memset.
+__global__ void scatter_rows_kernel(const uint4* __restrict__ dy, const int32_t* __restrict__ idx,
+                                    int T_, int k, int row_vecs, uint4* __restrict__ dx) {
+  const int t = blockIdx.x, b = blockIdx.y;
+  int src = -1;
+  if (t == 0) {
+    src = 0;
+  } else {
+    const int32_t* row = idx + (int64_t)b * k;
+    int lo = 0, hi = k - 1;
+    while (lo <= hi) {
+      int mid = (lo + hi) >> 1;
+      int v = row[mid];
+      if (v == t - 1) { src = 1 + mid; break; }
+      if (v < t - 1) lo = mid + 1; else hi = mid - 1;
+    }
+  }
+  uint4* d = dx + ((int64_t)b * T_ + t) * row_vecs;
+  if (src < 0) {
+    for (int v = threadIdx.x; v < row_vecs; v += blockDim.x) d[v] = make_uint4(0, 0, 0, 0);
+  } else {
+    const uint4* s = dy + ((int64_t)b * (k + 1) + src) * row_vecs;
+    for (int v = threadIdx.x; v < row_vecs; v += blockDim.x) d[v] = s[v];
+  }
+}
+
+// ---------------------------------------------------------------- head helpers
+template <typename T>
+__global__ void extract_cls_kernel(const T* __restrict__ x, int T_, int D, float* __restrict__ out) {
+  const int b = blockIdx.x;
+  for (int j = threadIdx.x; j < D; j += blockDim.x) out[(int64_t)b * D + j] = (float)x[(int64_t)b * T_ * D + j];
+}
+
+template <typename T>
+__global__ void place_cls_grad_kernel(const float* __restrict__ dxc, int T_, int D, T* __restrict__ dx) {
+  const int t = blockIdx.x, b = blockIdx.y;
+  T* d = dx + ((int64_t)b * T_ + t) * D;
+  for (int j = threadIdx.x; j < D; j += blockDim.x) d[j] = (t == 0) ? (T)dxc[(int64_t)b * D + j] : (T)0.f;
+}
+
+// One wavefront per image: loss_b = logsumexp(z) - z[y]; dlogits = (softmax(z) - onehot) / B.
+__global__ __launch_bounds__(WAVE) void cross_entropy_kernel(const float* __restrict__ logits,
+                                                             const int32_t* __restrict__ labels, int B,
+                                                             int C, float* __restrict__ loss_rows,
+                                                             float* __restrict__ dlogits) {
+  const int b = blockIdx.x, lane = threadIdx.x;
+  const float* z = logits + (int64_t)b * C;
+  float mx = -INFINITY;
+  for (int c = lane; c < C; c += WAVE) mx = fmaxf(mx, z[c]);
+  mx = wave_max(mx);
+  float s = 0.f;
+  for (int c = lane; c < C; c += WAVE) s += expf(z[c] - mx);
+  const float lse = mx + logf(wave_sum(s));
+  const int y = labels[b];
+  if (lane == 0) loss_rows[b] = lse - ((y >= 0 && y < C) ? z[y] : 0.f);
+  for (int c = lane; c < C; c += WAVE)
+    dlogits[(int64_t)b * C + c] = (expf(z[c] - lse) - (c == y ? 1.f : 0.f)) / (float)B;
+}
+
+__global__ void mean_of_rows_kernel(const float* __restrict__ v, int n, float scale, float* __restrict__ out) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) {
+    float s = 0.f;
+    for (int i = 0; i < n; ++i) s += v[i];
+    *out = s * scale;
+  }
+}
+
+constexpr int MSQ_BLOCKS = 256;
+template <typename T>
+__global__ __launch_bounds__(256) void mean_sq_kernel(const T* __restrict__ x, int64_t n,
+                                                      float* __restrict__ partial, T* __restrict__ dx) {
+  __shared__ float red[4];
+  const int64_t per = (n + MSQ_BLOCKS - 1) / MSQ_BLOCKS;
+  const int64_t i0 = (int64_t)blockIdx.x * per, i1 = min(i0 + per, n);
+  const float g = 2.0f / (float)n;
+  float s = 0.f;
+  for (int64_t i = i0 + threadIdx.x; i < i1; i += blockDim.x) {
+    float v = (float)x[i];
+    s += v * v;
+    if (dx) dx[i] = (T)(v * g);
+  }
+  s = wave_sum(s);
+  if (threadIdx.x % WAVE == 0) red[threadIdx.x / WAVE] = s;
+  __syncthreads();
+  if (threadIdx.x == 0) partial[blockIdx.x] = red[0] + red[1] + red[2] + red[3];
+}
+
+// ---------------------------------------------------------------- weights: casts and SGD
+// 32x32 tiles through LDS so that both the straight [rows,cols] and the transposed [cols,rows]
+// bf16 copies are written with contiguous rows.  With UPDATE the tile is first updated by SGD:
+//   g' = g + wd*w;  mu > 0: m = mu*m + g', w -= lr*m;  else w -= lr*g'   (Sec. 5 of the paper).
+template <bool UPDATE>
+__global__ __launch_bounds__(256) void matrix_tile_kernel(float* __restrict__ w, const float* __restrict__ g,
+                                                          float* __restrict__ mom, int rows, int cols,
+                                                          float lr, float mu, float wd,
+                                                          bf16* __restrict__ straight,
+                                                          bf16* __restrict__ transposed) {
+  __shared__ float tile[32][33];
+  const int tx = threadIdx.x % 32, ty = threadIdx.x / 32;
+  const int c0 = blockIdx.x * 32, r0 = blockIdx.y * 32;
+  for (int i = ty; i < 32; i += 8) {
+    const int r = r0 + i, c = c0 + tx;
+    float v = 0.f;
+    if (r < rows && c < cols) {
+      const int64_t off = (int64_t)r * cols + c;
+      v = w[off];
+      if (UPDATE) {
+        float gp = g[off] + wd * v;
+        if (mu > 0.f) {
+          float m = mu * mom[off] + gp;
+          mom[off] = m;
+          v -= lr * m;
+        } else {
+          v -= lr * gp;
+        }
+        w[off] = v;
+      }
+      if (straight) straight[off] = (bf16)v;
+    }
+    tile[i][tx] = v;
+  }
+  __syncthreads();
+  if (transposed) {
+    for (int i = ty; i < 32; i += 8) {
+      const int c = c0 + i, r = r0 + tx;
+      if (r < rows && c < cols) transposed[(int64_t)c * rows + r] = (bf16)tile[tx][i];
+    }
+  }
+}
+
+__global__ void sgd_vector_kernel(float* __restrict__ w, const float* __restrict__ g,
+                                  float* __restrict__ mom, int64_t n, float lr, float mu, float wd) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  float v = w[i];
+  float gp = g[i] + wd * v;
+  if (mu > 0.f) {
+    float m = mu * mom[i] + gp;
+    mom[i] = m;
+    v -= lr * m;
+  } else {
+    v -= lr * gp;
+  }
+  w[i] = v;
+}
+
+inline int rows_per_chunk(int64_t M) { return (int)((M + COLSUM_R - 1) / COLSUM_R); }
+inline int chunks_of(int64_t M) {
+  int rpc = rows_per_chunk(M);
+  return (int)((M + rpc - 1) / rpc);
+}
+
+}  // namespace
+
+// ---------------------------------------------------------------- launchers
+
+void layernorm_fwd(const void* x, int64_t M, int D, const float* gamma, const float* beta, float eps,
+                   bool f32, void* y, float* mean, float* rstd, hipStream_t s) {
+  if (M <= 0) return;
+  dim3 grid((unsigned)((M + 3) / 4));
+  if (f32) ln_fwd_kernel<float><<<grid, 256, 0, s>>>((const float*)x, M, D, gamma, beta, eps, (float*)y, mean, rstd);
+  else ln_fwd_kernel<bf16><<<grid, 256, 0, s>>>((const bf16*)x, M, D, gamma, beta, eps, (bf16*)y, mean, rstd);
+}
+
+void layernorm_bwd_dx(const void* dy, const void* x, const float* mean, const float* rstd,
+                      const float* gamma, const void* res, int64_t M, int D, bool f32, void* dx,
+                      hipStream_t s) {
+  if (M <= 0 || !dx) return;
+  dim3 grid((unsigned)((M + 3) / 4));
+  if (f32)
+    ln_bwd_dx_kernel<float><<<grid, 256, 0, s>>>((const float*)dy, (const float*)x, mean, rstd, gamma,
+                                                  (const float*)res, M, D, (float*)dx);
+  else
+    ln_bwd_dx_kernel<bf16><<<grid, 256, 0, s>>>((const bf16*)dy, (const bf16*)x, mean, rstd, gamma,
+                                                 (const bf16*)res, M, D, (bf16*)dx);
+}
+
+size_t colsum_partial_floats(int64_t, int N) { return (size_t)2 * COLSUM_R * (size_t)N; }
+
+void layernorm_bwd_params(const void* dy, const void* x, const float* mean, const float* rstd,
+                          int64_t M, int D, bool f32, float* partial, float* dgamma, float* dbeta,
+                          hipStream_t s) {
+  if (M <= 0) return;
+  const int rpc = rows_per_chunk(M), ch = chunks_of(M);
+  dim3 grid((D + WAVE - 1) / WAVE, ch);
+  if (f32)
+    colsum_partial_kernel<float, true><<<grid, 256, 0, s>>>((const float*)dy, D, (const float*)x, mean, rstd, M, D, rpc, partial);
+  else
+    colsum_partial_kernel<bf16, true><<<grid, 256, 0, s>>>((const bf16*)dy, D, (const bf16*)x, mean, rstd, M, D, rpc, partial);
+  colsum_final_kernel<<<(D + 255) / 256, 256, 0, s>>>(partial, D, ch, dgamma, dbeta);
+}
+
+void colsum(const void* a, int64_t M, int N, int64_t ld, bool f32, float* partial, float* out,
+            hipStream_t s) {
+  if (M <= 0) return;
+  const int rpc = rows_per_chunk(M), ch = chunks_of(M);
+  dim3 grid((N + WAVE - 1) / WAVE, ch);
+  if (f32)
+    colsum_partial_kernel<float, false><<<grid, 256, 0, s>>>((const float*)a, ld, nullptr, nullptr, nullptr, M, N, rpc, partial);
+  else
+    colsum_partial_kernel<bf16, false><<<grid, 256, 0, s>>>((const bf16*)a, ld, nullptr, nullptr, nullptr, M, N, rpc, partial);
+  colsum_final_kernel<<<(N + 255) / 256, 256, 0, s>>>(partial, N, ch, out, nullptr);
+}
+
+void patchify(const void* img, int B, int C, int S, int P, bool f32, void* out, hipStream_t s) {
+  const int64_t total = (int64_t)B * C * S * S;
+  const unsigned grid = (unsigned)std::min<int64_t>((total + 255) / 256, 65536);
+  if (f32) patchify_kernel<float><<<grid, 256, 0, s>>>((const float*)img, B, C, S, P, (float*)out);
+  else patchify_kernel<bf16><<<grid, 256, 0, s>>>((const bf16*)img, B, C, S, P, (bf16*)out);
+}
+
+void write_cls_rows(const float* cls, const float* pos, int B, int T, int D, bool f32, void* x,
+                    hipStream_t s) {
+  if (f32) write_cls_rows_kernel<float><<<B, 256, 0, s>>>(cls, pos, B, T, D, (float*)x);
+  else write_cls_rows_kernel<bf16><<<B, 256, 0, s>>>(cls, pos, B, T, D, (bf16*)x);
+}
+
+void cls_head_mean(const float* cls_prob, int B, int H, int T, float* scores, hipStream_t s) {
+  const int64_t total = (int64_t)B * (T - 1);
+  if (total <= 0) return;
+  cls_head_mean_kernel<<<(unsigned)((total + 255) / 256), 256, 0, s>>>(cls_prob, B, H, T, scores);
+}
+
+void topk_select(const float* scores, int B, int n, int k, int32_t* idx, hipStream_t s) {
+  if (B <= 0 || k <= 0) return;
+  topk_select_kernel<<<B, WAVE, 0, s>>>(scores, n, k, idx);
+}
+
+void gather_tokens(const void* x, const int32_t* idx, int B, int T, int k, int D, bool f32, void* y,
+                   hipStream_t s) {
+  const int row_vecs = D * (f32 ? 4 : 2) / 16;
+  gather_rows_kernel<<<dim3(k + 1, B), 64, 0, s>>>((const uint4*)x, idx, T, k, row_vecs, (uint4*)y);
+}
+
+void scatter_tokens(const void* dy, const int32_t* idx, int B, int T, int k, int D, bool f32,
+                    void* dx, hipStream_t s) {
+  const int row_vecs = D * (f32 ? 4 : 2) / 16;
+  scatter_rows_kernel<<<dim3(T, B), 64, 0, s>>>((const uint4*)dy, idx, T, k, row_vecs, (uint4*)dx);
+}
+
+void extract_cls(const void* x, int B, int T, int D, bool f32, float* out, hipStream_t s) {
+  if (f32) extract_cls_kernel<float><<<B, 256, 0, s>>>((const float*)x, T, D, out);
+  else extract_cls_kernel<bf16><<<B, 256, 0, s>>>((const bf16*)x, T, D, out);
+}
+
+void place_cls_grad(const float* dxc, int B, int T, int D, bool f32, void* dx, hipStream_t s) {
+  if (f32) place_cls_grad_kernel<float><<<dim3(T, B), 128, 0, s>>>(dxc, T, D, (float*)dx);
+  else place_cls_grad_kernel<bf16><<<dim3(T, B), 128, 0, s>>>(dxc, T, D, (bf16*)dx);
+}
+
+void cross_entropy(const float* logits, const int32_t* labels, int B, int C, float* loss_rows,
+                   float* dlogits, float* loss, hipStream_t s) {
+  cross_entropy_kernel<<<B, WAVE, 0, s>>>(logits, labels, B, C, loss_rows, dlogits);
+  mean_of_rows_kernel<<<1, 64, 0, s>>>(loss_rows, B, 1.0f / (float)B, loss);
+}
+
+size_t mean_sq_partial_floats() { return MSQ_BLOCKS; }
+
+void mean_sq_loss(const void* x, int64_t n, bool f32, float* partial, float* loss, void* dx,
+                  hipStream_t s) {
+  if (f32) mean_sq_kernel<float><<<MSQ_BLOCKS, 256, 0, s>>>((const float*)x, n, partial, (float*)dx);
+  else mean_sq_kernel<bf16><<<MSQ_BLOCKS, 256, 0, s>>>((const bf16*)x, n, partial, (bf16*)dx);
+  mean_of_rows_kernel<<<1, 64, 0, s>>>(partial, MSQ_BLOCKS, 1.0f / (float)n, loss);
+}
+
+void cast_matrix(const float* w, int rows, int cols, bf16* straight, bf16* transposed, hipStream_t s) {
+  dim3 grid((cols + 31) / 32, (rows + 31) / 32);
+  matrix_tile_kernel<false><<<grid, 256, 0, s>>>(const_cast<float*>(w), nullptr, nullptr, rows, cols,
+                                                 0.f, 0.f, 0.f, straight, transposed);
+}
+
+void sgd_update(float* w, const float* g, float* m, int rows, int cols, float lr, float mu, float wd,
+                bf16* straight, bf16* transposed, hipStream_t s) {
+  if (!straight && !transposed) {
+    const int64_t n = (int64_t)rows * cols;
+    sgd_vector_kernel<<<(unsigned)((n + 255) / 256), 256, 0, s>>>(w, g, m, n, lr, mu, wd);
+    return;
+  }
+  dim3 grid((cols + 31) / 32, (rows + 31) / 32);
+  matrix_tile_kernel<true><<<grid, 256, 0, s>>>(w, g, m, rows, cols, lr, mu, wd, straight, transposed);
+}
+
+}  // namespace bsr
