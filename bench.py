@@ -1,0 +1,172 @@
+#!/usr/bin/env python3
+"""Benchmark of the BSR fine-tuning step on one MI355X.
+
+One "step" = bsr_forward_frozen -> bsr_train_blocks_fwd_bwd -> bsr_sgd_step on one batch of synthetic
+ViT-B/16-shaped inputs already resident in HBM.  Prints ONE JSON line: images/sec, the roofline of
+the dominant kernel class (the bf16 MFMA GEMMs) and the CPU oracle timed on the host cores.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
+PEAK_FP32_TFLOPS = 157.3
+
+
+def build_context(cfg, batch, seed=0):
+    import bsr_synth as S
+    import paper_2405_10951_amd as P
+    params = S.make_params(cfg, seed=seed)
+    ctx = P.Context(cfg, params, batch)
+    return ctx
+
+
+def time_steps(ctx, cfg, batch, steps, warmup, profile_steps=0):
+    import torch
+    import bsr_synth as S
+    dev = ctx.device
+    x, y = S.make_inputs(cfg, batch=batch)
+    xin = torch.as_tensor(x).to(dev).to(ctx.act_dtype).contiguous()
+    lab = torch.as_tensor(y, dtype=torch.int32).to(dev)
+    grads = ctx.new_grads()
+    mom = {n: torch.zeros_like(g) for n, g in grads.items()}
+    x_f = torch.empty((batch, ctx.T_f, cfg["dim"]), dtype=ctx.act_dtype, device=dev)
+    loss = torch.zeros(4, dtype=torch.float32, device=dev)
+
+    def step():
+        ctx.bsr_forward_frozen(xin, x_out=x_f)
+        ctx.bsr_train_blocks_fwd_bwd(x_f, lab, grads, loss_out=loss)
+        ctx.bsr_sgd_step(grads, mom, lr=1e-3, momentum=0.9, weight_decay=1e-4)
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for _ in range(steps):
+        step()
+    e1.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_events = e0.elapsed_time(e1)
+    prof = None
+    if profile_steps:
+        ctx.bsr_profile_begin()
+        for _ in range(profile_steps):
+            step()
+        prof = ctx.bsr_profile_end()
+        prof = {k: (v[0] / profile_steps, v[1] / profile_steps, v[2] // profile_steps) for k, v in prof.items()}
+    return dict(wall_s=wall, ms_per_step=1e3 * wall / steps, ms_per_step_events=ms_events / steps,
+                loss=float(loss[0].item()), prof=prof)
+
+
+def cpu_baseline(cfg, sample_batch):
+    """The oracle as it stands (float build, OpenMP), one full step on a bounded sample."""
+    import bsr_synth as S
+    from oracle import Oracle
+    orc = Oracle("f32")
+    p = S.make_params(cfg)
+    x, y = S.make_inputs(cfg, batch=sample_batch)
+    t0 = time.perf_counter()
+    r = orc.step(cfg, p, x, y)
+    dt = time.perf_counter() - t0
+    cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+    return dict(value=sample_batch / dt, unit="images/sec", cores=cores, kind="oracle",
+                sample=f"one full step (frozen forward, selection, trainable fwd+bwd) of the same "
+                       f"workload on {sample_batch} of the {cfg['batch']} images, fp32 C oracle with "
+                       f"OpenMP, {dt:.1f} s", loss=r["loss"])
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="c3_vit_b")
+    ap.add_argument("--batch", type=int, default=None)
+    ap.add_argument("--keep-ratio", type=float, default=None)
+    ap.add_argument("--trainable", type=int, default=None, help="number of trainable blocks (suffix)")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--no-compare", action="store_true", help="skip the keep-1.0 / full-fine-tuning legs")
+    ap.add_argument("--cpu-sample", type=int, default=16)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build measures ONE GPU; --gpus must be 1 (no multi-GPU path exists)")
+
+    import torch
+    import bsr_synth as S
+    import paper_2405_10951_amd as P
+    from paper_2405_10951_amd.flops import step_flops
+    if not torch.cuda.is_available():
+        sys.exit("bench.py needs an MI355X (no CPU fallback exists)")
+    P.load_library()
+
+    cfg = S.get_config(args.workload)
+    if args.keep_ratio is not None:
+        cfg["keep_ratio"] = args.keep_ratio
+    if args.trainable is not None:
+        cfg["first_trainable"] = cfg["depth"] - args.trainable
+    batch = args.batch or cfg["batch"]
+    cfg["batch"] = batch
+
+    def flops_of(c, ctx):
+        pd = c["in_chans"] * c["patch_size"] ** 2
+        return step_flops(c["dim"], c["mlp_hidden"], c["num_classes"], pd, ctx.tokens_attn[0] - 1,
+                          ctx.tokens_attn, ctx.tokens_mlp, c["first_trainable"], batch)
+
+    ctx = build_context(cfg, batch)
+    r = time_steps(ctx, cfg, batch, args.steps, args.warmup, profile_steps=min(args.steps, 10))
+    fl = flops_of(cfg, ctx)
+    ips = batch * args.steps / r["wall_s"]
+    gemm_ms, gemm_flops, gemm_n = r["prof"]["gemm"]
+    bf16 = cfg["dtype"] == "bf16"
+    peak = PEAK_BF16_TFLOPS if bf16 else PEAK_FP32_TFLOPS
+    achieved = gemm_flops / (gemm_ms * 1e-3) / 1e12
+    out = {
+        "metric": "BSR train images/sec, ViT-B/16 bs32 on 1 MI355X; % bf16 MFMA peak",
+        "value": ips, "unit": "images/sec", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": r["ms_per_step"], "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": cfg["dtype"], "data": "synthetic",
+        "config": {"workload": f"{args.workload}: ViT dim {cfg['dim']} depth {cfg['depth']} batch {batch}, "
+                               f"keep {cfg['keep_ratio']} at blocks {cfg['drop_blocks']}, "
+                               f"trainable blocks {cfg['first_trainable']}..{cfg['depth'] - 1} + head, "
+                               f"SGD momentum 0.9",
+                   "global_batch": batch, "tokens_per_block": ctx.tokens_attn},
+        "step_gflop": fl["total"] / 1e9,
+        "step_pct_of_bf16_mfma_peak": 100.0 * fl["total"] / (r["ms_per_step"] * 1e-3) / (peak * 1e12),
+        "ms_per_step_hip_events": r["ms_per_step_events"],
+        "loss": r["loss"],
+        "roofline": {"bound": "mfma", "kernel": "GEMM launches of the step (forward, dgrad, wgrad)",
+                     "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak,
+                     "traffic": None, "launches_per_step": gemm_n, "ms_per_step": gemm_ms,
+                     "gflop_per_step": gemm_flops / 1e9},
+        "kernel_classes_ms_per_step": {k: v[0] for k, v in r["prof"].items()},
+    }
+    del ctx
+    if not args.no_compare:
+        cmp_steps = max(5, args.steps // 5)
+        for key, over in (("speedup_vs_keep_1.0", dict(keep_ratio=1.0)),
+                          ("speedup_vs_full_finetune", dict(keep_ratio=1.0, first_trainable=0))):
+            c2 = dict(cfg, **over)
+            ctx2 = build_context(c2, batch)
+            r2 = time_steps(ctx2, c2, batch, cmp_steps, max(2, args.warmup // 2))
+            out[key] = r2["ms_per_step"] / r["ms_per_step"]
+            out[key + "_algorithmic"] = flops_of(c2, ctx2)["total"] / fl["total"]
+            del ctx2
+            torch.cuda.empty_cache()
+    if not args.no_cpu:
+        out["cpu_baseline"] = cpu_baseline(cfg, min(args.cpu_sample, batch))
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -182,6 +182,19 @@ int32_t bsr_train_blocks_fwd_bwd(bsr_ctx* ctx, const void* x_in, const int32_t* 
 int32_t bsr_sgd_step(bsr_ctx* ctx, const bsr_params* grads, const bsr_params* momenta, float lr,
                      float momentum, float weight_decay, void* stream);
 
+/*
+ * Profiling mode, for measurement only.  Between bsr_profile_begin and bsr_profile_end every launch
+ * of the classes below is bracketed by a pair of HIP events on the call's stream (created on first
+ * use and kept by the context).  bsr_profile_end WAITS for the recorded work, then adds up, per
+ * class, the elapsed milliseconds, the floating-point operations launched (2*M*N*K per GEMM; 4*T*T*d
+ * per head for attention forward, 10*T*T*d backward) and the number of launches.
+ *   ms, flops, launches  host arrays of BSR_PROF_CLASSES entries
+ * Errors: INVALID_ARG, HIP.
+ */
+enum { BSR_PROF_GEMM = 0, BSR_PROF_ATTN_FWD = 1, BSR_PROF_ATTN_BWD = 2, BSR_PROF_CLASSES = 3 };
+int32_t bsr_profile_begin(bsr_ctx* ctx);
+int32_t bsr_profile_end(bsr_ctx* ctx, double* ms, double* flops, int32_t* launches);
+
 /* Release the host-side context (no device memory is touched). */
 int32_t bsr_destroy(bsr_ctx* ctx);
 

@@ -63,7 +63,7 @@ def load_library():
     lib.bsr_last_error.argtypes = [C.c_void_p]
     for name in ("bsr_token_schedule", "bsr_workspace_bytes", "bsr_init", "bsr_refresh_weights",
                  "bsr_forward_frozen", "bsr_select_tokens", "bsr_train_blocks_fwd_bwd",
-                 "bsr_sgd_step", "bsr_destroy"):
+                 "bsr_sgd_step", "bsr_destroy", "bsr_profile_begin", "bsr_profile_end"):
         getattr(lib, name).restype = C.c_int32
     lib.bsr_token_schedule.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
     lib.bsr_workspace_bytes.argtypes = [C.c_void_p, C.POINTER(C.c_size_t)]
@@ -78,6 +78,8 @@ def load_library():
                                              C.c_void_p, C.c_void_p]
     lib.bsr_sgd_step.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_float, C.c_float, C.c_float, C.c_void_p]
     lib.bsr_destroy.argtypes = [C.c_void_p]
+    lib.bsr_profile_begin.argtypes = [C.c_void_p]
+    lib.bsr_profile_end.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
     _lib = lib
     return lib
 
@@ -233,6 +235,17 @@ class Context:
         self._chk(self.lib.bsr_sgd_step(self.ctx, C.byref(gs), C.byref(ms) if ms is not None else None,
                                         C.c_float(lr), C.c_float(momentum), C.c_float(weight_decay),
                                         self._stream()))
+
+    def bsr_profile_begin(self):
+        self._chk(self.lib.bsr_profile_begin(self.ctx))
+
+    def bsr_profile_end(self) -> dict:
+        """-> {class: (ms, flops, launches)} for gemm / attn_fwd / attn_bwd; waits for the stream."""
+        ms = (C.c_double * 3)()
+        fl = (C.c_double * 3)()
+        n = (C.c_int32 * 3)()
+        self._chk(self.lib.bsr_profile_end(self.ctx, ms, fl, n))
+        return {name: (ms[i], fl[i], n[i]) for i, name in enumerate(("gemm", "attn_fwd", "attn_bwd"))}
 
     def bsr_destroy(self):
         if self.ctx:

@@ -8,6 +8,7 @@
 
 #include <algorithm>
 #include <new>
+#include <vector>
 
 #include "../../include/bsr.h"
 #include "bsr_internal.h"
@@ -53,7 +54,16 @@ struct Buffers {
 
 }  // namespace
 
+struct ProfRec {
+  hipEvent_t start, stop;
+  int cls;
+  double flops;
+};
+
 struct bsr_ctx {
+  std::vector<ProfRec> prof;   // event pairs of the profiling mode (bsr_profile_begin / _end)
+  size_t prof_used = 0;
+  bool prof_on = false;
   bsr_config cfg;
   bsr_params p;
   Schedule sc;
@@ -264,20 +274,45 @@ GemmDesc wgrad_desc(const bsr_ctx* c, const void* x, const void* dy, int M, int 
   return g;
 }
 
-void gemm(const bsr_ctx*, const GemmDesc& g, hipStream_t s) {
+// Profiling mode: an event pair around one launch (or a short launch group) of a kernel class.
+struct ProfScope {
+  bsr_ctx* c;
+  hipStream_t s;
+  ProfRec* r = nullptr;
+  ProfScope(bsr_ctx* c_, int cls, double flops, hipStream_t s_) : c(c_), s(s_) {
+    if (!c->prof_on) return;
+    if (c->prof_used == c->prof.size()) {
+      ProfRec n{};
+      if (hipEventCreate(&n.start) != hipSuccess || hipEventCreate(&n.stop) != hipSuccess) return;
+      c->prof.push_back(n);
+    }
+    r = &c->prof[c->prof_used++];
+    r->cls = cls;
+    r->flops = flops;
+    (void)hipEventRecord(r->start, s);
+  }
+  ~ProfScope() {
+    if (r) (void)hipEventRecord(r->stop, s);
+  }
+};
+
+void gemm(bsr_ctx* c, const GemmDesc& g, hipStream_t s) {
+  ProfScope ps(c, BSR_PROF_GEMM, 2.0 * g.M * g.N * g.K, s);
   if (gemm_mfma_supported(g)) gemm_mfma(g, s);
   else gemm_generic(g, s);
 }
 
-void attention_fwd(const bsr_ctx* c, const void* qkv, int B, int T, void* out, float* lse, float* clsp,
+void attention_fwd(bsr_ctx* c, const void* qkv, int B, int T, void* out, float* lse, float* clsp,
                    hipStream_t s) {
   const int H = c->cfg.heads, d = c->cfg.dim / H;
+  ProfScope ps(c, BSR_PROF_ATTN_FWD, 4.0 * B * H * (double)T * T * d, s);
   attn_fwd_generic(qkv, B, T, H, d, c->f32, out, lse, clsp, s);
 }
 
-void attention_bwd(const bsr_ctx* c, const void* qkv, const void* out, const void* dout, const float* lse,
+void attention_bwd(bsr_ctx* c, const void* qkv, const void* out, const void* dout, const float* lse,
                    int B, int T, void* dqkv, hipStream_t s) {
   const int H = c->cfg.heads, d = c->cfg.dim / H;
+  ProfScope ps(c, BSR_PROF_ATTN_BWD, 10.0 * B * H * (double)T * T * d, s);
   attn_bwd_generic(qkv, out, dout, lse, B, T, H, d, c->f32, c->b.delta, dqkv, s);
 }
 
@@ -667,7 +702,35 @@ int32_t bsr_sgd_step(bsr_ctx* c, const bsr_params* grads, const bsr_params* mome
   return check_hip(c, "bsr_sgd_step");
 }
 
+int32_t bsr_profile_begin(bsr_ctx* c) {
+  if (!c) return fail(nullptr, BSR_ERR_INVALID_ARG, "ctx is NULL");
+  c->prof_used = 0;
+  c->prof_on = true;
+  return BSR_OK;
+}
+
+int32_t bsr_profile_end(bsr_ctx* c, double* ms, double* flops, int32_t* launches) {
+  if (!c) return fail(nullptr, BSR_ERR_INVALID_ARG, "ctx is NULL");
+  if (!ms || !flops || !launches) return fail(c, BSR_ERR_INVALID_ARG, "output arrays are NULL");
+  c->prof_on = false;
+  for (int k = 0; k < BSR_PROF_CLASSES; ++k) { ms[k] = 0; flops[k] = 0; launches[k] = 0; }
+  for (size_t i = 0; i < c->prof_used; ++i) {
+    ProfRec& r = c->prof[i];
+    float t = 0.f;
+    if (hipEventSynchronize(r.stop) != hipSuccess || hipEventElapsedTime(&t, r.start, r.stop) != hipSuccess)
+      return fail(c, BSR_ERR_HIP, "bsr_profile_end: %s", hipGetErrorString(hipGetLastError()));
+    ms[r.cls] += t;
+    flops[r.cls] += r.flops;
+    launches[r.cls] += 1;
+  }
+  c->prof_used = 0;
+  return BSR_OK;
+}
+
 int32_t bsr_destroy(bsr_ctx* c) {
+  if (c) {
+    for (ProfRec& r : c->prof) { (void)hipEventDestroy(r.start); (void)hipEventDestroy(r.stop); }
+  }
   delete c;
   return BSR_OK;
 }

@@ -1,0 +1,25 @@
+"""Algorithmic floating-point operations of one BSR step (2 x multiply-accumulates on the reduced
+token sets the method actually processes; Sec. 4.3 Discussion 3 for the token counts).  Used by the
+benchmark to turn a step time into a fraction of the MFMA roofline."""
+from __future__ import annotations
+
+
+def step_flops(dim: int, mlp_hidden: int, num_classes: int, patch_dim: int, n_patches: int,
+               tokens_attn: list[int], tokens_mlp: list[int], first_trainable: int, batch: int) -> dict:
+    D, F = dim, mlp_hidden
+    fwd_gemm = fwd_attn = bwd_gemm = bwd_attn = 0.0
+    for l, (Ta, Tm) in enumerate(zip(tokens_attn, tokens_mlp)):
+        g = 2.0 * (4 * Ta * D * D + 2 * Tm * D * F)      # QKV + proj + fc1 + fc2
+        a = 4.0 * Ta * Ta * D                            # Q K^T and P V over all heads
+        fwd_gemm += g
+        fwd_attn += a
+        if l >= first_trainable:
+            bwd_gemm += 2.0 * g                          # dgrad + wgrad of every linear (Eq. 2, 4)
+            bwd_attn += 2.5 * a                          # dV, dP, dQ, dK and the recomputed Q K^T
+    stem = 2.0 * n_patches * patch_dim * D
+    head = 3 * 2.0 * D * num_classes
+    per_image = dict(fwd_gemm=fwd_gemm + stem, fwd_attn=fwd_attn, bwd_gemm=bwd_gemm, bwd_attn=bwd_attn,
+                     head=head)
+    out = {k: v * batch for k, v in per_image.items()}
+    out["total"] = sum(out.values())
+    return out

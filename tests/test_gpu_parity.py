@@ -68,3 +68,118 @@ def test_fp32_c1_exact_config(hip, orc64):
     x, y = S.make_inputs(cfg)
     got, ref, ok = check_step(hip, orc64, cfg, p, x, y, TOL_FP32, free_running=False)
     assert got["keep_k"] == [44] and got["x_final"].shape == (2, 45, 192)
+
+
+# ------------------------------------------------------------------ bf16 mode
+
+def bf16_setup(name, peaky=1.0, std=0.02, **over):
+    cfg = S.get_config(name, dtype="bf16", **over)
+    p = S.make_params(cfg, std=std, peaky=peaky)      # bf16-representable values
+    x, y = S.make_inputs(cfg)
+    return cfg, p, x, y
+
+
+@pytest.mark.parametrize("name,over", [("mini_4blk", {}), ("c2_deit_s", dict(batch=4)),
+                                       ("c1_block_fp32", dict())])
+def test_bf16_step_matches_oracle_forced_indices(hip, orc64, name, over):
+    cfg, p, x, y = bf16_setup(name, **over)
+    check_step(hip, orc64, cfg, p, x, y, TOL_BF16, free_running=False)
+
+
+def test_select_tokens_bit_exact_on_identical_scores(hip, orc32):
+    # same fp32 scores on both sides -> the kept set is unique (ties to the lower index) and must
+    # match bit for bit, for every shape of the token schedule, with ties, and at the edges
+    import torch
+    import paper_2405_10951_amd as P
+    cfg = S.get_config("mini_4blk", dtype="bf16")
+    ctx = P.Context(cfg, S.make_params(cfg), 4)
+    rng = np.random.default_rng(11)
+    for n, k in [(196, 137), (137, 95), (95, 66), (64, 44), (196, 98), (98, 49), (49, 24), (1, 1),
+                 (1, 0), (7, 7), (65, 1), (1024, 511), (300, 0)]:
+        B = 5
+        a = rng.standard_normal((B, n)).astype(np.float32)
+        a[1] = np.round(a[1], 1)            # many exact ties
+        a[2] = 0.25                         # all equal -> the first k indices
+        x = rng.standard_normal((B, n + 1, cfg["dim"])).astype(np.float32)
+        xt = torch.as_tensor(x).cuda().to(torch.bfloat16)
+        idx, xo = ctx.bsr_select_tokens(torch.as_tensor(a).cuda(), xt, k)
+        torch.cuda.synchronize()
+        idx = idx.cpu().numpy()
+        for b in range(B):
+            ref = orc32.topk(a[b], k)
+            assert np.array_equal(idx[b], ref), (n, k, b)
+        ref_x = orc32.gather(xt.float().cpu().numpy(), idx.astype(np.int32).reshape(B, k))
+        assert np.array_equal(xo.float().cpu().numpy(), ref_x), (n, k)
+
+
+def test_kept_indices_are_the_top_k_of_the_scores_the_gpu_ranked(hip, orc32):
+    # the decision is taken in fp32 on both sides: the GPU's kept set equals the reference
+    # selection applied to the GPU's own fp32 scores, at every drop, for every image
+    cfg, p, x, y = bf16_setup("c2_deit_s", batch=8)
+    got = hip.run_hip_step(cfg, p, x, y)
+    for i, k in enumerate(got["keep_k"]):
+        for b in range(x.shape[0]):
+            assert np.array_equal(got["kept_idx"][i][b], orc32.topk(got["scores"][i][b], k)), (i, b)
+
+
+def test_bf16_free_running_indices_under_the_gap_test(hip, orc64):
+    # Free-running selection against the oracle.  Random-weight attention is nearly uniform: at
+    # K = 0.7 n the oracle's k-th / (k+1)-th gap is ~1e-5, below bf16 resolution, so no gap test can
+    # fire there.  This input has a real gap: K = 44 salient patch tokens are noisy copies of the CLS
+    # token and W_k = W_q, so their CLS attention (~1/45 each) dwarfs the other 20 tokens'.  The
+    # oracle's gap is > 1e-3 for every image and the kept sets must match bit for bit.
+    cfg = S.get_config("c1_block_fp32", dtype="bf16", batch=8)
+    D = cfg["dim"]
+    p = S.make_params(cfg, peaky=4.0, bf16_exact=False)
+    p["blocks.0.w_qkv"][:, D:2 * D] = p["blocks.0.w_qkv"][:, :D]
+    p["blocks.0.b_qkv"][D:2 * D] = p["blocks.0.b_qkv"][:D]
+    p = {n: S.round_to_bf16(v) for n, v in p.items()}
+    x, y = S.make_inputs(cfg, bf16_exact=False)
+    rng = np.random.default_rng(5)
+    salient = []
+    for b in range(x.shape[0]):
+        sal = np.sort(rng.choice(64, 44, replace=False))
+        salient.append(sal)
+        x[b, 1 + sal] = x[b, 0] + 0.1 * rng.standard_normal((44, D)).astype(np.float32)
+    x = S.round_to_bf16(x)
+    ref = orc64.step(cfg, p, x, y, want_grads=False)
+    got = hip.run_hip_step(cfg, p, x, y)
+    for b in range(x.shape[0]):
+        s = np.sort(ref["scores"][0][b])[::-1]
+        assert s[43] - s[44] > 1e-3, "the constructed input must pass the gap test"
+        assert np.array_equal(ref["kept_idx"][0][b], salient[b])
+        assert np.array_equal(got["kept_idx"][0][b], ref["kept_idx"][0][b]), b
+
+
+def test_bf16_free_running_overlap_on_model_shaped_input(hip, orc64):
+    # DeiT-S shape, peaky attention, default keep ratio: report how far free-running selection
+    # agrees with the oracle when the gaps are at bf16 resolution (no exact match can be demanded)
+    cfg, p, x, y = bf16_setup("c2_deit_s", peaky=3.0, batch=8)
+    ref = orc64.step(cfg, p, x, y, want_grads=False)
+    got = hip.run_hip_step(cfg, p, x, y)
+    k0 = ref["keep_k"][0]
+    err = max(float(np.max(np.abs(got["scores"][0][b] - ref["scores"][0][b])) / ref["scores"][0][b].max())
+              for b in range(x.shape[0]))
+    assert err < 5e-2, f"score error {err:.3g} of the largest score"
+    for b in range(x.shape[0]):
+        overlap = len(set(got["kept_idx"][0][b]) & set(ref["kept_idx"][0][b])) / k0
+        assert overlap >= 0.97, (b, overlap)
+        s = np.sort(ref["scores"][0][b])[::-1]
+        if s[k0 - 1] - s[k0] > 1e-3:
+            assert np.array_equal(got["kept_idx"][0][b], ref["kept_idx"][0][b]), b
+
+
+def test_fp32_free_running_indices_relative_gap(hip, orc64):
+    cfg = S.get_config("c2_deit_s", dtype="fp32", batch=4, depth=5, first_trainable=4, drop_blocks=[3])
+    p = S.make_params(cfg, bf16_exact=False)
+    x, y = S.make_inputs(cfg, bf16_exact=False)
+    ref = orc64.step(cfg, p, x, y, want_grads=False)
+    got = hip.run_hip_step(cfg, p, x, y)
+    k0 = ref["keep_k"][0]
+    fired = 0
+    for b in range(x.shape[0]):
+        s = np.sort(ref["scores"][0][b])[::-1]
+        if s[k0 - 1] - s[k0] > 1e-4 * s[k0 - 1]:
+            fired += 1
+            assert np.array_equal(got["kept_idx"][0][b], ref["kept_idx"][0][b]), b
+    assert fired >= 2
