@@ -183,6 +183,31 @@ int32_t bsr_sgd_step(bsr_ctx* ctx, const bsr_params* grads, const bsr_params* mo
                      float momentum, float weight_decay, void* stream);
 
 /*
+ * Single layers in bf16, as the step runs them (for kernel-level parity tests and benchmarks; no
+ * context needed).  All pointers are device pointers, 16-byte aligned; bf16 tensors unless noted.
+ * *used_mfma (host, may be NULL) is set to 1 when the MFMA kernel took the shape, 0 when the
+ * generic kernel did.  Errors: INVALID_ARG, HIP.
+ *
+ * bsr_linear_forward: y[M,out] = act(x[M,in] . W + bias) (+ res), the a_{i+1} = W a_i + b of Sec. 3.2.
+ *   w_t   bf16 copy of W stored [out,in]        bias  fp32 [out], may be NULL
+ *   act   0: none, 1: exact-erf GELU            u_out [M,out], may be NULL: pre-activation (act = 1)
+ *   res   [M,out], may be NULL: added last      y     [M,out]
+ * bsr_linear_dgrad (Eq. 2): dx[M,in] = dy[M,out] . W^T, optionally times GELU'(u) element-wise.
+ *   w_s   bf16 copy of W stored [in,out]        u     [M,in], may be NULL
+ * bsr_linear_wgrad (Eq. 4): dw[in,out] (fp32) = x[M,in]^T . dy[M,out], summed over all M rows.
+ *   workspace  device fp32 scratch of workspace_floats elements, may be NULL.  With at least
+ *              2*in*out floats the sum over M is split over several workgroups per output tile
+ *              (partial sums are added in a fixed order: results are bit-reproducible).
+ */
+int32_t bsr_linear_forward(const void* x, int32_t M, int32_t in, int32_t out, const void* w_t,
+                           const float* bias, int32_t act, void* u_out, const void* res, void* y,
+                           int32_t* used_mfma, void* stream);
+int32_t bsr_linear_dgrad(const void* dy, int32_t M, int32_t in, int32_t out, const void* w_s,
+                         const void* u, void* dx, int32_t* used_mfma, void* stream);
+int32_t bsr_linear_wgrad(const void* x, const void* dy, int32_t M, int32_t in, int32_t out, float* dw,
+                         float* workspace, size_t workspace_floats, int32_t* used_mfma, void* stream);
+
+/*
  * Profiling mode, for measurement only.  Between bsr_profile_begin and bsr_profile_end every launch
  * of the classes below is bracketed by a pair of HIP events on the call's stream (created on first
  * use and kept by the context).  bsr_profile_end WAITS for the recorded work, then adds up, per

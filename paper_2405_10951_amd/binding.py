@@ -78,6 +78,15 @@ def load_library():
                                              C.c_void_p, C.c_void_p]
     lib.bsr_sgd_step.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_float, C.c_float, C.c_float, C.c_void_p]
     lib.bsr_destroy.argtypes = [C.c_void_p]
+    lib.bsr_linear_forward.restype = C.c_int32
+    lib.bsr_linear_forward.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
+                                       C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.bsr_linear_dgrad.restype = C.c_int32
+    lib.bsr_linear_dgrad.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
+                                     C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.bsr_linear_wgrad.restype = C.c_int32
+    lib.bsr_linear_wgrad.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
+                                     C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
     lib.bsr_profile_begin.argtypes = [C.c_void_p]
     lib.bsr_profile_end.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
     _lib = lib
@@ -128,6 +137,51 @@ def bsr_workspace_bytes(cfg: bsr_config) -> int:
     n = C.c_size_t(0)
     _check(load_library().bsr_workspace_bytes(C.byref(cfg), C.byref(n)))
     return int(n.value)
+
+
+def _cur_stream(t):
+    import torch
+    return C.c_void_p(torch.cuda.current_stream(t.device).cuda_stream)
+
+
+def bsr_linear_forward(x, w_t, bias=None, act=0, u_out=None, res=None, y=None):
+    """x [M,in] bf16, w_t [out,in] bf16 -> (y [M,out] bf16, used_mfma)."""
+    import torch
+    M, kin = x.shape
+    out = w_t.shape[0]
+    if y is None:
+        y = torch.empty((M, out), dtype=torch.bfloat16, device=x.device)
+    used = C.c_int32(-1)
+    _check(load_library().bsr_linear_forward(_dp(x), M, kin, out, _dp(w_t), _dp(bias), act, _dp(u_out),
+                                             _dp(res), _dp(y), C.byref(used), _cur_stream(x)))
+    return y, used.value
+
+
+def bsr_linear_dgrad(dy, w_s, u=None, dx=None):
+    """dy [M,out] bf16, w_s [in,out] bf16 -> (dx [M,in] bf16, used_mfma)."""
+    import torch
+    M, out = dy.shape
+    kin = w_s.shape[0]
+    if dx is None:
+        dx = torch.empty((M, kin), dtype=torch.bfloat16, device=dy.device)
+    used = C.c_int32(-1)
+    _check(load_library().bsr_linear_dgrad(_dp(dy), M, kin, out, _dp(w_s), _dp(u), _dp(dx), C.byref(used),
+                                           _cur_stream(dy)))
+    return dx, used.value
+
+
+def bsr_linear_wgrad(x, dy, dw=None, workspace=None):
+    """x [M,in], dy [M,out] bf16 -> (dw [in,out] fp32, used_mfma).  workspace: fp32 tensor or None."""
+    import torch
+    M, kin = x.shape
+    out = dy.shape[1]
+    if dw is None:
+        dw = torch.empty((kin, out), dtype=torch.float32, device=x.device)
+    used = C.c_int32(-1)
+    _check(load_library().bsr_linear_wgrad(_dp(x), _dp(dy), M, kin, out, _dp(dw), _dp(workspace),
+                                           C.c_size_t(0 if workspace is None else workspace.numel()),
+                                           C.byref(used), _cur_stream(x)))
+    return dw, used.value
 
 
 def _params_struct(tensors: dict) -> bsr_params:

@@ -47,7 +47,8 @@ struct Buffers {
   int32_t* idx_tmp = nullptr;
   SavedBlock sv[BSR_MAX_BLOCKS] = {};
   char *dxa = nullptr, *dxb = nullptr, *dgu = nullptr, *dh = nullptr, *dqkv = nullptr;
-  float *delta = nullptr, *partial = nullptr;
+  float *delta = nullptr, *partial = nullptr, *splitk = nullptr;
+  size_t splitk_floats = 0;
   float *xc = nullptr, *z = nullptr, *dz = nullptr, *dxc = nullptr, *meanf = nullptr, *rstdf = nullptr;
   float *logits = nullptr, *dlogits = nullptr, *loss_rows = nullptr;
 };
@@ -225,6 +226,8 @@ size_t carve(const bsr_config& c, const Schedule& s, char* base, Buffers* out) {
   b.dqkv = w.take<char>(B * Tmax * 3 * D * E);
   b.delta = w.take<float>(B * H * Tmax);
   b.partial = w.take<float>(std::max(colsum_partial_floats(0, (int)std::max(3 * D, F)), mean_sq_partial_floats()));
+  b.splitk_floats = f32 ? 0 : gemm_splitk_ws_floats((int)D, (int)F);
+  if (ft < L && b.splitk_floats) b.splitk = w.take<float>(b.splitk_floats);
   const size_t C = std::max(c.num_classes, 1);
   b.xc = w.take<float>(B * D);
   b.z = w.take<float>(B * D);
@@ -298,7 +301,7 @@ struct ProfScope {
 
 void gemm(bsr_ctx* c, const GemmDesc& g, hipStream_t s) {
   ProfScope ps(c, BSR_PROF_GEMM, 2.0 * g.M * g.N * g.K, s);
-  if (gemm_mfma_supported(g)) gemm_mfma(g, s);
+  if (gemm_mfma_supported(g)) gemm_mfma(g, c->b.splitk, c->b.splitk_floats, s);
   else gemm_generic(g, s);
 }
 
@@ -700,6 +703,49 @@ int32_t bsr_sgd_step(bsr_ctx* c, const bsr_params* grads, const bsr_params* mome
   }
 #undef UPD
   return check_hip(c, "bsr_sgd_step");
+}
+
+static int32_t run_layer(const GemmDesc& g, int32_t* used_mfma, void* stream, const char* where,
+                         float* ws = nullptr, size_t ws_floats = 0) {
+  const bool mfma = gemm_mfma_supported(g);
+  if (used_mfma) *used_mfma = mfma ? 1 : 0;
+  if (mfma) gemm_mfma(g, ws, ws_floats, (hipStream_t)stream);
+  else gemm_generic(g, (hipStream_t)stream);
+  return check_hip(nullptr, where);
+}
+
+int32_t bsr_linear_forward(const void* x, int32_t M, int32_t in, int32_t out, const void* w_t,
+                           const float* bias, int32_t act, void* u_out, const void* res, void* y,
+                           int32_t* used_mfma, void* stream) {
+  if (!aligned16(x) || !aligned16(w_t) || !aligned16(y) || M < 1 || in < 1 || out < 1 || (act != 0 && act != 1))
+    return fail(nullptr, BSR_ERR_INVALID_ARG, "bsr_linear_forward: bad argument");
+  GemmDesc g;
+  g.A = x; g.a_rs = in; g.a_cs = 1; g.B = w_t; g.b_rs = 1; g.b_cs = in;
+  g.C = y; g.ldc = out; g.M = M; g.N = out; g.K = in;
+  g.bias = bias; g.act = act ? ACT_GELU : ACT_NONE; g.aux = act ? u_out : nullptr; g.res = res;
+  return run_layer(g, used_mfma, stream, "bsr_linear_forward");
+}
+
+int32_t bsr_linear_dgrad(const void* dy, int32_t M, int32_t in, int32_t out, const void* w_s,
+                         const void* u, void* dx, int32_t* used_mfma, void* stream) {
+  if (!aligned16(dy) || !aligned16(w_s) || !aligned16(dx) || M < 1 || in < 1 || out < 1)
+    return fail(nullptr, BSR_ERR_INVALID_ARG, "bsr_linear_dgrad: bad argument");
+  GemmDesc g;
+  g.A = dy; g.a_rs = out; g.a_cs = 1; g.B = w_s; g.b_rs = 1; g.b_cs = out;
+  g.C = dx; g.ldc = in; g.M = M; g.N = in; g.K = out;
+  if (u) { g.act = ACT_GELU_BWD; g.aux = const_cast<void*>(u); }
+  return run_layer(g, used_mfma, stream, "bsr_linear_dgrad");
+}
+
+int32_t bsr_linear_wgrad(const void* x, const void* dy, int32_t M, int32_t in, int32_t out, float* dw,
+                         float* workspace, size_t workspace_floats, int32_t* used_mfma, void* stream) {
+  if (!aligned16(x) || !aligned16(dy) || !aligned16(dw) || M < 1 || in < 1 || out < 1)
+    return fail(nullptr, BSR_ERR_INVALID_ARG, "bsr_linear_wgrad: bad argument");
+  GemmDesc g;
+  g.A = x; g.a_rs = 1; g.a_cs = in; g.B = dy; g.b_rs = out; g.b_cs = 1;
+  g.C = dw; g.ldc = out; g.M = in; g.N = out; g.K = M; g.out_f32 = true;
+  if (workspace && !aligned16(workspace)) return fail(nullptr, BSR_ERR_INVALID_ARG, "bsr_linear_wgrad: workspace misaligned");
+  return run_layer(g, used_mfma, stream, "bsr_linear_wgrad", workspace, workspace_floats);
 }
 
 int32_t bsr_profile_begin(bsr_ctx* c) {

@@ -37,7 +37,9 @@ void attn_bwd_generic(const void* qkv, const void* out, const void* dout, const 
 
 // ---- bf16 MFMA paths --------------------------------------------------------------------------
 bool gemm_mfma_supported(const GemmDesc& g);
-void gemm_mfma(const GemmDesc& g, hipStream_t s);
+// splitk_ws: fp32 scratch for the partial sums of split-K weight gradients (may be null: no split)
+void gemm_mfma(const GemmDesc& g, float* splitk_ws, size_t splitk_ws_floats, hipStream_t s);
+size_t gemm_splitk_ws_floats(int dim, int mlp_hidden);
 
 // ---- row-wise / element-wise kernels ------------------------------------------------------------
 void layernorm_fwd(const void* x, int64_t M, int D, const float* gamma, const float* beta, float eps,

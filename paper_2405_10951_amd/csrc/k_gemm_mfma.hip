@@ -1,9 +1,509 @@
-// bf16 MFMA GEMM for gfx950 (placeholder until the tiled kernels land: nothing is routed here yet).
+// bf16 MFMA GEMMs for gfx950 (CDNA4), the hot kernels of the BSR step.
+//
+// Two kernels, both C = epilogue(sum_k A(m,k) B(k,n)) with fp32 accumulation in
+// v_mfma_f32_32x32x16_bf16 tiles staged through LDS:
+//   NT: A[M,K] and B^T[N,K] both have the contraction index contiguous.  Covers the forward linears
+//       (activations x bf16 weight copy stored [out,in]) and the input gradients of Eq. 2
+//       (dY x weight copy stored [in,out]).
+//   TN: A^T[K,M] and B[K,N] both have the contraction index strided (rows are tokens).  Covers the
+//       weight gradients of Eq. 4, dW = X^T dY, contraction over all tokens of the batch.
+//
+// Block = 256 threads = 4 wavefronts in a 2x2 grid; block tile BM x BN x 64, wave tile (BM/2)x(BN/2)
+// made of 32x32 MFMA tiles.  LDS is double buffered; the next k-tile is fetched into registers
+// while the current one feeds the matrix cores.  Workgroups are renumbered so that each XCD (the
+// hardware deals consecutive workgroup ids round-robin over 8 XCDs) works on a contiguous range of
+// tiles and its L2 sees whole operand panels.
+#include <stdlib.h>
+
+#include <algorithm>
+
 #include "bsr_internal.h"
 
 namespace bsr {
 
-bool gemm_mfma_supported(const GemmDesc&) { return false; }
-void gemm_mfma(const GemmDesc&, hipStream_t) {}
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));   // a 16-byte chunk in registers
+
+constexpr int BK = 64;        // k-tile: 64 bf16 = 8 chunks of 16 bytes per row
+constexpr int NXCD = 8;
+
+__device__ inline float gelu_f(float u) { return 0.5f * u * (1.0f + erff(u * 0.70710678118654752f)); }
+__device__ inline float gelu_grad_f(float u) {
+  float cdf = 0.5f * (1.0f + erff(u * 0.70710678118654752f));
+  float pdf = __expf(-0.5f * u * u) * 0.39894228040143268f;
+  return cdf + u * pdf;
+}
+
+// LDS chunk swizzle: 16 consecutive rows reading the same logical 16-byte chunk hit 16 different
+// (row parity, chunk position) pairs, i.e. all 64 banks once; 8 consecutive rows hit 8 positions.
+__device__ inline int swz(int row) { return (row & 7) ^ ((row >> 3) & 1); }
+
+// Logical tile id of this workgroup: XCD x owns the contiguous range [start(x), start(x+1)).
+__device__ inline int xcd_remap(int pid, int nblocks) {
+  const int base = nblocks / NXCD, rem = nblocks % NXCD;
+  const int x = pid % NXCD, local = pid / NXCD;
+  return x * base + min(x, rem) + local;
+}
+
+// Epilogue of one wave tile.  The fp32 accumulators (element r of a 32x32 tile sits at row
+// 8*(r/4) + 4*(lane/32) + r%4, column lane%32) go through a per-wave LDS patch, 32 rows at a time,
+// and come back row-major so that each lane owns 8 consecutive columns of one row: bias, GELU,
+// GELU', positional embedding and residual are applied on 8-wide vectors and C is written with
+// 16-byte stores (32 bytes for fp32 output).
+template <int MI, int NI>
+__device__ __forceinline__ void epilogue(const GemmDesc& g, f32x16 (&acc)[MI][NI], int row0, int col0, int lane,
+                                float* patch) {
+  constexpr int TN = NI * 32, LDP = TN + 4;     // +4 floats: rows start in different banks
+  constexpr int CPR = TN / 8;                   // 8-column chunks per row
+  constexpr int RPI = 64 / CPR;                 // rows handled per pass of the wave
+  const int lc = lane & 31, lh = lane >> 5;
+  const int my_chunk = lane % CPR, my_row = lane / CPR;
+  const int col = col0 + my_chunk * 8;
+  const bool col_ok = col < g.N;                // N is a multiple of 8 on this path
+  float bias[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) bias[j] = (g.bias && col_ok) ? g.bias[col + j] : 0.f;
+#pragma unroll
+  for (int mi = 0; mi < MI; ++mi) {
+#pragma unroll
+    for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+      for (int r = 0; r < 16; ++r)
+        patch[(8 * (r >> 2) + 4 * lh + (r & 3)) * LDP + ni * 32 + lc] = acc[mi][ni][r];
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int pass = 0; pass < 32 / RPI; ++pass) {
+      const int lr = pass * RPI + my_row;
+      const int m = row0 + mi * 32 + lr;
+      if (m >= g.M || !col_ok) continue;
+      float v[8];
+      const float4 p0 = *(const float4*)(patch + lr * LDP + my_chunk * 8);
+      const float4 p1 = *(const float4*)(patch + lr * LDP + my_chunk * 8 + 4);
+      v[0] = p0.x; v[1] = p0.y; v[2] = p0.z; v[3] = p0.w; v[4] = p1.x; v[5] = p1.y; v[6] = p1.z; v[7] = p1.w;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) v[j] += bias[j];
+      int64_t row = m;
+      if (g.remap_np > 0) {
+        row = (int64_t)m + m / g.remap_np + 1;
+        const float* pr = g.pos + (int64_t)(m % g.remap_np + 1) * g.N + col;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) v[j] += pr[j];
+      }
+      const int64_t off = row * g.ldc + col;
+      if (g.act == ACT_GELU) {
+        if (g.aux) {
+          bf16x8 u;
+#pragma unroll
+          for (int j = 0; j < 8; ++j) u[j] = (bf16)v[j];
+          *(bf16x8*)((bf16*)g.aux + off) = u;
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) v[j] = gelu_f(v[j]);
+      } else if (g.act == ACT_GELU_BWD) {
+        const bf16x8 u = *(const bf16x8*)((const bf16*)g.aux + off);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) v[j] *= gelu_grad_f((float)u[j]);
+      }
+      if (g.out_f32) {
+        float* c = (float*)g.C + off;
+        *(float4*)c = make_float4(v[0], v[1], v[2], v[3]);
+        *(float4*)(c + 4) = make_float4(v[4], v[5], v[6], v[7]);
+      } else {
+        if (g.res) {
+          const bf16x8 rr = *(const bf16x8*)((const bf16*)g.res + off);
+#pragma unroll
+          for (int j = 0; j < 8; ++j) v[j] += (float)rr[j];
+        }
+        bf16x8 o;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) o[j] = (bf16)v[j];
+        *(bf16x8*)((bf16*)g.C + off) = o;
+      }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+  }
+}
+
+// ------------------------------------------------------------------------------------------ NT
+// LDS tile: rows of 8 chunks (16 B each), chunk kc of row r stored at position kc ^ swz(r).
+// Software pipeline of one k-tile (4 MFMA steps of k = 16):
+//   step 0,1: MFMAs on fragment set s while the fragments of the next step load into set s^1
+//   step 2  : as above; the registers holding k-tile kt+1 go to the other LDS buffer and the global
+//             loads of k-tile kt+2 are issued (they have a full k-tile of matrix work to land)
+//   barrier ; step 3: MFMAs of the last fragments while the first fragments of k-tile kt+1 load.
+// Rows beyond M (or N) are clamped to the last valid row: they only feed accumulators that are
+// never stored.  KTAIL zero-fills chunks beyond K (K % 64 != 0).
+template <int BM, int BN, int WM, int WN, bool KTAIL>
+__global__ __launch_bounds__(WM * WN * 64) void gemm_nt_kernel(GemmDesc g) {
+  constexpr int NT = WM * WN * 64;
+  constexpr int TM = BM / WM, TN = BN / WN, MI = TM / 32, NI = TN / 32;
+  constexpr int ACH = BM * 8 / NT, BCH = BN * 8 / NT;     // 16-byte chunks per thread per tile
+  static_assert(ACH >= 1 && BCH >= 1 && MI >= 1 && NI >= 1, "tile too small for the thread count");
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  u32x4* As = (u32x4*)smem;                    // [2][BM*8]
+  u32x4* Bs = As + 2 * BM * 8;                 // [2][BN*8]
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / WN, wn = wave % WN;
+  const int ntn = (g.N + BN - 1) / BN;
+  const int tile = xcd_remap(blockIdx.x, gridDim.x);
+  const int m0 = (tile / ntn) * BM, n0 = (tile % ntn) * BN;
+  const bf16* __restrict__ A = (const bf16*)g.A;
+  const bf16* __restrict__ Bt = (const bf16*)g.B;
+
+  // per-thread chunk coordinates are the same for every k-tile
+  const bf16* pa[ACH];
+  const bf16* pb[BCH];
+  int sa[ACH], sb[BCH];
+  const int kc8 = (tid & 7) * 8;               // NT is a multiple of 8: every chunk of a thread has the same kc
+#pragma unroll
+  for (int i = 0; i < ACH; ++i) {
+    const int row = (tid + NT * i) >> 3;
+    pa[i] = A + (int64_t)min(m0 + row, g.M - 1) * g.a_rs + kc8;
+    sa[i] = row * 8 + ((tid & 7) ^ swz(row));
+  }
+#pragma unroll
+  for (int i = 0; i < BCH; ++i) {
+    const int row = (tid + NT * i) >> 3;
+    pb[i] = Bt + (int64_t)min(n0 + row, g.N - 1) * g.b_cs + kc8;
+    sb[i] = row * 8 + ((tid & 7) ^ swz(row));
+  }
+  u32x4 ra[ACH], rb[BCH];
+  auto fetch = [&](int k0) {
+    if (KTAIL) {
+      const bool oob = k0 + kc8 >= g.K;
+      const int kk = oob ? 0 : k0;
+#pragma unroll
+      for (int i = 0; i < ACH; ++i) {
+        ra[i] = *(const u32x4*)(pa[i] + kk - (oob ? kc8 : 0));
+        if (oob) ra[i] = u32x4{0u, 0u, 0u, 0u};
+      }
+#pragma unroll
+      for (int i = 0; i < BCH; ++i) {
+        rb[i] = *(const u32x4*)(pb[i] + kk - (oob ? kc8 : 0));
+        if (oob) rb[i] = u32x4{0u, 0u, 0u, 0u};
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < ACH; ++i) ra[i] = *(const u32x4*)(pa[i] + k0);
+#pragma unroll
+      for (int i = 0; i < BCH; ++i) rb[i] = *(const u32x4*)(pb[i] + k0);
+    }
+  };
+  auto stash = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < ACH; ++i) As[buf * BM * 8 + sa[i]] = ra[i];
+#pragma unroll
+    for (int i = 0; i < BCH; ++i) Bs[buf * BN * 8 + sb[i]] = rb[i];
+  };
+
+  f32x16 acc[MI][NI];
+#pragma unroll
+  for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+    for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.f;
+
+  const int lr = lane & 31, lh = lane >> 5;
+  int offa[MI], offb[NI];
+#pragma unroll
+  for (int mi = 0; mi < MI; ++mi) offa[mi] = (wm * TM + mi * 32 + lr) * 8;
+#pragma unroll
+  for (int ni = 0; ni < NI; ++ni) offb[ni] = (wn * TN + ni * 32 + lr) * 8;
+  const int sw = swz(lr);
+
+  bf16x8 fa[2][MI], fb[2][NI];
+  auto load_frags = [&](int set, const u32x4* Ab, const u32x4* Bb, int ks) {
+    const int kc = (ks * 2 + lh) ^ sw;
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi) fa[set][mi] = *(const bf16x8*)(Ab + offa[mi] + kc);
+#pragma unroll
+    for (int ni = 0; ni < NI; ++ni) fb[set][ni] = *(const bf16x8*)(Bb + offb[ni] + kc);
+  };
+  auto mma = [&](int set) {
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+      for (int ni = 0; ni < NI; ++ni)
+        acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[set][mi], fb[set][ni], acc[mi][ni], 0, 0, 0);
+  };
+
+  const int nk = (g.K + BK - 1) / BK;
+  fetch(0);
+  stash(0);
+  if (nk > 1) fetch(BK);
+  __syncthreads();
+  load_frags(0, As, Bs, 0);
+  for (int kt = 0; kt < nk; ++kt) {
+    const int buf = kt & 1;
+    const u32x4* Ab = As + buf * BM * 8;
+    const u32x4* Bb = Bs + buf * BN * 8;
+    load_frags(1, Ab, Bb, 1);
+    mma(0);
+    load_frags(0, Ab, Bb, 2);
+    mma(1);
+    load_frags(1, Ab, Bb, 3);
+    if (kt + 1 < nk) stash(buf ^ 1);
+    if (kt + 2 < nk) fetch((kt + 2) * BK);
+    mma(0);
+    __syncthreads();
+    if (kt + 1 < nk) load_frags(0, As + (buf ^ 1) * BM * 8, Bs + (buf ^ 1) * BN * 8, 0);
+    mma(1);
+  }
+  __syncthreads();
+  // the tile buffers are free now: reuse them as per-wave epilogue patches
+  float* patch = (float*)smem + wave * (32 * (TN + 4));
+  epilogue<MI, NI>(g, acc, m0 + wm * TM, n0 + wn * TN, lane, patch);
+}
+
+template <int BM, int BN, int WM, int WN>
+void launch_nt(const GemmDesc& g, hipStream_t s) {
+  static bool attr_set = false;
+  constexpr size_t lds = (size_t)2 * (BM + BN) * BK * sizeof(bf16);
+  static_assert(lds >= (size_t)WM * WN * 32 * (BN / WN + 4) * sizeof(float), "epilogue patches must fit");
+  if (!attr_set) {
+    (void)hipFuncSetAttribute((const void*)gemm_nt_kernel<BM, BN, WM, WN, false>,
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    (void)hipFuncSetAttribute((const void*)gemm_nt_kernel<BM, BN, WM, WN, true>,
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    attr_set = true;
+  }
+  const int tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
+  if (g.K % BK == 0) gemm_nt_kernel<BM, BN, WM, WN, false><<<tiles, WM * WN * 64, lds, s>>>(g);
+  else gemm_nt_kernel<BM, BN, WM, WN, true><<<tiles, WM * WN * 64, lds, s>>>(g);
+}
+
+// ------------------------------------------------------------------------------------------ TN
+// Weight gradient dW[Mo,No] = sum_t X[t,Mo]^T dY[t,No] (Eq. 4): both operands have the contraction
+// index t (tokens) as their row index, so a fragment (8 consecutive t for one column) is strided in
+// memory.  Each thread loads 4 token rows x 8 columns (16-byte chunks), transposes them in
+// registers with v_perm_b32 and stores, per column, 4 consecutive tokens as one 8-byte unit:
+//   LDS[kq = t/4][column][t%4].  A fragment is then two 8-byte reads (kq, kq+1).
+// The 16-byte slots (column pairs) of a row are permuted inside each 32-column block b by
+// slot ^ b, which keeps the reads of 32 consecutive columns conflict-free and spreads the 16
+// writers of a row over all banks.
+// Split-K: workgroup z handles k-tiles [z*kt_per, (z+1)*kt_per) and writes its own fp32 partial;
+// a second kernel adds the partials in a fixed order (bit-reproducible, no atomics).
+__device__ inline int tn_unit(int col) {       // 8-byte unit index of a column inside its LDS row
+  const int b = col >> 5, slot = (col >> 1) & 15;
+  return ((b << 4) + (slot ^ b)) * 2 + (col & 1);
+}
+
+template <int BM, int BN>
+__global__ __launch_bounds__(256) void gemm_tn_kernel(GemmDesc g, float* partial, int kt_per) {
+  constexpr int TM = BM / 2, TN = BN / 2, MI = TM / 32, NI = TN / 32;
+  constexpr int ACH = BM * 8 / 256 / 4, BCH = BN * 8 / 256 / 4;   // 4-token groups per thread per tile
+  static_assert(BM == 128 && BN == 128, "thread mapping below assumes 16 column chunks per row");
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  uint2* As = (uint2*)smem;                    // [2][16 kq][BM] 8-byte units
+  uint2* Bs = As + 2 * 16 * BM;                // [2][16 kq][BN]
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int ntn = (g.N + BN - 1) / BN;
+  const int ntiles = gridDim.x;
+  const int tile = xcd_remap(blockIdx.x, ntiles);
+  const int m0 = (tile / ntn) * BM, n0 = (tile % ntn) * BN;
+  const int nk_all = (g.K + BK - 1) / BK;
+  const int kt0 = blockIdx.y * kt_per, kt1 = min(kt0 + kt_per, nk_all);
+  const bf16* __restrict__ X = (const bf16*)g.A;     // [K tokens, Mo], row stride a_cs
+  const bf16* __restrict__ Y = (const bf16*)g.B;     // [K tokens, No], row stride b_rs
+  const int fc = tid & 15, tg = tid >> 4;            // column chunk (8 columns), token group (4 tokens)
+  const int colA = min(m0 + fc * 8, g.M - 8), colB = min(n0 + fc * 8, g.N - 8);
+
+  u32x4 ra[ACH][4], rb[BCH][4];
+  auto fetch = [&](int kt) {
+#pragma unroll
+    for (int i = 0; i < ACH; ++i)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int t = kt * BK + (tg + 16 * i) * 4 + j;
+        ra[i][j] = *(const u32x4*)(X + (int64_t)min(t, g.K - 1) * g.a_cs + colA);
+        if (t >= g.K) ra[i][j] = u32x4{0u, 0u, 0u, 0u};
+      }
+#pragma unroll
+    for (int i = 0; i < BCH; ++i)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int t = kt * BK + (tg + 16 * i) * 4 + j;
+        rb[i][j] = *(const u32x4*)(Y + (int64_t)min(t, g.K - 1) * g.b_rs + colB);
+        if (t >= g.K) rb[i][j] = u32x4{0u, 0u, 0u, 0u};
+      }
+  };
+  // 16-byte slot d of this thread's 8 columns: columns (8fc+2d, 8fc+2d+1) x 4 tokens
+  const int wb = fc >> 2;
+  auto stash_one = [&](uint2* dst_row, const u32x4 (&r)[4]) {
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+      u32x4 w;
+      w[0] = __builtin_amdgcn_perm(r[1][d], r[0][d], 0x05040100u);
+      w[1] = __builtin_amdgcn_perm(r[3][d], r[2][d], 0x05040100u);
+      w[2] = __builtin_amdgcn_perm(r[1][d], r[0][d], 0x07060302u);
+      w[3] = __builtin_amdgcn_perm(r[3][d], r[2][d], 0x07060302u);
+      const int slot = ((fc & 3) << 2) + d;
+      *(u32x4*)(dst_row + ((wb << 4) + (slot ^ wb)) * 2) = w;
+    }
+  };
+  auto stash = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < ACH; ++i) stash_one(As + (buf * 16 + tg + 16 * i) * BM, ra[i]);
+#pragma unroll
+    for (int i = 0; i < BCH; ++i) stash_one(Bs + (buf * 16 + tg + 16 * i) * BN, rb[i]);
+  };
+
+  f32x16 acc[MI][NI];
+#pragma unroll
+  for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+    for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.f;
+
+  const int lr = lane & 31, lh = lane >> 5;
+  int ua[MI], ub[NI];
+#pragma unroll
+  for (int mi = 0; mi < MI; ++mi) ua[mi] = tn_unit(wm * TM + mi * 32 + lr);
+#pragma unroll
+  for (int ni = 0; ni < NI; ++ni) ub[ni] = tn_unit(wn * TN + ni * 32 + lr);
+
+  union Frag { bf16x8 v; uint2 h[2]; };
+  Frag fa[2][MI], fb[2][NI];
+  auto load_frags = [&](int set, const uint2* Ab, const uint2* Bb, int ks) {
+    const int kq = ks * 4 + lh * 2;
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi) {
+      fa[set][mi].h[0] = Ab[kq * BM + ua[mi]];
+      fa[set][mi].h[1] = Ab[(kq + 1) * BM + ua[mi]];
+    }
+#pragma unroll
+    for (int ni = 0; ni < NI; ++ni) {
+      fb[set][ni].h[0] = Bb[kq * BN + ub[ni]];
+      fb[set][ni].h[1] = Bb[(kq + 1) * BN + ub[ni]];
+    }
+  };
+  auto mma = [&](int set) {
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+      for (int ni = 0; ni < NI; ++ni)
+        acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[set][mi].v, fb[set][ni].v, acc[mi][ni], 0, 0, 0);
+  };
+
+  const int nk = kt1 - kt0;
+  if (nk > 0) {
+    fetch(kt0);
+    stash(0);
+    if (nk > 1) fetch(kt0 + 1);
+    __syncthreads();
+    load_frags(0, As, Bs, 0);
+    for (int kt = 0; kt < nk; ++kt) {
+      const int buf = kt & 1;
+      const uint2* Ab = As + buf * 16 * BM;
+      const uint2* Bb = Bs + buf * 16 * BN;
+      load_frags(1, Ab, Bb, 1);
+      mma(0);
+      load_frags(0, Ab, Bb, 2);
+      mma(1);
+      load_frags(1, Ab, Bb, 3);
+      if (kt + 1 < nk) stash(buf ^ 1);
+      if (kt + 2 < nk) fetch(kt0 + kt + 2);
+      mma(0);
+      __syncthreads();
+      if (kt + 1 < nk) load_frags(0, As + (buf ^ 1) * 16 * BM, Bs + (buf ^ 1) * 16 * BN, 0);
+      mma(1);
+    }
+    __syncthreads();
+  }
+  GemmDesc o = g;
+  if (partial) {                                   // split-K: plain fp32 partial, no epilogue terms
+    o.C = partial + (int64_t)blockIdx.y * g.M * g.N;
+    o.ldc = g.N; o.bias = nullptr; o.act = ACT_NONE; o.res = nullptr; o.remap_np = 0; o.out_f32 = true;
+  }
+  float* patch = (float*)smem + wave * (32 * (TN + 4));
+  epilogue<MI, NI>(o, acc, m0 + wm * TM, n0 + wn * TN, lane, patch);
+}
+
+// out[i] = sum over splits, ascending
+__global__ void splitk_reduce_kernel(const float* __restrict__ partial, int64_t n, int splits, float* __restrict__ out) {
+  const int64_t i = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * 4;
+  if (i >= n) return;
+  float4 s = *(const float4*)(partial + i);
+  for (int z = 1; z < splits; ++z) {
+    const float4 v = *(const float4*)(partial + (int64_t)z * n + i);
+    s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+  }
+  *(float4*)(out + i) = s;
+}
+
+bool is_tn(const GemmDesc& g) {
+  return !g.in_f32 && g.out_f32 && g.a_rs == 1 && g.b_cs == 1 && g.M % 8 == 0 && g.N % 8 == 0 && g.M >= 8 &&
+         g.N >= 8 && g.a_cs % 8 == 0 && g.b_rs % 8 == 0 && g.ldc % 8 == 0 && g.K > 0 && !g.res && g.act == ACT_NONE &&
+         g.remap_np == 0 && (((uintptr_t)g.A | (uintptr_t)g.B | (uintptr_t)g.C) & 15) == 0;
+}
+
+void launch_tn(const GemmDesc& g, float* ws, size_t ws_floats, hipStream_t s) {
+  constexpr int BM = 128, BN = 128;
+  static bool attr_set = false;
+  constexpr size_t lds = (size_t)2 * (BM + BN) * BK * sizeof(bf16);
+  if (!attr_set) {
+    (void)hipFuncSetAttribute((const void*)gemm_tn_kernel<BM, BN>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    attr_set = true;
+  }
+  const int tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
+  const int nk = (g.K + BK - 1) / BK;
+  // enough splits to give every CU about two workgroups, each with at least 4 k-tiles
+  int splits = 1;
+  const size_t mn = (size_t)g.M * g.N;
+  if (ws && mn % 4 == 0) {
+    splits = std::max(1, std::min({512 / tiles, nk / 4, (int)(ws_floats / mn), 16}));
+  }
+  int kt_per = (nk + splits - 1) / splits;
+  splits = (nk + kt_per - 1) / kt_per;
+  if (splits <= 1) {
+    gemm_tn_kernel<BM, BN><<<dim3(tiles, 1), 256, lds, s>>>(g, nullptr, nk);
+  } else {
+    gemm_tn_kernel<BM, BN><<<dim3(tiles, splits), 256, lds, s>>>(g, ws, kt_per);
+    splitk_reduce_kernel<<<(unsigned)((mn / 4 + 255) / 256), 256, 0, s>>>(ws, (int64_t)mn, splits, (float*)g.C);
+  }
+}
+
+bool is_nt(const GemmDesc& g) {
+  return !g.in_f32 && g.a_cs == 1 && g.b_rs == 1 && g.K % 8 == 0 && g.a_rs % 8 == 0 && g.b_cs % 8 == 0 &&
+         g.N % 8 == 0 && g.ldc % 8 == 0 && (((uintptr_t)g.A | (uintptr_t)g.B | (uintptr_t)g.C) & 15) == 0 &&
+         (((uintptr_t)g.aux | (uintptr_t)g.res) & 15) == 0 && g.M > 0 && g.N > 0 && g.K > 0;
+}
+
+}  // namespace
+
+// room for 8 partial copies of the largest weight gradient of a block ([D,3D] or [D,F])
+size_t gemm_splitk_ws_floats(int dim, int mlp_hidden) {
+  return (size_t)8 * std::max((size_t)3 * dim * dim, (size_t)dim * mlp_hidden);
+}
+
+bool gemm_mfma_supported(const GemmDesc& g) { return is_nt(g) || is_tn(g); }
+
+// Tile choice.  A 256x256 tile moves half the bytes per flop of a 128x128 tile (the L2 -> LDS path
+// is what bounds these kernels), but the step's matrices are small: use the largest tile that still
+// gives every CU work, and fall back to 128x128 (two workgroups per CU) otherwise.
+void gemm_mfma(const GemmDesc& g, float* splitk_ws, size_t splitk_ws_floats, hipStream_t s) {
+  if (is_tn(g)) {
+    launch_tn(g, splitk_ws, splitk_ws_floats, s);
+    return;
+  }
+  static const int forced = [] { const char* e = getenv("BSR_NT_TILE"); return e ? atoi(e) : 0; }();
+  auto tiles = [&](int bm, int bn) { return (int64_t)((g.M + bm - 1) / bm) * ((g.N + bn - 1) / bn); };
+  int pick = forced;
+  if (!pick) pick = 128128;
+  (void)tiles;
+  switch (pick) {
+    case 256256: launch_nt<256, 256, 2, 4>(g, s); break;
+    case 256128: launch_nt<256, 128, 4, 2>(g, s); break;
+    default: launch_nt<128, 128, 2, 2>(g, s); break;
+  }
+}
 
 }  // namespace bsr

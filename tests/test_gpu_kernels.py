@@ -1,0 +1,102 @@
+"""Kernel-level GPU parity: the bf16 MFMA GEMMs at the real shapes of the ViT-B/16 workload
+(M = B*T in {6304, 4416, 3072, 2144}, widths 768 / 2304 / 3072) plus ragged sizes, against the
+oracle's linear layers on sampled rows (rows of a linear layer are independent)."""
+import numpy as np
+import pytest
+
+import bsr_synth as S
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def env():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a HIP device")
+    import paper_2405_10951_amd as P
+    return torch, P
+
+
+def bf16_np(rng, shape, scale=1.0):
+    return S.round_to_bf16((rng.standard_normal(shape) * scale).astype(np.float32))
+
+
+def to_dev(torch, a, dtype=None):
+    t = torch.as_tensor(a).cuda()
+    return t.to(dtype) if dtype is not None else t
+
+
+def assert_close(got, ref, what, tol=1e-2):
+    got, ref = np.asarray(got, np.float64), np.asarray(ref, np.float64)
+    err = np.abs(got - ref)
+    assert err.max() <= tol * np.abs(ref).max(), f"{what}: max err {err.max():.3g} vs max {np.abs(ref).max():.3g}"
+    rms = np.sqrt(np.mean(ref ** 2))
+    bad = err > tol * np.abs(ref) + tol * rms
+    assert bad.mean() < 1e-4, f"{what}: {bad.mean():.2%} elements outside tolerance"
+
+
+SHAPES = [(6304, 768, 2304), (4416, 768, 768), (3072, 768, 3072), (2144, 3072, 768),
+          (2144, 768, 2304), (333, 200, 72), (1, 64, 8), (130, 776, 136)]
+
+
+@pytest.mark.parametrize("M,kin,out", SHAPES)
+def test_linear_forward(env, orc64, M, kin, out):
+    torch, P = env
+    rng = np.random.default_rng(M + kin + out)
+    x = bf16_np(rng, (M, kin)); w = bf16_np(rng, (kin, out), 0.05); b = rng.standard_normal(out).astype(np.float32)
+    res = bf16_np(rng, (M, out))
+    rows = np.unique(np.concatenate([rng.choice(M, min(M, 192), replace=False), np.arange(max(0, M - 40), M)]))
+    xt = to_dev(torch, x, torch.bfloat16)
+    wt = to_dev(torch, np.ascontiguousarray(w.T), torch.bfloat16)
+    bt = to_dev(torch, b)
+    # plain: y = x W + b
+    y, used = P.bsr_linear_forward(xt, wt, bt)
+    torch.cuda.synchronize()
+    ref = orc64.linear(x[rows], w, b)
+    assert used == 1, "the MFMA kernel must take this shape"
+    assert_close(y.float().cpu().numpy()[rows], ref, "linear")
+    # GELU epilogue with the stored pre-activation, and the residual epilogue
+    u = torch.empty((M, out), dtype=torch.bfloat16, device="cuda")
+    g, _ = P.bsr_linear_forward(xt, wt, bt, act=1, u_out=u)
+    r, _ = P.bsr_linear_forward(xt, wt, bt, res=to_dev(torch, res, torch.bfloat16))
+    torch.cuda.synchronize()
+    assert_close(u.float().cpu().numpy()[rows], ref, "pre-activation")
+    assert_close(g.float().cpu().numpy()[rows], orc64.gelu(ref), "gelu")
+    assert_close(r.float().cpu().numpy()[rows], ref + res[rows], "residual")
+
+
+@pytest.mark.parametrize("M,kin,out", SHAPES)
+def test_linear_dgrad(env, orc64, M, kin, out):
+    torch, P = env
+    rng = np.random.default_rng(7 * M + kin + out)
+    dy = bf16_np(rng, (M, out)); w = bf16_np(rng, (kin, out), 0.05); u = bf16_np(rng, (M, kin))
+    rows = np.unique(np.concatenate([rng.choice(M, min(M, 192), replace=False), np.arange(max(0, M - 40), M)]))
+    dyt = to_dev(torch, dy, torch.bfloat16); wst = to_dev(torch, w, torch.bfloat16)
+    dx, used = P.bsr_linear_dgrad(dyt, wst)
+    du, _ = P.bsr_linear_dgrad(dyt, wst, u=to_dev(torch, u, torch.bfloat16))
+    torch.cuda.synchronize()
+    assert used == 1
+    ref = orc64.linear_dgrad(dy[rows], w)                       # Eq. 2
+    assert_close(dx.float().cpu().numpy()[rows], ref, "dgrad")
+    assert_close(du.float().cpu().numpy()[rows], orc64.gelu_bwd(ref, u[rows]), "dgrad * GELU'")
+
+
+@pytest.mark.parametrize("M,kin,out", [(3072, 768, 2304), (2144, 3072, 768), (2144, 768, 3072),
+                                       (3072, 768, 768), (333, 200, 72), (1, 64, 8), (67, 136, 776)])
+def test_linear_wgrad(env, orc64, M, kin, out):
+    torch, P = env
+    rng = np.random.default_rng(3 * M + kin + out)
+    x = bf16_np(rng, (M, kin)); dy = bf16_np(rng, (M, out))
+    cols = np.unique(rng.choice(kin, min(kin, 96), replace=False))    # rows of dW are independent
+    xt, dyt = to_dev(torch, x, torch.bfloat16), to_dev(torch, dy, torch.bfloat16)
+    dw, used = P.bsr_linear_wgrad(xt, dyt)
+    ws = torch.empty(8 * kin * out, dtype=torch.float32, device="cuda")
+    dw_split, _ = P.bsr_linear_wgrad(xt, dyt, workspace=ws)            # split over the token sum
+    dw_again, _ = P.bsr_linear_wgrad(xt, dyt, workspace=ws)
+    torch.cuda.synchronize()
+    assert used == 1, "the MFMA kernel must take this shape"
+    ref, _ = orc64.linear_wgrad(np.ascontiguousarray(x[:, cols]), dy)  # Eq. 4
+    assert_close(dw.cpu().numpy()[cols], ref, "wgrad", tol=2e-3)
+    assert_close(dw_split.cpu().numpy()[cols], ref, "wgrad split-K", tol=2e-3)
+    assert torch.equal(dw_split, dw_again), "split-K must be bit-reproducible"
