@@ -208,6 +208,24 @@ int32_t bsr_linear_wgrad(const void* x, const void* dy, int32_t M, int32_t in, i
                          float* workspace, size_t workspace_floats, int32_t* used_mfma, void* stream);
 
 /*
+ * Multi-head softmax attention in bf16 (Eq. 1), as the step runs it.  qkv is [B,T,3*H*d] with
+ * columns [q|k|v], head h owning columns h*d .. h*d+d-1 of each third.
+ * bsr_attention_forward:
+ *   out      [B,T,H*d] bf16: per-head Softmax(Q K^T / sqrt d) V, heads concatenated
+ *   lse      fp32 [B,H,T], may be NULL: log-sum-exp of every score row (what backward keeps instead
+ *            of the T x T softmax input of Table 1)
+ *   cls_prob fp32 [B,H,T], may be NULL: softmax row of query 0, the CLS token (Eq. 6)
+ * bsr_attention_backward (Eq. 3, 5): dqkv [B,T,3*H*d] bf16 from qkv, out, dout [B,T,H*d] and lse;
+ *   delta    fp32 [B,H,T] scratch.
+ * Limits: T <= 1024, d <= 256.  Errors: INVALID_ARG, HIP.
+ */
+int32_t bsr_attention_forward(const void* qkv, int32_t B, int32_t T, int32_t H, int32_t d, void* out,
+                              float* lse, float* cls_prob, int32_t* used_mfma, void* stream);
+int32_t bsr_attention_backward(const void* qkv, const void* out, const void* dout, const float* lse,
+                               int32_t B, int32_t T, int32_t H, int32_t d, float* delta, void* dqkv,
+                               int32_t* used_mfma, void* stream);
+
+/*
  * Profiling mode, for measurement only.  Between bsr_profile_begin and bsr_profile_end every launch
  * of the classes below is bracketed by a pair of HIP events on the call's stream (created on first
  * use and kept by the context).  bsr_profile_end WAITS for the recorded work, then adds up, per

@@ -87,6 +87,12 @@ def load_library():
     lib.bsr_linear_wgrad.restype = C.c_int32
     lib.bsr_linear_wgrad.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
                                      C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
+    lib.bsr_attention_forward.restype = C.c_int32
+    lib.bsr_attention_forward.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
+                                          C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.bsr_attention_backward.restype = C.c_int32
+    lib.bsr_attention_backward.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32,
+                                           C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
     lib.bsr_profile_begin.argtypes = [C.c_void_p]
     lib.bsr_profile_end.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
     _lib = lib
@@ -182,6 +188,33 @@ def bsr_linear_wgrad(x, dy, dw=None, workspace=None):
                                            C.c_size_t(0 if workspace is None else workspace.numel()),
                                            C.byref(used), _cur_stream(x)))
     return dw, used.value
+
+
+def bsr_attention_forward(qkv, heads, want_lse=True, want_cls=True):
+    """qkv [B,T,3D] bf16 -> (out [B,T,D] bf16, lse [B,H,T] | None, cls_prob [B,H,T] | None, used_mfma)."""
+    import torch
+    B, T, D3 = qkv.shape
+    D = D3 // 3
+    out = torch.empty((B, T, D), dtype=torch.bfloat16, device=qkv.device)
+    lse = torch.empty((B, heads, T), dtype=torch.float32, device=qkv.device) if want_lse else None
+    cls = torch.empty((B, heads, T), dtype=torch.float32, device=qkv.device) if want_cls else None
+    used = C.c_int32(-1)
+    _check(load_library().bsr_attention_forward(_dp(qkv), B, T, heads, D // heads, _dp(out), _dp(lse), _dp(cls),
+                                                C.byref(used), _cur_stream(qkv)))
+    return out, lse, cls, used.value
+
+
+def bsr_attention_backward(qkv, out, dout, lse, heads):
+    """-> (dqkv [B,T,3D] bf16, used_mfma)."""
+    import torch
+    B, T, D3 = qkv.shape
+    D = D3 // 3
+    dqkv = torch.empty_like(qkv)
+    delta = torch.empty((B, heads, T), dtype=torch.float32, device=qkv.device)
+    used = C.c_int32(-1)
+    _check(load_library().bsr_attention_backward(_dp(qkv), _dp(out), _dp(dout), _dp(lse), B, T, heads, D // heads,
+                                                 _dp(delta), _dp(dqkv), C.byref(used), _cur_stream(qkv)))
+    return dqkv, used.value
 
 
 def _params_struct(tensors: dict) -> bsr_params:

@@ -309,7 +309,8 @@ void attention_fwd(bsr_ctx* c, const void* qkv, int B, int T, void* out, float* 
                    hipStream_t s) {
   const int H = c->cfg.heads, d = c->cfg.dim / H;
   ProfScope ps(c, BSR_PROF_ATTN_FWD, 4.0 * B * H * (double)T * T * d, s);
-  attn_fwd_generic(qkv, B, T, H, d, c->f32, out, lse, clsp, s);
+  if (!c->f32 && attn_mfma_supported(T, d)) attn_fwd_mfma(qkv, B, T, H, out, lse, clsp, s);
+  else attn_fwd_generic(qkv, B, T, H, d, c->f32, out, lse, clsp, s);
 }
 
 void attention_bwd(bsr_ctx* c, const void* qkv, const void* out, const void* dout, const float* lse,
@@ -746,6 +747,28 @@ int32_t bsr_linear_wgrad(const void* x, const void* dy, int32_t M, int32_t in, i
   g.C = dw; g.ldc = out; g.M = in; g.N = out; g.K = M; g.out_f32 = true;
   if (workspace && !aligned16(workspace)) return fail(nullptr, BSR_ERR_INVALID_ARG, "bsr_linear_wgrad: workspace misaligned");
   return run_layer(g, used_mfma, stream, "bsr_linear_wgrad", workspace, workspace_floats);
+}
+
+int32_t bsr_attention_forward(const void* qkv, int32_t B, int32_t T, int32_t H, int32_t d, void* out,
+                              float* lse, float* cls_prob, int32_t* used_mfma, void* stream) {
+  if (!aligned16(qkv) || !aligned16(out) || B < 1 || T < 1 || T > 1024 || H < 1 || d < 1 || d > 256 || (H * d) % 8)
+    return fail(nullptr, BSR_ERR_INVALID_ARG, "bsr_attention_forward: bad argument");
+  const bool mfma = attn_mfma_supported(T, d);
+  if (used_mfma) *used_mfma = mfma ? 1 : 0;
+  if (mfma) attn_fwd_mfma(qkv, B, T, H, out, lse, cls_prob, (hipStream_t)stream);
+  else attn_fwd_generic(qkv, B, T, H, d, false, out, lse, cls_prob, (hipStream_t)stream);
+  return check_hip(nullptr, "bsr_attention_forward");
+}
+
+int32_t bsr_attention_backward(const void* qkv, const void* out, const void* dout, const float* lse,
+                               int32_t B, int32_t T, int32_t H, int32_t d, float* delta, void* dqkv,
+                               int32_t* used_mfma, void* stream) {
+  if (!aligned16(qkv) || !aligned16(out) || !aligned16(dout) || !aligned16(dqkv) || !lse || !delta || B < 1 ||
+      T < 1 || T > 1024 || H < 1 || d < 1 || d > 256 || (H * d) % 8)
+    return fail(nullptr, BSR_ERR_INVALID_ARG, "bsr_attention_backward: bad argument");
+  if (used_mfma) *used_mfma = 0;
+  attn_bwd_generic(qkv, out, dout, lse, B, T, H, d, false, delta, dqkv, (hipStream_t)stream);
+  return check_hip(nullptr, "bsr_attention_backward");
 }
 
 int32_t bsr_profile_begin(bsr_ctx* c) {

@@ -41,6 +41,9 @@ bool gemm_mfma_supported(const GemmDesc& g);
 void gemm_mfma(const GemmDesc& g, float* splitk_ws, size_t splitk_ws_floats, hipStream_t s);
 size_t gemm_splitk_ws_floats(int dim, int mlp_hidden);
 
+bool attn_mfma_supported(int T, int d);
+void attn_fwd_mfma(const void* qkv, int B, int T, int H, void* out, float* lse, float* cls_prob, hipStream_t s);
+
 // ---- row-wise / element-wise kernels ------------------------------------------------------------
 void layernorm_fwd(const void* x, int64_t M, int D, const float* gamma, const float* beta, float eps,
                    bool f32, void* y, float* mean, float* rstd, hipStream_t s);

@@ -1,0 +1,203 @@
+// bf16 MFMA softmax attention (Eq. 1 of the paper) for head size 64 and up to 256 tokens, the shape
+// of every ViT-B/16 and DeiT-S block after token dropping.  The CLS row of the softmax map, which
+// Eq. 6 ranks tokens by, leaves the forward kernel in fp32 as a by-product.
+//
+// Forward.  One workgroup = one (image, head) and 128 query rows; each of its 4 wavefronts owns 32
+// queries.  K of the head sits in LDS row-major (swizzled 16-byte chunks), V sits transposed
+// (feature-major).  The wave computes S^T = K Q^T with 32x32x16 MFMAs, so that a lane owns one query
+// and the softmax reductions over keys are in-register (plus one exchange between the two halves of
+// the wave).  The normalised P^T accumulators are, as they lie in registers, the A operand of the
+// second product O = P V: MFMA contracts over a dummy index, so the key order that the accumulator
+// layout dictates is simply applied to the V^T reads as well.  No T x T tensor ever leaves registers.
+#include "bsr_internal.h"
+
+namespace bsr {
+
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+
+constexpr int HD = 64;          // head size
+constexpr int VP = 260;         // V^T row pitch in bf16: 520 B = 2*256 + 8, so 32 rows hit all 64 banks
+
+__device__ inline int swz(int row) { return (row & 7) ^ ((row >> 3) & 1); }
+
+// key index of accumulator element r (of key block jb) held by a lane of wave half lh
+__device__ inline int key_of(int jb, int r, int lh) { return jb * 32 + 8 * (r >> 2) + 4 * lh + (r & 3); }
+
+// K rows [T,64] of one head -> LDS chunks; rows >= T are zero.
+__device__ inline void load_k(const bf16* base, int64_t row_stride, int T, int Tpad, u32x4* Ks, int tid) {
+  for (int c = tid; c < Tpad * 8; c += 256) {
+    const int row = c >> 3, kc = c & 7;
+    u32x4 v = {0u, 0u, 0u, 0u};
+    if (row < T) v = *(const u32x4*)(base + (int64_t)row * row_stride + kc * 8);
+    Ks[row * 8 + (kc ^ swz(row))] = v;
+  }
+}
+
+// Rows [T,64] -> transposed LDS [64][VP]: 4 rows x 8 columns per thread, transposed in registers.
+__device__ inline void load_transposed(const bf16* base, int64_t row_stride, int T, int Tpad, bf16* Vt, int tid) {
+  for (int c = tid; c < (Tpad / 4) * 8; c += 256) {
+    const int fc = c & 7, kg = c >> 3;
+    u32x4 r[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int t = kg * 4 + j;
+      r[j] = u32x4{0u, 0u, 0u, 0u};
+      if (t < T) r[j] = *(const u32x4*)(base + (int64_t)t * row_stride + fc * 8);
+    }
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+      u32x2 lo, hi;
+      lo[0] = __builtin_amdgcn_perm(r[1][d], r[0][d], 0x05040100u);
+      lo[1] = __builtin_amdgcn_perm(r[3][d], r[2][d], 0x05040100u);
+      hi[0] = __builtin_amdgcn_perm(r[1][d], r[0][d], 0x07060302u);
+      hi[1] = __builtin_amdgcn_perm(r[3][d], r[2][d], 0x07060302u);
+      *(u32x2*)(Vt + (fc * 8 + 2 * d) * VP + kg * 4) = lo;
+      *(u32x2*)(Vt + (fc * 8 + 2 * d + 1) * VP + kg * 4) = hi;
+    }
+  }
+}
+
+template <int NJ>
+__global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(const bf16* __restrict__ qkv, int T, int H,
+                                                            bf16* __restrict__ out, float* __restrict__ lse,
+                                                            float* __restrict__ cls_prob) {
+  constexpr int Tpad = NJ * 32;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  u32x4* Ks = (u32x4*)smem;                         // [Tpad][8 chunks]
+  bf16* Vt = (bf16*)(smem + (size_t)Tpad * 128);    // [64][VP]
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int lr = lane & 31, lh = lane >> 5;
+  const int b = blockIdx.y / H, h = blockIdx.y % H;
+  const int D = H * HD;
+  const int64_t rs = 3 * (int64_t)D;
+  const bf16* base = qkv + (int64_t)b * T * rs + h * HD;
+  load_k(base + D, rs, T, Tpad, Ks, tid);
+  load_transposed(base + 2 * D, rs, T, Tpad, Vt, tid);
+  __syncthreads();
+  const int q0 = blockIdx.x * 128 + wave * 32;
+  if (q0 >= T) return;
+
+  // Q fragments straight from global memory: lane (query lr, half lh) needs chunks 2ks + lh
+  bf16x8 qf[4];
+  {
+    const bf16* qrow = base + (int64_t)min(q0 + lr, T - 1) * rs;
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) qf[ks] = *(const bf16x8*)(qrow + (2 * ks + lh) * 8);
+  }
+  // S^T[key, query] = K Q^T
+  f32x16 s[NJ];
+  const int sw = swz(lr);
+#pragma unroll
+  for (int jb = 0; jb < NJ; ++jb) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r) s[jb][r] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      const bf16x8 kf = *(const bf16x8*)(Ks + (jb * 32 + lr) * 8 + ((2 * ks + lh) ^ sw));
+      s[jb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], s[jb], 0, 0, 0);
+    }
+  }
+  // softmax over keys: this lane holds, for query q0 + lr, the keys key_of(jb, r, lh)
+  const float c = 0.125f * 1.44269504088896341f;    // 1/sqrt(64) * log2(e)
+  float mx = -INFINITY;
+#pragma unroll
+  for (int jb = 0; jb < NJ; ++jb)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      if (key_of(jb, r, lh) >= T) s[jb][r] = -INFINITY;
+      mx = fmaxf(mx, s[jb][r]);
+    }
+  mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+  float sum = 0.f;
+#pragma unroll
+  for (int jb = 0; jb < NJ; ++jb)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      s[jb][r] = __builtin_amdgcn_exp2f((s[jb][r] - mx) * c);
+      sum += s[jb][r];
+    }
+  sum += __shfl_xor(sum, 32, 64);
+  const float inv = 1.0f / sum;
+  const int qi = q0 + lr;
+  if (lse && lh == 0 && qi < T) lse[((int64_t)b * H + h) * T + qi] = mx * 0.125f + __logf(sum);
+  bf16x8 pf[2 * NJ];
+#pragma unroll
+  for (int jb = 0; jb < NJ; ++jb)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const float p = s[jb][r] * inv;
+      s[jb][r] = p;
+      pf[2 * jb + (r >> 3)][r & 7] = (bf16)p;
+    }
+  if (cls_prob && qi == 0) {   // the CLS query: its softmax row in fp32 (Eq. 6)
+    float* dst = cls_prob + ((int64_t)b * H + h) * T;
+#pragma unroll
+    for (int jb = 0; jb < NJ; ++jb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int j = key_of(jb, r, lh);
+        if (j < T) dst[j] = s[jb][r];
+      }
+  }
+  // O = P V, contraction over keys in the order the accumulators hold them:
+  // step st covers keys 16 st + {4 lh .. 4 lh + 3} and 16 st + 8 + {4 lh .. 4 lh + 3}
+  f32x16 o[2];
+#pragma unroll
+  for (int nb = 0; nb < 2; ++nb) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r) o[nb][r] = 0.f;
+    const bf16* vrow = Vt + (nb * 32 + lr) * VP + 4 * lh;
+#pragma unroll
+    for (int st = 0; st < 2 * NJ; ++st) {
+      union { bf16x8 v; u32x2 hpart[2]; } vf;
+      vf.hpart[0] = *(const u32x2*)(vrow + 16 * st);
+      vf.hpart[1] = *(const u32x2*)(vrow + 16 * st + 8);
+      o[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pf[st], vf.v, o[nb], 0, 0, 0);
+    }
+  }
+#pragma unroll
+  for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int i = q0 + 8 * (r >> 2) + 4 * lh + (r & 3);
+      if (i < T) out[((int64_t)b * T + i) * D + h * HD + nb * 32 + lr] = (bf16)o[nb][r];
+    }
+}
+
+template <int NJ>
+void launch_fwd(const bf16* qkv, int B, int T, int H, bf16* out, float* lse, float* cls_prob, hipStream_t s) {
+  static bool attr_set = false;
+  constexpr size_t lds = (size_t)NJ * 32 * 128 + (size_t)HD * VP * sizeof(bf16);
+  if (!attr_set) {
+    (void)hipFuncSetAttribute((const void*)attn_fwd_mfma_kernel<NJ>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    attr_set = true;
+  }
+  attn_fwd_mfma_kernel<NJ><<<dim3((T + 127) / 128, B * H), 256, lds, s>>>(qkv, T, H, out, lse, cls_prob);
+}
+
+}  // namespace
+
+bool attn_mfma_supported(int T, int d) { return d == HD && T >= 1 && T <= 256; }
+
+void attn_fwd_mfma(const void* qkv, int B, int T, int H, void* out, float* lse, float* cls_prob, hipStream_t s) {
+  const bf16* q = (const bf16*)qkv;
+  bf16* o = (bf16*)out;
+  switch ((T + 31) / 32) {
+    case 1: launch_fwd<1>(q, B, T, H, o, lse, cls_prob, s); break;
+    case 2: launch_fwd<2>(q, B, T, H, o, lse, cls_prob, s); break;
+    case 3: launch_fwd<3>(q, B, T, H, o, lse, cls_prob, s); break;
+    case 4: launch_fwd<4>(q, B, T, H, o, lse, cls_prob, s); break;
+    case 5: launch_fwd<5>(q, B, T, H, o, lse, cls_prob, s); break;
+    case 6: launch_fwd<6>(q, B, T, H, o, lse, cls_prob, s); break;
+    case 7: launch_fwd<7>(q, B, T, H, o, lse, cls_prob, s); break;
+    default: launch_fwd<8>(q, B, T, H, o, lse, cls_prob, s); break;
+  }
+}
+
+}  // namespace bsr

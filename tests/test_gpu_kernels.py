@@ -100,3 +100,42 @@ def test_linear_wgrad(env, orc64, M, kin, out):
     assert_close(dw.cpu().numpy()[cols], ref, "wgrad", tol=2e-3)
     assert_close(dw_split.cpu().numpy()[cols], ref, "wgrad split-K", tol=2e-3)
     assert torch.equal(dw_split, dw_again), "split-K must be bit-reproducible"
+
+
+ATTN_SHAPES = [(2, 197, 12), (2, 138, 12), (3, 96, 6), (2, 67, 12), (2, 25, 3), (1, 1, 2), (2, 33, 2), (1, 256, 2)]
+
+
+@pytest.mark.parametrize("B,T,H", ATTN_SHAPES)
+def test_attention_forward(env, orc64, B, T, H):
+    torch, P = env
+    rng = np.random.default_rng(B * 1000 + T + H)
+    qkv = bf16_np(rng, (B, T, 3 * H * 64), 1.5)          # logits with std ~ 2: a peaky softmax
+    out, lse, cls, used = P.bsr_attention_forward(to_dev(torch, qkv, torch.bfloat16), H)
+    torch.cuda.synchronize()
+    assert used == 1, "the MFMA kernel must take head size 64 and T <= 256"
+    Pm, o = orc64.attention(qkv, H)                       # Eq. 1
+    assert_close(out.float().cpu().numpy(), o, "attention output")
+    assert_close(cls.cpu().numpy(), Pm[:, :, 0, :], "CLS softmax row", tol=2e-3)   # fp32 by-product (Eq. 6)
+    s = np.einsum("bihe,bjhe->bhij", qkv[..., :H * 64].reshape(B, T, H, 64).astype(np.float64),
+                  qkv[..., H * 64:2 * H * 64].reshape(B, T, H, 64).astype(np.float64)) / 8.0
+    ref_lse = np.log(np.exp(s - s.max(-1, keepdims=True)).sum(-1)) + s.max(-1)
+    assert np.max(np.abs(lse.cpu().numpy() - ref_lse)) < 1e-3
+    assert abs(float(cls.sum(-1).mean().item()) - 1.0) < 1e-5      # softmax rows sum to 1
+
+
+@pytest.mark.parametrize("B,T,H", ATTN_SHAPES)
+def test_attention_backward(env, orc64, B, T, H):
+    torch, P = env
+    rng = np.random.default_rng(B * 999 + T + H)
+    qkv = bf16_np(rng, (B, T, 3 * H * 64), 1.0)
+    dout = bf16_np(rng, (B, T, H * 64), 1.0)
+    qt = to_dev(torch, qkv, torch.bfloat16)
+    out, lse, _, _ = P.bsr_attention_forward(qt, H)
+    dqkv, used = P.bsr_attention_backward(qt, out, to_dev(torch, dout, torch.bfloat16), lse, H)
+    torch.cuda.synchronize()
+    Pm, _ = orc64.attention(qkv, H)
+    ref = orc64.attention_bwd(qkv, Pm, dout, H)           # Eq. 3, 5
+    got = dqkv.float().cpu().numpy()
+    D = H * 64
+    for name, sl in (("dq", slice(0, D)), ("dk", slice(D, 2 * D)), ("dv", slice(2 * D, 3 * D))):
+        assert_close(got[..., sl], ref[..., sl], name, tol=1.5e-2)
