@@ -317,7 +317,8 @@ void attention_bwd(bsr_ctx* c, const void* qkv, const void* out, const void* dou
                    int B, int T, void* dqkv, hipStream_t s) {
   const int H = c->cfg.heads, d = c->cfg.dim / H;
   ProfScope ps(c, BSR_PROF_ATTN_BWD, 10.0 * B * H * (double)T * T * d, s);
-  attn_bwd_generic(qkv, out, dout, lse, B, T, H, d, c->f32, c->b.delta, dqkv, s);
+  if (!c->f32 && attn_mfma_supported(T, d)) attn_bwd_mfma(qkv, out, dout, lse, B, T, H, c->b.delta, dqkv, s);
+  else attn_bwd_generic(qkv, out, dout, lse, B, T, H, d, c->f32, c->b.delta, dqkv, s);
 }
 
 // Rank the patch tokens of a drop location and hand CLS + the K best to the FFN (Sec. 4.1).
@@ -766,8 +767,10 @@ int32_t bsr_attention_backward(const void* qkv, const void* out, const void* dou
   if (!aligned16(qkv) || !aligned16(out) || !aligned16(dout) || !aligned16(dqkv) || !lse || !delta || B < 1 ||
       T < 1 || T > 1024 || H < 1 || d < 1 || d > 256 || (H * d) % 8)
     return fail(nullptr, BSR_ERR_INVALID_ARG, "bsr_attention_backward: bad argument");
-  if (used_mfma) *used_mfma = 0;
-  attn_bwd_generic(qkv, out, dout, lse, B, T, H, d, false, delta, dqkv, (hipStream_t)stream);
+  const bool mfma = attn_mfma_supported(T, d);
+  if (used_mfma) *used_mfma = mfma ? 1 : 0;
+  if (mfma) attn_bwd_mfma(qkv, out, dout, lse, B, T, H, delta, dqkv, (hipStream_t)stream);
+  else attn_bwd_generic(qkv, out, dout, lse, B, T, H, d, false, delta, dqkv, (hipStream_t)stream);
   return check_hip(nullptr, "bsr_attention_backward");
 }
 

@@ -43,6 +43,8 @@ size_t gemm_splitk_ws_floats(int dim, int mlp_hidden);
 
 bool attn_mfma_supported(int T, int d);
 void attn_fwd_mfma(const void* qkv, int B, int T, int H, void* out, float* lse, float* cls_prob, hipStream_t s);
+void attn_bwd_mfma(const void* qkv, const void* out, const void* dout, const float* lse, int B, int T, int H,
+                   float* delta, void* dqkv, hipStream_t s);
 
 // ---- row-wise / element-wise kernels ------------------------------------------------------------
 void layernorm_fwd(const void* x, int64_t M, int D, const float* gamma, const float* beta, float eps,

@@ -181,6 +181,217 @@ void launch_fwd(const bf16* qkv, int B, int T, int H, bf16* out, float* lse, flo
   attn_fwd_mfma_kernel<NJ><<<dim3((T + 127) / 128, B * H), 256, lds, s>>>(qkv, T, H, out, lse, cls_prob);
 }
 
+
+// ------------------------------------------------------------------------------------------ backward
+// Backward of Eq. 1 per head (the "non-linear layer" case of Eq. 3 / Eq. 5: it needs the stored
+// q, k, v and the softmax statistics).  With P_ij = exp(s_ij / 8 - lse_i), dP_ij = dO_i . v_j,
+// delta_i = dO_i . O_i (= sum_j P_ij dP_ij) and dS_ij = P_ij (dP_ij - delta_i) / 8:
+//   dQ_i = sum_j dS_ij k_j      (kernel "dq":  a wave owns 32 queries, sweeps the key blocks)
+//   dK_j = sum_i dS_ij q_i,  dV_j = sum_i P_ij dO_i   (kernel "dkv": a wave owns 32 keys, sweeps
+//                                                      the query blocks)
+// Both recompute S with MFMAs; nothing T x T is stored or exchanged between wavefronts, and no
+// atomics are used.  As in the forward kernel the lane that owns the output row keeps the
+// contraction index in accumulator order and the transposed operand in LDS is read in that order.
+
+__device__ inline bf16x8 lds_frag(const u32x4* rows, int row, int chunk) {
+  return *(const bf16x8*)(rows + row * 8 + (chunk ^ swz(row)));
+}
+
+__device__ inline bf16x8 lds_frag_t(const bf16* tr, int row, int lh, int st) {
+  union { bf16x8 v; u32x2 h[2]; } f;
+  const bf16* p = tr + row * VP + 4 * lh + 16 * st;
+  f.h[0] = *(const u32x2*)p;
+  f.h[1] = *(const u32x2*)(p + 8);
+  return f.v;
+}
+
+template <int NJ>
+__global__ __launch_bounds__(256) void attn_bwd_dq_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ out,
+                                                          const bf16* __restrict__ dout, const float* __restrict__ lse,
+                                                          int T, int H, float* __restrict__ delta,
+                                                          bf16* __restrict__ dqkv) {
+  constexpr int Tpad = NJ * 32;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  u32x4* Ks = (u32x4*)smem;
+  u32x4* Vs = Ks + Tpad * 8;
+  bf16* Kt = (bf16*)(Vs + Tpad * 8);
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int lr = lane & 31, lh = lane >> 5;
+  const int b = blockIdx.y / H, h = blockIdx.y % H;
+  const int D = H * HD;
+  const int64_t rs = 3 * (int64_t)D;
+  const bf16* base = qkv + (int64_t)b * T * rs + h * HD;
+  load_k(base + D, rs, T, Tpad, Ks, tid);
+  load_k(base + 2 * D, rs, T, Tpad, Vs, tid);
+  load_transposed(base + D, rs, T, Tpad, Kt, tid);
+  __syncthreads();
+  const int q0 = blockIdx.x * 128 + wave * 32;
+  if (q0 >= T) return;
+  const int qi = q0 + lr, qc = min(qi, T - 1);
+  bf16x8 qf[4], dof[4];
+  float dl = 0.f;
+  {
+    const bf16* qrow = base + (int64_t)qc * rs;
+    const bf16* dorow = dout + ((int64_t)b * T + qc) * D + h * HD;
+    const bf16* orow = out + ((int64_t)b * T + qc) * D + h * HD;
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      qf[ks] = *(const bf16x8*)(qrow + (2 * ks + lh) * 8);
+      dof[ks] = *(const bf16x8*)(dorow + (2 * ks + lh) * 8);
+      const bf16x8 of = *(const bf16x8*)(orow + (2 * ks + lh) * 8);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) dl += (float)dof[ks][e] * (float)of[e];
+    }
+  }
+  dl += __shfl_xor(dl, 32, 64);
+  const float l2 = lse[((int64_t)b * H + h) * T + qc] * 1.44269504088896341f;
+  if (lh == 0 && qi < T) delta[((int64_t)b * H + h) * T + qi] = dl;
+  const float c = 0.125f * 1.44269504088896341f;
+  f32x16 o[2];
+#pragma unroll
+  for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) o[nb][r] = 0.f;
+#pragma unroll
+  for (int jb = 0; jb < NJ; ++jb) {
+    f32x16 sa, dp;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) { sa[r] = 0.f; dp[r] = 0.f; }
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      sa = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_frag(Ks, jb * 32 + lr, 2 * ks + lh), qf[ks], sa, 0, 0, 0);
+      dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_frag(Vs, jb * 32 + lr, 2 * ks + lh), dof[ks], dp, 0, 0, 0);
+    }
+    bf16x8 dsf[2];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      float pr = __builtin_amdgcn_exp2f(sa[r] * c - l2);
+      if (key_of(jb, r, lh) >= T) pr = 0.f;
+      dsf[r >> 3][r & 7] = (bf16)(pr * (dp[r] - dl) * 0.125f);
+    }
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+      for (int hf = 0; hf < 2; ++hf)
+        o[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dsf[hf], lds_frag_t(Kt, nb * 32 + lr, lh, 2 * jb + hf), o[nb], 0, 0, 0);
+  }
+#pragma unroll
+  for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int i = q0 + 8 * (r >> 2) + 4 * lh + (r & 3);
+      if (i < T) dqkv[((int64_t)b * T + i) * rs + h * HD + nb * 32 + lr] = (bf16)o[nb][r];
+    }
+}
+
+template <int NJ>
+__global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ dout,
+                                                           const float* __restrict__ lse, const float* __restrict__ delta,
+                                                           int T, int H, bf16* __restrict__ dqkv) {
+  constexpr int Tpad = NJ * 32;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  u32x4* Qs = (u32x4*)smem;
+  u32x4* dOs = Qs + Tpad * 8;
+  bf16* Qt = (bf16*)(dOs + Tpad * 8);
+  bf16* dOt = Qt + HD * VP;
+  float* lse_s = (float*)(dOt + HD * VP);       // [Tpad], pre-multiplied by log2(e); +inf beyond T
+  float* del_s = lse_s + Tpad;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int lr = lane & 31, lh = lane >> 5;
+  const int b = blockIdx.y / H, h = blockIdx.y % H;
+  const int D = H * HD;
+  const int64_t rs = 3 * (int64_t)D;
+  const bf16* base = qkv + (int64_t)b * T * rs + h * HD;
+  const bf16* dobase = dout + (int64_t)b * T * D + h * HD;
+  load_k(base, rs, T, Tpad, Qs, tid);
+  load_k(dobase, D, T, Tpad, dOs, tid);
+  load_transposed(base, rs, T, Tpad, Qt, tid);
+  load_transposed(dobase, D, T, Tpad, dOt, tid);
+  for (int i = tid; i < Tpad; i += 256) {
+    lse_s[i] = (i < T) ? lse[((int64_t)b * H + h) * T + i] * 1.44269504088896341f : INFINITY;
+    del_s[i] = (i < T) ? delta[((int64_t)b * H + h) * T + i] : 0.f;
+  }
+  __syncthreads();
+  const int j0 = blockIdx.x * 128 + wave * 32;
+  if (j0 >= T) return;
+  const int jc = min(j0 + lr, T - 1);
+  bf16x8 kf[4], vf[4];
+  {
+    const bf16* krow = base + (int64_t)jc * rs + D;
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      kf[ks] = *(const bf16x8*)(krow + (2 * ks + lh) * 8);
+      vf[ks] = *(const bf16x8*)(krow + D + (2 * ks + lh) * 8);
+    }
+  }
+  const float c = 0.125f * 1.44269504088896341f;
+  f32x16 ok[2], ov[2];
+#pragma unroll
+  for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) { ok[nb][r] = 0.f; ov[nb][r] = 0.f; }
+#pragma unroll
+  for (int ib = 0; ib < NJ; ++ib) {
+    f32x16 sa, dp;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) { sa[r] = 0.f; dp[r] = 0.f; }
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      sa = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_frag(Qs, ib * 32 + lr, 2 * ks + lh), kf[ks], sa, 0, 0, 0);
+      dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_frag(dOs, ib * 32 + lr, 2 * ks + lh), vf[ks], dp, 0, 0, 0);
+    }
+    bf16x8 pf[2], dsf[2];
+#pragma unroll
+    for (int g4 = 0; g4 < 4; ++g4) {           // queries 32 ib + 8 g4 + 4 lh + {0..3}
+      const float4 l4 = *(const float4*)(lse_s + ib * 32 + 8 * g4 + 4 * lh);
+      const float4 d4 = *(const float4*)(del_s + ib * 32 + 8 * g4 + 4 * lh);
+      const float lv[4] = {l4.x, l4.y, l4.z, l4.w};
+      const float dv[4] = {d4.x, d4.y, d4.z, d4.w};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int r = g4 * 4 + e;
+        const float pr = __builtin_amdgcn_exp2f(sa[r] * c - lv[e]);
+        pf[r >> 3][r & 7] = (bf16)pr;
+        dsf[r >> 3][r & 7] = (bf16)(pr * (dp[r] - dv[e]) * 0.125f);
+      }
+    }
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+      for (int hf = 0; hf < 2; ++hf) {
+        ov[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pf[hf], lds_frag_t(dOt, nb * 32 + lr, lh, 2 * ib + hf), ov[nb], 0, 0, 0);
+        ok[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dsf[hf], lds_frag_t(Qt, nb * 32 + lr, lh, 2 * ib + hf), ok[nb], 0, 0, 0);
+      }
+  }
+#pragma unroll
+  for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int j = j0 + 8 * (r >> 2) + 4 * lh + (r & 3);
+      if (j < T) {
+        bf16* dst = dqkv + ((int64_t)b * T + j) * rs + h * HD + nb * 32 + lr;
+        dst[D] = (bf16)ok[nb][r];
+        dst[2 * D] = (bf16)ov[nb][r];
+      }
+    }
+}
+
+template <int NJ>
+void launch_bwd(const bf16* qkv, const bf16* out, const bf16* dout, const float* lse, int B, int T, int H,
+                float* delta, bf16* dqkv, hipStream_t s) {
+  static bool attr_set = false;
+  constexpr size_t lds_q = (size_t)2 * NJ * 32 * 128 + (size_t)HD * VP * sizeof(bf16);
+  constexpr size_t lds_kv = (size_t)2 * NJ * 32 * 128 + (size_t)2 * HD * VP * sizeof(bf16) + (size_t)2 * NJ * 32 * sizeof(float);
+  if (!attr_set) {
+    (void)hipFuncSetAttribute((const void*)attn_bwd_dq_kernel<NJ>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_q);
+    (void)hipFuncSetAttribute((const void*)attn_bwd_dkv_kernel<NJ>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_kv);
+    attr_set = true;
+  }
+  const dim3 grid((T + 127) / 128, B * H);
+  attn_bwd_dq_kernel<NJ><<<grid, 256, lds_q, s>>>(qkv, out, dout, lse, T, H, delta, dqkv);
+  attn_bwd_dkv_kernel<NJ><<<grid, 256, lds_kv, s>>>(qkv, dout, lse, delta, T, H, dqkv);
+}
+
 }  // namespace
 
 bool attn_mfma_supported(int T, int d) { return d == HD && T >= 1 && T <= 256; }
@@ -197,6 +408,28 @@ void attn_fwd_mfma(const void* qkv, int B, int T, int H, void* out, float* lse, 
     case 6: launch_fwd<6>(q, B, T, H, o, lse, cls_prob, s); break;
     case 7: launch_fwd<7>(q, B, T, H, o, lse, cls_prob, s); break;
     default: launch_fwd<8>(q, B, T, H, o, lse, cls_prob, s); break;
+  }
+}
+
+}  // namespace bsr
+
+namespace bsr {
+
+void attn_bwd_mfma(const void* qkv, const void* out, const void* dout, const float* lse, int B, int T, int H,
+                   float* delta, void* dqkv, hipStream_t s) {
+  const bf16* q = (const bf16*)qkv;
+  const bf16* o = (const bf16*)out;
+  const bf16* d = (const bf16*)dout;
+  bf16* g = (bf16*)dqkv;
+  switch ((T + 31) / 32) {
+    case 1: launch_bwd<1>(q, o, d, lse, B, T, H, delta, g, s); break;
+    case 2: launch_bwd<2>(q, o, d, lse, B, T, H, delta, g, s); break;
+    case 3: launch_bwd<3>(q, o, d, lse, B, T, H, delta, g, s); break;
+    case 4: launch_bwd<4>(q, o, d, lse, B, T, H, delta, g, s); break;
+    case 5: launch_bwd<5>(q, o, d, lse, B, T, H, delta, g, s); break;
+    case 6: launch_bwd<6>(q, o, d, lse, B, T, H, delta, g, s); break;
+    case 7: launch_bwd<7>(q, o, d, lse, B, T, H, delta, g, s); break;
+    default: launch_bwd<8>(q, o, d, lse, B, T, H, delta, g, s); break;
   }
 }
 

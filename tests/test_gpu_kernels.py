@@ -133,6 +133,7 @@ def test_attention_backward(env, orc64, B, T, H):
     out, lse, _, _ = P.bsr_attention_forward(qt, H)
     dqkv, used = P.bsr_attention_backward(qt, out, to_dev(torch, dout, torch.bfloat16), lse, H)
     torch.cuda.synchronize()
+    assert used == 1
     Pm, _ = orc64.attention(qkv, H)
     ref = orc64.attention_bwd(qkv, Pm, dout, H)           # Eq. 3, 5
     got = dqkv.float().cpu().numpy()
