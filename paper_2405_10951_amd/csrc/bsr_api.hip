@@ -600,17 +600,17 @@ int32_t bsr_train_blocks_fwd_bwd(bsr_ctx* c, const void* x_in, const int32_t* la
     gl.A = b.z; gl.a_rs = D; gl.a_cs = 1; gl.B = c->p.w_head; gl.b_rs = C; gl.b_cs = 1;
     gl.C = b.logits; gl.ldc = C; gl.M = B; gl.N = C; gl.K = D; gl.in_f32 = gl.out_f32 = true;
     gl.bias = (const float*)c->p.b_head;
-    gemm_generic(gl, s);
+    gemm_small_f32(gl, s);
     cross_entropy(b.logits, labels, B, C, b.loss_rows, b.dlogits, loss_out, s);
     if (logits_out) (void)hipMemcpyAsync(logits_out, b.logits, sizeof(float) * (size_t)B * C, hipMemcpyDeviceToDevice, s);
     GemmDesc gz;   // dz = dlogits . W_h^T
     gz.A = b.dlogits; gz.a_rs = C; gz.a_cs = 1; gz.B = c->p.w_head; gz.b_rs = 1; gz.b_cs = C;
     gz.C = b.dz; gz.ldc = D; gz.M = B; gz.N = D; gz.K = C; gz.in_f32 = gz.out_f32 = true;
-    gemm_generic(gz, s);
+    gemm_small_f32(gz, s);
     GemmDesc gw;   // dW_h = z^T . dlogits
     gw.A = b.z; gw.a_rs = 1; gw.a_cs = D; gw.B = b.dlogits; gw.b_rs = C; gw.b_cs = 1;
     gw.C = grads->w_head; gw.ldc = C; gw.M = D; gw.N = C; gw.K = B; gw.in_f32 = gw.out_f32 = true;
-    gemm_generic(gw, s);
+    gemm_small_f32(gw, s);
     colsum(b.dlogits, B, C, C, true, b.partial, (float*)grads->b_head, s);
     layernorm_bwd_params(b.dz, b.xc, b.meanf, b.rstdf, B, D, true, b.partial, (float*)grads->lnf_g, (float*)grads->lnf_b, s);
     layernorm_bwd_dx(b.dz, b.xc, b.meanf, b.rstdf, (const float*)c->p.lnf_g, nullptr, B, D, true, b.dxc, s);
@@ -681,29 +681,38 @@ int32_t bsr_sgd_step(bsr_ctx* c, const bsr_params* grads, const bsr_params* mome
   hipStream_t s = (hipStream_t)stream;
   const int D = cf.dim, F = cf.mlp_hidden;
   const bool mom = momentum > 0.f;
-#define UPD(field, rows, cols, sp, tp)                                                              \
-  sgd_update((float*)W.field, (const float*)G.field, mom ? (float*)Mo.field : nullptr, rows, cols, lr, \
-             momentum, weight_decay, sp, tp, s)
+  SgdTable tab;
+  int ntab = 0;
+  auto vec = [&](void* w, const void* g, void* m, int64_t n) {
+    tab.e[ntab++] = SgdEntry{(float*)w, (const float*)g, mom ? (float*)m : nullptr, n};
+    if (ntab == SGD_TABLE_MAX) { sgd_table(tab, ntab, lr, momentum, weight_decay, s); ntab = 0; }
+  };
+  auto mat = [&](void* w, const void* g, void* m, int rows, int cols, bf16* sp, bf16* tp) {
+    if (!sp && !tp) vec(w, g, m, (int64_t)rows * cols);
+    else sgd_update((float*)w, (const float*)g, mom ? (float*)m : nullptr, rows, cols, lr, momentum, weight_decay, sp, tp, s);
+  };
   for (int l = cf.first_trainable_block; l < cf.depth; ++l) {
     const bsr_block_params& W = c->p.blocks[l];
     const bsr_block_params& G = grads->blocks[l];
     const bsr_block_params& Mo = mom ? momenta->blocks[l] : grads->blocks[l];
     const Shadow& sh = c->b.sh[l];
-    UPD(ln1_g, 1, D, nullptr, nullptr); UPD(ln1_b, 1, D, nullptr, nullptr);
-    UPD(w_qkv, D, 3 * D, sh.s_qkv, sh.t_qkv); UPD(b_qkv, 1, 3 * D, nullptr, nullptr);
-    UPD(w_proj, D, D, sh.s_proj, sh.t_proj); UPD(b_proj, 1, D, nullptr, nullptr);
-    UPD(ln2_g, 1, D, nullptr, nullptr); UPD(ln2_b, 1, D, nullptr, nullptr);
-    UPD(w_fc1, D, F, sh.s_fc1, sh.t_fc1); UPD(b_fc1, 1, F, nullptr, nullptr);
-    UPD(w_fc2, F, D, sh.s_fc2, sh.t_fc2); UPD(b_fc2, 1, D, nullptr, nullptr);
+    vec(W.ln1_g, G.ln1_g, Mo.ln1_g, D); vec(W.ln1_b, G.ln1_b, Mo.ln1_b, D);
+    vec(W.b_qkv, G.b_qkv, Mo.b_qkv, 3 * D); vec(W.b_proj, G.b_proj, Mo.b_proj, D);
+    vec(W.ln2_g, G.ln2_g, Mo.ln2_g, D); vec(W.ln2_b, G.ln2_b, Mo.ln2_b, D);
+    vec(W.b_fc1, G.b_fc1, Mo.b_fc1, F); vec(W.b_fc2, G.b_fc2, Mo.b_fc2, D);
+    mat(W.w_qkv, G.w_qkv, Mo.w_qkv, D, 3 * D, sh.s_qkv, sh.t_qkv);
+    mat(W.w_proj, G.w_proj, Mo.w_proj, D, D, sh.s_proj, sh.t_proj);
+    mat(W.w_fc1, G.w_fc1, Mo.w_fc1, D, F, sh.s_fc1, sh.t_fc1);
+    mat(W.w_fc2, G.w_fc2, Mo.w_fc2, F, D, sh.s_fc2, sh.t_fc2);
   }
   if (cf.num_classes > 0) {
     const bsr_params& W = c->p;
     const bsr_params& G = *grads;
     const bsr_params& Mo = mom ? *momenta : *grads;
-    UPD(lnf_g, 1, D, nullptr, nullptr); UPD(lnf_b, 1, D, nullptr, nullptr);
-    UPD(w_head, 1, D * cf.num_classes, nullptr, nullptr); UPD(b_head, 1, cf.num_classes, nullptr, nullptr);
+    vec(W.lnf_g, G.lnf_g, Mo.lnf_g, D); vec(W.lnf_b, G.lnf_b, Mo.lnf_b, D);
+    vec(W.w_head, G.w_head, Mo.w_head, (int64_t)D * cf.num_classes); vec(W.b_head, G.b_head, Mo.b_head, cf.num_classes);
   }
-#undef UPD
+  sgd_table(tab, ntab, lr, momentum, weight_decay, s);
   return check_hip(c, "bsr_sgd_step");
 }
 

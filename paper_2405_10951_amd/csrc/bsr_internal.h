@@ -80,6 +80,14 @@ void mean_sq_loss(const void* x, int64_t n, bool f32, float* partial, float* los
 size_t mean_sq_partial_floats();
 
 void cast_matrix(const float* w, int rows, int cols, bf16* straight, bf16* transposed, hipStream_t s);
+// SGD on up to SGD_TABLE_MAX tensors without bf16 copies in one launch (the table travels as a
+// kernel argument)
+constexpr int SGD_TABLE_MAX = 96;
+struct SgdEntry { float* w; const float* g; float* m; int64_t n; };
+struct SgdTable { SgdEntry e[SGD_TABLE_MAX]; };
+void sgd_table(const SgdTable& t, int count, float lr, float mu, float wd, hipStream_t s);
+// fp32 C[M,N] = A.B (+bias) for tiny problems (the classification head): one thread per output
+void gemm_small_f32(const GemmDesc& g, hipStream_t s);
 // SGD on one tensor; matrices (rows > 1) also refresh their bf16 copies (either may be null)
 void sgd_update(float* w, const float* g, float* m, int rows, int cols, float lr, float mu, float wd,
                 bf16* straight, bf16* transposed, hipStream_t s);

@@ -2,6 +2,8 @@
 // (bias and LayerNorm parameter gradients), patch extraction, CLS-attention ranking (Eq. 6 of the
 // paper), token gather / scatter, losses, SGD and weight casts.  All are HBM-bound; reductions are
 // two-pass with a fixed order, so results are bit-reproducible run to run.
+#include <algorithm>
+
 #include "bsr_internal.h"
 
 namespace bsr {
@@ -118,18 +120,27 @@ __global__ __launch_bounds__(256) void colsum_partial_kernel(const T* __restrict
   }
 }
 
-// Pass 2: out[col] = sum over chunks in ascending order.
-__global__ void colsum_final_kernel(const float* __restrict__ partial, int N, int chunks,
-                                    float* __restrict__ out0, float* __restrict__ out1) {
-  const int col = blockIdx.x * blockDim.x + threadIdx.x;
-  if (col >= N) return;
-  float s = 0.f;
-  for (int r = 0; r < chunks; ++r) s += partial[(int64_t)r * N + col];
-  out0[col] = s;
-  if (out1) {
-    float t = 0.f;
-    for (int r = 0; r < chunks; ++r) t += partial[(int64_t)(COLSUM_R + r) * N + col];
-    out1[col] = t;
+// Pass 2: out[col] = sum over chunks.  Wave w of the block adds chunks w, w+4, ... in ascending
+// order, then the four wave sums are added in wave order: a fixed order, bit-reproducible.
+__global__ __launch_bounds__(256) void colsum_final_kernel(const float* __restrict__ partial, int N, int chunks,
+                                                           float* __restrict__ out0, float* __restrict__ out1) {
+  __shared__ float red[2][4][WAVE];
+  const int lane = threadIdx.x % WAVE, w = threadIdx.x / WAVE;
+  const int col = blockIdx.x * WAVE + lane;
+  float s = 0.f, t = 0.f;
+  if (col < N) {
+#pragma unroll 4
+    for (int r = w; r < chunks; r += 4) {
+      s += partial[(int64_t)r * N + col];
+      if (out1) t += partial[(int64_t)(COLSUM_R + r) * N + col];
+    }
+  }
+  red[0][w][lane] = s;
+  red[1][w][lane] = t;
+  __syncthreads();
+  if (w == 0 && col < N) {
+    out0[col] = red[0][0][lane] + red[0][1][lane] + red[0][2][lane] + red[0][3][lane];
+    if (out1) out1[col] = red[1][0][lane] + red[1][1][lane] + red[1][2][lane] + red[1][3][lane];
   }
 }
 
@@ -341,20 +352,26 @@ __global__ __launch_bounds__(256) void matrix_tile_kernel(float* __restrict__ w,
   }
 }
 
-__global__ void sgd_vector_kernel(float* __restrict__ w, const float* __restrict__ g,
-                                  float* __restrict__ mom, int64_t n, float lr, float mu, float wd) {
-  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= n) return;
-  float v = w[i];
-  float gp = g[i] + wd * v;
-  if (mu > 0.f) {
-    float m = mu * mom[i] + gp;
-    mom[i] = m;
-    v -= lr * m;
-  } else {
-    v -= lr * gp;
+// SGD on a table of small tensors (biases, LayerNorm parameters, the head) in one launch:
+// blockIdx.y picks the tensor, blockIdx.x a slice of 1024 elements.
+__global__ __launch_bounds__(256) void sgd_table_kernel(SgdTable t, float lr, float mu, float wd) {
+  const SgdEntry e = t.e[blockIdx.y];
+  const int64_t i0 = (int64_t)blockIdx.x * 1024 + threadIdx.x;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int64_t i = i0 + 256 * j;
+    if (i >= e.n) break;
+    float v = e.w[i];
+    float gp = e.g[i] + wd * v;
+    if (mu > 0.f) {
+      float m = mu * e.m[i] + gp;
+      e.m[i] = m;
+      v -= lr * m;
+    } else {
+      v -= lr * gp;
+    }
+    e.w[i] = v;
   }
-  w[i] = v;
 }
 
 inline int rows_per_chunk(int64_t M) { return (int)((M + COLSUM_R - 1) / COLSUM_R); }
@@ -400,7 +417,7 @@ void layernorm_bwd_params(const void* dy, const void* x, const float* mean, cons
     colsum_partial_kernel<float, true><<<grid, 256, 0, s>>>((const float*)dy, D, (const float*)x, mean, rstd, M, D, rpc, partial);
   else
     colsum_partial_kernel<bf16, true><<<grid, 256, 0, s>>>((const bf16*)dy, D, (const bf16*)x, mean, rstd, M, D, rpc, partial);
-  colsum_final_kernel<<<(D + 255) / 256, 256, 0, s>>>(partial, D, ch, dgamma, dbeta);
+  colsum_final_kernel<<<(D + WAVE - 1) / WAVE, 256, 0, s>>>(partial, D, ch, dgamma, dbeta);
 }
 
 void colsum(const void* a, int64_t M, int N, int64_t ld, bool f32, float* partial, float* out,
@@ -412,7 +429,7 @@ void colsum(const void* a, int64_t M, int N, int64_t ld, bool f32, float* partia
     colsum_partial_kernel<float, false><<<grid, 256, 0, s>>>((const float*)a, ld, nullptr, nullptr, nullptr, M, N, rpc, partial);
   else
     colsum_partial_kernel<bf16, false><<<grid, 256, 0, s>>>((const bf16*)a, ld, nullptr, nullptr, nullptr, M, N, rpc, partial);
-  colsum_final_kernel<<<(N + 255) / 256, 256, 0, s>>>(partial, N, ch, out, nullptr);
+  colsum_final_kernel<<<(N + WAVE - 1) / WAVE, 256, 0, s>>>(partial, N, ch, out, nullptr);
 }
 
 void patchify(const void* img, int B, int C, int S, int P, bool f32, void* out, hipStream_t s) {
@@ -482,11 +499,19 @@ void cast_matrix(const float* w, int rows, int cols, bf16* straight, bf16* trans
                                                  0.f, 0.f, 0.f, straight, transposed);
 }
 
+void sgd_table(const SgdTable& t, int count, float lr, float mu, float wd, hipStream_t s) {
+  if (count <= 0) return;
+  int64_t nmax = 0;
+  for (int i = 0; i < count; ++i) nmax = std::max(nmax, t.e[i].n);
+  sgd_table_kernel<<<dim3((unsigned)((nmax + 1023) / 1024), count), 256, 0, s>>>(t, lr, mu, wd);
+}
+
 void sgd_update(float* w, const float* g, float* m, int rows, int cols, float lr, float mu, float wd,
                 bf16* straight, bf16* transposed, hipStream_t s) {
   if (!straight && !transposed) {
-    const int64_t n = (int64_t)rows * cols;
-    sgd_vector_kernel<<<(unsigned)((n + 255) / 256), 256, 0, s>>>(w, g, m, n, lr, mu, wd);
+    SgdTable t;
+    t.e[0] = SgdEntry{w, g, m, (int64_t)rows * cols};
+    sgd_table(t, 1, lr, mu, wd, s);
     return;
   }
   dim3 grid((cols + 31) / 32, (rows + 31) / 32);

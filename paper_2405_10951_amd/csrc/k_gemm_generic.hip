@@ -88,7 +88,35 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(GemmDesc g) {
   }
 }
 
+// One thread per output element; for the head's tiny fp32 products (at most a few 10^4 outputs) this
+// beats a tiled kernel that would fill one or two workgroups.
+__global__ __launch_bounds__(256) void gemm_small_f32_kernel(GemmDesc g) {
+  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= (int64_t)g.M * g.N) return;
+  const int m = (int)(idx / g.N), n = (int)(idx % g.N);
+  const float* A = (const float*)g.A + (int64_t)m * g.a_rs;
+  const float* B = (const float*)g.B + (int64_t)n * g.b_cs;
+  float acc0 = 0.f, acc1 = 0.f, acc2 = 0.f, acc3 = 0.f;
+  int k = 0;
+  for (; k + 3 < g.K; k += 4) {
+    acc0 = fmaf(A[(int64_t)k * g.a_cs], B[(int64_t)k * g.b_rs], acc0);
+    acc1 = fmaf(A[(int64_t)(k + 1) * g.a_cs], B[(int64_t)(k + 1) * g.b_rs], acc1);
+    acc2 = fmaf(A[(int64_t)(k + 2) * g.a_cs], B[(int64_t)(k + 2) * g.b_rs], acc2);
+    acc3 = fmaf(A[(int64_t)(k + 3) * g.a_cs], B[(int64_t)(k + 3) * g.b_rs], acc3);
+  }
+  for (; k < g.K; ++k) acc0 = fmaf(A[(int64_t)k * g.a_cs], B[(int64_t)k * g.b_rs], acc0);
+  float v = (acc0 + acc1) + (acc2 + acc3);
+  if (g.bias) v += g.bias[n];
+  ((float*)g.C)[(int64_t)m * g.ldc + n] = v;
+}
+
 }  // namespace
+
+void gemm_small_f32(const GemmDesc& g, hipStream_t s) {
+  const int64_t total = (int64_t)g.M * g.N;
+  if (total <= 0) return;
+  gemm_small_f32_kernel<<<(unsigned)((total + 255) / 256), 256, 0, s>>>(g);
+}
 
 void gemm_generic(const GemmDesc& g, hipStream_t s) {
   if (g.M <= 0 || g.N <= 0) return;

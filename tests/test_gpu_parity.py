@@ -183,3 +183,43 @@ def test_fp32_free_running_indices_relative_gap(hip, orc64):
             fired += 1
             assert np.array_equal(got["kept_idx"][0][b], ref["kept_idx"][0][b]), b
     assert fired >= 2
+
+
+# ------------------------------------------------------------------ SGD (Sec. 5) and a second step
+
+@pytest.mark.parametrize("dtype,mu,wd", [("fp32", 0.0, 0.0), ("fp32", 0.9, 1e-4), ("bf16", 0.9, 1e-4)])
+def test_sgd_update_and_second_step(hip, orc64, dtype, mu, wd):
+    import torch
+    cfg = S.get_config("mini_4blk", dtype=dtype)
+    p = S.make_params(cfg, std=0.05)
+    x, y = S.make_inputs(cfg)
+    tol = TOL_FP32 if dtype == "fp32" else TOL_BF16
+    lr = 0.05
+    ref1 = orc64.step(cfg, p, x, y)
+    # oracle: two updates with its own gradients (the second one exercises the momentum buffer)
+    p_ref, m_ref = dict(p), {n: np.zeros_like(g) for n, g in ref1["grads"].items()}
+    ref = ref1
+    for _ in range(2):
+        for n, g in ref["grads"].items():
+            w, m = orc64.sgd(p_ref[n], g, m_ref[n] if mu > 0 else None, lr, mu, wd)
+            p_ref[n] = w.reshape(p[n].shape)
+            if mu > 0:
+                m_ref[n] = m.reshape(p[n].shape)
+        ref = orc64.step(cfg, p_ref, x, y, forced_idx=ref1["kept_idx"])
+    # GPU: same two steps through bsr_sgd_step
+    got = hip.run_hip_step(cfg, p, x, y, forced_idx=ref1["kept_idx"])
+    ctx = got["ctx"]
+    mom = {n: torch.zeros_like(t) for n, t in ctx.new_grads().items()} if mu > 0 else None
+    for _ in range(2):
+        got = hip.run_hip_step(cfg, p, x, y, forced_idx=ref1["kept_idx"], ctx=ctx,
+                               sgd=dict(lr=lr, momentum=mu, weight_decay=wd, momenta=mom))
+    for n in ref1["grads"]:
+        assert hip.rel(got["new_params"][n], p_ref[n]) < tol, n
+    # a third forward on the updated weights (in bf16 mode through the refreshed bf16 copies)
+    got3 = hip.run_hip_step(cfg, p, x, y, forced_idx=ref1["kept_idx"], ctx=ctx)
+    assert abs(got3["loss"] - ref["loss"]) < tol * max(1.0, abs(ref["loss"]))
+    assert hip.rel(got3["logits"], ref["logits"]) < tol
+    # frozen tensors are untouched
+    for n, t in ctx.params.items():
+        if n not in ctx.trainable_names:
+            assert np.array_equal(t.cpu().numpy(), p[n].astype(np.float32)), n
