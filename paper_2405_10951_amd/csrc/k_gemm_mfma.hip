@@ -8,9 +8,9 @@
 //   TN: A^T[K,M] and B[K,N] both have the contraction index strided (rows are tokens).  Covers the
 //       weight gradients of Eq. 4, dW = X^T dY, contraction over all tokens of the batch.
 //
-// Block = 256 threads = 4 wavefronts in a 2x2 grid; block tile BM x BN x 64, wave tile (BM/2)x(BN/2)
-// made of 32x32 MFMA tiles.  LDS is double buffered; the next k-tile is fetched into registers
-// while the current one feeds the matrix cores.  Workgroups are renumbered so that each XCD (the
+// Block tile BM x BN x 64 shared by WM x WN wavefronts, each owning a wave tile of 32x32 MFMA tiles.
+// LDS is double buffered; the next k-tiles wait in registers while the current one feeds the
+// matrix cores.  Workgroups are renumbered so that each XCD (the
 // hardware deals consecutive workgroup ids round-robin over 8 XCDs) works on a contiguous range of
 // tiles and its L2 sees whole operand panels.
 #include <stdlib.h>
@@ -35,6 +35,15 @@ __device__ inline float gelu_grad_f(float u) {
   float cdf = 0.5f * (1.0f + erff(u * 0.70710678118654752f));
   float pdf = __expf(-0.5f * u * u) * 0.39894228040143268f;
   return cdf + u * pdf;
+}
+
+template <int V> struct IC { static constexpr int value = V; };
+template <int B, int E, typename F>
+__device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (B < E) {
+    f(IC<B>{});
+    static_for<B + 1, E>(f);
+  }
 }
 
 // LDS chunk swizzle: 16 consecutive rows reading the same logical 16-byte chunk hit 16 different
@@ -138,7 +147,7 @@ __device__ __forceinline__ void epilogue(const GemmDesc& g, f32x16 (&acc)[MI][NI
 //   barrier ; step 3: MFMAs of the last fragments while the first fragments of k-tile kt+1 load.
 // Rows beyond M (or N) are clamped to the last valid row: they only feed accumulators that are
 // never stored.  KTAIL zero-fills chunks beyond K (K % 64 != 0).
-template <int BM, int BN, int WM, int WN, bool KTAIL>
+template <int BM, int BN, int WM, int WN, int R, bool KTAIL>
 __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_kernel(GemmDesc g) {
   constexpr int NT = WM * WN * 64;
   constexpr int TM = BM / WM, TN = BN / WN, MI = TM / 32, NI = TN / 32;
@@ -172,33 +181,35 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_kernel(GemmDesc g) {
     pb[i] = Bt + (int64_t)min(n0 + row, g.N - 1) * g.b_cs + kc8;
     sb[i] = row * 8 + ((tid & 7) ^ swz(row));
   }
-  u32x4 ra[ACH], rb[BCH];
-  auto fetch = [&](int k0) {
+  u32x4 ra[R][ACH], rb[R][BCH];          // R register sets: k-tile t waits in set t % R
+  auto fetch = [&](auto SET, int k0) {
+    constexpr int set = decltype(SET)::value;
     if (KTAIL) {
       const bool oob = k0 + kc8 >= g.K;
       const int kk = oob ? 0 : k0;
 #pragma unroll
       for (int i = 0; i < ACH; ++i) {
-        ra[i] = *(const u32x4*)(pa[i] + kk - (oob ? kc8 : 0));
-        if (oob) ra[i] = u32x4{0u, 0u, 0u, 0u};
+        ra[set][i] = *(const u32x4*)(pa[i] + kk - (oob ? kc8 : 0));
+        if (oob) ra[set][i] = u32x4{0u, 0u, 0u, 0u};
       }
 #pragma unroll
       for (int i = 0; i < BCH; ++i) {
-        rb[i] = *(const u32x4*)(pb[i] + kk - (oob ? kc8 : 0));
-        if (oob) rb[i] = u32x4{0u, 0u, 0u, 0u};
+        rb[set][i] = *(const u32x4*)(pb[i] + kk - (oob ? kc8 : 0));
+        if (oob) rb[set][i] = u32x4{0u, 0u, 0u, 0u};
       }
     } else {
 #pragma unroll
-      for (int i = 0; i < ACH; ++i) ra[i] = *(const u32x4*)(pa[i] + k0);
+      for (int i = 0; i < ACH; ++i) ra[set][i] = *(const u32x4*)(pa[i] + k0);
 #pragma unroll
-      for (int i = 0; i < BCH; ++i) rb[i] = *(const u32x4*)(pb[i] + k0);
+      for (int i = 0; i < BCH; ++i) rb[set][i] = *(const u32x4*)(pb[i] + k0);
     }
   };
-  auto stash = [&](int buf) {
+  auto stash = [&](auto SET, int buf) {
+    constexpr int set = decltype(SET)::value;
 #pragma unroll
-    for (int i = 0; i < ACH; ++i) As[buf * BM * 8 + sa[i]] = ra[i];
+    for (int i = 0; i < ACH; ++i) As[buf * BM * 8 + sa[i]] = ra[set][i];
 #pragma unroll
-    for (int i = 0; i < BCH; ++i) Bs[buf * BN * 8 + sb[i]] = rb[i];
+    for (int i = 0; i < BCH; ++i) Bs[buf * BN * 8 + sb[i]] = rb[set][i];
   };
 
   f32x16 acc[MI][NI];
@@ -234,12 +245,15 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_kernel(GemmDesc g) {
   };
 
   const int nk = (g.K + BK - 1) / BK;
-  fetch(0);
-  stash(0);
-  if (nk > 1) fetch(BK);
+  // prologue: k-tile 0 into LDS buffer 0, k-tiles 1 .. R in flight in their register sets
+  fetch(IC<0>{}, 0);
+  stash(IC<0>{}, 0);
+  static_for<1, R>([&](auto T) { if (decltype(T)::value < nk) fetch(T, decltype(T)::value * BK); });
+  if (R < nk) fetch(IC<0>{}, R * BK);
   __syncthreads();
   load_frags(0, As, Bs, 0);
-  for (int kt = 0; kt < nk; ++kt) {
+  // one k-tile; P = (kt + 1) % R is the register set that holds k-tile kt + 1
+  auto ktile = [&](auto P, int kt) {
     const int buf = kt & 1;
     const u32x4* Ab = As + buf * BM * 8;
     const u32x4* Bb = Bs + buf * BN * 8;
@@ -248,34 +262,40 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_kernel(GemmDesc g) {
     load_frags(0, Ab, Bb, 2);
     mma(1);
     load_frags(1, Ab, Bb, 3);
-    if (kt + 1 < nk) stash(buf ^ 1);
-    if (kt + 2 < nk) fetch((kt + 2) * BK);
+    if (kt + 1 < nk) stash(P, buf ^ 1);
+    if (kt + 1 + R < nk) fetch(P, (kt + 1 + R) * BK);
     mma(0);
     __syncthreads();
     if (kt + 1 < nk) load_frags(0, As + (buf ^ 1) * BM * 8, Bs + (buf ^ 1) * BN * 8, 0);
     mma(1);
-  }
+  };
+  for (int kt0 = 0; kt0 < nk; kt0 += R)
+    static_for<0, R>([&](auto J) {
+      constexpr int j = decltype(J)::value;
+      if (kt0 + j < nk) ktile(IC<(j + 1) % R>{}, kt0 + j);
+    });
   __syncthreads();
   // the tile buffers are free now: reuse them as per-wave epilogue patches
   float* patch = (float*)smem + wave * (32 * (TN + 4));
   epilogue<MI, NI>(g, acc, m0 + wm * TM, n0 + wn * TN, lane, patch);
 }
 
-template <int BM, int BN, int WM, int WN>
+template <int BM, int BN, int WM, int WN, int R>
 void launch_nt(const GemmDesc& g, hipStream_t s) {
   static bool attr_set = false;
-  constexpr size_t lds = (size_t)2 * (BM + BN) * BK * sizeof(bf16);
-  static_assert(lds >= (size_t)WM * WN * 32 * (BN / WN + 4) * sizeof(float), "epilogue patches must fit");
+  constexpr size_t lds_tiles = (size_t)2 * (BM + BN) * BK * sizeof(bf16);
+  constexpr size_t lds_patch = (size_t)WM * WN * 32 * (BN / WN + 4) * sizeof(float);   // epilogue patches
+  constexpr size_t lds = lds_tiles > lds_patch ? lds_tiles : lds_patch;
   if (!attr_set) {
-    (void)hipFuncSetAttribute((const void*)gemm_nt_kernel<BM, BN, WM, WN, false>,
+    (void)hipFuncSetAttribute((const void*)gemm_nt_kernel<BM, BN, WM, WN, R, false>,
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    (void)hipFuncSetAttribute((const void*)gemm_nt_kernel<BM, BN, WM, WN, true>,
+    (void)hipFuncSetAttribute((const void*)gemm_nt_kernel<BM, BN, WM, WN, R, true>,
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     attr_set = true;
   }
   const int tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
-  if (g.K % BK == 0) gemm_nt_kernel<BM, BN, WM, WN, false><<<tiles, WM * WN * 64, lds, s>>>(g);
-  else gemm_nt_kernel<BM, BN, WM, WN, true><<<tiles, WM * WN * 64, lds, s>>>(g);
+  if (g.K % BK == 0) gemm_nt_kernel<BM, BN, WM, WN, R, false><<<tiles, WM * WN * 64, lds, s>>>(g);
+  else gemm_nt_kernel<BM, BN, WM, WN, R, true><<<tiles, WM * WN * 64, lds, s>>>(g);
 }
 
 // ------------------------------------------------------------------------------------------ TN
@@ -486,23 +506,24 @@ size_t gemm_splitk_ws_floats(int dim, int mlp_hidden) {
 
 bool gemm_mfma_supported(const GemmDesc& g) { return is_nt(g) || is_tn(g); }
 
-// Tile choice.  A 256x256 tile moves half the bytes per flop of a 128x128 tile (the L2 -> LDS path
-// is what bounds these kernels), but the step's matrices are small: use the largest tile that still
-// gives every CU work, and fall back to 128x128 (two workgroups per CU) otherwise.
+// Tile choice, from measurements on the step's shapes (M = 2144 .. 6304 rows, N and K in
+// {768, 2304, 3072}).  Both variants keep 16 wavefronts on a CU: LDS traffic per MFMA (one 16-byte
+// fragment read per MFMA with 64x64 wave tiles, plus the tile writes) and the L2 -> LDS stream
+// bound these kernels long before the matrix cores do, and more resident waves hide those queues
+// best.  The 256x128 tile moves 25 % fewer bytes per flop; it is used when it still yields enough
+// workgroups for most of the 256 CUs.
 void gemm_mfma(const GemmDesc& g, float* splitk_ws, size_t splitk_ws_floats, hipStream_t s) {
   if (is_tn(g)) {
     launch_tn(g, splitk_ws, splitk_ws_floats, s);
     return;
   }
   static const int forced = [] { const char* e = getenv("BSR_NT_TILE"); return e ? atoi(e) : 0; }();
-  auto tiles = [&](int bm, int bn) { return (int64_t)((g.M + bm - 1) / bm) * ((g.N + bn - 1) / bn); };
-  int pick = forced;
-  if (!pick) pick = 128128;
-  (void)tiles;
+  const int64_t big_tiles = (int64_t)((g.M + 255) / 256) * ((g.N + 127) / 128);
+  const int pick = forced ? forced : (big_tiles >= 144 ? 256128 : 128128);
   switch (pick) {
-    case 256256: launch_nt<256, 256, 2, 4>(g, s); break;
-    case 256128: launch_nt<256, 128, 4, 2>(g, s); break;
-    default: launch_nt<128, 128, 2, 2>(g, s); break;
+    case 256256: launch_nt<256, 256, 2, 4, 1>(g, s); break;     // kept for tuning runs
+    case 256128: launch_nt<256, 128, 4, 4, 1>(g, s); break;
+    default: launch_nt<128, 128, 4, 2, 1>(g, s); break;
   }
 }
 
