@@ -86,6 +86,23 @@ def cpu_baseline(cfg, sample_batch):
                        f"OpenMP, {dt:.1f} s", loss=r["loss"])
 
 
+def recorded_traffic():
+    """HBM bytes per GEMM launch from the committed rocprofv3 counter runs (profiles/gemm_traffic.json),
+    or None when there is no record or the GEMM source has changed since it was taken."""
+    import hashlib
+    rec = os.path.join(ROOT, "profiles", "gemm_traffic.json")
+    src = os.path.join(ROOT, "paper_2405_10951_amd", "csrc", "k_gemm_mfma.hip")
+    try:
+        with open(rec) as f:
+            d = json.load(f)
+        with open(src, "rb") as f:
+            if hashlib.sha256(f.read()).hexdigest() != d["kernel_source_sha256"]:
+                return None
+        return d["hbm_bytes_per_launch"]
+    except (OSError, KeyError, ValueError):
+        return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -98,6 +115,8 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--no-compare", action="store_true", help="skip the keep-1.0 / full-fine-tuning legs")
     ap.add_argument("--cpu-sample", type=int, default=16)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 256 MiB device copy (reference for the HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build measures ONE GPU; --gpus must be 1 (no multi-GPU path exists)")
@@ -151,6 +170,14 @@ def main():
                      "gflop_per_step": gemm_flops / 1e9},
         "kernel_classes_ms_per_step": {k: v[0] for k, v in r["prof"].items()},
     }
+    out["roofline"]["traffic"] = recorded_traffic()
+    if args.calibrate_copy:
+        a = torch.empty(64 << 20, dtype=torch.float32, device="cuda").normal_()
+        b = torch.empty_like(a)
+        torch.cuda.synchronize()
+        b.copy_(a)                      # 256 MiB read + 256 MiB written by one elementwise copy kernel
+        torch.cuda.synchronize()
+        del a, b
     del ctx
     if not args.no_compare:
         cmp_steps = max(5, args.steps // 5)

@@ -1,0 +1,60 @@
+"""Turn two rocprofv3 --pmc runs of bench.py (FETCH_SIZE, then WRITE_SIZE; both with
+--calibrate-copy) into the HBM bytes per GEMM launch that bench.py reports as roofline.traffic.
+
+    python -m paper_2405_10951_amd.traffic <fetch_counter_collection.csv> <write_counter_collection.csv>
+
+Each counter is scaled by what it reads for the plain 256 MiB copy kernel of the same run (the
+counters are in KiB per dispatch; the copy reads 256 MiB and writes 256 MiB).  Writes
+profiles/gemm_traffic.json together with a hash of the GEMM source, so that the figure is dropped
+once the kernel changes."""
+from __future__ import annotations
+
+import csv
+import hashlib
+import json
+import os
+import sys
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+COPY_BYTES = 256 << 20
+
+
+def per_kernel(path: str, counter: str):
+    gemm, copy = [], []
+    with open(path) as f:
+        for r in csv.DictReader(f):
+            if r["Counter_Name"] != counter:
+                continue
+            name, v = r["Kernel_Name"], float(r["Counter_Value"])
+            if "gemm_nt_kernel" in name or "gemm_tn_kernel" in name:
+                gemm.append(v)
+            elif "copybuffer" in name.lower():      # the runtime's plain device-to-device copy kernel
+                copy.append(v)
+    return gemm, copy
+
+
+def main(fetch_csv: str, write_csv: str) -> None:
+    gf, cf = per_kernel(fetch_csv, "FETCH_SIZE")
+    gw, cw = per_kernel(write_csv, "WRITE_SIZE")
+    if not (gf and gw and cf and cw):
+        sys.exit("counter files lack GEMM or copy-kernel rows")
+    # the calibration copy is the largest copy dispatch of the run
+    scale_f = COPY_BYTES / max(cf)
+    scale_w = COPY_BYTES / max(cw)
+    fetch = sum(gf) / len(gf) * scale_f
+    write = sum(gw) / len(gw) * scale_w
+    with open(os.path.join(ROOT, "paper_2405_10951_amd", "csrc", "k_gemm_mfma.hip"), "rb") as f:
+        sha = hashlib.sha256(f.read()).hexdigest()
+    rec = {"hbm_bytes_per_launch": fetch + write, "fetch_bytes_per_launch": fetch,
+           "write_bytes_per_launch": write, "gemm_launches_counted": len(gf),
+           "copy_fetch_counter_KiB": max(cf), "copy_write_counter_KiB": max(cw),
+           "bytes_per_counter_unit_fetch": scale_f, "bytes_per_counter_unit_write": scale_w,
+           "kernel_source_sha256": sha}
+    out = os.path.join(ROOT, "profiles", "gemm_traffic.json")
+    with open(out, "w") as f:
+        json.dump(rec, f, indent=1)
+    print(json.dumps(rec))
+
+
+if __name__ == "__main__":
+    main(sys.argv[1], sys.argv[2])
