@@ -83,6 +83,114 @@ __global__ __launch_bounds__(256) void ln_bwd_dx_kernel(const T* __restrict__ dy
   }
 }
 
+// bf16 rows whose length is a multiple of 8 and at most 2048: one wavefront per row, the row is read
+// once with 16-byte loads and stays in registers (up to 4 chunks of 8 per lane).
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+constexpr int LN_MAXC = 4;
+
+__global__ __launch_bounds__(256) void ln_fwd_vec_kernel(const bf16* __restrict__ x, int64_t M, int D,
+                                                         const float* __restrict__ gamma,
+                                                         const float* __restrict__ beta, float eps,
+                                                         bf16* __restrict__ y, float* __restrict__ mean,
+                                                         float* __restrict__ rstd) {
+  const int lane = threadIdx.x % WAVE;
+  const int64_t m = (int64_t)blockIdx.x * 4 + threadIdx.x / WAVE;
+  if (m >= M) return;
+  const int nch = D / 8;
+  const bf16x8_t* xr = (const bf16x8_t*)(x + m * D);
+  float v[LN_MAXC][8];
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < LN_MAXC; ++i) {
+    const int c = lane + i * WAVE;
+    if (c < nch) {
+      const bf16x8_t t = xr[c];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) { v[i][e] = (float)t[e]; s += v[i][e]; }
+    }
+  }
+  const float mu = wave_sum(s) / (float)D;
+  float q = 0.f;
+#pragma unroll
+  for (int i = 0; i < LN_MAXC; ++i)
+    if (lane + i * WAVE < nch)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) { const float d0 = v[i][e] - mu; q += d0 * d0; }
+  const float rs = rsqrtf(wave_sum(q) / (float)D + eps);
+  if (lane == 0) {
+    if (mean) mean[m] = mu;
+    if (rstd) rstd[m] = rs;
+  }
+  bf16x8_t* yr = (bf16x8_t*)(y + m * D);
+#pragma unroll
+  for (int i = 0; i < LN_MAXC; ++i) {
+    const int c = lane + i * WAVE;
+    if (c < nch) {
+      const float4 g0 = *(const float4*)(gamma + c * 8), g1 = *(const float4*)(gamma + c * 8 + 4);
+      const float4 b0 = *(const float4*)(beta + c * 8), b1 = *(const float4*)(beta + c * 8 + 4);
+      const float gg[8] = {g0.x, g0.y, g0.z, g0.w, g1.x, g1.y, g1.z, g1.w};
+      const float bb[8] = {b0.x, b0.y, b0.z, b0.w, b1.x, b1.y, b1.z, b1.w};
+      bf16x8_t o;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) o[e] = (bf16)((v[i][e] - mu) * rs * gg[e] + bb[e]);
+      yr[c] = o;
+    }
+  }
+}
+
+// dx = res + rstd * (g - mean(g) - xhat * mean(g * xhat)),  g = dy * gamma   (same row layout)
+__global__ __launch_bounds__(256) void ln_bwd_dx_vec_kernel(const bf16* __restrict__ dy, const bf16* __restrict__ x,
+                                                            const float* __restrict__ mean,
+                                                            const float* __restrict__ rstd,
+                                                            const float* __restrict__ gamma,
+                                                            const bf16* __restrict__ res, int64_t M, int D,
+                                                            bf16* __restrict__ dx) {
+  const int lane = threadIdx.x % WAVE;
+  const int64_t m = (int64_t)blockIdx.x * 4 + threadIdx.x / WAVE;
+  if (m >= M) return;
+  const int nch = D / 8;
+  const float mu = mean[m], rs = rstd[m];
+  const bf16x8_t* dyr = (const bf16x8_t*)(dy + m * D);
+  const bf16x8_t* xr = (const bf16x8_t*)(x + m * D);
+  float g[LN_MAXC][8], xh[LN_MAXC][8];
+  float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+  for (int i = 0; i < LN_MAXC; ++i) {
+    const int c = lane + i * WAVE;
+    if (c < nch) {
+      const bf16x8_t a = dyr[c], t = xr[c];
+      const float4 g0 = *(const float4*)(gamma + c * 8), g1 = *(const float4*)(gamma + c * 8 + 4);
+      const float gg[8] = {g0.x, g0.y, g0.z, g0.w, g1.x, g1.y, g1.z, g1.w};
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        g[i][e] = (float)a[e] * gg[e];
+        xh[i][e] = ((float)t[e] - mu) * rs;
+        s1 += g[i][e];
+        s2 += g[i][e] * xh[i][e];
+      }
+    }
+  }
+  const float m1 = wave_sum(s1) / (float)D, m2 = wave_sum(s2) / (float)D;
+  const bf16x8_t* rr = res ? (const bf16x8_t*)(res + m * D) : nullptr;
+  bf16x8_t* dxr = (bf16x8_t*)(dx + m * D);
+#pragma unroll
+  for (int i = 0; i < LN_MAXC; ++i) {
+    const int c = lane + i * WAVE;
+    if (c < nch) {
+      bf16x8_t o;
+      bf16x8_t r8;
+      if (rr) r8 = rr[c];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        float t = rs * (g[i][e] - m1 - xh[i][e] * m2);
+        if (rr) t += (float)r8[e];
+        o[e] = (bf16)t;
+      }
+      dxr[c] = o;
+    }
+  }
+}
+
 // Pass 1 of a column reduction over M rows: block (cx, r) sums rows of chunk r for 64 columns.
 // WITH_XHAT: two sums, dy*xhat (slot 0) and dy (slot 1); otherwise the plain column sum (slot 0).
 template <typename T, bool WITH_XHAT>
@@ -184,21 +292,25 @@ __global__ void cls_head_mean_kernel(const float* __restrict__ cls_prob, int B, 
   scores[i] = s / (float)H;
 }
 
-// One wavefront per image.  Token j is kept when fewer than k tokens beat it (larger score, or the
-// same score and a lower index); kept indices are written in ascending order by a ballot prefix.
-__global__ __launch_bounds__(WAVE) void topk_select_kernel(const float* __restrict__ scores, int n,
-                                                            int k, int32_t* __restrict__ idx) {
+// One workgroup of 4 wavefronts per image.  Token j is kept when fewer than k tokens beat it (larger
+// score, or the same score and a lower index).  Each thread ranks one token per pass of 256; kept
+// indices are written in ascending order through ballot prefixes within a wave and a running
+// offset across waves and passes.
+__global__ __launch_bounds__(256) void topk_select_kernel(const float* __restrict__ scores, int n,
+                                                          int k, int32_t* __restrict__ idx) {
   __shared__ float sc[1024];
-  const int b = blockIdx.x, lane = threadIdx.x;
-  for (int j = lane; j < n; j += WAVE) sc[j] = scores[(int64_t)b * n + j];
+  __shared__ int wave_count[4];
+  const int b = blockIdx.x, tid = threadIdx.x, lane = tid % WAVE, w = tid / WAVE;
+  for (int j = tid; j < n; j += 256) sc[j] = scores[(int64_t)b * n + j];
   __syncthreads();
   int base = 0;
-  for (int c0 = 0; c0 < n; c0 += WAVE) {
-    const int j = c0 + lane;
+  for (int c0 = 0; c0 < n; c0 += 256) {
+    const int j = c0 + tid;
     bool keep = false;
     if (j < n) {
       const float mine = sc[j];
       int ahead = 0;
+#pragma unroll 8
       for (int i = 0; i < n; ++i) {
         const float o = sc[i];
         ahead += (o > mine || (o == mine && i < j)) ? 1 : 0;
@@ -206,8 +318,13 @@ __global__ __launch_bounds__(WAVE) void topk_select_kernel(const float* __restri
       keep = ahead < k;
     }
     const unsigned long long mask = __ballot(keep);
-    if (keep) idx[(int64_t)b * k + base + __popcll(mask & ((1ull << lane) - 1ull))] = j;
-    base += __popcll(mask);
+    if (lane == 0) wave_count[w] = __popcll(mask);
+    __syncthreads();
+    int before = base;
+    for (int v = 0; v < w; ++v) before += wave_count[v];
+    if (keep) idx[(int64_t)b * k + before + __popcll(mask & ((1ull << lane) - 1ull))] = j;
+    base += wave_count[0] + wave_count[1] + wave_count[2] + wave_count[3];
+    __syncthreads();
   }
 }
 
@@ -389,6 +506,8 @@ void layernorm_fwd(const void* x, int64_t M, int D, const float* gamma, const fl
   if (M <= 0) return;
   dim3 grid((unsigned)((M + 3) / 4));
   if (f32) ln_fwd_kernel<float><<<grid, 256, 0, s>>>((const float*)x, M, D, gamma, beta, eps, (float*)y, mean, rstd);
+  else if (D % 8 == 0 && D <= 8 * WAVE * LN_MAXC)
+    ln_fwd_vec_kernel<<<grid, 256, 0, s>>>((const bf16*)x, M, D, gamma, beta, eps, (bf16*)y, mean, rstd);
   else ln_fwd_kernel<bf16><<<grid, 256, 0, s>>>((const bf16*)x, M, D, gamma, beta, eps, (bf16*)y, mean, rstd);
 }
 
@@ -400,6 +519,9 @@ void layernorm_bwd_dx(const void* dy, const void* x, const float* mean, const fl
   if (f32)
     ln_bwd_dx_kernel<float><<<grid, 256, 0, s>>>((const float*)dy, (const float*)x, mean, rstd, gamma,
                                                   (const float*)res, M, D, (float*)dx);
+  else if (D % 8 == 0 && D <= 8 * WAVE * LN_MAXC)
+    ln_bwd_dx_vec_kernel<<<grid, 256, 0, s>>>((const bf16*)dy, (const bf16*)x, mean, rstd, gamma,
+                                              (const bf16*)res, M, D, (bf16*)dx);
   else
     ln_bwd_dx_kernel<bf16><<<grid, 256, 0, s>>>((const bf16*)dy, (const bf16*)x, mean, rstd, gamma,
                                                  (const bf16*)res, M, D, (bf16*)dx);
@@ -453,7 +575,7 @@ void cls_head_mean(const float* cls_prob, int B, int H, int T, float* scores, hi
 
 void topk_select(const float* scores, int B, int n, int k, int32_t* idx, hipStream_t s) {
   if (B <= 0 || k <= 0) return;
-  topk_select_kernel<<<B, WAVE, 0, s>>>(scores, n, k, idx);
+  topk_select_kernel<<<B, 256, 0, s>>>(scores, n, k, idx);
 }
 
 void gather_tokens(const void* x, const int32_t* idx, int B, int T, int k, int D, bool f32, void* y,

@@ -110,12 +110,28 @@ __global__ __launch_bounds__(256) void gemm_small_f32_kernel(GemmDesc g) {
   ((float*)g.C)[(int64_t)m * g.ldc + n] = v;
 }
 
+// Long contractions (the logits: K = D): one wavefront per output element, lanes stride over k.
+__global__ __launch_bounds__(256) void gemm_small_f32_wave_kernel(GemmDesc g) {
+  const int64_t idx = (int64_t)blockIdx.x * 4 + threadIdx.x / 64;
+  if (idx >= (int64_t)g.M * g.N) return;
+  const int lane = threadIdx.x % 64;
+  const int m = (int)(idx / g.N), n = (int)(idx % g.N);
+  const float* A = (const float*)g.A + (int64_t)m * g.a_rs;
+  const float* B = (const float*)g.B + (int64_t)n * g.b_cs;
+  float acc = 0.f;
+  for (int k = lane; k < g.K; k += 64) acc = fmaf(A[(int64_t)k * g.a_cs], B[(int64_t)k * g.b_rs], acc);
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o, 64);
+  if (lane == 0) ((float*)g.C)[(int64_t)m * g.ldc + n] = acc + (g.bias ? g.bias[n] : 0.f);
+}
+
 }  // namespace
 
 void gemm_small_f32(const GemmDesc& g, hipStream_t s) {
   const int64_t total = (int64_t)g.M * g.N;
   if (total <= 0) return;
-  gemm_small_f32_kernel<<<(unsigned)((total + 255) / 256), 256, 0, s>>>(g);
+  if (g.K >= 256) gemm_small_f32_wave_kernel<<<(unsigned)((total + 3) / 4), 256, 0, s>>>(g);
+  else gemm_small_f32_kernel<<<(unsigned)((total + 255) / 256), 256, 0, s>>>(g);
 }
 
 void gemm_generic(const GemmDesc& g, hipStream_t s) {
