@@ -329,10 +329,11 @@ const int32_t* drop_tokens(bsr_ctx* c, int B, int T, int k, const void* x_full, 
   const int n = T - 1, H = c->cfg.heads, D = c->cfg.dim;
   float* scores = scores_out ? scores_out : c->b.scores;
   const int32_t* idx = forced;
-  if (!forced || scores_out) cls_head_mean(c->b.clsp, B, H, T, scores, s);
   if (!forced) {
-    topk_select(scores, B, n, k, idx_own, s);
+    topk_select_from_cls(c->b.clsp, B, H, T, k, scores, idx_own, s);
     idx = idx_own;
+  } else if (scores_out) {
+    cls_head_mean(c->b.clsp, B, H, T, scores, s);
   }
   if (idx_out && k > 0)
     (void)hipMemcpyAsync(idx_out, idx, sizeof(int32_t) * (size_t)B * k, hipMemcpyDeviceToDevice, s);
@@ -344,16 +345,22 @@ void build_shadows(bsr_ctx* c, int first_block, hipStream_t s) {
   if (c->f32) return;
   const bsr_config& cf = c->cfg;
   const int D = cf.dim, F = cf.mlp_hidden;
+  MatTable tab;
+  auto add = [&](const void* w, int rows, int cols, bf16* sp, bf16* tp) {
+    matrix_table_add(tab, (float*)const_cast<void*>(w), nullptr, nullptr, rows, cols, sp, tp);
+    if (tab.count == MAT_TABLE_MAX) { matrix_table_run(tab, false, 0.f, 0.f, 0.f, s); tab = MatTable(); }
+  };
   if (first_block == 0 && cf.image_size)
-    cast_matrix((const float*)c->p.w_patch, cf.in_chans * cf.patch_size * cf.patch_size, D, nullptr, c->b.t_patch, s);
+    add(c->p.w_patch, cf.in_chans * cf.patch_size * cf.patch_size, D, nullptr, c->b.t_patch);
   for (int l = first_block; l < cf.depth; ++l) {
     const bsr_block_params& w = c->p.blocks[l];
     Shadow& sh = c->b.sh[l];
-    cast_matrix((const float*)w.w_qkv, D, 3 * D, sh.s_qkv, sh.t_qkv, s);
-    cast_matrix((const float*)w.w_proj, D, D, sh.s_proj, sh.t_proj, s);
-    cast_matrix((const float*)w.w_fc1, D, F, sh.s_fc1, sh.t_fc1, s);
-    cast_matrix((const float*)w.w_fc2, F, D, sh.s_fc2, sh.t_fc2, s);
+    add(w.w_qkv, D, 3 * D, sh.s_qkv, sh.t_qkv);
+    add(w.w_proj, D, D, sh.s_proj, sh.t_proj);
+    add(w.w_fc1, D, F, sh.s_fc1, sh.t_fc1);
+    add(w.w_fc2, F, D, sh.s_fc2, sh.t_fc2);
   }
+  matrix_table_run(tab, false, 0.f, 0.f, 0.f, s);
 }
 
 int check_params(const bsr_config& cf, const bsr_params* p, int first_block, bool need_stem, const char** which) {
@@ -687,9 +694,11 @@ int32_t bsr_sgd_step(bsr_ctx* c, const bsr_params* grads, const bsr_params* mome
     tab.e[ntab++] = SgdEntry{(float*)w, (const float*)g, mom ? (float*)m : nullptr, n};
     if (ntab == SGD_TABLE_MAX) { sgd_table(tab, ntab, lr, momentum, weight_decay, s); ntab = 0; }
   };
+  MatTable mats;
   auto mat = [&](void* w, const void* g, void* m, int rows, int cols, bf16* sp, bf16* tp) {
-    if (!sp && !tp) vec(w, g, m, (int64_t)rows * cols);
-    else sgd_update((float*)w, (const float*)g, mom ? (float*)m : nullptr, rows, cols, lr, momentum, weight_decay, sp, tp, s);
+    if (!sp && !tp) { vec(w, g, m, (int64_t)rows * cols); return; }
+    matrix_table_add(mats, (float*)w, (const float*)g, mom ? (float*)m : nullptr, rows, cols, sp, tp);
+    if (mats.count == MAT_TABLE_MAX) { matrix_table_run(mats, true, lr, momentum, weight_decay, s); mats = MatTable(); }
   };
   for (int l = cf.first_trainable_block; l < cf.depth; ++l) {
     const bsr_block_params& W = c->p.blocks[l];
@@ -713,6 +722,7 @@ int32_t bsr_sgd_step(bsr_ctx* c, const bsr_params* grads, const bsr_params* mome
     vec(W.w_head, G.w_head, Mo.w_head, (int64_t)D * cf.num_classes); vec(W.b_head, G.b_head, Mo.b_head, cf.num_classes);
   }
   sgd_table(tab, ntab, lr, momentum, weight_decay, s);
+  matrix_table_run(mats, true, lr, momentum, weight_decay, s);
   return check_hip(c, "bsr_sgd_step");
 }
 

@@ -67,6 +67,9 @@ void write_cls_rows(const float* cls, const float* pos, int B, int T, int D, boo
                     hipStream_t s);
 void cls_head_mean(const float* cls_prob, int B, int H, int T, float* scores, hipStream_t s);
 void topk_select(const float* scores, int B, int n, int k, int32_t* idx, hipStream_t s);
+// head mean of the CLS softmax rows [B,H,T] -> scores [B,T-1], then the selection, in one launch
+void topk_select_from_cls(const float* cls_prob, int B, int H, int T, int k, float* scores, int32_t* idx,
+                          hipStream_t s);
 void gather_tokens(const void* x, const int32_t* idx, int B, int T, int k, int D, bool f32, void* y,
                    hipStream_t s);
 void scatter_tokens(const void* dy, const int32_t* idx, int B, int T, int k, int D, bool f32,
@@ -79,17 +82,22 @@ void mean_sq_loss(const void* x, int64_t n, bool f32, float* partial, float* los
                   hipStream_t s);
 size_t mean_sq_partial_floats();
 
-void cast_matrix(const float* w, int rows, int cols, bf16* straight, bf16* transposed, hipStream_t s);
+// A table of weight matrices handled by one launch: bf16 copies (straight and / or transposed) of
+// each, optionally after an SGD update.  The table travels as a kernel argument.
+constexpr int MAT_TABLE_MAX = 64;
+struct MatEntry { float* w; const float* g; float* m; bf16* s; bf16* t; int rows, cols, tile_start; };
+struct MatTable { MatEntry e[MAT_TABLE_MAX]; int count = 0; int total_tiles = 0; };
+void matrix_table_add(MatTable& t, float* w, const float* g, float* m, int rows, int cols, bf16* straight,
+                      bf16* transposed);
+void matrix_table_run(const MatTable& t, bool update, float lr, float mu, float wd, hipStream_t s);
+
 // SGD on up to SGD_TABLE_MAX tensors without bf16 copies in one launch (the table travels as a
 // kernel argument)
 constexpr int SGD_TABLE_MAX = 96;
 struct SgdEntry { float* w; const float* g; float* m; int64_t n; };
 struct SgdTable { SgdEntry e[SGD_TABLE_MAX]; };
 void sgd_table(const SgdTable& t, int count, float lr, float mu, float wd, hipStream_t s);
-// fp32 C[M,N] = A.B (+bias) for tiny problems (the classification head): one thread per output
+// fp32 C[M,N] = A.B (+bias) for tiny problems (the classification head)
 void gemm_small_f32(const GemmDesc& g, hipStream_t s);
-// SGD on one tensor; matrices (rows > 1) also refresh their bf16 copies (either may be null)
-void sgd_update(float* w, const float* g, float* m, int rows, int cols, float lr, float mu, float wd,
-                bf16* straight, bf16* transposed, hipStream_t s);
 
 }  // namespace bsr

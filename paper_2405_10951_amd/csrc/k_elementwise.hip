@@ -296,12 +296,26 @@ __global__ void cls_head_mean_kernel(const float* __restrict__ cls_prob, int B, 
 // score, or the same score and a lower index).  Each thread ranks one token per pass of 256; kept
 // indices are written in ascending order through ballot prefixes within a wave and a running
 // offset across waves and passes.
-__global__ __launch_bounds__(256) void topk_select_kernel(const float* __restrict__ scores, int n,
-                                                          int k, int32_t* __restrict__ idx) {
+// With cls_prob given, the scores are first formed here as the head mean of the CLS softmax rows
+// (heads added in ascending order, then divided by H, as in cls_head_mean_kernel) and stored.
+__global__ __launch_bounds__(256) void topk_select_kernel(float* __restrict__ scores, int n, int k,
+                                                          int32_t* __restrict__ idx,
+                                                          const float* __restrict__ cls_prob, int H) {
   __shared__ float sc[1024];
   __shared__ int wave_count[4];
   const int b = blockIdx.x, tid = threadIdx.x, lane = tid % WAVE, w = tid / WAVE;
-  for (int j = tid; j < n; j += 256) sc[j] = scores[(int64_t)b * n + j];
+  for (int j = tid; j < n; j += 256) {
+    float v;
+    if (cls_prob) {
+      v = 0.f;
+      for (int h = 0; h < H; ++h) v += cls_prob[((int64_t)b * H + h) * (n + 1) + 1 + j];
+      v /= (float)H;
+      scores[(int64_t)b * n + j] = v;
+    } else {
+      v = scores[(int64_t)b * n + j];
+    }
+    sc[j] = v;
+  }
   __syncthreads();
   int base = 0;
   for (int c0 = 0; c0 < n; c0 += 256) {
@@ -427,44 +441,59 @@ __global__ __launch_bounds__(256) void mean_sq_kernel(const T* __restrict__ x, i
 }
 
 // ---------------------------------------------------------------- weights: casts and SGD
-// 32x32 tiles through LDS so that both the straight [rows,cols] and the transposed [cols,rows]
-// bf16 copies are written with contiguous rows.  With UPDATE the tile is first updated by SGD:
-//   g' = g + wd*w;  mu > 0: m = mu*m + g', w -= lr*m;  else w -= lr*g'   (Sec. 5 of the paper).
+// A table of matrices in one launch.  64x64 tiles, 16-byte accesses; the tile goes through LDS so
+// that both the straight [rows,cols] and the transposed [cols,rows] bf16 copies are written with
+// contiguous rows.  With UPDATE the tile is first updated by SGD (Sec. 5 of the paper):
+//   g' = g + wd*w;  mu > 0: m = mu*m + g', w -= lr*m;  else w -= lr*g'.
+// rows and cols are multiples of 4.
+typedef __bf16 bf16x4_t __attribute__((ext_vector_type(4)));
+
 template <bool UPDATE>
-__global__ __launch_bounds__(256) void matrix_tile_kernel(float* __restrict__ w, const float* __restrict__ g,
-                                                          float* __restrict__ mom, int rows, int cols,
-                                                          float lr, float mu, float wd,
-                                                          bf16* __restrict__ straight,
-                                                          bf16* __restrict__ transposed) {
-  __shared__ float tile[32][33];
-  const int tx = threadIdx.x % 32, ty = threadIdx.x / 32;
-  const int c0 = blockIdx.x * 32, r0 = blockIdx.y * 32;
-  for (int i = ty; i < 32; i += 8) {
-    const int r = r0 + i, c = c0 + tx;
-    float v = 0.f;
-    if (r < rows && c < cols) {
-      const int64_t off = (int64_t)r * cols + c;
-      v = w[off];
+__global__ __launch_bounds__(256) void matrix_table_kernel(MatTable t, float lr, float mu, float wd) {
+  __shared__ float tile[64][65];
+  int ei = 0;
+  while (ei + 1 < t.count && (int)blockIdx.x >= t.e[ei + 1].tile_start) ++ei;
+  const MatEntry e = t.e[ei];
+  const int local = blockIdx.x - e.tile_start, tiles_x = (e.cols + 63) / 64;
+  const int c0 = (local % tiles_x) * 64, r0 = (local / tiles_x) * 64;
+  const int tx = threadIdx.x % 16, ty = threadIdx.x / 16;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int lr_ = ty + 16 * i, r = r0 + lr_, c = c0 + 4 * tx;
+    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (r < e.rows && c < e.cols) {
+      const int64_t off = (int64_t)r * e.cols + c;
+      v = *(const float4*)(e.w + off);
       if (UPDATE) {
-        float gp = g[off] + wd * v;
+        const float4 g = *(const float4*)(e.g + off);
+        float4 gp = make_float4(g.x + wd * v.x, g.y + wd * v.y, g.z + wd * v.z, g.w + wd * v.w);
         if (mu > 0.f) {
-          float m = mu * mom[off] + gp;
-          mom[off] = m;
-          v -= lr * m;
-        } else {
-          v -= lr * gp;
+          const float4 m0 = *(const float4*)(e.m + off);
+          gp = make_float4(mu * m0.x + gp.x, mu * m0.y + gp.y, mu * m0.z + gp.z, mu * m0.w + gp.w);
+          *(float4*)(e.m + off) = gp;
         }
-        w[off] = v;
+        v = make_float4(v.x - lr * gp.x, v.y - lr * gp.y, v.z - lr * gp.z, v.w - lr * gp.w);
+        *(float4*)(e.w + off) = v;
       }
-      if (straight) straight[off] = (bf16)v;
+      if (e.s) {
+        bf16x4_t o;
+        o[0] = (bf16)v.x; o[1] = (bf16)v.y; o[2] = (bf16)v.z; o[3] = (bf16)v.w;
+        *(bf16x4_t*)(e.s + off) = o;
+      }
     }
-    tile[i][tx] = v;
+    tile[lr_][4 * tx + 0] = v.x; tile[lr_][4 * tx + 1] = v.y; tile[lr_][4 * tx + 2] = v.z; tile[lr_][4 * tx + 3] = v.w;
   }
   __syncthreads();
-  if (transposed) {
-    for (int i = ty; i < 32; i += 8) {
-      const int c = c0 + i, r = r0 + tx;
-      if (r < rows && c < cols) transposed[(int64_t)c * rows + r] = (bf16)tile[tx][i];
+  if (e.t) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int cc = ty + 16 * i, c = c0 + cc, r = r0 + 4 * tx;
+      if (c < e.cols && r < e.rows) {
+        bf16x4_t o;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) o[j] = (bf16)tile[4 * tx + j][cc];
+        *(bf16x4_t*)(e.t + (int64_t)c * e.rows + r) = o;
+      }
     }
   }
 }
@@ -575,7 +604,13 @@ void cls_head_mean(const float* cls_prob, int B, int H, int T, float* scores, hi
 
 void topk_select(const float* scores, int B, int n, int k, int32_t* idx, hipStream_t s) {
   if (B <= 0 || k <= 0) return;
-  topk_select_kernel<<<B, 256, 0, s>>>(scores, n, k, idx);
+  topk_select_kernel<<<B, 256, 0, s>>>(const_cast<float*>(scores), n, k, idx, nullptr, 0);
+}
+
+void topk_select_from_cls(const float* cls_prob, int B, int H, int T, int k, float* scores, int32_t* idx,
+                          hipStream_t s) {
+  if (B <= 0) return;
+  topk_select_kernel<<<B, 256, 0, s>>>(scores, T - 1, k, idx, cls_prob, H);
 }
 
 void gather_tokens(const void* x, const int32_t* idx, int B, int T, int k, int D, bool f32, void* y,
@@ -615,10 +650,19 @@ void mean_sq_loss(const void* x, int64_t n, bool f32, float* partial, float* los
   mean_of_rows_kernel<<<1, 64, 0, s>>>(partial, MSQ_BLOCKS, 1.0f / (float)n, loss);
 }
 
-void cast_matrix(const float* w, int rows, int cols, bf16* straight, bf16* transposed, hipStream_t s) {
-  dim3 grid((cols + 31) / 32, (rows + 31) / 32);
-  matrix_tile_kernel<false><<<grid, 256, 0, s>>>(const_cast<float*>(w), nullptr, nullptr, rows, cols,
-                                                 0.f, 0.f, 0.f, straight, transposed);
+void matrix_table_add(MatTable& t, float* w, const float* g, float* m, int rows, int cols, bf16* straight,
+                      bf16* transposed) {
+  MatEntry& e = t.e[t.count];
+  e.w = w; e.g = g; e.m = m; e.s = straight; e.t = transposed; e.rows = rows; e.cols = cols;
+  e.tile_start = t.total_tiles;
+  t.total_tiles += ((rows + 63) / 64) * ((cols + 63) / 64);
+  ++t.count;
+}
+
+void matrix_table_run(const MatTable& t, bool update, float lr, float mu, float wd, hipStream_t s) {
+  if (t.count == 0) return;
+  if (update) matrix_table_kernel<true><<<t.total_tiles, 256, 0, s>>>(t, lr, mu, wd);
+  else matrix_table_kernel<false><<<t.total_tiles, 256, 0, s>>>(t, 0.f, 0.f, 0.f);
 }
 
 void sgd_table(const SgdTable& t, int count, float lr, float mu, float wd, hipStream_t s) {
@@ -626,18 +670,6 @@ void sgd_table(const SgdTable& t, int count, float lr, float mu, float wd, hipSt
   int64_t nmax = 0;
   for (int i = 0; i < count; ++i) nmax = std::max(nmax, t.e[i].n);
   sgd_table_kernel<<<dim3((unsigned)((nmax + 1023) / 1024), count), 256, 0, s>>>(t, lr, mu, wd);
-}
-
-void sgd_update(float* w, const float* g, float* m, int rows, int cols, float lr, float mu, float wd,
-                bf16* straight, bf16* transposed, hipStream_t s) {
-  if (!straight && !transposed) {
-    SgdTable t;
-    t.e[0] = SgdEntry{w, g, m, (int64_t)rows * cols};
-    sgd_table(t, 1, lr, mu, wd, s);
-    return;
-  }
-  dim3 grid((cols + 31) / 32, (rows + 31) / 32);
-  matrix_tile_kernel<true><<<grid, 256, 0, s>>>(w, g, m, rows, cols, lr, mu, wd, straight, transposed);
 }
 
 }  // namespace bsr
