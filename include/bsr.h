@@ -195,8 +195,10 @@ int32_t bsr_sgd_step(bsr_ctx* ctx, const bsr_params* grads, const bsr_params* mo
  * bsr_linear_dgrad (Eq. 2): dx[M,in] = dy[M,out] . W^T, optionally times GELU'(u) element-wise.
  *   w_s   bf16 copy of W stored [in,out]        u     [M,in], may be NULL
  * bsr_linear_wgrad (Eq. 4): dw[in,out] (fp32) = x[M,in]^T . dy[M,out], summed over all M rows.
+ *   db         fp32 [out], may be NULL: the bias gradient, db[o] = sum over rows of dy[:,o], from the
+ *              same launch when the MFMA kernel takes the shape (otherwise it needs the workspace)
  *   workspace  device fp32 scratch of workspace_floats elements, may be NULL.  With at least
- *              2*in*out floats the sum over M is split over several workgroups per output tile
+ *              2*(in+1)*out floats the sum over M is split over several workgroups per output tile
  *              (partial sums are added in a fixed order: results are bit-reproducible).
  */
 int32_t bsr_linear_forward(const void* x, int32_t M, int32_t in, int32_t out, const void* w_t,
@@ -205,7 +207,7 @@ int32_t bsr_linear_forward(const void* x, int32_t M, int32_t in, int32_t out, co
 int32_t bsr_linear_dgrad(const void* dy, int32_t M, int32_t in, int32_t out, const void* w_s,
                          const void* u, void* dx, int32_t* used_mfma, void* stream);
 int32_t bsr_linear_wgrad(const void* x, const void* dy, int32_t M, int32_t in, int32_t out, float* dw,
-                         float* workspace, size_t workspace_floats, int32_t* used_mfma, void* stream);
+                         float* db, float* workspace, size_t workspace_floats, int32_t* used_mfma, void* stream);
 
 /*
  * Multi-head softmax attention in bf16 (Eq. 1), as the step runs it.  qkv is [B,T,3*H*d] with

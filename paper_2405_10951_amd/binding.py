@@ -86,7 +86,7 @@ def load_library():
                                      C.c_void_p, C.c_void_p, C.c_void_p]
     lib.bsr_linear_wgrad.restype = C.c_int32
     lib.bsr_linear_wgrad.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
-                                     C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
+                                     C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
     lib.bsr_attention_forward.restype = C.c_int32
     lib.bsr_attention_forward.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
                                           C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
@@ -176,15 +176,16 @@ def bsr_linear_dgrad(dy, w_s, u=None, dx=None):
     return dx, used.value
 
 
-def bsr_linear_wgrad(x, dy, dw=None, workspace=None):
-    """x [M,in], dy [M,out] bf16 -> (dw [in,out] fp32, used_mfma).  workspace: fp32 tensor or None."""
+def bsr_linear_wgrad(x, dy, dw=None, workspace=None, db=None):
+    """x [M,in], dy [M,out] bf16 -> (dw [in,out] fp32, used_mfma).  workspace: fp32 tensor or None;
+    db: fp32 [out] tensor that receives the bias gradient, or None."""
     import torch
     M, kin = x.shape
     out = dy.shape[1]
     if dw is None:
         dw = torch.empty((kin, out), dtype=torch.float32, device=x.device)
     used = C.c_int32(-1)
-    _check(load_library().bsr_linear_wgrad(_dp(x), _dp(dy), M, kin, out, _dp(dw), _dp(workspace),
+    _check(load_library().bsr_linear_wgrad(_dp(x), _dp(dy), M, kin, out, _dp(dw), _dp(db), _dp(workspace),
                                            C.c_size_t(0 if workspace is None else workspace.numel()),
                                            C.byref(used), _cur_stream(x)))
     return dw, used.value

@@ -305,6 +305,19 @@ void gemm(bsr_ctx* c, const GemmDesc& g, hipStream_t s) {
   else gemm_generic(g, s);
 }
 
+// Eq. 4 for one linear layer: dW = x^T dy and db = column sums of dy.  The MFMA kernel produces db
+// alongside dW; other shapes (and fp32 mode) take the separate column-sum kernels.
+void wgrad(bsr_ctx* c, const void* x, const void* dy, int M, int in, int out, void* dw, void* db, hipStream_t s) {
+  GemmDesc g = wgrad_desc(c, x, dy, M, in, out, dw);
+  if (gemm_mfma_supported(g)) {
+    g.bsum = (float*)db;
+    gemm(c, g, s);
+  } else {
+    gemm(c, g, s);
+    colsum(dy, M, out, out, c->f32, c->b.partial, (float*)db, s);
+  }
+}
+
 void attention_fwd(bsr_ctx* c, const void* qkv, int B, int T, void* out, float* lse, float* clsp,
                    hipStream_t s) {
   const int H = c->cfg.heads, d = c->cfg.dim / H;
@@ -641,13 +654,11 @@ int32_t bsr_train_blocks_fwd_bwd(bsr_ctx* c, const void* x_in, const int32_t* la
     d1.act = ACT_GELU_BWD;
     d1.aux = v.u;
     gemm(c, d1, s);
-    gemm(c, wgrad_desc(c, v.g, dx, M2, F, D, gw.w_fc2), s);
-    colsum(dx, M2, D, D, f32, b.partial, (float*)gw.b_fc2, s);
+    wgrad(c, v.g, dx, M2, F, D, gw.w_fc2, gw.b_fc2, s);
     gemm(c, dgrad_desc(c, b.dgu, M2, D, F, w.w_fc1, sh.s_fc1, b.dh), s);
-    gemm(c, wgrad_desc(c, v.h2, b.dgu, M2, D, F, gw.w_fc1), s);
-    colsum(b.dgu, M2, F, F, f32, b.partial, (float*)gw.b_fc1, s);
-    layernorm_bwd_params(b.dh, v.xmid, v.mean2, v.rstd2, M2, D, f32, b.partial, (float*)gw.ln2_g, (float*)gw.ln2_b, s);
-    layernorm_bwd_dx(b.dh, v.xmid, v.mean2, v.rstd2, (const float*)w.ln2_g, dx, M2, D, f32, dx_other, s);
+    wgrad(c, v.h2, b.dgu, M2, D, F, gw.w_fc1, gw.b_fc1, s);
+    layernorm_bwd(b.dh, v.xmid, v.mean2, v.rstd2, (const float*)w.ln2_g, dx, M2, D, f32, dx_other, b.partial,
+                  (float*)gw.ln2_g, (float*)gw.ln2_b, s);
     std::swap(dx, dx_other);   // dx: gradient at x_mid (kept tokens)
 
     // adjoint of the token drop: dropped tokens receive nothing from the FFN side
@@ -658,17 +669,14 @@ int32_t bsr_train_blocks_fwd_bwd(bsr_ctx* c, const void* x_in, const int32_t* la
 
     // MHSA branch.  dO = dx . Wproj^T; dWproj = o^T dx; attention backward; dWqkv = h1^T dqkv
     gemm(c, dgrad_desc(c, dx, M, D, D, w.w_proj, sh.s_proj, b.dh), s);
-    gemm(c, wgrad_desc(c, v.o, dx, M, D, D, gw.w_proj), s);
-    colsum(dx, M, D, D, f32, b.partial, (float*)gw.b_proj, s);
+    wgrad(c, v.o, dx, M, D, D, gw.w_proj, gw.b_proj, s);
     attention_bwd(c, v.qkv, v.o, b.dh, v.lse, B, Ta, b.dqkv, s);
-    gemm(c, wgrad_desc(c, v.h1, b.dqkv, M, D, 3 * D, gw.w_qkv), s);
-    colsum(b.dqkv, M, 3 * D, 3 * D, f32, b.partial, (float*)gw.b_qkv, s);
+    wgrad(c, v.h1, b.dqkv, M, D, 3 * D, gw.w_qkv, gw.b_qkv, s);
     gemm(c, dgrad_desc(c, b.dqkv, M, D, 3 * D, w.w_qkv, sh.s_qkv, b.dh), s);
-    layernorm_bwd_params(b.dh, xin, v.mean1, v.rstd1, M, D, f32, b.partial, (float*)gw.ln1_g, (float*)gw.ln1_b, s);
-    if (l > ft) {   // the gradient is not carried below the earliest trainable block (Fig. 2)
-      layernorm_bwd_dx(b.dh, xin, v.mean1, v.rstd1, (const float*)w.ln1_g, dx, M, D, f32, dx_other, s);
-      std::swap(dx, dx_other);
-    }
+    // the gradient is not carried below the earliest trainable block (Fig. 2): no dx there
+    layernorm_bwd(b.dh, xin, v.mean1, v.rstd1, (const float*)w.ln1_g, dx, M, D, f32, l > ft ? dx_other : nullptr,
+                  b.partial, (float*)gw.ln1_g, (float*)gw.ln1_b, s);
+    if (l > ft) std::swap(dx, dx_other);
   }
   return check_hip(c, "bsr_train_blocks_fwd_bwd");
 }
@@ -759,13 +767,21 @@ int32_t bsr_linear_dgrad(const void* dy, int32_t M, int32_t in, int32_t out, con
 }
 
 int32_t bsr_linear_wgrad(const void* x, const void* dy, int32_t M, int32_t in, int32_t out, float* dw,
-                         float* workspace, size_t workspace_floats, int32_t* used_mfma, void* stream) {
+                         float* db, float* workspace, size_t workspace_floats, int32_t* used_mfma, void* stream) {
   if (!aligned16(x) || !aligned16(dy) || !aligned16(dw) || M < 1 || in < 1 || out < 1)
     return fail(nullptr, BSR_ERR_INVALID_ARG, "bsr_linear_wgrad: bad argument");
   GemmDesc g;
   g.A = x; g.a_rs = 1; g.a_cs = in; g.B = dy; g.b_rs = out; g.b_cs = 1;
   g.C = dw; g.ldc = out; g.M = in; g.N = out; g.K = M; g.out_f32 = true;
   if (workspace && !aligned16(workspace)) return fail(nullptr, BSR_ERR_INVALID_ARG, "bsr_linear_wgrad: workspace misaligned");
+  if (db && gemm_mfma_supported(g)) {
+    g.bsum = db;
+  } else if (db) {   // shapes the MFMA kernel does not take: separate column sums, staged in the workspace
+    if (!workspace || workspace_floats < colsum_partial_floats(M, out))
+      return fail(nullptr, BSR_ERR_INVALID_ARG, "bsr_linear_wgrad: db for this shape needs a workspace of %zu floats",
+                  colsum_partial_floats(M, out));
+    colsum(dy, M, out, out, false, workspace, db, (hipStream_t)stream);
+  }
   return run_layer(g, used_mfma, stream, "bsr_linear_wgrad", workspace, workspace_floats);
 }
 

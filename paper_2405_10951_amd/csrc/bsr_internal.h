@@ -26,6 +26,8 @@ struct GemmDesc {
   const void* res = nullptr; // residual added last (dtype of C, ld = ldc, same row mapping)
   int remap_np = 0;          // > 0 (patch embedding): row(m) = m + m / np + 1, and pos[(m % np + 1), n]
   const float* pos = nullptr;//   is added; rows of CLS tokens are left untouched
+  float* bsum = nullptr;     // weight-gradient form only (A^T and B share the token index k): if set,
+                             //   receives sum_k B(k,n), the bias gradient of the same layer
 };
 
 // ---- generic (any shape, fp32 or bf16 storage, fp32 arithmetic) ---------------------------------
@@ -57,6 +59,10 @@ void layernorm_bwd_dx(const void* dy, const void* x, const float* mean, const fl
 void layernorm_bwd_params(const void* dy, const void* x, const float* mean, const float* rstd,
                           int64_t M, int D, bool f32, float* partial, float* dgamma, float* dbeta,
                           hipStream_t s);
+// both of the above; one pass over dy and x on the bf16 path
+void layernorm_bwd(const void* dy, const void* x, const float* mean, const float* rstd, const float* gamma,
+                   const void* res, int64_t M, int D, bool f32, void* dx, float* partial, float* dgamma,
+                   float* dbeta, hipStream_t s);
 // out[j] = sum_m a[m*ld + j]
 void colsum(const void* a, int64_t M, int N, int64_t ld, bool f32, float* partial, float* out,
             hipStream_t s);

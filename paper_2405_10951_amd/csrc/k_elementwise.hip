@@ -191,6 +191,126 @@ __global__ __launch_bounds__(256) void ln_bwd_dx_vec_kernel(const bf16* __restri
   }
 }
 
+// LayerNorm backward in one pass over dy and x: dx as above (skipped when dx is null) and, per
+// workgroup, the partial sums over its rows of dy * xhat (dgamma) and dy (dbeta).  A wavefront walks
+// rows blockIdx.x * 4 + wave + k * 4 * gridDim.x with the next row's loads in flight; the four wave
+// partials are added in wave order and land in partial[blockIdx.x] (dgamma) and
+// partial[LN_BWD_BLOCKS + blockIdx.x] (dbeta); colsum_final_kernel adds the workgroups.
+constexpr int LN_BWD_BLOCKS = 256;
+
+__global__ __launch_bounds__(256) void ln_bwd_fused_vec_kernel(const bf16* __restrict__ dy, const bf16* __restrict__ x,
+                                                               const float* __restrict__ mean,
+                                                               const float* __restrict__ rstd,
+                                                               const float* __restrict__ gamma,
+                                                               const bf16* __restrict__ res, int64_t M, int D,
+                                                               bf16* __restrict__ dx, float* __restrict__ partial) {
+  __shared__ float red[3][8 * WAVE * LN_MAXC];
+  const int lane = threadIdx.x % WAVE, w = threadIdx.x / WAVE;
+  const int nch = D / 8;
+  const int64_t stride = (int64_t)gridDim.x * 4;
+  float gg[LN_MAXC][8];
+  float dg[LN_MAXC][8], db[LN_MAXC][8];
+#pragma unroll
+  for (int i = 0; i < LN_MAXC; ++i) {
+    const int c = lane + i * WAVE;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { dg[i][e] = 0.f; db[i][e] = 0.f; gg[i][e] = 0.f; }
+    if (c < nch) {
+      const float4 g0 = *(const float4*)(gamma + c * 8), g1 = *(const float4*)(gamma + c * 8 + 4);
+      gg[i][0] = g0.x; gg[i][1] = g0.y; gg[i][2] = g0.z; gg[i][3] = g0.w;
+      gg[i][4] = g1.x; gg[i][5] = g1.y; gg[i][6] = g1.z; gg[i][7] = g1.w;
+    }
+  }
+  bf16x8_t na[LN_MAXC], nt[LN_MAXC];     // the next row, already loading
+  float nmu = 0.f, nrs = 0.f;
+  auto prefetch = [&](int64_t m) {
+    if (m >= M) return;
+    const bf16x8_t* dyr = (const bf16x8_t*)(dy + m * D);
+    const bf16x8_t* xr = (const bf16x8_t*)(x + m * D);
+#pragma unroll
+    for (int i = 0; i < LN_MAXC; ++i) {
+      const int c = lane + i * WAVE;
+      if (c < nch) { na[i] = dyr[c]; nt[i] = xr[c]; }
+    }
+    nmu = mean[m]; nrs = rstd[m];
+  };
+  int64_t m = (int64_t)blockIdx.x * 4 + w;
+  prefetch(m);
+  for (; m < M; m += stride) {
+    bf16x8_t a[LN_MAXC], t[LN_MAXC];
+#pragma unroll
+    for (int i = 0; i < LN_MAXC; ++i) { a[i] = na[i]; t[i] = nt[i]; }
+    const float mu = nmu, rs = nrs;
+    prefetch(m + stride);
+    float g[LN_MAXC][8], xh[LN_MAXC][8];
+    float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+    for (int i = 0; i < LN_MAXC; ++i) {
+      if (lane + i * WAVE < nch) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const float d0 = (float)a[i][e];
+          xh[i][e] = ((float)t[i][e] - mu) * rs;
+          g[i][e] = d0 * gg[i][e];
+          dg[i][e] += d0 * xh[i][e];
+          db[i][e] += d0;
+          s1 += g[i][e];
+          s2 += g[i][e] * xh[i][e];
+        }
+      }
+    }
+    if (dx) {
+      const float m1 = wave_sum(s1) / (float)D, m2 = wave_sum(s2) / (float)D;
+      const bf16x8_t* rr = res ? (const bf16x8_t*)(res + m * D) : nullptr;
+      bf16x8_t* dxr = (bf16x8_t*)(dx + m * D);
+#pragma unroll
+      for (int i = 0; i < LN_MAXC; ++i) {
+        const int c = lane + i * WAVE;
+        if (c < nch) {
+          bf16x8_t o;
+          bf16x8_t r8;
+          if (rr) r8 = rr[c];
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            float v = rs * (g[i][e] - m1 - xh[i][e] * m2);
+            if (rr) v += (float)r8[e];
+            o[e] = (bf16)v;
+          }
+          dxr[c] = o;
+        }
+      }
+    }
+  }
+  // workgroup partials: waves 1..3 park their sums in LDS, wave 0 adds them in wave order
+#pragma unroll
+  for (int pass = 0; pass < 2; ++pass) {
+    if (pass) __syncthreads();
+    if (w > 0) {
+#pragma unroll
+      for (int i = 0; i < LN_MAXC; ++i)
+        if (lane + i * WAVE < nch)
+#pragma unroll
+          for (int e = 0; e < 8; ++e) red[w - 1][(lane + i * WAVE) * 8 + e] = pass ? db[i][e] : dg[i][e];
+    }
+    __syncthreads();
+    if (w == 0) {
+      float* dst = partial + ((int64_t)pass * LN_BWD_BLOCKS + blockIdx.x) * D;
+#pragma unroll
+      for (int i = 0; i < LN_MAXC; ++i) {
+        const int c = lane + i * WAVE;
+        if (c < nch) {
+          float o[8];
+#pragma unroll
+          for (int e = 0; e < 8; ++e)
+            o[e] = (((pass ? db[i][e] : dg[i][e]) + red[0][c * 8 + e]) + red[1][c * 8 + e]) + red[2][c * 8 + e];
+          *(float4*)(dst + c * 8) = make_float4(o[0], o[1], o[2], o[3]);
+          *(float4*)(dst + c * 8 + 4) = make_float4(o[4], o[5], o[6], o[7]);
+        }
+      }
+    }
+  }
+}
+
 // Pass 1 of a column reduction over M rows: block (cx, r) sums rows of chunk r for 64 columns.
 // WITH_XHAT: two sums, dy*xhat (slot 0) and dy (slot 1); otherwise the plain column sum (slot 0).
 template <typename T, bool WITH_XHAT>
@@ -228,27 +348,34 @@ __global__ __launch_bounds__(256) void colsum_partial_kernel(const T* __restrict
   }
 }
 
-// Pass 2: out[col] = sum over chunks.  Wave w of the block adds chunks w, w+4, ... in ascending
-// order, then the four wave sums are added in wave order: a fixed order, bit-reproducible.
-__global__ __launch_bounds__(256) void colsum_final_kernel(const float* __restrict__ partial, int N, int chunks,
-                                                           float* __restrict__ out0, float* __restrict__ out1) {
-  __shared__ float red[2][4][WAVE];
+// Pass 2: out[col] = sum over chunks.  Wave w of the block adds chunks w, w+16, ... in ascending
+// order, then the wave sums are added in wave order: a fixed order, bit-reproducible.  The second
+// sum (if out1) starts `second` rows into the partial buffer.
+constexpr int FINAL_WAVES = 16;
+__global__ __launch_bounds__(FINAL_WAVES * WAVE) void colsum_final_kernel(const float* __restrict__ partial, int N,
+                                                                          int chunks, int second,
+                                                                          float* __restrict__ out0,
+                                                                          float* __restrict__ out1) {
+  __shared__ float red[2][FINAL_WAVES][WAVE];
   const int lane = threadIdx.x % WAVE, w = threadIdx.x / WAVE;
   const int col = blockIdx.x * WAVE + lane;
   float s = 0.f, t = 0.f;
   if (col < N) {
 #pragma unroll 4
-    for (int r = w; r < chunks; r += 4) {
+    for (int r = w; r < chunks; r += FINAL_WAVES) {
       s += partial[(int64_t)r * N + col];
-      if (out1) t += partial[(int64_t)(COLSUM_R + r) * N + col];
+      if (out1) t += partial[(int64_t)(second + r) * N + col];
     }
   }
   red[0][w][lane] = s;
   red[1][w][lane] = t;
   __syncthreads();
   if (w == 0 && col < N) {
-    out0[col] = red[0][0][lane] + red[0][1][lane] + red[0][2][lane] + red[0][3][lane];
-    if (out1) out1[col] = red[1][0][lane] + red[1][1][lane] + red[1][2][lane] + red[1][3][lane];
+    float a0 = red[0][0][lane], a1 = red[1][0][lane];
+#pragma unroll
+    for (int i = 1; i < FINAL_WAVES; ++i) { a0 += red[0][i][lane]; a1 += red[1][i][lane]; }
+    out0[col] = a0;
+    if (out1) out1[col] = a1;
   }
 }
 
@@ -556,7 +683,23 @@ void layernorm_bwd_dx(const void* dy, const void* x, const float* mean, const fl
                                                  (const bf16*)res, M, D, (bf16*)dx);
 }
 
-size_t colsum_partial_floats(int64_t, int N) { return (size_t)2 * COLSUM_R * (size_t)N; }
+void layernorm_bwd(const void* dy, const void* x, const float* mean, const float* rstd, const float* gamma,
+                   const void* res, int64_t M, int D, bool f32, void* dx, float* partial, float* dgamma,
+                   float* dbeta, hipStream_t s) {
+  if (M <= 0) return;
+  if (!f32 && D % 8 == 0 && D <= 8 * WAVE * LN_MAXC) {
+    const int blocks = (int)std::min<int64_t>(LN_BWD_BLOCKS, (M + 3) / 4);
+    ln_bwd_fused_vec_kernel<<<blocks, 256, 0, s>>>((const bf16*)dy, (const bf16*)x, mean, rstd, gamma,
+                                                   (const bf16*)res, M, D, (bf16*)dx, partial);
+    colsum_final_kernel<<<(D + WAVE - 1) / WAVE, FINAL_WAVES * WAVE, 0, s>>>(partial, D, blocks, LN_BWD_BLOCKS,
+                                                                           dgamma, dbeta);
+    return;
+  }
+  layernorm_bwd_params(dy, x, mean, rstd, M, D, f32, partial, dgamma, dbeta, s);
+  layernorm_bwd_dx(dy, x, mean, rstd, gamma, res, M, D, f32, dx, s);
+}
+
+size_t colsum_partial_floats(int64_t, int N) { return (size_t)2 * std::max(COLSUM_R, LN_BWD_BLOCKS) * (size_t)N; }
 
 void layernorm_bwd_params(const void* dy, const void* x, const float* mean, const float* rstd,
                           int64_t M, int D, bool f32, float* partial, float* dgamma, float* dbeta,
@@ -568,7 +711,7 @@ void layernorm_bwd_params(const void* dy, const void* x, const float* mean, cons
     colsum_partial_kernel<float, true><<<grid, 256, 0, s>>>((const float*)dy, D, (const float*)x, mean, rstd, M, D, rpc, partial);
   else
     colsum_partial_kernel<bf16, true><<<grid, 256, 0, s>>>((const bf16*)dy, D, (const bf16*)x, mean, rstd, M, D, rpc, partial);
-  colsum_final_kernel<<<(D + WAVE - 1) / WAVE, 256, 0, s>>>(partial, D, ch, dgamma, dbeta);
+  colsum_final_kernel<<<(D + WAVE - 1) / WAVE, FINAL_WAVES * WAVE, 0, s>>>(partial, D, ch, COLSUM_R, dgamma, dbeta);
 }
 
 void colsum(const void* a, int64_t M, int N, int64_t ld, bool f32, float* partial, float* out,
@@ -580,7 +723,7 @@ void colsum(const void* a, int64_t M, int N, int64_t ld, bool f32, float* partia
     colsum_partial_kernel<float, false><<<grid, 256, 0, s>>>((const float*)a, ld, nullptr, nullptr, nullptr, M, N, rpc, partial);
   else
     colsum_partial_kernel<bf16, false><<<grid, 256, 0, s>>>((const bf16*)a, ld, nullptr, nullptr, nullptr, M, N, rpc, partial);
-  colsum_final_kernel<<<(N + WAVE - 1) / WAVE, 256, 0, s>>>(partial, N, ch, out, nullptr);
+  colsum_final_kernel<<<(N + WAVE - 1) / WAVE, FINAL_WAVES * WAVE, 0, s>>>(partial, N, ch, 0, out, nullptr);
 }
 
 void patchify(const void* img, int B, int C, int S, int P, bool f32, void* out, hipStream_t s) {

@@ -309,13 +309,16 @@ void launch_nt(const GemmDesc& g, hipStream_t s) {
 // writers of a row over all banks.
 // Split-K: workgroup z handles k-tiles [z*kt_per, (z+1)*kt_per) and writes its own fp32 partial;
 // a second kernel adds the partials in a fixed order (bit-reproducible, no atomics).
+// Bias gradient: the workgroups of the first row of tiles also multiply every dY fragment by an
+// all-ones A fragment, which leaves the column sums of dY (db = 1^T dY) in one more accumulator per
+// 32 columns; they travel through the same partial / reduce path as dW.
 __device__ inline int tn_unit(int col) {       // 8-byte unit index of a column inside its LDS row
   const int b = col >> 5, slot = (col >> 1) & 15;
   return ((b << 4) + (slot ^ b)) * 2 + (col & 1);
 }
 
 template <int BM, int BN>
-__global__ __launch_bounds__(256) void gemm_tn_kernel(GemmDesc g, float* partial, int kt_per) {
+__global__ __launch_bounds__(256) void gemm_tn_kernel(GemmDesc g, float* partial, float* bpartial, int kt_per) {
   constexpr int TM = BM / 2, TN = BN / 2, MI = TM / 32, NI = TN / 32;
   constexpr int ACH = BM * 8 / 256 / 4, BCH = BN * 8 / 256 / 4;   // 4-token groups per thread per tile
   static_assert(BM == 128 && BN == 128, "thread mapping below assumes 16 column chunks per row");
@@ -390,6 +393,16 @@ __global__ __launch_bounds__(256) void gemm_tn_kernel(GemmDesc g, float* partial
 #pragma unroll
   for (int ni = 0; ni < NI; ++ni) ub[ni] = tn_unit(wn * TN + ni * 32 + lr);
 
+  const bool do_bsum = g.bsum && m0 == 0 && wm == 0;     // uniform over the wavefront
+  f32x16 accb[NI];
+  bf16x8 ones;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) ones[e] = (bf16)1.0f;
+#pragma unroll
+  for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) accb[ni][r] = 0.f;
+
   union Frag { bf16x8 v; uint2 h[2]; };
   Frag fa[2][MI], fb[2][NI];
   auto load_frags = [&](int set, const uint2* Ab, const uint2* Bb, int ks) {
@@ -411,6 +424,11 @@ __global__ __launch_bounds__(256) void gemm_tn_kernel(GemmDesc g, float* partial
 #pragma unroll
       for (int ni = 0; ni < NI; ++ni)
         acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[set][mi].v, fb[set][ni].v, acc[mi][ni], 0, 0, 0);
+    if (do_bsum) {
+#pragma unroll
+      for (int ni = 0; ni < NI; ++ni)
+        accb[ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones, fb[set][ni].v, accb[ni], 0, 0, 0);
+    }
   };
 
   const int nk = kt1 - kt0;
@@ -445,12 +463,28 @@ __global__ __launch_bounds__(256) void gemm_tn_kernel(GemmDesc g, float* partial
   }
   float* patch = (float*)smem + wave * (32 * (TN + 4));
   epilogue<MI, NI>(o, acc, m0 + wm * TM, n0 + wn * TN, lane, patch);
+  if (do_bsum && lh == 0) {                        // every row of accb holds the column sums
+    float* dst = bpartial ? bpartial + (int64_t)blockIdx.y * g.N : g.bsum;
+#pragma unroll
+    for (int ni = 0; ni < NI; ++ni) {
+      const int col = n0 + wn * TN + ni * 32 + lr;
+      if (col < g.N) dst[col] = accb[ni][0];
+    }
+  }
 }
 
-// out[i] = sum over splits, ascending
-__global__ void splitk_reduce_kernel(const float* __restrict__ partial, int64_t n, int splits, float* __restrict__ out) {
+// out[i] = sum over splits, ascending; the threads past the matrix do the same for the nb column sums
+__global__ void splitk_reduce_kernel(const float* __restrict__ partial, int64_t n, int splits, float* __restrict__ out,
+                                     const float* __restrict__ bpartial, int nb, float* __restrict__ bout) {
   const int64_t i = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * 4;
-  if (i >= n) return;
+  if (i >= n) {
+    for (int64_t j = i - n; j < min(i - n + 4, (int64_t)nb); ++j) {
+      float s = bpartial[j];
+      for (int z = 1; z < splits; ++z) s += bpartial[(int64_t)z * nb + j];
+      bout[j] = s;
+    }
+    return;
+  }
   float4 s = *(const float4*)(partial + i);
   for (int z = 1; z < splits; ++z) {
     const float4 v = *(const float4*)(partial + (int64_t)z * n + i);
@@ -478,16 +512,20 @@ void launch_tn(const GemmDesc& g, float* ws, size_t ws_floats, hipStream_t s) {
   // enough splits to give every CU about two workgroups, each with at least 4 k-tiles
   int splits = 1;
   const size_t mn = (size_t)g.M * g.N;
+  const size_t per_split = mn + (g.bsum ? (size_t)g.N : 0);   // partial dW, then partial column sums
   if (ws && mn % 4 == 0) {
-    splits = std::max(1, std::min({512 / tiles, nk / 4, (int)(ws_floats / mn), 16}));
+    splits = std::max(1, std::min({512 / tiles, nk / 4, (int)(ws_floats / per_split), 16}));
   }
   int kt_per = (nk + splits - 1) / splits;
   splits = (nk + kt_per - 1) / kt_per;
   if (splits <= 1) {
-    gemm_tn_kernel<BM, BN><<<dim3(tiles, 1), 256, lds, s>>>(g, nullptr, nk);
+    gemm_tn_kernel<BM, BN><<<dim3(tiles, 1), 256, lds, s>>>(g, nullptr, nullptr, nk);
   } else {
-    gemm_tn_kernel<BM, BN><<<dim3(tiles, splits), 256, lds, s>>>(g, ws, kt_per);
-    splitk_reduce_kernel<<<(unsigned)((mn / 4 + 255) / 256), 256, 0, s>>>(ws, (int64_t)mn, splits, (float*)g.C);
+    float* bws = g.bsum ? ws + (size_t)splits * mn : nullptr;
+    const int nb = g.bsum ? g.N : 0;
+    gemm_tn_kernel<BM, BN><<<dim3(tiles, splits), 256, lds, s>>>(g, ws, bws, kt_per);
+    splitk_reduce_kernel<<<(unsigned)((mn / 4 + (nb + 3) / 4 + 255) / 256), 256, 0, s>>>(ws, (int64_t)mn, splits, (float*)g.C,
+                                                                               bws, nb, g.bsum);
   }
 }
 
@@ -499,9 +537,11 @@ bool is_nt(const GemmDesc& g) {
 
 }  // namespace
 
-// room for 8 partial copies of the largest weight gradient of a block ([D,3D] or [D,F])
+// room for 8 partial copies of the largest weight gradient of a block ([D,3D] or [D,F]) and of its
+// bias gradient (16 for the smaller matrices, which split further)
 size_t gemm_splitk_ws_floats(int dim, int mlp_hidden) {
-  return (size_t)8 * std::max((size_t)3 * dim * dim, (size_t)dim * mlp_hidden);
+  return (size_t)8 * std::max((size_t)3 * dim * dim, (size_t)dim * mlp_hidden) +
+         (size_t)16 * std::max(3 * dim, mlp_hidden);
 }
 
 bool gemm_mfma_supported(const GemmDesc& g) { return is_nt(g) || is_tn(g); }

@@ -90,16 +90,22 @@ def test_linear_wgrad(env, orc64, M, kin, out):
     x = bf16_np(rng, (M, kin)); dy = bf16_np(rng, (M, out))
     cols = np.unique(rng.choice(kin, min(kin, 96), replace=False))    # rows of dW are independent
     xt, dyt = to_dev(torch, x, torch.bfloat16), to_dev(torch, dy, torch.bfloat16)
-    dw, used = P.bsr_linear_wgrad(xt, dyt)
-    ws = torch.empty(8 * kin * out, dtype=torch.float32, device="cuda")
-    dw_split, _ = P.bsr_linear_wgrad(xt, dyt, workspace=ws)            # split over the token sum
-    dw_again, _ = P.bsr_linear_wgrad(xt, dyt, workspace=ws)
+    db = [torch.full((out,), float("nan"), dtype=torch.float32, device="cuda") for _ in range(3)]
+    dw, used = P.bsr_linear_wgrad(xt, dyt, db=db[0])
+    dw_nob, _ = P.bsr_linear_wgrad(xt, dyt)                             # db is optional
+    ws = torch.empty(8 * (kin + 1) * out, dtype=torch.float32, device="cuda")
+    dw_split, _ = P.bsr_linear_wgrad(xt, dyt, workspace=ws, db=db[1])  # split over the token sum
+    dw_again, _ = P.bsr_linear_wgrad(xt, dyt, workspace=ws, db=db[2])
     torch.cuda.synchronize()
     assert used == 1, "the MFMA kernel must take this shape"
     ref, _ = orc64.linear_wgrad(np.ascontiguousarray(x[:, cols]), dy)  # Eq. 4
+    _, ref_db = orc64.linear_wgrad(np.ascontiguousarray(x[:, :1]), dy)
     assert_close(dw.cpu().numpy()[cols], ref, "wgrad", tol=2e-3)
+    assert torch.equal(dw, dw_nob)
     assert_close(dw_split.cpu().numpy()[cols], ref, "wgrad split-K", tol=2e-3)
-    assert torch.equal(dw_split, dw_again), "split-K must be bit-reproducible"
+    assert_close(db[0].cpu().numpy(), ref_db, "bias grad", tol=2e-3)
+    assert_close(db[1].cpu().numpy(), ref_db, "bias grad split-K", tol=2e-3)
+    assert torch.equal(dw_split, dw_again) and torch.equal(db[1], db[2]), "split-K must be bit-reproducible"
 
 
 ATTN_SHAPES = [(2, 197, 12), (2, 138, 12), (3, 96, 6), (2, 67, 12), (2, 25, 3), (1, 1, 2), (2, 33, 2), (1, 256, 2)]
