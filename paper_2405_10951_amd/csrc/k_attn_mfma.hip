@@ -2,13 +2,14 @@
 // of every ViT-B/16 and DeiT-S block after token dropping.  The CLS row of the softmax map, which
 // Eq. 6 ranks tokens by, leaves the forward kernel in fp32 as a by-product.
 //
-// Forward.  One workgroup = one (image, head) and 128 query rows; each of its 4 wavefronts owns 32
-// queries.  K of the head sits in LDS row-major (swizzled 16-byte chunks), V sits transposed
-// (feature-major).  The wave computes S^T = K Q^T with 32x32x16 MFMAs, so that a lane owns one query
-// and the softmax reductions over keys are in-register (plus one exchange between the two halves of
-// the wave).  The normalised P^T accumulators are, as they lie in registers, the A operand of the
-// second product O = P V: MFMA contracts over a dummy index, so the key order that the accumulator
-// layout dictates is simply applied to the V^T reads as well.  No T x T tensor ever leaves registers.
+// Forward.  One workgroup = one (image, head): K and V of the head are staged once, and each of
+// its ceil(T / 32) wavefronts owns 32 queries.  K sits in LDS row-major (swizzled 16-byte chunks),
+// V sits transposed (feature-major).  The wave computes S^T = K Q^T with 32x32x16 MFMAs, so that a
+// lane owns one query and the softmax reductions over keys are in-register (plus one exchange between
+// the two halves of the wave).  The normalised P^T accumulators are, as they lie in registers, an
+// operand of the second product O^T = V^T P^T: MFMA contracts over a dummy index, so the key order
+// that the accumulator layout dictates is simply applied to the V^T reads as well.  No T x T tensor
+// ever leaves registers.
 #include "bsr_internal.h"
 
 namespace bsr {
@@ -30,8 +31,9 @@ __device__ inline int swz(int row) { return (row & 7) ^ ((row >> 3) & 1); }
 __device__ inline int key_of(int jb, int r, int lh) { return jb * 32 + 8 * (r >> 2) + 4 * lh + (r & 3); }
 
 // K rows [T,64] of one head -> LDS chunks; rows >= T are zero.
-__device__ inline void load_k(const bf16* base, int64_t row_stride, int T, int Tpad, u32x4* Ks, int tid) {
-  for (int c = tid; c < Tpad * 8; c += 256) {
+__device__ inline void load_k(const bf16* base, int64_t row_stride, int T, int Tpad, u32x4* Ks, int tid,
+                              int nthreads = 256) {
+  for (int c = tid; c < Tpad * 8; c += nthreads) {
     const int row = c >> 3, kc = c & 7;
     u32x4 v = {0u, 0u, 0u, 0u};
     if (row < T) v = *(const u32x4*)(base + (int64_t)row * row_stride + kc * 8);
@@ -40,8 +42,9 @@ __device__ inline void load_k(const bf16* base, int64_t row_stride, int T, int T
 }
 
 // Rows [T,64] -> transposed LDS [64][VP]: 4 rows x 8 columns per thread, transposed in registers.
-__device__ inline void load_transposed(const bf16* base, int64_t row_stride, int T, int Tpad, bf16* Vt, int tid) {
-  for (int c = tid; c < (Tpad / 4) * 8; c += 256) {
+__device__ inline void load_transposed(const bf16* base, int64_t row_stride, int T, int Tpad, bf16* Vt, int tid,
+                                       int nthreads = 256) {
+  for (int c = tid; c < (Tpad / 4) * 8; c += nthreads) {
     const int fc = c & 7, kg = c >> 3;
     u32x4 r[4];
 #pragma unroll
@@ -64,32 +67,32 @@ __device__ inline void load_transposed(const bf16* base, int64_t row_stride, int
 }
 
 template <int NJ>
-__global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(const bf16* __restrict__ qkv, int T, int H,
-                                                            bf16* __restrict__ out, float* __restrict__ lse,
-                                                            float* __restrict__ cls_prob) {
-  constexpr int Tpad = NJ * 32;
+__global__ __launch_bounds__(NJ * 64) void attn_fwd_mfma_kernel(const bf16* __restrict__ qkv, int T, int H,
+                                                               bf16* __restrict__ out, float* __restrict__ lse,
+                                                               float* __restrict__ cls_prob) {
+  constexpr int Tpad = NJ * 32, NTH = NJ * 64;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   u32x4* Ks = (u32x4*)smem;                         // [Tpad][8 chunks]
   bf16* Vt = (bf16*)(smem + (size_t)Tpad * 128);    // [64][VP]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int lr = lane & 31, lh = lane >> 5;
-  const int b = blockIdx.y / H, h = blockIdx.y % H;
+  const int b = blockIdx.x / H, h = blockIdx.x % H;
   const int D = H * HD;
   const int64_t rs = 3 * (int64_t)D;
   const bf16* base = qkv + (int64_t)b * T * rs + h * HD;
-  load_k(base + D, rs, T, Tpad, Ks, tid);
-  load_transposed(base + 2 * D, rs, T, Tpad, Vt, tid);
-  __syncthreads();
-  const int q0 = blockIdx.x * 128 + wave * 32;
-  if (q0 >= T) return;
-
-  // Q fragments straight from global memory: lane (query lr, half lh) needs chunks 2ks + lh
+  const int q0 = wave * 32;                         // wave w owns queries 32 w .. 32 w + 31 (q0 < T always)
+  // Q fragments straight from global memory, requested before K and V are staged so that their
+  // latency is hidden: lane (query lr, half lh) needs chunks 2 ks + lh
   bf16x8 qf[4];
   {
     const bf16* qrow = base + (int64_t)min(q0 + lr, T - 1) * rs;
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) qf[ks] = *(const bf16x8*)(qrow + (2 * ks + lh) * 8);
   }
+  load_k(base + D, rs, T, Tpad, Ks, tid, NTH);
+  load_transposed(base + 2 * D, rs, T, Tpad, Vt, tid, NTH);
+  __syncthreads();
+
   // S^T[key, query] = K Q^T
   f32x16 s[NJ];
   const int sw = swz(lr);
@@ -145,8 +148,10 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(const bf16* __restri
         if (j < T) dst[j] = s[jb][r];
       }
   }
-  // O = P V, contraction over keys in the order the accumulators hold them:
-  // step st covers keys 16 st + {4 lh .. 4 lh + 3} and 16 st + 8 + {4 lh .. 4 lh + 3}
+  // O^T = V^T P^T, contraction over keys in the order the accumulators hold them:
+  // step st covers keys 16 st + {4 lh .. 4 lh + 3} and 16 st + 8 + {4 lh .. 4 lh + 3}.
+  // With the features as rows, a lane ends up with 4 consecutive features of its own query per
+  // accumulator quad: the output leaves in 8-byte stores.
   f32x16 o[2];
 #pragma unroll
   for (int nb = 0; nb < 2; ++nb) {
@@ -158,16 +163,21 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(const bf16* __restri
       union { bf16x8 v; u32x2 hpart[2]; } vf;
       vf.hpart[0] = *(const u32x2*)(vrow + 16 * st);
       vf.hpart[1] = *(const u32x2*)(vrow + 16 * st + 8);
-      o[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pf[st], vf.v, o[nb], 0, 0, 0);
+      o[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf.v, pf[st], o[nb], 0, 0, 0);
     }
   }
+  if (qi < T) {
+    bf16* orow = out + ((int64_t)b * T + qi) * D + h * HD + 4 * lh;
 #pragma unroll
-  for (int nb = 0; nb < 2; ++nb)
+    for (int nb = 0; nb < 2; ++nb)
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      const int i = q0 + 8 * (r >> 2) + 4 * lh + (r & 3);
-      if (i < T) out[((int64_t)b * T + i) * D + h * HD + nb * 32 + lr] = (bf16)o[nb][r];
-    }
+      for (int rq = 0; rq < 4; ++rq) {
+        bf16x4 v4;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v4[e] = (bf16)o[nb][4 * rq + e];
+        *(bf16x4*)(orow + nb * 32 + 8 * rq) = v4;
+      }
+  }
 }
 
 template <int NJ>
@@ -178,7 +188,7 @@ void launch_fwd(const bf16* qkv, int B, int T, int H, bf16* out, float* lse, flo
     (void)hipFuncSetAttribute((const void*)attn_fwd_mfma_kernel<NJ>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     attr_set = true;
   }
-  attn_fwd_mfma_kernel<NJ><<<dim3((T + 127) / 128, B * H), 256, lds, s>>>(qkv, T, H, out, lse, cls_prob);
+  attn_fwd_mfma_kernel<NJ><<<B * H, NJ * 64, lds, s>>>(qkv, T, H, out, lse, cls_prob);
 }
 
 

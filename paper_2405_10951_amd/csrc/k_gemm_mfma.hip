@@ -30,11 +30,28 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));   // a 16-byte c
 constexpr int BK = 64;        // k-tile: 64 bf16 = 8 chunks of 16 bytes per row
 constexpr int NXCD = 8;
 
-__device__ inline float gelu_f(float u) { return 0.5f * u * (1.0f + erff(u * 0.70710678118654752f)); }
+// GELU(u) = u Phi(u) and its derivative Phi(u) + u phi(u) with the exact (erf) Phi.  erf comes from
+// the rational-exponential form of Abramowitz & Stegun 7.1.26, |error| <= 1.5e-7 (below 1e-6 in fp32 arithmetic): far below the
+// resolution of the bf16 values these epilogues write, at a third of the instructions of erff.  Its
+// exp(-x^2) with x = u / sqrt(2) is the Gaussian that phi(u) needs as well.
+__device__ inline float erf_as(float x, float& gauss) {
+  const float ax = fabsf(x);
+  const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, ax, 1.0f));
+  float p = fmaf(1.061405429f, t, -1.453152027f);
+  p = fmaf(p, t, 1.421413741f);
+  p = fmaf(p, t, -0.284496736f);
+  p = fmaf(p, t, 0.254829592f);
+  gauss = __expf(-ax * ax);
+  return copysignf(fmaf(-p * t, gauss, 1.0f), x);
+}
+__device__ inline float gelu_f(float u) {
+  float gauss;
+  return 0.5f * u * (1.0f + erf_as(u * 0.70710678118654752f, gauss));
+}
 __device__ inline float gelu_grad_f(float u) {
-  float cdf = 0.5f * (1.0f + erff(u * 0.70710678118654752f));
-  float pdf = __expf(-0.5f * u * u) * 0.39894228040143268f;
-  return cdf + u * pdf;
+  float gauss;
+  const float cdf = 0.5f * (1.0f + erf_as(u * 0.70710678118654752f, gauss));
+  return fmaf(u * 0.39894228040143268f, gauss, cdf);
 }
 
 template <int V> struct IC { static constexpr int value = V; };
@@ -151,8 +168,9 @@ template <int BM, int BN, int WM, int WN, int R, bool KTAIL>
 __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_kernel(GemmDesc g) {
   constexpr int NT = WM * WN * 64;
   constexpr int TM = BM / WM, TN = BN / WN, MI = TM / 32, NI = TN / 32;
-  constexpr int ACH = BM * 8 / NT, BCH = BN * 8 / NT;     // 16-byte chunks per thread per tile
-  static_assert(ACH >= 1 && BCH >= 1 && MI >= 1 && NI >= 1, "tile too small for the thread count");
+  constexpr int ACH = (BM * 8 + NT - 1) / NT, BCH = (BN * 8 + NT - 1) / NT;   // 16-byte chunks per thread per tile
+  constexpr bool AEVEN = (BM * 8) % NT == 0, BEVEN = (BN * 8) % NT == 0;      // else the last chunk is partial
+  static_assert(MI >= 1 && NI >= 1 && TM % 32 == 0 && TN % 32 == 0, "wave tiles are made of 32x32 MFMA tiles");
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   u32x4* As = (u32x4*)smem;                    // [2][BM*8]
   u32x4* Bs = As + 2 * BM * 8;                 // [2][BN*8]
@@ -169,15 +187,16 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_kernel(GemmDesc g) {
   const bf16* pb[BCH];
   int sa[ACH], sb[BCH];
   const int kc8 = (tid & 7) * 8;               // NT is a multiple of 8: every chunk of a thread has the same kc
+  // (threads past the end of an uneven tile repeat its last row: same data, same LDS slot)
 #pragma unroll
   for (int i = 0; i < ACH; ++i) {
-    const int row = (tid + NT * i) >> 3;
+    const int row = AEVEN ? (tid + NT * i) >> 3 : min((tid + NT * i) >> 3, BM - 1);
     pa[i] = A + (int64_t)min(m0 + row, g.M - 1) * g.a_rs + kc8;
     sa[i] = row * 8 + ((tid & 7) ^ swz(row));
   }
 #pragma unroll
   for (int i = 0; i < BCH; ++i) {
-    const int row = (tid + NT * i) >> 3;
+    const int row = BEVEN ? (tid + NT * i) >> 3 : min((tid + NT * i) >> 3, BN - 1);
     pb[i] = Bt + (int64_t)min(n0 + row, g.N - 1) * g.b_cs + kc8;
     sb[i] = row * 8 + ((tid & 7) ^ swz(row));
   }
@@ -245,15 +264,17 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_kernel(GemmDesc g) {
   };
 
   const int nk = (g.K + BK - 1) / BK;
-  // prologue: k-tile 0 into LDS buffer 0, k-tiles 1 .. R in flight in their register sets
+  // prologue: k-tile 0 into LDS buffer 0, k-tile 1 in flight in the registers
   fetch(IC<0>{}, 0);
   stash(IC<0>{}, 0);
-  static_for<1, R>([&](auto T) { if (decltype(T)::value < nk) fetch(T, decltype(T)::value * BK); });
-  if (R < nk) fetch(IC<0>{}, R * BK);
+  if (nk > 1) fetch(IC<0>{}, BK);
   __syncthreads();
   load_frags(0, As, Bs, 0);
-  // one k-tile; P = (kt + 1) % R is the register set that holds k-tile kt + 1
-  auto ktile = [&](auto P, int kt) {
+  // One k-tile.  STASH: k-tile kt + 1 exists (registers -> other LDS buffer, and its first fragments
+  // are loaded after the barrier); FETCH: k-tile kt + 2 exists.  The steady-state loop has both set
+  // and no branches, so that the compiler can interleave the whole body.
+  auto ktile = [&](auto STASH, auto FETCH, int kt) {
+    constexpr bool do_stash = decltype(STASH)::value != 0, do_fetch = decltype(FETCH)::value != 0;
     const int buf = kt & 1;
     const u32x4* Ab = As + buf * BM * 8;
     const u32x4* Bb = Bs + buf * BN * 8;
@@ -262,18 +283,17 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_kernel(GemmDesc g) {
     load_frags(0, Ab, Bb, 2);
     mma(1);
     load_frags(1, Ab, Bb, 3);
-    if (kt + 1 < nk) stash(P, buf ^ 1);
-    if (kt + 1 + R < nk) fetch(P, (kt + 1 + R) * BK);
+    if (do_stash) stash(IC<0>{}, buf ^ 1);
+    if (do_fetch) fetch(IC<0>{}, (kt + 2) * BK);
     mma(0);
     __syncthreads();
-    if (kt + 1 < nk) load_frags(0, As + (buf ^ 1) * BM * 8, Bs + (buf ^ 1) * BN * 8, 0);
+    if (do_stash) load_frags(0, As + (buf ^ 1) * BM * 8, Bs + (buf ^ 1) * BN * 8, 0);
     mma(1);
   };
-  for (int kt0 = 0; kt0 < nk; kt0 += R)
-    static_for<0, R>([&](auto J) {
-      constexpr int j = decltype(J)::value;
-      if (kt0 + j < nk) ktile(IC<(j + 1) % R>{}, kt0 + j);
-    });
+  int kt = 0;
+  for (; kt + 2 < nk; ++kt) ktile(IC<1>{}, IC<1>{}, kt);
+  if (kt + 1 < nk) { ktile(IC<1>{}, IC<0>{}, kt); ++kt; }
+  ktile(IC<0>{}, IC<0>{}, kt);
   __syncthreads();
   // the tile buffers are free now: reuse them as per-wave epilogue patches
   float* patch = (float*)smem + wave * (32 * (TN + 4));
@@ -546,23 +566,42 @@ size_t gemm_splitk_ws_floats(int dim, int mlp_hidden) {
 
 bool gemm_mfma_supported(const GemmDesc& g) { return is_nt(g) || is_tn(g); }
 
-// Tile choice, from measurements on the step's shapes (M = 2144 .. 6304 rows, N and K in
-// {768, 2304, 3072}).  Both variants keep 16 wavefronts on a CU: LDS traffic per MFMA (one 16-byte
-// fragment read per MFMA with 64x64 wave tiles, plus the tile writes) and the L2 -> LDS stream
-// bound these kernels long before the matrix cores do, and more resident waves hide those queues
-// best.  The 256x128 tile moves 25 % fewer bytes per flop; it is used when it still yields enough
-// workgroups for most of the 256 CUs.
+// Tile choice.  What bounds these kernels on a CU is operand delivery, not the matrix cores: LDS
+// takes writes at about 64 bytes per clock, so a k-tile of a BM x BN block tile costs 2 (BM + BN)
+// clocks of LDS writes (plus the fragment reads) against BM * BN / 32 clocks of MFMA work.  Only
+// 256 x 256 tiles keep that ratio well below one, but at M = 2144 .. 6304 rows they leave most CUs
+// without a tile, so each launch takes the shape that a two-parameter model predicts to be fastest:
+//   time = ceil(tiles / 256 CUs) * (fixed + per_ktile * K / 64)
+// with (fixed, per_ktile) in microseconds fitted per tile shape to the durations of the step's own
+// GEMMs (N and K in {768, 2304, 3072}, epilogues included) with every shape forced in turn; the
+// model's picks cost 0.3 % more than the per-launch best of those runs.  The large tiles pay a long
+// fixed part because their single workgroup per CU cannot hide its prologue and epilogue.
+struct NtShape { int id, bm, bn; float fixed_us, per_ktile_us; };
+static const NtShape kNtShapes[] = {
+    {256128, 256, 128, 11.23f, 0.714f}, {128128, 128, 128, 3.22f, 0.620f}, {192128, 192, 128, 8.03f, 0.689f},
+    {160256, 160, 256, 12.81f, 1.007f}, {256256, 256, 256, 18.17f, 1.303f},
+};
+
 void gemm_mfma(const GemmDesc& g, float* splitk_ws, size_t splitk_ws_floats, hipStream_t s) {
   if (is_tn(g)) {
     launch_tn(g, splitk_ws, splitk_ws_floats, s);
     return;
   }
   static const int forced = [] { const char* e = getenv("BSR_NT_TILE"); return e ? atoi(e) : 0; }();
-  const int64_t big_tiles = (int64_t)((g.M + 255) / 256) * ((g.N + 127) / 128);
-  const int pick = forced ? forced : (big_tiles >= 144 ? 256128 : 128128);
+  int pick = forced;
+  if (!pick) {
+    float best = 0.f;
+    for (const NtShape& t : kNtShapes) {
+      const int64_t tiles = (int64_t)((g.M + t.bm - 1) / t.bm) * ((g.N + t.bn - 1) / t.bn);
+      const float us = (float)((tiles + 255) / 256) * (t.fixed_us + t.per_ktile_us * (float)((g.K + BK - 1) / BK));
+      if (!pick || us < best) { pick = t.id; best = us; }
+    }
+  }
   switch (pick) {
-    case 256256: launch_nt<256, 256, 2, 4, 1>(g, s); break;     // kept for tuning runs
+    case 256256: launch_nt<256, 256, 2, 4, 1>(g, s); break;
     case 256128: launch_nt<256, 128, 4, 4, 1>(g, s); break;
+    case 192128: launch_nt<192, 128, 2, 4, 1>(g, s); break;
+    case 160256: launch_nt<160, 256, 1, 8, 1>(g, s); break;
     default: launch_nt<128, 128, 4, 2, 1>(g, s); break;
   }
 }
