@@ -746,7 +746,8 @@ static int32_t run_layer(const GemmDesc& g, int32_t* used_mfma, void* stream, co
 int32_t bsr_linear_forward(const void* x, int32_t M, int32_t in, int32_t out, const void* w_t,
                            const float* bias, int32_t act, void* u_out, const void* res, void* y,
                            int32_t* used_mfma, void* stream) {
-  if (!aligned16(x) || !aligned16(w_t) || !aligned16(y) || M < 1 || in < 1 || out < 1 || (act != 0 && act != 1))
+  if (!aligned16(x) || !aligned16(w_t) || !aligned16(y) || M < 1 || in < 1 || out < 1 || (act != 0 && act != 1) ||
+      (bias && !aligned16(bias)) || (u_out && !aligned16(u_out)) || (res && !aligned16(res)))
     return fail(nullptr, BSR_ERR_INVALID_ARG, "bsr_linear_forward: bad argument");
   GemmDesc g;
   g.A = x; g.a_rs = in; g.a_cs = 1; g.B = w_t; g.b_rs = 1; g.b_cs = in;

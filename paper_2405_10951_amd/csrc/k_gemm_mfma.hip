@@ -9,10 +9,10 @@
 //       weight gradients of Eq. 4, dW = X^T dY, contraction over all tokens of the batch.
 //
 // Block tile BM x BN x 64 shared by WM x WN wavefronts, each owning a wave tile of 32x32 MFMA tiles.
-// LDS is double buffered; the next k-tiles wait in registers while the current one feeds the
-// matrix cores.  Workgroups are renumbered so that each XCD (the
-// hardware deals consecutive workgroup ids round-robin over 8 XCDs) works on a contiguous range of
-// tiles and its L2 sees whole operand panels.
+// LDS is double buffered; the next k-tile waits in registers while the current one feeds the
+// matrix cores.  Workgroups are renumbered so that each XCD (the hardware deals consecutive
+// workgroup ids round-robin over 8 XCDs) works on a contiguous range of tiles and its L2 sees whole
+// operand panels.
 #include <stdlib.h>
 
 #include <algorithm>
@@ -31,9 +31,10 @@ constexpr int BK = 64;        // k-tile: 64 bf16 = 8 chunks of 16 bytes per row
 constexpr int NXCD = 8;
 
 // GELU(u) = u Phi(u) and its derivative Phi(u) + u phi(u) with the exact (erf) Phi.  erf comes from
-// the rational-exponential form of Abramowitz & Stegun 7.1.26, |error| <= 1.5e-7 (below 1e-6 in fp32 arithmetic): far below the
-// resolution of the bf16 values these epilogues write, at a third of the instructions of erff.  Its
-// exp(-x^2) with x = u / sqrt(2) is the Gaussian that phi(u) needs as well.
+// the rational-exponential form of Abramowitz & Stegun 7.1.26, |error| <= 1.5e-7 (below 1e-6 in
+// fp32 arithmetic): far below the resolution of the bf16 values these epilogues write, at a fraction
+// of the instructions of erff.  Its exp(-x^2) with x = u / sqrt(2) is the Gaussian that phi(u) needs
+// as well.
 __device__ inline float erf_as(float x, float& gauss) {
   const float ax = fabsf(x);
   const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, ax, 1.0f));
@@ -54,14 +55,7 @@ __device__ inline float gelu_grad_f(float u) {
   return fmaf(u * 0.39894228040143268f, gauss, cdf);
 }
 
-template <int V> struct IC { static constexpr int value = V; };
-template <int B, int E, typename F>
-__device__ __forceinline__ void static_for(F&& f) {
-  if constexpr (B < E) {
-    f(IC<B>{});
-    static_for<B + 1, E>(f);
-  }
-}
+template <int V> struct IC { static constexpr int value = V; };   // compile-time flag for generic lambdas
 
 // LDS chunk swizzle: 16 consecutive rows reading the same logical 16-byte chunk hit 16 different
 // (row parity, chunk position) pairs, i.e. all 64 banks once; 8 consecutive rows hit 8 positions.
@@ -164,7 +158,7 @@ __device__ __forceinline__ void epilogue(const GemmDesc& g, f32x16 (&acc)[MI][NI
 //   barrier ; step 3: MFMAs of the last fragments while the first fragments of k-tile kt+1 load.
 // Rows beyond M (or N) are clamped to the last valid row: they only feed accumulators that are
 // never stored.  KTAIL zero-fills chunks beyond K (K % 64 != 0).
-template <int BM, int BN, int WM, int WN, int R, bool KTAIL>
+template <int BM, int BN, int WM, int WN, bool KTAIL>
 __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_kernel(GemmDesc g) {
   constexpr int NT = WM * WN * 64;
   constexpr int TM = BM / WM, TN = BN / WN, MI = TM / 32, NI = TN / 32;
@@ -200,35 +194,33 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_kernel(GemmDesc g) {
     pb[i] = Bt + (int64_t)min(n0 + row, g.N - 1) * g.b_cs + kc8;
     sb[i] = row * 8 + ((tid & 7) ^ swz(row));
   }
-  u32x4 ra[R][ACH], rb[R][BCH];          // R register sets: k-tile t waits in set t % R
-  auto fetch = [&](auto SET, int k0) {
-    constexpr int set = decltype(SET)::value;
+  u32x4 ra[ACH], rb[BCH];                // the next k-tile waits here while the current one is multiplied
+  auto fetch = [&](int k0) {
     if (KTAIL) {
       const bool oob = k0 + kc8 >= g.K;
       const int kk = oob ? 0 : k0;
 #pragma unroll
       for (int i = 0; i < ACH; ++i) {
-        ra[set][i] = *(const u32x4*)(pa[i] + kk - (oob ? kc8 : 0));
-        if (oob) ra[set][i] = u32x4{0u, 0u, 0u, 0u};
+        ra[i] = *(const u32x4*)(pa[i] + kk - (oob ? kc8 : 0));
+        if (oob) ra[i] = u32x4{0u, 0u, 0u, 0u};
       }
 #pragma unroll
       for (int i = 0; i < BCH; ++i) {
-        rb[set][i] = *(const u32x4*)(pb[i] + kk - (oob ? kc8 : 0));
-        if (oob) rb[set][i] = u32x4{0u, 0u, 0u, 0u};
+        rb[i] = *(const u32x4*)(pb[i] + kk - (oob ? kc8 : 0));
+        if (oob) rb[i] = u32x4{0u, 0u, 0u, 0u};
       }
     } else {
 #pragma unroll
-      for (int i = 0; i < ACH; ++i) ra[set][i] = *(const u32x4*)(pa[i] + k0);
+      for (int i = 0; i < ACH; ++i) ra[i] = *(const u32x4*)(pa[i] + k0);
 #pragma unroll
-      for (int i = 0; i < BCH; ++i) rb[set][i] = *(const u32x4*)(pb[i] + k0);
+      for (int i = 0; i < BCH; ++i) rb[i] = *(const u32x4*)(pb[i] + k0);
     }
   };
-  auto stash = [&](auto SET, int buf) {
-    constexpr int set = decltype(SET)::value;
+  auto stash = [&](int buf) {
 #pragma unroll
-    for (int i = 0; i < ACH; ++i) As[buf * BM * 8 + sa[i]] = ra[set][i];
+    for (int i = 0; i < ACH; ++i) As[buf * BM * 8 + sa[i]] = ra[i];
 #pragma unroll
-    for (int i = 0; i < BCH; ++i) Bs[buf * BN * 8 + sb[i]] = rb[set][i];
+    for (int i = 0; i < BCH; ++i) Bs[buf * BN * 8 + sb[i]] = rb[i];
   };
 
   f32x16 acc[MI][NI];
@@ -265,9 +257,9 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_kernel(GemmDesc g) {
 
   const int nk = (g.K + BK - 1) / BK;
   // prologue: k-tile 0 into LDS buffer 0, k-tile 1 in flight in the registers
-  fetch(IC<0>{}, 0);
-  stash(IC<0>{}, 0);
-  if (nk > 1) fetch(IC<0>{}, BK);
+  fetch(0);
+  stash(0);
+  if (nk > 1) fetch(BK);
   __syncthreads();
   load_frags(0, As, Bs, 0);
   // One k-tile.  STASH: k-tile kt + 1 exists (registers -> other LDS buffer, and its first fragments
@@ -283,8 +275,8 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_kernel(GemmDesc g) {
     load_frags(0, Ab, Bb, 2);
     mma(1);
     load_frags(1, Ab, Bb, 3);
-    if (do_stash) stash(IC<0>{}, buf ^ 1);
-    if (do_fetch) fetch(IC<0>{}, (kt + 2) * BK);
+    if (do_stash) stash(buf ^ 1);
+    if (do_fetch) fetch((kt + 2) * BK);
     mma(0);
     __syncthreads();
     if (do_stash) load_frags(0, As + (buf ^ 1) * BM * 8, Bs + (buf ^ 1) * BN * 8, 0);
@@ -300,22 +292,22 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_kernel(GemmDesc g) {
   epilogue<MI, NI>(g, acc, m0 + wm * TM, n0 + wn * TN, lane, patch);
 }
 
-template <int BM, int BN, int WM, int WN, int R>
+template <int BM, int BN, int WM, int WN>
 void launch_nt(const GemmDesc& g, hipStream_t s) {
   static bool attr_set = false;
   constexpr size_t lds_tiles = (size_t)2 * (BM + BN) * BK * sizeof(bf16);
   constexpr size_t lds_patch = (size_t)WM * WN * 32 * (BN / WN + 4) * sizeof(float);   // epilogue patches
   constexpr size_t lds = lds_tiles > lds_patch ? lds_tiles : lds_patch;
   if (!attr_set) {
-    (void)hipFuncSetAttribute((const void*)gemm_nt_kernel<BM, BN, WM, WN, R, false>,
+    (void)hipFuncSetAttribute((const void*)gemm_nt_kernel<BM, BN, WM, WN, false>,
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    (void)hipFuncSetAttribute((const void*)gemm_nt_kernel<BM, BN, WM, WN, R, true>,
+    (void)hipFuncSetAttribute((const void*)gemm_nt_kernel<BM, BN, WM, WN, true>,
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     attr_set = true;
   }
   const int tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
-  if (g.K % BK == 0) gemm_nt_kernel<BM, BN, WM, WN, R, false><<<tiles, WM * WN * 64, lds, s>>>(g);
-  else gemm_nt_kernel<BM, BN, WM, WN, R, true><<<tiles, WM * WN * 64, lds, s>>>(g);
+  if (g.K % BK == 0) gemm_nt_kernel<BM, BN, WM, WN, false><<<tiles, WM * WN * 64, lds, s>>>(g);
+  else gemm_nt_kernel<BM, BN, WM, WN, true><<<tiles, WM * WN * 64, lds, s>>>(g);
 }
 
 // ------------------------------------------------------------------------------------------ TN
@@ -598,11 +590,11 @@ void gemm_mfma(const GemmDesc& g, float* splitk_ws, size_t splitk_ws_floats, hip
     }
   }
   switch (pick) {
-    case 256256: launch_nt<256, 256, 2, 4, 1>(g, s); break;
-    case 256128: launch_nt<256, 128, 4, 4, 1>(g, s); break;
-    case 192128: launch_nt<192, 128, 2, 4, 1>(g, s); break;
-    case 160256: launch_nt<160, 256, 1, 8, 1>(g, s); break;
-    default: launch_nt<128, 128, 4, 2, 1>(g, s); break;
+    case 256256: launch_nt<256, 256, 2, 4>(g, s); break;
+    case 256128: launch_nt<256, 128, 4, 4>(g, s); break;
+    case 192128: launch_nt<192, 128, 2, 4>(g, s); break;
+    case 160256: launch_nt<160, 256, 1, 8>(g, s); break;
+    default: launch_nt<128, 128, 4, 2>(g, s); break;
   }
 }
 
