@@ -12,6 +12,8 @@ Parameter tensors (all float32, linears row-major [in, out]):
            ln2_g ln2_b [D]  w_fc1 [D, F]   b_fc1 [F]   w_fc2 [F, D]   b_fc2 [D]
   head   : lnf_g lnf_b [D]  w_head [D, C]  b_head [C]
 Columns of w_qkv are ordered [q | k | v], each split into H heads of d = D/H.
+A mixture-of-experts block (config keys n_experts, moe_top_k, moe_blocks) holds one FFN per expert
+and a router: w_router [D, E]  w_fc1 [E, D, F]  b_fc1 [E, F]  w_fc2 [E, F, D]  b_fc2 [E, D].
 """
 from __future__ import annotations
 
@@ -20,6 +22,7 @@ import numpy as np
 
 BLOCK_TENSORS = ("ln1_g", "ln1_b", "w_qkv", "b_qkv", "w_proj", "b_proj",
                  "ln2_g", "ln2_b", "w_fc1", "b_fc1", "w_fc2", "b_fc2")
+MOE_TENSORS = ("w_router",)      # present in mixture-of-experts blocks only
 STEM_TENSORS = ("w_patch", "b_patch", "cls", "pos")
 HEAD_TENSORS = ("lnf_g", "lnf_b", "w_head", "b_head")
 
@@ -52,6 +55,24 @@ CONFIGS = {
                       dim=128, heads=4, mlp_hidden=256, depth=4, num_classes=10,
                       drop_blocks=[1, 2], keep_ratio=0.7, first_trainable=2,
                       dtype="fp32", loss=LOSS_CE, batch=5),
+    # ViT-S shape with a 16-expert, top-2 mixture-of-experts FFN in every other block (Sec. 5.3 shape
+    # of the method; expert count from the paper, top-2 softmax gating as the workload states it)
+    "c5_vit_s_moe": dict(image_size=224, patch_size=16, in_chans=3, tokens_in=0,
+                         dim=384, heads=6, mlp_hidden=1536, depth=12, num_classes=100,
+                         drop_blocks=[3, 6, 9], keep_ratio=0.7, first_trainable=8,
+                         n_experts=16, moe_top_k=2, moe_blocks=[1, 3, 5, 7, 9, 11],
+                         dtype="bf16", loss=LOSS_CE, batch=32),
+    # small mixture-of-experts models
+    "tiny_moe": dict(image_size=16, patch_size=4, in_chans=3, tokens_in=0,
+                     dim=32, heads=2, mlp_hidden=48, depth=3, num_classes=5,
+                     drop_blocks=[1], keep_ratio=0.6, first_trainable=0,
+                     n_experts=4, moe_top_k=2, moe_blocks=[0, 2],
+                     dtype="fp32", loss=LOSS_CE, batch=3),
+    "mini_moe": dict(image_size=64, patch_size=8, in_chans=3, tokens_in=0,
+                     dim=128, heads=2, mlp_hidden=256, depth=4, num_classes=10,
+                     drop_blocks=[1, 2], keep_ratio=0.7, first_trainable=2,
+                     n_experts=8, moe_top_k=2, moe_blocks=[1, 3],
+                     dtype="bf16", loss=LOSS_CE, batch=6),
 }
 
 
@@ -86,14 +107,20 @@ def param_shapes(cfg: dict) -> dict:
         pdim = cfg["in_chans"] * cfg["patch_size"] ** 2
         shapes.update({"w_patch": (pdim, D), "b_patch": (D,), "cls": (D,),
                        "pos": (tokens_at_input(cfg), D)})
+    E = cfg.get("n_experts", 0)
     for i in range(cfg["depth"]):
         pre = f"blocks.{i}."
         shapes.update({pre + "ln1_g": (D,), pre + "ln1_b": (D,),
                        pre + "w_qkv": (D, 3 * D), pre + "b_qkv": (3 * D,),
                        pre + "w_proj": (D, D), pre + "b_proj": (D,),
-                       pre + "ln2_g": (D,), pre + "ln2_b": (D,),
-                       pre + "w_fc1": (D, F), pre + "b_fc1": (F,),
-                       pre + "w_fc2": (F, D), pre + "b_fc2": (D,)})
+                       pre + "ln2_g": (D,), pre + "ln2_b": (D,)})
+        if E and i in cfg.get("moe_blocks", ()):
+            shapes.update({pre + "w_router": (D, E),
+                           pre + "w_fc1": (E, D, F), pre + "b_fc1": (E, F),
+                           pre + "w_fc2": (E, F, D), pre + "b_fc2": (E, D)})
+        else:
+            shapes.update({pre + "w_fc1": (D, F), pre + "b_fc1": (F,),
+                           pre + "w_fc2": (F, D), pre + "b_fc2": (D,)})
     if C:
         shapes.update({"lnf_g": (D,), "lnf_b": (D,), "w_head": (D, C), "b_head": (C,)})
     return shapes
@@ -116,6 +143,8 @@ def make_params(cfg: dict, seed: int = 0, std: float = 0.02, peaky: float = 1.0,
             a = a + np.float32(1.0)
         if leaf == "w_qkv" and peaky != 1.0:
             a[:, : 2 * D] *= np.float32(peaky)
+        if leaf == "w_router":   # N(0, 1/D): router logits of a normalised token are ~ N(0, 1)
+            a = a * np.float32(1.0 / (std * np.sqrt(D)))
         out[name] = round_to_bf16(a) if bf16_exact else a
     return out
 

@@ -52,11 +52,12 @@ class _Config(C.Structure):
                 ("mlp_hidden", C.c_int32), ("depth", C.c_int32), ("num_classes", C.c_int32),
                 ("n_drop", C.c_int32), ("drop_blocks", C.c_int32 * MAX_BLOCKS),
                 ("keep_k", C.c_int32 * MAX_BLOCKS), ("first_trainable", C.c_int32),
-                ("loss", C.c_int32), ("ln_eps", C.c_double)]
+                ("loss", C.c_int32), ("ln_eps", C.c_double),
+                ("n_experts", C.c_int32), ("moe_top_k", C.c_int32), ("moe_block", C.c_int32 * MAX_BLOCKS)]
 
 
 class _Block(C.Structure):
-    _fields_ = [(f, C.c_void_p) for f in BLOCK_FIELDS]
+    _fields_ = [(f, C.c_void_p) for f in BLOCK_FIELDS] + [("w_router", C.c_void_p)]
 
 
 class _Params(C.Structure):
@@ -79,6 +80,7 @@ class Oracle:
         self.lib = C.CDLL(_lib_path(precision))
         assert self.lib.orc_sizeof_real() == np.dtype(self.dtype).itemsize
         self.lib.orc_step.restype = C.c_int32
+        self.lib.orc_step_moe.restype = C.c_int32
         self.lib.orc_cross_entropy.restype = C.c_double if precision == "f64" else C.c_float
 
     # ---- marshalling -------------------------------------------------------------------
@@ -99,6 +101,10 @@ class Oracle:
         for i, (b, k) in enumerate(zip(drops, keep_k)):
             c.drop_blocks[i] = b
             c.keep_k[i] = k
+        c.n_experts = int(cfg.get("n_experts", 0))
+        c.moe_top_k = int(cfg.get("moe_top_k", 0))
+        for l in cfg.get("moe_blocks", ()):
+            c.moe_block[l] = 1
         return c
 
     def _params(self, tensors: dict, keep: list) -> _Params:
@@ -118,10 +124,11 @@ class Oracle:
 
     # ---- the whole step ----------------------------------------------------------------
     def step(self, cfg: dict, params: dict, x, labels, forced_idx=None, want_grads=True,
-             want_dx=False, keep_k=None) -> dict:
-        """Run orc_step.  Returns a dict with kept_idx (list per drop of [B,k]), scores (list per
+             want_dx=False, keep_k=None, forced_experts=None) -> dict:
+        """Run orc_step_moe.  Returns a dict with kept_idx (list per drop of [B,k]), scores (list per
         drop of [B,n]), x_trainable, x_final, logits, loss, grads (dict name -> array for the
-        trainable tensors), and dx_trainable when want_dx."""
+        trainable tensors), dx_trainable when want_dx and, for mixture-of-experts blocks, experts
+        (dict block -> [B*T,K]) and router_logits (dict block -> [B*T,E])."""
         c = self._config(cfg, keep_k)
         x = self.arr(x)
         B = x.shape[0]
@@ -140,6 +147,16 @@ class Oracle:
                 T = ks[di] + 1
                 di += 1
         T_last = T
+        moe = sorted(cfg.get("moe_blocks", ()))
+        E, K = int(cfg.get("n_experts", 0)), int(cfg.get("moe_top_k", 0))
+        Tm_at_block = [T_at_block[l + 1] if l + 1 < L else T_last for l in range(L)]   # tokens in the FFN
+        m_rows = [B * Tm_at_block[l] for l in moe]
+        ex_out = np.zeros(max(1, sum(m_rows) * max(K, 1)), dtype=np.int32)
+        rl_out = np.zeros(max(1, sum(m_rows) * max(E, 1)), dtype=self.dtype)
+        fex = None
+        if forced_experts is not None:
+            fex = np.ascontiguousarray(np.concatenate(
+                [np.asarray(forced_experts[l], dtype=np.int32).reshape(-1) for l in moe]))
         ft = cfg["first_trainable"]
         T_f = T_at_block[ft] if ft < L else T_last
         keepalive = []
@@ -165,10 +182,10 @@ class Oracle:
                     grads[name] = np.zeros(a.shape, dtype=self.dtype)
             gp = self._params(grads, keepalive)
         dx_tr = np.zeros((B, T_f, D), dtype=self.dtype) if (want_dx and want_grads) else None
-        rc = self.lib.orc_step(C.byref(c), C.byref(p), _ptr(x), _ptr(labels), C.c_int32(B),
-                               _ptr(forced), _ptr(x_tr), _ptr(kept), _ptr(scores), _ptr(x_fin),
-                               _ptr(logits), _ptr(loss), C.byref(gp) if gp is not None else None,
-                               _ptr(dx_tr))
+        rc = self.lib.orc_step_moe(C.byref(c), C.byref(p), _ptr(x), _ptr(labels), C.c_int32(B),
+                                   _ptr(forced), _ptr(x_tr), _ptr(kept), _ptr(scores), _ptr(x_fin),
+                                   _ptr(logits), _ptr(loss), C.byref(gp) if gp is not None else None,
+                                   _ptr(dx_tr), _ptr(fex), _ptr(ex_out), _ptr(rl_out))
         if rc != 0:
             raise ValueError(f"orc_step rejected the configuration (code {rc})")
         out_idx, out_sc, o1, o2 = [], [], 0, 0
@@ -177,9 +194,54 @@ class Oracle:
             out_sc.append(scores[o2:o2 + B * n].reshape(B, n).copy())
             o1 += B * k
             o2 += B * n
+        experts, router_logits, o1, o2 = {}, {}, 0, 0
+        for l, m in zip(moe, m_rows):
+            experts[l] = ex_out[o1:o1 + m * K].reshape(m, K).copy()
+            router_logits[l] = rl_out[o2:o2 + m * E].reshape(m, E).copy()
+            o1 += m * K
+            o2 += m * E
         return dict(kept_idx=out_idx, scores=out_sc, x_trainable=x_tr, x_final=x_fin,
                     logits=logits if Cn else None, loss=float(loss[0]), grads=grads,
-                    dx_trainable=dx_tr, keep_k=ks, tokens_per_block=T_at_block, T_last=T_last)
+                    dx_trainable=dx_tr, keep_k=ks, tokens_per_block=T_at_block, T_last=T_last,
+                    experts=experts, router_logits=router_logits)
+
+    # ---- mixture-of-experts FFN, for pins ----------------------------------------------
+    def moe_route(self, logits, K, forced=None):
+        logits = self.arr(logits); M, E = logits.shape
+        ex = np.empty((M, K), np.int32); gates = np.empty((M, K), self.dtype)
+        f = None if forced is None else np.ascontiguousarray(forced, dtype=np.int32)
+        self.lib.orc_moe_route(_ptr(logits), C.c_int64(M), C.c_int32(E), C.c_int32(K), _ptr(f), _ptr(ex), _ptr(gates))
+        return ex, gates
+
+    def moe_ffn(self, h, w_router, w1, b1, w2, b2, K, forced=None):
+        """Returns y and the saved tensors (dict) that moe_ffn_bwd takes."""
+        h = self.arr(h); M, D = h.shape
+        w_router, w1, b1, w2, b2 = (self.arr(a) for a in (w_router, w1, b1, w2, b2))
+        E, _, F = w1.shape
+        sv = dict(logits=np.empty((M, E), self.dtype), experts=np.empty((M, K), np.int32),
+                  gates=np.empty((M, K), self.dtype), u=np.empty((M, K, F), self.dtype),
+                  g=np.empty((M, K, F), self.dtype), ye=np.empty((M, K, D), self.dtype))
+        y = np.empty((M, D), self.dtype)
+        f = None if forced is None else np.ascontiguousarray(forced, dtype=np.int32)
+        self.lib.orc_moe_ffn(_ptr(h), C.c_int64(M), C.c_int32(D), C.c_int32(F), C.c_int32(E), C.c_int32(K),
+                             _ptr(w_router), _ptr(w1), _ptr(b1), _ptr(w2), _ptr(b2), _ptr(f), _ptr(sv["logits"]),
+                             _ptr(sv["experts"]), _ptr(sv["gates"]), _ptr(sv["u"]), _ptr(sv["g"]), _ptr(sv["ye"]), _ptr(y))
+        return y, sv
+
+    def moe_ffn_bwd(self, dy, h, w_router, w1, w2, sv):
+        dy = self.arr(dy); h = self.arr(h); M, D = h.shape
+        w_router, w1, w2 = (self.arr(a) for a in (w_router, w1, w2))
+        E, _, F = w1.shape
+        K = sv["experts"].shape[1]
+        dh = np.empty((M, D), self.dtype)
+        g = dict(w_router=np.empty((D, E), self.dtype), w_fc1=np.empty((E, D, F), self.dtype),
+                 b_fc1=np.empty((E, F), self.dtype), w_fc2=np.empty((E, F, D), self.dtype),
+                 b_fc2=np.empty((E, D), self.dtype))
+        self.lib.orc_moe_ffn_bwd(_ptr(dy), _ptr(h), C.c_int64(M), C.c_int32(D), C.c_int32(F), C.c_int32(E), C.c_int32(K),
+                                 _ptr(w_router), _ptr(w1), _ptr(w2), _ptr(sv["experts"]), _ptr(sv["gates"]),
+                                 _ptr(sv["u"]), _ptr(sv["g"]), _ptr(sv["ye"]), _ptr(dh), _ptr(g["w_router"]),
+                                 _ptr(g["w_fc1"]), _ptr(g["b_fc1"]), _ptr(g["w_fc2"]), _ptr(g["b_fc2"]))
+        return dh, g
 
     # ---- single layers, for pins -------------------------------------------------------
     def layernorm(self, x, gamma, beta, eps=1e-6):

@@ -13,6 +13,9 @@
  *   Fig. 2, Eq. 8   only the chosen blocks and the head are trained; no gradient flows beyond
  *                   the earliest trainable block
  *   Sec. 5          SGD update
+ *   Sec. 5.3        mixture-of-experts FFN: a router activates a few of the expert MLPs per token
+ *                   and their outputs are added (here: top-K by router logit, weighted by the
+ *                   softmax over the K selected logits, as the workload definition states it)
  * Readings taken where the paper is silent: pre-norm blocks with biases; exact erf GELU; the
  * importance of a patch token is the mean over heads of the post-softmax CLS row; CLS is always
  * kept; ties go to the lower index; kept tokens stay in ascending original order; dropped tokens
@@ -51,10 +54,13 @@ typedef struct {
   int32_t first_trainable;                  /* blocks [first_trainable, depth) + head are trained */
   int32_t loss;
   double ln_eps;
+  int32_t n_experts, moe_top_k;             /* mixture-of-experts FFN: E experts, K active per token */
+  int32_t moe_block[ORC_MAX_BLOCKS];        /* 1: the FFN of this block is a mixture of experts     */
 } orc_config;
 
 typedef struct {
   real *ln1_g, *ln1_b, *w_qkv, *b_qkv, *w_proj, *b_proj, *ln2_g, *ln2_b, *w_fc1, *b_fc1, *w_fc2, *b_fc2;
+  real* w_router; /* [D,E]; in a mixture-of-experts block w_fc1 [E,D,F], b_fc1 [E,F], w_fc2 [E,F,D], b_fc2 [E,D] */
 } orc_block;
 
 typedef struct {
@@ -64,6 +70,8 @@ typedef struct {
 } orc_params;
 
 int32_t orc_sizeof_real(void) { return (int32_t)sizeof(real); }
+
+static real* ralloc(int64_t n) { return (real*)malloc(sizeof(real) * (size_t)(n > 0 ? n : 1)); }
 
 /* ---------------------------------------------------------------- elementary layers (forward) */
 
@@ -402,6 +410,135 @@ void orc_sgd(real* w, const real* g, real* m, int64_t n, double lr, double mu, d
   }
 }
 
+/* ---------------------------------------------------------------- mixture-of-experts FFN (Sec. 5.3) */
+
+/* Routing of one token: the K experts with the largest router logits (ties: lower expert index
+ * first), in descending order of logit, and their gate weights = softmax over those K logits.
+ * forced (may be NULL) replaces the ranking; the gates still come from the logits. */
+void orc_moe_route(const real* logits, int64_t M, int32_t E, int32_t K, const int32_t* forced,
+                   int32_t* experts, real* gates) {
+#pragma omp parallel for schedule(static)
+  for (int64_t t = 0; t < M; ++t) {
+    const real* lg = logits + t * E;
+    int32_t* ex = experts + t * K;
+    if (forced) {
+      for (int32_t s = 0; s < K; ++s) ex[s] = forced[t * K + s];
+    } else {
+      for (int32_t s = 0; s < K; ++s) {
+        int32_t best = -1;
+        for (int32_t e = 0; e < E; ++e) {
+          int32_t taken = 0;
+          for (int32_t j = 0; j < s; ++j) taken |= (ex[j] == e);
+          if (taken) continue;
+          if (best < 0 || lg[e] > lg[best]) best = e; /* strict >: a tie keeps the lower index */
+        }
+        ex[s] = best;
+      }
+    }
+    real mx = lg[ex[0]];
+    for (int32_t s = 1; s < K; ++s) if (lg[ex[s]] > mx) mx = lg[ex[s]];
+    real sum = 0;
+    for (int32_t s = 0; s < K; ++s) { gates[t * K + s] = (real)exp((double)(lg[ex[s]] - mx)); sum += gates[t * K + s]; }
+    for (int32_t s = 0; s < K; ++s) gates[t * K + s] /= sum;
+  }
+}
+
+/* y[t] = sum_s gate[t,s] * FFN_{e(t,s)}(h[t]),  FFN_e(h) = GELU(h W1_e + b1_e) W2_e + b2_e.
+ * Kept for the backward pass: logits [M,E], experts [M,K], gates [M,K], u and g [M,K,F] (input and
+ * output of GELU per active expert), ye [M,K,D] (each active expert's output). */
+void orc_moe_ffn(const real* h, int64_t M, int32_t D, int32_t F, int32_t E, int32_t K,
+                 const real* w_router, const real* w1, const real* b1, const real* w2, const real* b2,
+                 const int32_t* forced, real* logits, int32_t* experts, real* gates, real* u, real* g,
+                 real* ye, real* y) {
+  orc_linear(h, M, D, w_router, NULL, E, logits);
+  orc_moe_route(logits, M, E, K, forced, experts, gates);
+#pragma omp parallel for schedule(static)
+  for (int64_t t = 0; t < M; ++t) {
+    for (int32_t j = 0; j < D; ++j) y[t * D + j] = 0;
+    for (int32_t s = 0; s < K; ++s) {
+      const int32_t e = experts[t * K + s];
+      real* ur = u + (t * K + s) * F;
+      real* gr = g + (t * K + s) * F;
+      real* yr = ye + (t * K + s) * D;
+      orc_linear(h + t * D, 1, D, w1 + (int64_t)e * D * F, b1 + (int64_t)e * F, F, ur);
+      orc_gelu(ur, F, gr);
+      orc_linear(gr, 1, F, w2 + (int64_t)e * F * D, b2 + (int64_t)e * D, D, yr);
+      for (int32_t j = 0; j < D; ++j) y[t * D + j] += gates[t * K + s] * yr[j];
+    }
+  }
+}
+
+/* Backward of orc_moe_ffn.  The expert choice is a constant; the gates are differentiated through
+ * the softmax over the selected logits:  dgate_s = <dy, ye_s>,  dlogit_{e_s} = gate_s (dgate_s -
+ * sum_j gate_j dgate_j).  Expert weights receive Eq. 4 over the tokens routed to them (ascending
+ * token order), the router receives dW_r = h^T dlogits.  dh [M,D] is overwritten. */
+void orc_moe_ffn_bwd(const real* dy, const real* h, int64_t M, int32_t D, int32_t F, int32_t E, int32_t K,
+                     const real* w_router, const real* w1, const real* w2, const int32_t* experts,
+                     const real* gates, const real* u, const real* g, const real* ye, real* dh,
+                     real* dw_router, real* dw1, real* db1, real* dw2, real* db2) {
+  real* du = ralloc(M * K * F);     /* gradient at the GELU input of every (token, slot) */
+  real* dye = ralloc(M * K * D);    /* gradient at every active expert's output         */
+  real* dlog = ralloc(M * E);
+#pragma omp parallel for schedule(static)
+  for (int64_t t = 0; t < M; ++t) {
+    real dgate[16];
+    real mix = 0;
+    for (int32_t s = 0; s < K; ++s) {
+      real a = 0;
+      for (int32_t j = 0; j < D; ++j) a += dy[t * D + j] * ye[(t * K + s) * D + j];
+      dgate[s] = a;
+      mix += gates[t * K + s] * a;
+    }
+    for (int32_t e = 0; e < E; ++e) dlog[t * E + e] = 0;
+    for (int32_t j = 0; j < D; ++j) dh[t * D + j] = 0;
+    for (int32_t s = 0; s < K; ++s) {
+      const int32_t e = experts[t * K + s];
+      dlog[t * E + e] = gates[t * K + s] * (dgate[s] - mix);
+      real* dyr = dye + (t * K + s) * D;
+      for (int32_t j = 0; j < D; ++j) dyr[j] = gates[t * K + s] * dy[t * D + j];
+      real* dg = ralloc(F);
+      orc_linear_dgrad(dyr, 1, D, w2 + (int64_t)e * F * D, F, dg);                 /* Eq. 2 */
+      orc_gelu_bwd(dg, u + (t * K + s) * F, F, du + (t * K + s) * F);
+      free(dg);
+      real* dhe = ralloc(D);
+      orc_linear_dgrad(du + (t * K + s) * F, 1, F, w1 + (int64_t)e * D * F, D, dhe);
+      for (int32_t j = 0; j < D; ++j) dh[t * D + j] += dhe[j];
+      free(dhe);
+    }
+    /* router path: dh += dlogits W_r^T */
+    for (int32_t j = 0; j < D; ++j) {
+      real a = 0;
+      for (int32_t e = 0; e < E; ++e) a += dlog[t * E + e] * w_router[(int64_t)j * E + e];
+      dh[t * D + j] += a;
+    }
+  }
+  if (dw_router) orc_linear_wgrad(h, dlog, M, D, E, dw_router, NULL);
+  /* expert weights: one expert per thread, its tokens in ascending order */
+#pragma omp parallel for schedule(dynamic, 1)
+  for (int32_t e = 0; e < E; ++e) {
+    real* a1 = dw1 ? dw1 + (int64_t)e * D * F : NULL;
+    real* c1 = db1 ? db1 + (int64_t)e * F : NULL;
+    real* a2 = dw2 ? dw2 + (int64_t)e * F * D : NULL;
+    real* c2 = db2 ? db2 + (int64_t)e * D : NULL;
+    if (a1) for (int64_t i = 0; i < (int64_t)D * F; ++i) a1[i] = 0;
+    if (c1) for (int32_t i = 0; i < F; ++i) c1[i] = 0;
+    if (a2) for (int64_t i = 0; i < (int64_t)F * D; ++i) a2[i] = 0;
+    if (c2) for (int32_t i = 0; i < D; ++i) c2[i] = 0;
+    for (int64_t t = 0; t < M; ++t)
+      for (int32_t s = 0; s < K; ++s) {
+        if (experts[t * K + s] != e) continue;
+        const real* dur = du + (t * K + s) * F;
+        const real* dyr = dye + (t * K + s) * D;
+        const real* gr = g + (t * K + s) * F;
+        if (a1) for (int32_t i = 0; i < D; ++i) for (int32_t f = 0; f < F; ++f) a1[(int64_t)i * F + f] += h[t * D + i] * dur[f];
+        if (c1) for (int32_t f = 0; f < F; ++f) c1[f] += dur[f];
+        if (a2) for (int32_t f = 0; f < F; ++f) for (int32_t j = 0; j < D; ++j) a2[(int64_t)f * D + j] += gr[f] * dyr[j];
+        if (c2) for (int32_t j = 0; j < D; ++j) c2[j] += dyr[j];
+      }
+  }
+  free(du); free(dye); free(dlog);
+}
+
 /* ---------------------------------------------------------------- the whole step */
 
 typedef struct {         /* what a trainable block keeps for its backward pass (Sec. 3.2) */
@@ -410,13 +547,15 @@ typedef struct {         /* what a trainable block keeps for its backward pass (
   real *xhat1, *rstd1, *h1, *qkv, *P, *o;
   real *xhat2, *rstd2, *h2, *u, *g;
   int32_t* idx;
+  /* mixture-of-experts FFN: u and g are [M,K,F]; router logits, chosen experts, gates, expert outputs */
+  real *rlogits, *gates, *ye;
+  int32_t* experts;
 } saved_block;
-
-static real* ralloc(int64_t n) { return (real*)malloc(sizeof(real) * (size_t)(n > 0 ? n : 1)); }
 
 static void free_saved(saved_block* s) {
   free(s->xhat1); free(s->rstd1); free(s->h1); free(s->qkv); free(s->P); free(s->o);
   free(s->xhat2); free(s->rstd2); free(s->h2); free(s->u); free(s->g); free(s->idx);
+  free(s->rlogits); free(s->gates); free(s->ye); free(s->experts);
   memset(s, 0, sizeof(*s));
 }
 
@@ -437,15 +576,24 @@ static void free_saved(saved_block* s) {
  *              trainable tensors (overwritten)
  * dx_trainable out, may be NULL: dL/d(x_trainable), computed only on request (tests); the method
  *              itself never propagates this far (Fig. 2)
+ * forced_experts  NULL, or the expert choice to use in the mixture-of-experts blocks (concatenated
+ *              over those blocks in ascending order, block l holding [B*T_l, K])
+ * experts_out  out, may be NULL: the expert choice, laid out as forced_experts
+ * router_out   out, may be NULL: router logits, block l holding [B*T_l, E]
  * Returns 0, or a negative number for an inconsistent configuration.
  */
-int32_t orc_step(const orc_config* c, const orc_params* p, const real* input, const int32_t* labels,
-                 int32_t B, const int32_t* forced_idx, real* x_trainable, int32_t* kept_idx,
-                 real* cls_scores, real* x_final, real* logits, real* loss, const orc_params* grads,
-                 real* dx_trainable) {
+int32_t orc_step_moe(const orc_config* c, const orc_params* p, const real* input, const int32_t* labels,
+                     int32_t B, const int32_t* forced_idx, real* x_trainable, int32_t* kept_idx,
+                     real* cls_scores, real* x_final, real* logits, real* loss, const orc_params* grads,
+                     real* dx_trainable, const int32_t* forced_experts, int32_t* experts_out,
+                     real* router_out) {
   const int32_t D = c->dim, H = c->heads, F = c->mlp_hidden, L = c->depth, C = c->num_classes;
   if (D <= 0 || H <= 0 || D % H || L <= 0 || L > ORC_MAX_BLOCKS || B <= 0) return -1;
   if (c->first_trainable < 0 || c->first_trainable > L) return -1;
+  const int32_t E = c->n_experts, K = c->moe_top_k;
+  for (int32_t l = 0; l < L; ++l)
+    if (c->moe_block[l] && (E < 1 || K < 1 || K > E || K > 16)) return -3;
+  int64_t ex_off = 0, rl_off = 0;
   const int32_t d = D / H;
   int32_t T = c->image_size ? (c->image_size / c->patch_size) * (c->image_size / c->patch_size) + 1
                             : c->tokens_in;
@@ -526,12 +674,25 @@ int32_t orc_step(const orc_config* c, const orc_params* p, const real* input, co
     const int64_t M2 = (int64_t)B * T;
     s.xhat2 = ralloc(M2 * D); s.rstd2 = ralloc(M2); s.h2 = ralloc(M2 * D);
     orc_layernorm(x, M2, D, w->ln2_g, w->ln2_b, c->ln_eps, s.h2, s.xhat2, s.rstd2);
-    s.u = ralloc(M2 * F);
-    orc_linear(s.h2, M2, D, w->w_fc1, w->b_fc1, F, s.u);
-    s.g = ralloc(M2 * F);
-    orc_gelu(s.u, M2 * F, s.g);
     y = ralloc(M2 * D);
-    orc_linear(s.g, M2, F, w->w_fc2, w->b_fc2, D, y);
+    if (c->moe_block[l]) {   /* mixture of experts in place of the FFN (Sec. 5.3) */
+      s.u = ralloc(M2 * K * F); s.g = ralloc(M2 * K * F); s.ye = ralloc(M2 * K * D);
+      s.rlogits = ralloc(M2 * E); s.gates = ralloc(M2 * K);
+      s.experts = (int32_t*)malloc(sizeof(int32_t) * (size_t)(M2 * K));
+      orc_moe_ffn(s.h2, M2, D, F, E, K, w->w_router, w->w_fc1, w->b_fc1, w->w_fc2, w->b_fc2,
+                  forced_experts ? forced_experts + ex_off : NULL, s.rlogits, s.experts, s.gates, s.u, s.g,
+                  s.ye, y);
+      if (experts_out) memcpy(experts_out + ex_off, s.experts, sizeof(int32_t) * (size_t)(M2 * K));
+      if (router_out) memcpy(router_out + rl_off, s.rlogits, sizeof(real) * (size_t)(M2 * E));
+      ex_off += M2 * K;
+      rl_off += M2 * E;
+    } else {
+      s.u = ralloc(M2 * F);
+      orc_linear(s.h2, M2, D, w->w_fc1, w->b_fc1, F, s.u);
+      s.g = ralloc(M2 * F);
+      orc_gelu(s.u, M2 * F, s.g);
+      orc_linear(s.g, M2, F, w->w_fc2, w->b_fc2, D, y);
+    }
     for (int64_t i = 0; i < M2 * D; ++i) x[i] += y[i];
     free(y);
 
@@ -585,16 +746,21 @@ int32_t orc_step(const orc_config* c, const orc_params* p, const real* input, co
       const int64_t M2 = (int64_t)B * s->Tm, M = (int64_t)B * s->Ta;
 
       /* FFN branch: x_out = x_mid + fc2(GELU(fc1(LN2(x_mid)))) */
-      real* dg = ralloc(M2 * F);
-      orc_linear_dgrad(dx, M2, D, w->w_fc2, F, dg);
-      orc_linear_wgrad(s->g, dx, M2, F, D, g->w_fc2, g->b_fc2);
-      real* du = ralloc(M2 * F);
-      orc_gelu_bwd(dg, s->u, M2 * F, du);
-      free(dg);
       real* dh2 = ralloc(M2 * D);
-      orc_linear_dgrad(du, M2, F, w->w_fc1, D, dh2);
-      orc_linear_wgrad(s->h2, du, M2, D, F, g->w_fc1, g->b_fc1);
-      free(du);
+      if (c->moe_block[l]) {
+        orc_moe_ffn_bwd(dx, s->h2, M2, D, F, E, K, w->w_router, w->w_fc1, w->w_fc2, s->experts, s->gates,
+                        s->u, s->g, s->ye, dh2, g->w_router, g->w_fc1, g->b_fc1, g->w_fc2, g->b_fc2);
+      } else {
+        real* dg = ralloc(M2 * F);
+        orc_linear_dgrad(dx, M2, D, w->w_fc2, F, dg);
+        orc_linear_wgrad(s->g, dx, M2, F, D, g->w_fc2, g->b_fc2);
+        real* du = ralloc(M2 * F);
+        orc_gelu_bwd(dg, s->u, M2 * F, du);
+        free(dg);
+        orc_linear_dgrad(du, M2, F, w->w_fc1, D, dh2);
+        orc_linear_wgrad(s->h2, du, M2, D, F, g->w_fc1, g->b_fc1);
+        free(du);
+      }
       real* dxm = ralloc(M2 * D);
       orc_layernorm_bwd(dh2, s->xhat2, s->rstd2, w->ln2_g, M2, D, dxm, g->ln2_g, g->ln2_b);
       free(dh2);
@@ -637,4 +803,13 @@ int32_t orc_step(const orc_config* c, const orc_params* p, const real* input, co
   }
   free(dx);
   return 0;
+}
+
+/* The step without any mixture-of-experts arguments. */
+int32_t orc_step(const orc_config* c, const orc_params* p, const real* input, const int32_t* labels,
+                 int32_t B, const int32_t* forced_idx, real* x_trainable, int32_t* kept_idx,
+                 real* cls_scores, real* x_final, real* logits, real* loss, const orc_params* grads,
+                 real* dx_trainable) {
+  return orc_step_moe(c, p, input, labels, B, forced_idx, x_trainable, kept_idx, cls_scores, x_final, logits,
+                      loss, grads, dx_trainable, NULL, NULL, NULL);
 }

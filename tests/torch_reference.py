@@ -7,9 +7,31 @@ import torch
 import torch.nn.functional as F
 
 
-def run(cfg, params, x, labels, kept_idx, dtype=torch.float64, eps=1e-6):
-    """kept_idx: list per drop of [B,k] integer arrays (constants).  Returns dict with loss, logits,
-    x_final, grads (for trainable tensors), scores (per drop), x_trainable, dx_trainable."""
+def moe_ffn(h2, w_router, w1, b1, w2, b2, K, experts=None):
+    """Mixture-of-experts FFN on tokens h2 [M,D] from library primitives: torch.topk on the router
+    logits (or the given expert choice), softmax over the selected logits, one dense FFN per expert
+    on the tokens routed to it (index_select / index_add).  Returns (y [M,D], experts [M,K])."""
+    logits = h2 @ w_router
+    if experts is None:
+        experts = torch.topk(logits, K, dim=-1).indices
+    else:
+        experts = torch.as_tensor(experts, dtype=torch.long)
+    gates = torch.softmax(torch.gather(logits, 1, experts), dim=-1)
+    y = torch.zeros_like(h2)
+    for e in range(w1.shape[0]):
+        tok, slot = torch.nonzero(experts == e, as_tuple=True)
+        if tok.numel() == 0:
+            continue
+        he = h2.index_select(0, tok)
+        ye = F.linear(F.gelu(F.linear(he, w1[e].t(), b1[e])), w2[e].t(), b2[e])
+        y = y.index_add(0, tok, ye * gates[tok, slot][:, None])
+    return y, experts
+
+
+def run(cfg, params, x, labels, kept_idx, dtype=torch.float64, eps=1e-6, experts=None):
+    """kept_idx: list per drop of [B,k] integer arrays (constants); experts: dict block -> [M,K] expert
+    choice for mixture-of-experts blocks (constants; None: torch.topk).  Returns dict with loss,
+    logits, x_final, grads (for trainable tensors), scores (per drop), x_trainable, dx_trainable."""
     P = {k: torch.tensor(v, dtype=dtype) for k, v in params.items()}
     ft, L, D, H = cfg["first_trainable"], cfg["depth"], cfg["dim"], cfg["heads"]
     d = D // H
@@ -45,8 +67,13 @@ def run(cfg, params, x, labels, kept_idx, dtype=torch.float64, eps=1e-6):
             x = torch.gather(x, 1, full[:, :, None].expand(B, full.shape[1], D))
             di += 1
         h2 = F.layer_norm(x, (D,), g("ln2_g"), g("ln2_b"), eps)
-        u = F.linear(h2, g("w_fc1").t(), g("b_fc1"))
-        x = x + F.linear(F.gelu(u), g("w_fc2").t(), g("b_fc2"))
+        if l in cfg.get("moe_blocks", ()):
+            y, _ = moe_ffn(h2.reshape(-1, D), g("w_router"), g("w_fc1"), g("b_fc1"), g("w_fc2"), g("b_fc2"),
+                           cfg["moe_top_k"], None if experts is None else experts[l])
+            x = x + y.reshape(x.shape)
+        else:
+            u = F.linear(h2, g("w_fc1").t(), g("b_fc1"))
+            x = x + F.linear(F.gelu(u), g("w_fc2").t(), g("b_fc2"))
     if ft == L:
         x = x.detach().requires_grad_(True)
         x_tr = x
