@@ -70,15 +70,24 @@ typedef struct {
   int32_t dtype;                            /* BSR_BF16 or BSR_FP32                                */
   int32_t loss;                             /* BSR_LOSS_CE or BSR_LOSS_MEAN_SQ                     */
   float ln_eps;                             /* LayerNorm epsilon; 0 means 1e-6                     */
+  /* Mixture-of-experts FFN (Sec. 5.3: the FFN of chosen blocks is replaced by expert MLPs of which
+   * a router activates a few per token and adds their outputs).  bf16 only. */
+  int32_t n_experts;                        /* E, 0: every FFN is dense; at most 32                */
+  int32_t moe_top_k;                        /* K experts active per token, 1..4                    */
+  int32_t n_moe;                            /* number of mixture-of-experts blocks                 */
+  int32_t moe_blocks[BSR_MAX_BLOCKS];       /* their block indices, strictly ascending             */
 } bsr_config;
 
 /* Tables of device pointers, one per tensor (fp32).  The same struct describes parameters,
  * gradients and momenta.  Shapes: ln*_g, ln*_b, b_proj, b_fc2 [D]; w_qkv [D,3D] with columns
  * [q|k|v], each split into H heads of D/H; b_qkv [3D]; w_proj [D,D]; w_fc1 [D,F]; b_fc1 [F];
  * w_fc2 [F,D]; w_patch [C*P*P, D] with rows in (channel, row, column) order of a patch;
- * b_patch, cls [D]; pos [T,D]; lnf_g, lnf_b [D]; w_head [D,classes]; b_head [classes]. */
+ * b_patch, cls [D]; pos [T,D]; lnf_g, lnf_b [D]; w_head [D,classes]; b_head [classes].
+ * A mixture-of-experts block holds one FFN per expert and a router: w_router [D,E] (no bias),
+ * w_fc1 [E,D,F], b_fc1 [E,F], w_fc2 [E,F,D], b_fc2 [E,D]; w_router is NULL in dense blocks. */
 typedef struct {
   void *ln1_g, *ln1_b, *w_qkv, *b_qkv, *w_proj, *b_proj, *ln2_g, *ln2_b, *w_fc1, *b_fc1, *w_fc2, *b_fc2;
+  void *w_router;
 } bsr_block_params;
 
 typedef struct {
@@ -170,6 +179,23 @@ int32_t bsr_train_blocks_fwd_bwd(bsr_ctx* ctx, const void* x_in, const int32_t* 
                                  float* loss_out, float* logits_out, void* x_final_out,
                                  const bsr_params* grads, int32_t* kept_idx_out, float* scores_out,
                                  const int32_t* forced_idx, void* stream);
+
+/*
+ * Routing of the mixture-of-experts blocks (Sec. 5.3), for tests and inspection.  Per token the K
+ * experts with the largest router logits (logits = LN2(x) . w_router; ties: lower expert index) are
+ * active, ordered by descending logit, and weighted by the softmax over those K logits; the choice
+ * is a constant for the backward pass.  The three device pointers (each may be NULL) are remembered
+ * by the context and used by every later bsr_forward_frozen / bsr_train_blocks_fwd_bwd call until
+ * they are replaced; all are laid out block after block over the mixture-of-experts blocks in
+ * ascending order, block l holding B * tokens_mlp[l] rows:
+ *   forced_experts     int32 [rows, K]   use this choice instead of the ranking (gates still come
+ *                                        from the logits); values must lie in 0..E-1, distinct per row
+ *   experts_out        int32 [rows, K]   receives the choice
+ *   router_logits_out  fp32  [rows, E]   receives the router logits
+ * Errors: INVALID_ARG (ctx NULL, misaligned pointer).
+ */
+int32_t bsr_moe_routing_io(bsr_ctx* ctx, const int32_t* forced_experts, int32_t* experts_out,
+                           float* router_logits_out);
 
 /*
  * SGD update of the trainable tensors (Sec. 5, "SGD optimizer"), in place on the master weights

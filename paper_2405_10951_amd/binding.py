@@ -30,11 +30,13 @@ class bsr_config(C.Structure):
                 ("max_batch", C.c_int32), ("n_drop", C.c_int32),
                 ("drop_blocks", C.c_int32 * MAX_BLOCKS), ("keep_k", C.c_int32 * MAX_BLOCKS),
                 ("keep_ratio", C.c_float), ("first_trainable_block", C.c_int32),
-                ("dtype", C.c_int32), ("loss", C.c_int32), ("ln_eps", C.c_float)]
+                ("dtype", C.c_int32), ("loss", C.c_int32), ("ln_eps", C.c_float),
+                ("n_experts", C.c_int32), ("moe_top_k", C.c_int32), ("n_moe", C.c_int32),
+                ("moe_blocks", C.c_int32 * MAX_BLOCKS)]
 
 
 class bsr_block_params(C.Structure):
-    _fields_ = [(f, C.c_void_p) for f in BLOCK_FIELDS]
+    _fields_ = [(f, C.c_void_p) for f in BLOCK_FIELDS] + [("w_router", C.c_void_p)]
 
 
 class bsr_params(C.Structure):
@@ -63,7 +65,7 @@ def load_library():
     lib.bsr_last_error.argtypes = [C.c_void_p]
     for name in ("bsr_token_schedule", "bsr_workspace_bytes", "bsr_init", "bsr_refresh_weights",
                  "bsr_forward_frozen", "bsr_select_tokens", "bsr_train_blocks_fwd_bwd",
-                 "bsr_sgd_step", "bsr_destroy", "bsr_profile_begin", "bsr_profile_end"):
+                 "bsr_sgd_step", "bsr_destroy", "bsr_profile_begin", "bsr_profile_end", "bsr_moe_routing_io"):
         getattr(lib, name).restype = C.c_int32
     lib.bsr_token_schedule.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
     lib.bsr_workspace_bytes.argtypes = [C.c_void_p, C.POINTER(C.c_size_t)]
@@ -78,6 +80,7 @@ def load_library():
                                              C.c_void_p, C.c_void_p]
     lib.bsr_sgd_step.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_float, C.c_float, C.c_float, C.c_void_p]
     lib.bsr_destroy.argtypes = [C.c_void_p]
+    lib.bsr_moe_routing_io.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
     lib.bsr_linear_forward.restype = C.c_int32
     lib.bsr_linear_forward.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
                                        C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
@@ -121,6 +124,12 @@ def make_config(cfg: dict, max_batch: int, keep_k=None) -> bsr_config:
     if keep_k:
         for i, k in enumerate(keep_k):
             c.keep_k[i] = int(k)
+    moe = list(cfg.get("moe_blocks", []))
+    c.n_moe = len(moe)
+    for i, b in enumerate(moe):
+        c.moe_blocks[i] = int(b)
+    c.n_experts = int(cfg.get("n_experts", 0))
+    c.moe_top_k = int(cfg.get("moe_top_k", 0))
     return c
 
 
@@ -279,7 +288,18 @@ class Context:
     def new_grads(self) -> dict:
         return {n: self.torch.zeros_like(self.params[n]) for n in self.trainable_names}
 
+    def moe_rows(self, B: int) -> dict:
+        """block -> number of token rows (B * tokens of its FFN) for every mixture-of-experts block"""
+        return {self.c.moe_blocks[i]: B * self.tokens_mlp[self.c.moe_blocks[i]] for i in range(self.c.n_moe)}
+
     # ---- entry points ---------------------------------------------------------------------
+    def bsr_moe_routing_io(self, forced_experts=None, experts_out=None, router_logits_out=None):
+        """Device tensors laid out block after block over the mixture-of-experts blocks (see bsr.h);
+        the context only keeps the pointers, so the tensors are kept alive here."""
+        self._moe_io = (forced_experts, experts_out, router_logits_out)
+        self._chk(self.lib.bsr_moe_routing_io(self.ctx, _dp(forced_experts), _dp(experts_out),
+                                              _dp(router_logits_out)))
+
     def bsr_refresh_weights(self):
         self._chk(self.lib.bsr_refresh_weights(self.ctx, self._stream()))
 

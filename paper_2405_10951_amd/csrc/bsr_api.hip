@@ -26,16 +26,25 @@ struct Schedule {
   int Tm[BSR_MAX_BLOCKS] = {};      // tokens seen by FFN of block l
   int drop_of[BSR_MAX_BLOCKS];      // drop index of block l, or -1
   int T_last = 0;
+  bool moe[BSR_MAX_BLOCKS] = {};    // block l has a mixture-of-experts FFN
+  int moe_row0[BSR_MAX_BLOCKS] = {};// per image: tokens of the mixture blocks before l (routing I/O layout)
+};
+
+struct MoeBuf {      // routing and the expert-ordered tensors of one mixture-of-experts FFN
+  float *logits, *gates, *dsel;
+  int32_t *experts, *pos, *perm_tok, *off;
+  char *xg, *y;      // gathered tokens [M*K, D], expert outputs [M*K, D] (u and g live in the block's u / g)
 };
 
 struct SavedBlock {  // what a trainable block keeps for its backward pass (Sec. 3.2 of the paper)
   float *mean1, *rstd1, *mean2, *rstd2, *lse;
   char *h1, *qkv, *o, *xmid_full, *xmid, *h2, *u, *g, *xout;
   int32_t* idx;
+  MoeBuf moe;        // used when the block's FFN is a mixture of experts (u, g then have K rows per token)
 };
 
 struct Shadow {  // bf16 copies of a block's matrices: transposed [out,in] and, if trained, straight [in,out]
-  bf16 *t_qkv, *t_proj, *t_fc1, *t_fc2;
+  bf16 *t_qkv, *t_proj, *t_fc1, *t_fc2;     // (a mixture-of-experts block: E matrices each, expert-major)
   bf16 *s_qkv, *s_proj, *s_fc1, *s_fc2;
 };
 
@@ -46,6 +55,9 @@ struct Buffers {
   float *clsp = nullptr, *scores = nullptr;
   int32_t* idx_tmp = nullptr;
   SavedBlock sv[BSR_MAX_BLOCKS] = {};
+  MoeBuf moe = {};                      // frozen mixture blocks share this one
+  char *moe_u = nullptr;                // their GELU outputs [M*K, F]
+  char *moe_dy = nullptr, *moe_dxg = nullptr, *moe_dlog = nullptr;   // backward scratch
   char *dxa = nullptr, *dxb = nullptr, *dgu = nullptr, *dh = nullptr, *dqkv = nullptr;
   float *delta = nullptr, *partial = nullptr, *splitk = nullptr;
   size_t splitk_floats = 0;
@@ -74,6 +86,9 @@ struct bsr_ctx {
   float eps;
   char* ws;
   size_t ws_bytes;
+  const int32_t* forced_experts = nullptr;   // bsr_moe_routing_io
+  int32_t* experts_out = nullptr;
+  float* router_logits_out = nullptr;
   char err[512];
 };
 
@@ -148,6 +163,24 @@ int make_schedule(const bsr_config* c, Schedule* s, char* why, size_t whyn) {
     s->Tm[l] = T;
   }
   s->T_last = T;
+  if (c->n_moe < 0 || c->n_moe > BSR_MAX_BLOCKS) BAD("n_moe %d out of range", c->n_moe);
+  if (c->n_moe > 0) {
+    if (c->dtype != BSR_BF16) BAD("mixture-of-experts blocks need dtype bf16");
+    if (c->n_experts < 1 || c->n_experts > MOE_MAX_EXPERTS) BAD("n_experts %d must lie in 1..%d", c->n_experts, MOE_MAX_EXPERTS);
+    if (c->moe_top_k < 1 || c->moe_top_k > MOE_MAX_TOPK || c->moe_top_k > c->n_experts)
+      BAD("moe_top_k %d must lie in 1..min(%d, n_experts)", c->moe_top_k, MOE_MAX_TOPK);
+    for (int i = 0; i < c->n_moe; ++i) {
+      const int blk = c->moe_blocks[i];
+      if (blk < 0 || blk >= c->depth) BAD("moe_blocks[%d] = %d out of range", i, blk);
+      if (i && blk <= c->moe_blocks[i - 1]) BAD("moe_blocks must be strictly ascending");
+      s->moe[blk] = true;
+    }
+    int rows = 0;
+    for (int l = 0; l < c->depth; ++l) {
+      s->moe_row0[l] = rows;
+      if (s->moe[l]) rows += s->Tm[l];
+    }
+  }
   return BSR_OK;
 #undef BAD
 }
@@ -176,15 +209,16 @@ size_t carve(const bsr_config& c, const Schedule& s, char* base, Buffers* out) {
   if (!f32) {
     if (c.image_size) b.t_patch = w.take<bf16>(D * Kp);
     for (int l = 0; l < L; ++l) {
+      const size_t ne = s.moe[l] ? (size_t)c.n_experts : 1;    // FFN matrices per block
       b.sh[l].t_qkv = w.take<bf16>(3 * D * D);
       b.sh[l].t_proj = w.take<bf16>(D * D);
-      b.sh[l].t_fc1 = w.take<bf16>(D * F);
-      b.sh[l].t_fc2 = w.take<bf16>(D * F);
+      b.sh[l].t_fc1 = w.take<bf16>(ne * D * F);
+      b.sh[l].t_fc2 = w.take<bf16>(ne * D * F);
       if (l >= ft) {
         b.sh[l].s_qkv = w.take<bf16>(3 * D * D);
         b.sh[l].s_proj = w.take<bf16>(D * D);
-        b.sh[l].s_fc1 = w.take<bf16>(D * F);
-        b.sh[l].s_fc2 = w.take<bf16>(D * F);
+        b.sh[l].s_fc1 = w.take<bf16>(ne * D * F);
+        b.sh[l].s_fc2 = w.take<bf16>(ne * D * F);
       }
     }
   }
@@ -198,6 +232,24 @@ size_t carve(const bsr_config& c, const Schedule& s, char* base, Buffers* out) {
   b.clsp = w.take<float>(B * H * T0);
   b.scores = w.take<float>(B * T0);
   b.idx_tmp = w.take<int32_t>(B * T0);
+  const size_t KE = c.n_moe > 0 ? (size_t)c.moe_top_k : 1, NE = c.n_moe > 0 ? (size_t)c.n_experts : 0;
+  auto take_moe = [&](MoeBuf& m, size_t rows) {      // rows = tokens of the FFN
+    m.logits = w.take<float>(rows * NE);
+    m.gates = w.take<float>(rows * KE);
+    m.dsel = w.take<float>(rows * KE);
+    m.experts = w.take<int32_t>(rows * KE);
+    m.pos = w.take<int32_t>(rows * KE);
+    m.perm_tok = w.take<int32_t>(rows * KE);
+    m.off = w.take<int32_t>(NE + 1);
+    m.xg = w.take<char>(rows * KE * D * E);
+    m.y = w.take<char>(rows * KE * D * E);
+  };
+  bool frozen_moe = false;
+  for (int l = 0; l < ft && l < L; ++l) frozen_moe |= s.moe[l];
+  if (frozen_moe) {
+    take_moe(b.moe, B * T0);
+    b.moe_u = w.take<char>(B * T0 * KE * F * E);
+  }
   size_t Tmax = s.T_last;
   for (int l = ft; l < L; ++l) {
     const size_t Ta = s.Ta[l], Tm = s.Tm[l];
@@ -214,14 +266,23 @@ size_t carve(const bsr_config& c, const Schedule& s, char* base, Buffers* out) {
     v.xmid_full = w.take<char>(B * Ta * D * E);
     v.xmid = (s.drop_of[l] >= 0) ? w.take<char>(B * Tm * D * E) : v.xmid_full;
     v.h2 = w.take<char>(B * Tm * D * E);
-    v.u = w.take<char>(B * Tm * F * E);
-    v.g = w.take<char>(B * Tm * F * E);
+    const size_t kf = s.moe[l] ? KE : 1;               // a mixture block keeps u and g per (token, slot)
+    v.u = w.take<char>(B * Tm * kf * F * E);
+    v.g = w.take<char>(B * Tm * kf * F * E);
+    if (s.moe[l]) take_moe(v.moe, B * Tm);
     v.xout = w.take<char>(B * Tm * D * E);
     v.idx = w.take<int32_t>(B * Tm);
   }
   b.dxa = w.take<char>(B * Tmax * D * E);
   b.dxb = w.take<char>(B * Tmax * D * E);
-  b.dgu = w.take<char>(B * Tmax * F * E);
+  bool train_moe = false;
+  for (int l = ft; l < L; ++l) train_moe |= s.moe[l];
+  b.dgu = w.take<char>(B * Tmax * (train_moe ? KE : 1) * F * E);
+  if (train_moe) {
+    b.moe_dy = w.take<char>(B * Tmax * KE * D * E);
+    b.moe_dxg = w.take<char>(B * Tmax * KE * D * E);
+    b.moe_dlog = w.take<char>(B * Tmax * ((NE + 7) / 8 * 8) * 2);
+  }
   b.dh = w.take<char>(B * Tmax * D * E);
   b.dqkv = w.take<char>(B * Tmax * 3 * D * E);
   b.delta = w.take<float>(B * H * Tmax);
@@ -302,6 +363,7 @@ struct ProfScope {
 void gemm(bsr_ctx* c, const GemmDesc& g, hipStream_t s) {
   ProfScope ps(c, BSR_PROF_GEMM, 2.0 * g.M * g.N * g.K, s);
   if (gemm_mfma_supported(g)) gemm_mfma(g, c->b.splitk, c->b.splitk_floats, s);
+  else if (g.grp_off) fail(c, BSR_ERR_BAD_CONFIG, "grouped GEMM %d x %d x %d is not an MFMA shape", g.M, g.N, g.K);
   else gemm_generic(g, s);
 }
 
@@ -316,6 +378,69 @@ void wgrad(bsr_ctx* c, const void* x, const void* dy, int M, int in, int out, vo
     gemm(c, g, s);
     colsum(dy, M, out, out, c->f32, c->b.partial, (float*)db, s);
   }
+}
+
+// Mixture-of-experts FFN of block l on M2 tokens (Sec. 5.3):  x_out = x_res + sum_s gate_s FFN_{e_s}(h),
+// h = LN2(x_res).  Routing, stable sort of the (token, slot) pairs by expert, gather, two grouped
+// GEMMs over the expert ranges (fc1 + GELU, fc2), weighted un-permute.  u (pre-GELU, may be null)
+// and g are [M2*K, F] in expert order.
+void moe_ffn_forward(bsr_ctx* c, int l, int B, const void* h, const void* x_res, int M2, MoeBuf& m, void* u,
+                     void* gbuf, void* x_out, hipStream_t s) {
+  const bsr_config& cf = c->cfg;
+  const int D = cf.dim, F = cf.mlp_hidden, E = cf.n_experts, K = cf.moe_top_k;
+  const bsr_block_params& w = c->p.blocks[l];
+  const Shadow& sh = c->b.sh[l];
+  const size_t row0 = (size_t)B * c->sc.moe_row0[l];       // rows of the earlier mixture blocks in the routing I/O
+  moe_route(h, M2, D, (const float*)w.w_router, E, K, c->forced_experts ? c->forced_experts + row0 * K : nullptr,
+            m.logits, m.experts, m.gates, s);
+  if (c->experts_out)
+    (void)hipMemcpyAsync(c->experts_out + row0 * K, m.experts, sizeof(int32_t) * (size_t)M2 * K, hipMemcpyDeviceToDevice, s);
+  if (c->router_logits_out)
+    (void)hipMemcpyAsync(c->router_logits_out + row0 * E, m.logits, sizeof(float) * (size_t)M2 * E, hipMemcpyDeviceToDevice, s);
+  moe_sort(m.experts, M2, E, K, m.off, m.pos, m.perm_tok, s);
+  moe_gather_rows(h, m.perm_tok, (int64_t)M2 * K, D, m.xg, s);
+  GemmDesc g1 = fwd_desc(c, m.xg, M2 * K, D, F, nullptr, sh.t_fc1, gbuf);
+  g1.bias = (const float*)w.b_fc1; g1.act = ACT_GELU; g1.aux = u;
+  g1.grp_off = m.off; g1.groups = E; g1.b_gs = (int64_t)D * F; g1.bias_gs = F;
+  gemm(c, g1, s);
+  GemmDesc g2 = fwd_desc(c, gbuf, M2 * K, F, D, nullptr, sh.t_fc2, m.y);
+  g2.bias = (const float*)w.b_fc2;
+  g2.grp_off = m.off; g2.groups = E; g2.b_gs = (int64_t)D * F; g2.bias_gs = D;
+  gemm(c, g2, s);
+  moe_combine(m.y, m.pos, m.gates, x_res, M2, D, K, x_out, s);
+}
+
+// Backward of moe_ffn_forward for a trainable block: dx is the gradient at the block output [M2, D];
+// dh receives the gradient at h = LN2(x_mid).  The expert choice is a constant; the gates are
+// differentiated through the softmax over the selected logits.  Expert weights get Eq. 4 over the
+// rows routed to them (grouped wgrad), the router gets dW_r = h^T dlogits.
+void moe_ffn_backward(bsr_ctx* c, int l, const void* dx, int M2, SavedBlock& v, const bsr_block_params& gw, void* dh,
+                      hipStream_t s) {
+  const bsr_config& cf = c->cfg;
+  Buffers& b = c->b;
+  const int D = cf.dim, F = cf.mlp_hidden, E = cf.n_experts, K = cf.moe_top_k;
+  const bsr_block_params& w = c->p.blocks[l];
+  const Shadow& sh = b.sh[l];
+  MoeBuf& m = v.moe;
+  const int R = M2 * K;
+  moe_combine_bwd(dx, m.y, m.pos, m.experts, m.gates, M2, D, E, K, b.moe_dy, m.dsel, b.moe_dlog, s);
+  GemmDesc d1 = dgrad_desc(c, b.moe_dy, R, F, D, nullptr, sh.s_fc2, b.dgu);      // du = (dy W2^T) * GELU'(u)
+  d1.act = ACT_GELU_BWD; d1.aux = v.u;
+  d1.grp_off = m.off; d1.groups = E; d1.b_gs = (int64_t)D * F;
+  gemm(c, d1, s);
+  GemmDesc w2 = wgrad_desc(c, v.g, b.moe_dy, R, F, D, gw.w_fc2);
+  w2.bsum = (float*)gw.b_fc2;
+  w2.grp_off = m.off; w2.groups = E; w2.c_gs = (int64_t)F * D; w2.bsum_gs = D;
+  gemm(c, w2, s);
+  GemmDesc d2 = dgrad_desc(c, b.dgu, R, D, F, nullptr, sh.s_fc1, b.moe_dxg);     // gradient at the gathered tokens
+  d2.grp_off = m.off; d2.groups = E; d2.b_gs = (int64_t)D * F;
+  gemm(c, d2, s);
+  GemmDesc w1 = wgrad_desc(c, m.xg, b.dgu, R, D, F, gw.w_fc1);
+  w1.bsum = (float*)gw.b_fc1;
+  w1.grp_off = m.off; w1.groups = E; w1.c_gs = (int64_t)D * F; w1.bsum_gs = F;
+  gemm(c, w1, s);
+  moe_unpermute_bwd(b.moe_dxg, m.pos, m.experts, m.dsel, (const float*)w.w_router, M2, D, E, K, dh, s);
+  gemm(c, wgrad_desc(c, v.h2, b.moe_dlog, M2, D, E, gw.w_router), s);             // dW_r = h^T dlogits
 }
 
 void attention_fwd(bsr_ctx* c, const void* qkv, int B, int T, void* out, float* lse, float* clsp,
@@ -370,6 +495,14 @@ void build_shadows(bsr_ctx* c, int first_block, hipStream_t s) {
     Shadow& sh = c->b.sh[l];
     add(w.w_qkv, D, 3 * D, sh.s_qkv, sh.t_qkv);
     add(w.w_proj, D, D, sh.s_proj, sh.t_proj);
+    if (c->sc.moe[l]) {   // one entry per expert matrix
+      for (int e = 0; e < cf.n_experts; ++e) {
+        const size_t o = (size_t)e * D * F;
+        add((const float*)w.w_fc1 + o, D, F, sh.s_fc1 ? sh.s_fc1 + o : nullptr, sh.t_fc1 + o);
+        add((const float*)w.w_fc2 + o, F, D, sh.s_fc2 ? sh.s_fc2 + o : nullptr, sh.t_fc2 + o);
+      }
+      continue;
+    }
     add(w.w_fc1, D, F, sh.s_fc1, sh.t_fc1);
     add(w.w_fc2, F, D, sh.s_fc2, sh.t_fc2);
   }
@@ -384,6 +517,8 @@ int check_params(const bsr_config& cf, const bsr_params* p, int first_block, boo
     NEED(w.ln1_g, "ln1_g"); NEED(w.ln1_b, "ln1_b"); NEED(w.w_qkv, "w_qkv"); NEED(w.b_qkv, "b_qkv");
     NEED(w.w_proj, "w_proj"); NEED(w.b_proj, "b_proj"); NEED(w.ln2_g, "ln2_g"); NEED(w.ln2_b, "ln2_b");
     NEED(w.w_fc1, "w_fc1"); NEED(w.b_fc1, "b_fc1"); NEED(w.w_fc2, "w_fc2"); NEED(w.b_fc2, "b_fc2");
+    for (int i = 0; i < cf.n_moe; ++i)
+      if (cf.moe_blocks[i] == l) NEED(w.w_router, "w_router");
   }
   if (cf.num_classes > 0) { NEED(p->lnf_g, "lnf_g"); NEED(p->lnf_b, "lnf_b"); NEED(p->w_head, "w_head"); NEED(p->b_head, "b_head"); }
 #undef NEED
@@ -520,13 +655,17 @@ int32_t bsr_forward_frozen(bsr_ctx* c, const void* input, int32_t B, void* x_out
       idx_off += (size_t)B * k;
       sc_off += (size_t)B * (Ta - 1);
     }
-    // FFN: x <- x + fc2(GELU(fc1(LN2(x))))
+    // FFN: x <- x + fc2(GELU(fc1(LN2(x)))), or the mixture of expert FFNs
     layernorm_fwd(x, M2, D, (const float*)w.ln2_g, (const float*)w.ln2_b, c->eps, f32, b.h, nullptr, nullptr, s);
+    char* dest = (l == ft - 1) ? (char*)x_out : x;
+    if (sc.moe[l]) {
+      moe_ffn_forward(c, l, B, b.h, x, M2, b.moe, nullptr, b.moe_u, dest, s);
+      continue;
+    }
     GemmDesc g3 = fwd_desc(c, b.h, M2, D, F, w.w_fc1, sh.t_fc1, b.g);
     g3.bias = (const float*)w.b_fc1;
     g3.act = ACT_GELU;
     gemm(c, g3, s);
-    char* dest = (l == ft - 1) ? (char*)x_out : x;
     GemmDesc g4 = fwd_desc(c, b.g, M2, F, D, w.w_fc2, sh.t_fc2, dest);
     g4.bias = (const float*)w.b_fc2;
     g4.res = x;
@@ -595,15 +734,19 @@ int32_t bsr_train_blocks_fwd_bwd(bsr_ctx* c, const void* x_in, const int32_t* la
       sc_off += (size_t)B * (Ta - 1);
     }
     layernorm_fwd(v.xmid, M2, D, (const float*)w.ln2_g, (const float*)w.ln2_b, c->eps, f32, v.h2, v.mean2, v.rstd2, s);
-    GemmDesc g3 = fwd_desc(c, v.h2, M2, D, F, w.w_fc1, sh.t_fc1, v.g);
-    g3.bias = (const float*)w.b_fc1;
-    g3.act = ACT_GELU;
-    g3.aux = v.u;
-    gemm(c, g3, s);
-    GemmDesc g4 = fwd_desc(c, v.g, M2, F, D, w.w_fc2, sh.t_fc2, v.xout);
-    g4.bias = (const float*)w.b_fc2;
-    g4.res = v.xmid;
-    gemm(c, g4, s);
+    if (sc.moe[l]) {
+      moe_ffn_forward(c, l, B, v.h2, v.xmid, M2, v.moe, v.u, v.g, v.xout, s);
+    } else {
+      GemmDesc g3 = fwd_desc(c, v.h2, M2, D, F, w.w_fc1, sh.t_fc1, v.g);
+      g3.bias = (const float*)w.b_fc1;
+      g3.act = ACT_GELU;
+      g3.aux = v.u;
+      gemm(c, g3, s);
+      GemmDesc g4 = fwd_desc(c, v.g, M2, F, D, w.w_fc2, sh.t_fc2, v.xout);
+      g4.bias = (const float*)w.b_fc2;
+      g4.res = v.xmid;
+      gemm(c, g4, s);
+    }
     x = v.xout;
   }
   const int Tl = sc.T_last;
@@ -650,13 +793,17 @@ int32_t bsr_train_blocks_fwd_bwd(bsr_ctx* c, const void* x_in, const int32_t* la
     const char* xin = (l == ft) ? (const char*)x_in : b.sv[l - 1].xout;
 
     // FFN branch.  du = (dx . W2^T) * GELU'(u); dW2 = g^T dx; dh2 = du . W1^T; dW1 = h2^T du
-    GemmDesc d1 = dgrad_desc(c, dx, M2, F, D, w.w_fc2, sh.s_fc2, b.dgu);
-    d1.act = ACT_GELU_BWD;
-    d1.aux = v.u;
-    gemm(c, d1, s);
-    wgrad(c, v.g, dx, M2, F, D, gw.w_fc2, gw.b_fc2, s);
-    gemm(c, dgrad_desc(c, b.dgu, M2, D, F, w.w_fc1, sh.s_fc1, b.dh), s);
-    wgrad(c, v.h2, b.dgu, M2, D, F, gw.w_fc1, gw.b_fc1, s);
+    if (sc.moe[l]) {
+      moe_ffn_backward(c, l, dx, M2, v, gw, b.dh, s);
+    } else {
+      GemmDesc d1 = dgrad_desc(c, dx, M2, F, D, w.w_fc2, sh.s_fc2, b.dgu);
+      d1.act = ACT_GELU_BWD;
+      d1.aux = v.u;
+      gemm(c, d1, s);
+      wgrad(c, v.g, dx, M2, F, D, gw.w_fc2, gw.b_fc2, s);
+      gemm(c, dgrad_desc(c, b.dgu, M2, D, F, w.w_fc1, sh.s_fc1, b.dh), s);
+      wgrad(c, v.h2, b.dgu, M2, D, F, gw.w_fc1, gw.b_fc1, s);
+    }
     layernorm_bwd(b.dh, v.xmid, v.mean2, v.rstd2, (const float*)w.ln2_g, dx, M2, D, f32, dx_other, b.partial,
                   (float*)gw.ln2_g, (float*)gw.ln2_b, s);
     std::swap(dx, dx_other);   // dx: gradient at x_mid (kept tokens)
@@ -679,6 +826,18 @@ int32_t bsr_train_blocks_fwd_bwd(bsr_ctx* c, const void* x_in, const int32_t* la
     if (l > ft) std::swap(dx, dx_other);
   }
   return check_hip(c, "bsr_train_blocks_fwd_bwd");
+}
+
+int32_t bsr_moe_routing_io(bsr_ctx* c, const int32_t* forced_experts, int32_t* experts_out,
+                           float* router_logits_out) {
+  if (!c) return fail(nullptr, BSR_ERR_INVALID_ARG, "ctx is NULL");
+  if ((forced_experts && !aligned16(forced_experts)) || (experts_out && !aligned16(experts_out)) ||
+      (router_logits_out && !aligned16(router_logits_out)))
+    return fail(c, BSR_ERR_INVALID_ARG, "bsr_moe_routing_io: pointer not 16-byte aligned");
+  c->forced_experts = forced_experts;
+  c->experts_out = experts_out;
+  c->router_logits_out = router_logits_out;
+  return BSR_OK;
 }
 
 int32_t bsr_sgd_step(bsr_ctx* c, const bsr_params* grads, const bsr_params* momenta, float lr,
@@ -716,9 +875,20 @@ int32_t bsr_sgd_step(bsr_ctx* c, const bsr_params* grads, const bsr_params* mome
     vec(W.ln1_g, G.ln1_g, Mo.ln1_g, D); vec(W.ln1_b, G.ln1_b, Mo.ln1_b, D);
     vec(W.b_qkv, G.b_qkv, Mo.b_qkv, 3 * D); vec(W.b_proj, G.b_proj, Mo.b_proj, D);
     vec(W.ln2_g, G.ln2_g, Mo.ln2_g, D); vec(W.ln2_b, G.ln2_b, Mo.ln2_b, D);
-    vec(W.b_fc1, G.b_fc1, Mo.b_fc1, F); vec(W.b_fc2, G.b_fc2, Mo.b_fc2, D);
     mat(W.w_qkv, G.w_qkv, Mo.w_qkv, D, 3 * D, sh.s_qkv, sh.t_qkv);
     mat(W.w_proj, G.w_proj, Mo.w_proj, D, D, sh.s_proj, sh.t_proj);
+    if (c->sc.moe[l]) {   // router, E bias vectors each, E matrices each
+      const int E = cf.n_experts;
+      vec(W.w_router, G.w_router, Mo.w_router, (int64_t)D * E);
+      vec(W.b_fc1, G.b_fc1, Mo.b_fc1, (int64_t)E * F); vec(W.b_fc2, G.b_fc2, Mo.b_fc2, (int64_t)E * D);
+      for (int e = 0; e < E; ++e) {
+        const size_t o = (size_t)e * D * F;
+        mat((float*)W.w_fc1 + o, (const float*)G.w_fc1 + o, (float*)Mo.w_fc1 + o, D, F, sh.s_fc1 + o, sh.t_fc1 + o);
+        mat((float*)W.w_fc2 + o, (const float*)G.w_fc2 + o, (float*)Mo.w_fc2 + o, F, D, sh.s_fc2 + o, sh.t_fc2 + o);
+      }
+      continue;
+    }
+    vec(W.b_fc1, G.b_fc1, Mo.b_fc1, F); vec(W.b_fc2, G.b_fc2, Mo.b_fc2, D);
     mat(W.w_fc1, G.w_fc1, Mo.w_fc1, D, F, sh.s_fc1, sh.t_fc1);
     mat(W.w_fc2, G.w_fc2, Mo.w_fc2, F, D, sh.s_fc2, sh.t_fc2);
   }

@@ -28,6 +28,13 @@ struct GemmDesc {
   const float* pos = nullptr;//   is added; rows of CLS tokens are left untouched
   float* bsum = nullptr;     // weight-gradient form only (A^T and B share the token index k): if set,
                              //   receives sum_k B(k,n), the bias gradient of the same layer
+  // Grouped form (expert FFNs over routed tokens): the token rows are cut into `groups` consecutive
+  // ranges, range e = [grp_off[e], grp_off[e+1]) (device array), each with its own weight matrix.
+  //   forward / dgrad: rows of A and C in range e use B + e*b_gs and bias + e*bias_gs
+  //   wgrad:           the contraction runs over range e only and fills C + e*c_gs, bsum + e*bsum_gs
+  const int32_t* grp_off = nullptr;
+  int groups = 0;
+  int64_t b_gs = 0, bias_gs = 0, c_gs = 0, bsum_gs = 0;
 };
 
 // ---- generic (any shape, fp32 or bf16 storage, fp32 arithmetic) ---------------------------------
@@ -87,6 +94,30 @@ void cross_entropy(const float* logits, const int32_t* labels, int B, int C, flo
 void mean_sq_loss(const void* x, int64_t n, bool f32, float* partial, float* loss, void* dx,
                   hipStream_t s);
 size_t mean_sq_partial_floats();
+
+// ---- mixture-of-experts FFN (bf16) ----------------------------------------------------------------
+constexpr int MOE_MAX_EXPERTS = 32, MOE_MAX_TOPK = 4;
+// logits[t,:] = h[t,:] . w_router (fp32 accumulation); the K largest (ties: lower index) in descending
+// order, or the forced choice; gates = softmax over the K selected logits
+void moe_route(const void* h, int64_t M, int D, const float* w_router, int E, int K, const int32_t* forced,
+               float* logits, int32_t* experts, float* gates, hipStream_t s);
+// stable counting sort of the (token, slot) pairs by expert: off[E+1], pos[t*K+s] = row of the pair
+// in expert order, perm_tok[row] = t
+void moe_sort(const int32_t* experts, int64_t M, int E, int K, int32_t* off, int32_t* pos, int32_t* perm_tok,
+              hipStream_t s);
+// y[r,:] = x[src[r],:]   (rows of D bf16, D % 8 == 0)
+void moe_gather_rows(const void* x, const int32_t* src, int64_t rows, int D, void* y, hipStream_t s);
+// x_out[t,:] = res[t,:] + sum_s gates[t,s] * y[pos[t,s],:]
+void moe_combine(const void* y, const int32_t* pos, const float* gates, const void* res, int64_t M, int D, int K,
+                 void* x_out, hipStream_t s);
+// backward of moe_combine w.r.t. y and the gates: dy[pos[t,s],:] = gates[t,s] * dx[t,:];
+// dgate_s = <dx[t], y[pos[t,s]]>; dsel[t,s] = gates_s (dgate_s - sum_j gates_j dgate_j) (fp32) and the same
+// values scattered into dlogits[t, experts[t,s]] (bf16 [M,E], zero elsewhere)
+void moe_combine_bwd(const void* dx, const void* y, const int32_t* pos, const int32_t* experts, const float* gates,
+                     int64_t M, int D, int E, int K, void* dy, float* dsel, void* dlogits, hipStream_t s);
+// dh[t,:] = sum_s dxg[pos[t,s],:] + sum_s dsel[t,s] * w_router[:, experts[t,s]]
+void moe_unpermute_bwd(const void* dxg, const int32_t* pos, const int32_t* experts, const float* dsel,
+                       const float* w_router, int64_t M, int D, int E, int K, void* dh, hipStream_t s);
 
 // A table of weight matrices handled by one launch: bf16 copies (straight and / or transposed) of
 // each, optionally after an SGD update.  The table travels as a kernel argument.

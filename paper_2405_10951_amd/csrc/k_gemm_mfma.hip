@@ -172,7 +172,27 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_kernel(GemmDesc g) {
   const int wm = wave / WN, wn = wave % WN;
   const int ntn = (g.N + BN - 1) / BN;
   const int tile = xcd_remap(blockIdx.x, gridDim.x);
-  const int m0 = (tile / ntn) * BM, n0 = (tile % ntn) * BN;
+  int m0 = (tile / ntn) * BM;
+  const int n0 = (tile % ntn) * BN;
+  if (g.grp_off) {
+    // grouped form: the tile index counts row tiles group after group (a group's last tile may be
+    // partial); workgroups past the last group have nothing to do
+    int mt = tile / ntn, e = 0, found = 0;
+    for (; e < g.groups; ++e) {
+      const int r0 = g.grp_off[e], r1 = g.grp_off[e + 1];
+      const int nt_e = (r1 - r0 + BM - 1) / BM;
+      if (mt < nt_e) {
+        m0 = r0 + mt * BM;
+        g.M = r1;                                   // rows of this tile stop at the end of its group
+        found = 1;
+        break;
+      }
+      mt -= nt_e;
+    }
+    if (!found) return;
+    g.B = (const bf16*)g.B + (int64_t)e * g.b_gs;
+    if (g.bias) g.bias += (int64_t)e * g.bias_gs;
+  }
   const bf16* __restrict__ A = (const bf16*)g.A;
   const bf16* __restrict__ Bt = (const bf16*)g.B;
 
@@ -305,7 +325,8 @@ void launch_nt(const GemmDesc& g, hipStream_t s) {
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     attr_set = true;
   }
-  const int tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
+  // grouped: every group may end in one partial row tile
+  const int tiles = ((g.M + BM - 1) / BM + (g.grp_off ? g.groups : 0)) * ((g.N + BN - 1) / BN);
   if (g.K % BK == 0) gemm_nt_kernel<BM, BN, WM, WN, false><<<tiles, WM * WN * 64, lds, s>>>(g);
   else gemm_nt_kernel<BM, BN, WM, WN, true><<<tiles, WM * WN * 64, lds, s>>>(g);
 }
@@ -343,8 +364,20 @@ __global__ __launch_bounds__(256) void gemm_tn_kernel(GemmDesc g, float* partial
   const int ntiles = gridDim.x;
   const int tile = xcd_remap(blockIdx.x, ntiles);
   const int m0 = (tile / ntn) * BM, n0 = (tile % ntn) * BN;
+  if (g.grp_off) {
+    // grouped form: blockIdx.y is the group; the contraction runs over its token rows only
+    const int e = blockIdx.y, r0 = g.grp_off[e], r1 = g.grp_off[e + 1];
+    g.A = (const bf16*)g.A + (int64_t)r0 * g.a_cs;
+    g.B = (const bf16*)g.B + (int64_t)r0 * g.b_rs;
+    g.K = r1 - r0;
+    g.C = (float*)g.C + (int64_t)e * g.c_gs;
+    if (g.bsum) g.bsum += (int64_t)e * g.bsum_gs;
+    partial = nullptr;
+    bpartial = nullptr;
+    kt_per = (g.K + BK - 1) / BK;
+  }
   const int nk_all = (g.K + BK - 1) / BK;
-  const int kt0 = blockIdx.y * kt_per, kt1 = min(kt0 + kt_per, nk_all);
+  const int kt0 = g.grp_off ? 0 : blockIdx.y * kt_per, kt1 = min(kt0 + kt_per, nk_all);
   const bf16* __restrict__ X = (const bf16*)g.A;     // [K tokens, Mo], row stride a_cs
   const bf16* __restrict__ Y = (const bf16*)g.B;     // [K tokens, No], row stride b_rs
   const int fc = tid & 15, tg = tid >> 4;            // column chunk (8 columns), token group (4 tokens)
@@ -520,6 +553,10 @@ void launch_tn(const GemmDesc& g, float* ws, size_t ws_floats, hipStream_t s) {
     attr_set = true;
   }
   const int tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
+  if (g.grp_off) {   // one grid row per group, no split: tiles x groups already fills the machine
+    gemm_tn_kernel<BM, BN><<<dim3(tiles, g.groups), 256, lds, s>>>(g, nullptr, nullptr, 0);
+    return;
+  }
   const int nk = (g.K + BK - 1) / BK;
   // enough splits to give every CU about two workgroups, each with at least 4 k-tiles
   int splits = 1;
@@ -580,7 +617,7 @@ void gemm_mfma(const GemmDesc& g, float* splitk_ws, size_t splitk_ws_floats, hip
     return;
   }
   static const int forced = [] { const char* e = getenv("BSR_NT_TILE"); return e ? atoi(e) : 0; }();
-  int pick = forced;
+  int pick = g.grp_off ? 128128 : forced;     // groups are a few hundred rows: small tiles
   if (!pick) {
     float best = 0.f;
     for (const NtShape& t : kNtShapes) {

@@ -12,8 +12,10 @@ def rel(a, b):
     return float(np.max(np.abs(a - b)) / max(float(np.max(np.abs(b))), 1e-30))
 
 
-def run_hip_step(cfg, params, x, labels, forced_idx=None, max_batch=None, sgd=None, ctx=None):
+def run_hip_step(cfg, params, x, labels, forced_idx=None, max_batch=None, sgd=None, ctx=None,
+                 forced_experts=None):
     """One BSR step on cuda:0.  forced_idx: list per drop of [B,k] arrays (or None).
+    forced_experts: dict block -> [rows,K] expert choice for the mixture-of-experts blocks (or None).
     sgd: None or dict(lr=, momentum=, weight_decay=, momenta=dict|None).  Returns a dict."""
     dev = torch.device("cuda:0")
     B = x.shape[0]
@@ -36,6 +38,18 @@ def run_hip_step(cfg, params, x, labels, forced_idx=None, max_batch=None, sgd=No
         return (torch.full((max(nk, 4),), -1, dtype=torch.int32, device=dev),
                 torch.zeros(max(ns, 4), dtype=torch.float32, device=dev))
 
+    moe_rows = ctx.moe_rows(B)
+    ex_out = rl_out = None
+    if moe_rows:
+        K, E = ctx.c.moe_top_k, ctx.c.n_experts
+        total = sum(moe_rows.values())
+        ex_out = torch.full((total * K,), -1, dtype=torch.int32, device=dev)
+        rl_out = torch.zeros(total * E, dtype=torch.float32, device=dev)
+        fex = None
+        if forced_experts is not None:
+            fex = torch.as_tensor(np.concatenate([np.asarray(forced_experts[l], np.int32).reshape(-1)
+                                                  for l in sorted(moe_rows)]), dtype=torch.int32).to(dev)
+        ctx.bsr_moe_routing_io(fex, ex_out, rl_out)
     kf, sf = bufs(ctx.frozen_drops)
     kt, st = bufs(ctx.train_drops)
     x_f = ctx.bsr_forward_frozen(xin, kept_idx_out=kf, scores_out=sf, forced_idx=cat_idx(ctx.frozen_drops))
@@ -65,6 +79,14 @@ def run_hip_step(cfg, params, x, labels, forced_idx=None, max_batch=None, sgd=No
                x_final=x_final.float().cpu().numpy(), logits=logits.cpu().numpy(),
                loss=float(loss[0].item()), grads={n: g.cpu().numpy() for n, g in grads.items()},
                new_params=new_params, keep_k=ctx.keep_k, ctx=ctx)
+    if moe_rows:
+        K, E = ctx.c.moe_top_k, ctx.c.n_experts
+        out["experts"], out["router_logits"], o = {}, {}, 0
+        for l in sorted(moe_rows):
+            m = moe_rows[l]
+            out["experts"][l] = ex_out[o * K:(o + m) * K].cpu().numpy().reshape(m, K)
+            out["router_logits"][l] = rl_out[o * E:(o + m) * E].cpu().numpy().reshape(m, E)
+            o += m
     return out
 
 
