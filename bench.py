@@ -140,7 +140,9 @@ def main():
     def flops_of(c, ctx):
         pd = c["in_chans"] * c["patch_size"] ** 2
         return step_flops(c["dim"], c["mlp_hidden"], c["num_classes"], pd, ctx.tokens_attn[0] - 1,
-                          ctx.tokens_attn, ctx.tokens_mlp, c["first_trainable"], batch)
+                          ctx.tokens_attn, ctx.tokens_mlp, c["first_trainable"], batch,
+                          moe_blocks=tuple(c.get("moe_blocks", ())), n_experts=c.get("n_experts", 0),
+                          moe_top_k=c.get("moe_top_k", 0))
 
     ctx = build_context(cfg, batch)
     r = time_steps(ctx, cfg, batch, args.steps, args.warmup, profile_steps=min(args.steps, 10))
@@ -158,7 +160,9 @@ def main():
         "config": {"workload": f"{args.workload}: ViT dim {cfg['dim']} depth {cfg['depth']} batch {batch}, "
                                f"keep {cfg['keep_ratio']} at blocks {cfg['drop_blocks']}, "
                                f"trainable blocks {cfg['first_trainable']}..{cfg['depth'] - 1} + head, "
-                               f"SGD momentum 0.9",
+                               + (f"{cfg['n_experts']}-expert top-{cfg['moe_top_k']} FFN in blocks {cfg['moe_blocks']}, "
+                                  if cfg.get("moe_blocks") else "")
+                               + "SGD momentum 0.9",
                    "global_batch": batch, "tokens_per_block": ctx.tokens_attn},
         "step_gflop": fl["total"] / 1e9,
         "step_pct_of_bf16_mfma_peak": 100.0 * fl["total"] / (r["ms_per_step"] * 1e-3) / (peak * 1e12),

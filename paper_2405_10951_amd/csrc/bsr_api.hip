@@ -33,7 +33,8 @@ struct Schedule {
 struct MoeBuf {      // routing and the expert-ordered tensors of one mixture-of-experts FFN
   float *logits, *gates, *dsel;
   int32_t *experts, *pos, *perm_tok, *off;
-  char *xg, *y;      // gathered tokens [M*K, D], expert outputs [M*K, D] (u and g live in the block's u / g)
+  char *xg;          // gathered tokens [M*K, D] (u and g live in the block's u / g)
+  float *y;          // expert outputs [M*K, D], fp32: they are rounded once, after the weighted sum
 };
 
 struct SavedBlock {  // what a trainable block keeps for its backward pass (Sec. 3.2 of the paper)
@@ -46,6 +47,7 @@ struct SavedBlock {  // what a trainable block keeps for its backward pass (Sec.
 struct Shadow {  // bf16 copies of a block's matrices: transposed [out,in] and, if trained, straight [in,out]
   bf16 *t_qkv, *t_proj, *t_fc1, *t_fc2;     // (a mixture-of-experts block: E matrices each, expert-major)
   bf16 *s_qkv, *s_proj, *s_fc1, *s_fc2;
+  bf16 *t_router;                           // [E,D], mixture-of-experts blocks only
 };
 
 struct Buffers {
@@ -214,6 +216,7 @@ size_t carve(const bsr_config& c, const Schedule& s, char* base, Buffers* out) {
       b.sh[l].t_proj = w.take<bf16>(D * D);
       b.sh[l].t_fc1 = w.take<bf16>(ne * D * F);
       b.sh[l].t_fc2 = w.take<bf16>(ne * D * F);
+      if (s.moe[l]) b.sh[l].t_router = w.take<bf16>((size_t)c.n_experts * D);
       if (l >= ft) {
         b.sh[l].s_qkv = w.take<bf16>(3 * D * D);
         b.sh[l].s_proj = w.take<bf16>(D * D);
@@ -242,7 +245,7 @@ size_t carve(const bsr_config& c, const Schedule& s, char* base, Buffers* out) {
     m.perm_tok = w.take<int32_t>(rows * KE);
     m.off = w.take<int32_t>(NE + 1);
     m.xg = w.take<char>(rows * KE * D * E);
-    m.y = w.take<char>(rows * KE * D * E);
+    m.y = w.take<float>(rows * KE * D);
   };
   bool frozen_moe = false;
   for (int l = 0; l < ft && l < L; ++l) frozen_moe |= s.moe[l];
@@ -391,8 +394,10 @@ void moe_ffn_forward(bsr_ctx* c, int l, int B, const void* h, const void* x_res,
   const bsr_block_params& w = c->p.blocks[l];
   const Shadow& sh = c->b.sh[l];
   const size_t row0 = (size_t)B * c->sc.moe_row0[l];       // rows of the earlier mixture blocks in the routing I/O
-  moe_route(h, M2, D, (const float*)w.w_router, E, K, c->forced_experts ? c->forced_experts + row0 * K : nullptr,
-            m.logits, m.experts, m.gates, s);
+  GemmDesc gl = fwd_desc(c, h, M2, D, E, nullptr, sh.t_router, m.logits);       // router logits, fp32
+  gl.out_f32 = true;
+  gemm(c, gl, s);
+  moe_topk(m.logits, M2, E, K, c->forced_experts ? c->forced_experts + row0 * K : nullptr, m.experts, m.gates, s);
   if (c->experts_out)
     (void)hipMemcpyAsync(c->experts_out + row0 * K, m.experts, sizeof(int32_t) * (size_t)M2 * K, hipMemcpyDeviceToDevice, s);
   if (c->router_logits_out)
@@ -405,6 +410,7 @@ void moe_ffn_forward(bsr_ctx* c, int l, int B, const void* h, const void* x_res,
   gemm(c, g1, s);
   GemmDesc g2 = fwd_desc(c, gbuf, M2 * K, F, D, nullptr, sh.t_fc2, m.y);
   g2.bias = (const float*)w.b_fc2;
+  g2.out_f32 = true;
   g2.grp_off = m.off; g2.groups = E; g2.b_gs = (int64_t)D * F; g2.bias_gs = D;
   gemm(c, g2, s);
   moe_combine(m.y, m.pos, m.gates, x_res, M2, D, K, x_out, s);
@@ -507,6 +513,8 @@ void build_shadows(bsr_ctx* c, int first_block, hipStream_t s) {
     add(w.w_fc2, F, D, sh.s_fc2, sh.t_fc2);
   }
   matrix_table_run(tab, false, 0.f, 0.f, 0.f, s);
+  for (int l = first_block; l < cf.depth; ++l)
+    if (c->sc.moe[l]) moe_router_copy((const float*)c->p.blocks[l].w_router, D, cf.n_experts, c->b.sh[l].t_router, s);
 }
 
 int check_params(const bsr_config& cf, const bsr_params* p, int first_block, bool need_stem, const char** which) {
@@ -901,6 +909,8 @@ int32_t bsr_sgd_step(bsr_ctx* c, const bsr_params* grads, const bsr_params* mome
   }
   sgd_table(tab, ntab, lr, momentum, weight_decay, s);
   matrix_table_run(mats, true, lr, momentum, weight_decay, s);
+  for (int l = cf.first_trainable_block; l < cf.depth; ++l)      // the routers were updated as vectors
+    if (c->sc.moe[l]) moe_router_copy((const float*)c->p.blocks[l].w_router, D, cf.n_experts, c->b.sh[l].t_router, s);
   return check_hip(c, "bsr_sgd_step");
 }
 

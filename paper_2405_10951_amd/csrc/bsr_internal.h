@@ -97,17 +97,19 @@ size_t mean_sq_partial_floats();
 
 // ---- mixture-of-experts FFN (bf16) ----------------------------------------------------------------
 constexpr int MOE_MAX_EXPERTS = 32, MOE_MAX_TOPK = 4;
-// logits[t,:] = h[t,:] . w_router (fp32 accumulation); the K largest (ties: lower index) in descending
-// order, or the forced choice; gates = softmax over the K selected logits
-void moe_route(const void* h, int64_t M, int D, const float* w_router, int E, int K, const int32_t* forced,
-               float* logits, int32_t* experts, float* gates, hipStream_t s);
+// from the router logits [M,E]: the K largest (ties: lower index) in descending order, or the forced
+// choice; gates = softmax over the K selected logits
+void moe_topk(const float* logits, int64_t M, int E, int K, const int32_t* forced, int32_t* experts, float* gates,
+              hipStream_t s);
+// bf16 copy of w_router [D,E] stored [E,D]
+void moe_router_copy(const float* w_router, int D, int E, void* t_router, hipStream_t s);
 // stable counting sort of the (token, slot) pairs by expert: off[E+1], pos[t*K+s] = row of the pair
 // in expert order, perm_tok[row] = t
 void moe_sort(const int32_t* experts, int64_t M, int E, int K, int32_t* off, int32_t* pos, int32_t* perm_tok,
               hipStream_t s);
 // y[r,:] = x[src[r],:]   (rows of D bf16, D % 8 == 0)
 void moe_gather_rows(const void* x, const int32_t* src, int64_t rows, int D, void* y, hipStream_t s);
-// x_out[t,:] = res[t,:] + sum_s gates[t,s] * y[pos[t,s],:]
+// x_out[t,:] = res[t,:] + sum_s gates[t,s] * y[pos[t,s],:]   (y: fp32 expert outputs)
 void moe_combine(const void* y, const int32_t* pos, const float* gates, const void* res, int64_t M, int D, int K,
                  void* x_out, hipStream_t s);
 // backward of moe_combine w.r.t. y and the gates: dy[pos[t,s],:] = gates[t,s] * dx[t,:];

@@ -17,109 +17,114 @@ __device__ inline float wave_sum(float v) {
   return v;
 }
 
-// One wavefront per token.  Lane j accumulates its slice of the D-long dot products for all E experts;
-// the E sums are reduced over the wave and lane 0 ranks them.
-__global__ __launch_bounds__(256) void moe_route_kernel(const bf16* __restrict__ h, int64_t M, int D,
-                                                        const float* __restrict__ w_router, int E, int K,
-                                                        const int32_t* __restrict__ forced,
-                                                        float* __restrict__ logits, int32_t* __restrict__ experts,
-                                                        float* __restrict__ gates) {
-  const int lane = threadIdx.x % WAVE;
-  const int64_t t = (int64_t)blockIdx.x * 4 + threadIdx.x / WAVE;
+// Expert choice of one token per thread, from the router logits [M,E] (a GEMM wrote them): the K
+// largest logits (ties: lower index) in descending order, or the forced choice (clamped into
+// 0..E-1); gates = softmax over the K selected logits.  The logits sit in registers and are picked by
+// comparison, never by a computed register index.
+template <int EMAX>
+__global__ __launch_bounds__(256) void moe_topk_kernel(const float* __restrict__ logits, int64_t M, int E, int K,
+                                                       const int32_t* __restrict__ forced,
+                                                       int32_t* __restrict__ experts, float* __restrict__ gates) {
+  const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (t >= M) return;
-  float acc[MOE_MAX_EXPERTS];
+  float v[EMAX];
 #pragma unroll
-  for (int e = 0; e < MOE_MAX_EXPERTS; ++e) acc[e] = 0.f;
-  for (int j = lane; j < D; j += WAVE) {
-    const float x = (float)h[t * D + j];
-    const float* wr = w_router + (int64_t)j * E;
+  for (int e = 0; e < EMAX; ++e) v[e] = e < E ? logits[t * E + min(e, E - 1)] : -INFINITY;
+  int sel[MOE_MAX_TOPK] = {0, 0, 0, 0};
+  float lg[MOE_MAX_TOPK] = {0.f, 0.f, 0.f, 0.f};
+  unsigned taken = 0;
 #pragma unroll
-    for (int e = 0; e < MOE_MAX_EXPERTS; ++e)
-      if (e < E) acc[e] = fmaf(x, wr[e], acc[e]);
-  }
-#pragma unroll
-  for (int e = 0; e < MOE_MAX_EXPERTS; ++e)
-    if (e < E) acc[e] = wave_sum(acc[e]);
-  if (lane != 0) return;
-  if (logits)
-    for (int e = 0; e < E; ++e) logits[t * E + e] = acc[e];
-  int sel[MOE_MAX_TOPK];
-  float lg[MOE_MAX_TOPK];
-  for (int s = 0; s < K; ++s) {
-    int best = -1;
+  for (int s = 0; s < MOE_MAX_TOPK; ++s) {
+    if (s >= K) break;
+    int best = 0;
+    float bv = -INFINITY;
     if (forced) {
-      best = min(max(forced[t * K + s], 0), E - 1);   // a forced value outside 0..E-1 is clamped
-    } else {
-      for (int e = 0; e < E; ++e) {
-        bool taken = false;
-        for (int j = 0; j < s; ++j) taken |= (sel[j] == e);
-        if (taken) continue;
-        float ve = 0.f, vb = 0.f;
+      best = min(max(forced[t * K + s], 0), E - 1);
 #pragma unroll
-        for (int q = 0; q < MOE_MAX_EXPERTS; ++q) {   // register array: select by comparison, not by address
-          if (q == e) ve = acc[q];
-          if (q == best) vb = acc[q];
-        }
-        if (best < 0 || ve > vb) best = e;            // strict >: a tie keeps the lower index
+      for (int e = 0; e < EMAX; ++e)
+        if (e == best) bv = v[e];
+    } else {
+      bool have = false;
+#pragma unroll
+      for (int e = 0; e < EMAX; ++e) {
+        const bool ok = e < E && !((taken >> e) & 1u) && (!have || v[e] > bv);   // strict >: ties keep the lower index
+        if (ok) { best = e; bv = v[e]; have = true; }
       }
     }
-    float v = 0.f;
-#pragma unroll
-    for (int q = 0; q < MOE_MAX_EXPERTS; ++q)
-      if (q == best) v = acc[q];
+    taken |= 1u << best;
     sel[s] = best;
-    lg[s] = v;
+    lg[s] = bv;
   }
   float mx = lg[0];
-  for (int s = 1; s < K; ++s) mx = fmaxf(mx, lg[s]);
+#pragma unroll
+  for (int s = 1; s < MOE_MAX_TOPK; ++s)
+    if (s < K) mx = fmaxf(mx, lg[s]);
   float sum = 0.f;
-  for (int s = 0; s < K; ++s) { lg[s] = expf(lg[s] - mx); sum += lg[s]; }
-  for (int s = 0; s < K; ++s) {
-    experts[t * K + s] = sel[s];
-    gates[t * K + s] = lg[s] / sum;
-  }
+#pragma unroll
+  for (int s = 0; s < MOE_MAX_TOPK; ++s)
+    if (s < K) { lg[s] = expf(lg[s] - mx); sum += lg[s]; }
+#pragma unroll
+  for (int s = 0; s < MOE_MAX_TOPK; ++s)
+    if (s < K) {
+      experts[t * K + s] = sel[s];
+      gates[t * K + s] = lg[s] / sum;
+    }
 }
 
-// Stable counting sort by expert, one workgroup of 1024 threads.  Thread i owns the pairs
-// a in [i*chunk, (i+1)*chunk) (a = t*K + s); for every expert in turn the per-thread counts are
-// scanned over the workgroup, which gives each pair its row: pairs of one expert keep their order.
+// bf16 copy of the router matrix [D,E] stored [E,D] (the layout the logits GEMM reads)
+__global__ void moe_router_copy_kernel(const float* __restrict__ w, int D, int E, bf16* __restrict__ t) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= D * E) return;
+  const int e = i / D, j = i % D;
+  t[i] = (bf16)w[(int64_t)j * E + e];
+}
+
+// Stable counting sort by expert.  Workgroup e (1024 threads) handles expert e: thread i owns the pairs
+// a in [i*chunk, (i+1)*chunk) (a = t*K + s), counts those of its expert and those of lower experts;
+// the scan of the first over the workgroup gives each pair its row inside the expert's range, the
+// sum of the second is where that range starts.  Pairs of one expert keep their (token, slot) order.
 __global__ __launch_bounds__(1024) void moe_sort_kernel(const int32_t* __restrict__ experts, int64_t pairs, int E,
                                                         int K, int32_t* __restrict__ off, int32_t* __restrict__ pos,
                                                         int32_t* __restrict__ perm_tok) {
-  __shared__ int wsum[16];
-  __shared__ int total_s;
+  __shared__ int w_eq[16], w_lt[16];
+  const int e = blockIdx.x;
   const int tid = threadIdx.x, lane = tid % WAVE, wave = tid / WAVE;
   const int64_t chunk = (pairs + 1023) / 1024;
   const int64_t a0 = min((int64_t)tid * chunk, pairs), a1 = min(a0 + chunk, pairs);
-  int base = 0;                        // rows taken by the experts before e
-  if (tid == 0) off[0] = 0;
-  for (int e = 0; e < E; ++e) {
-    int cnt = 0;
-    for (int64_t a = a0; a < a1; ++a) cnt += (experts[a] == e);
-    // inclusive scan over the wave, then over the 16 wave totals
-    int incl = cnt;
-#pragma unroll
-    for (int o = 1; o < WAVE; o <<= 1) {
-      const int v = __shfl_up(incl, o, 64);
-      if (lane >= o) incl += v;
-    }
-    if (lane == WAVE - 1) wsum[wave] = incl;
-    __syncthreads();
-    int before = 0;
-    for (int w = 0; w < wave; ++w) before += wsum[w];
-    if (tid == 1023) total_s = before + incl;
-    int row = base + before + incl - cnt;
-    for (int64_t a = a0; a < a1; ++a)
-      if (experts[a] == e) {
-        pos[a] = row;
-        perm_tok[row] = (int32_t)(a / K);
-        ++row;
-      }
-    __syncthreads();
-    base += total_s;
-    if (tid == 0) off[e + 1] = base;
-    __syncthreads();
+  int eq = 0, lt = 0;
+  for (int64_t a = a0; a < a1; ++a) {
+    const int x = experts[a];
+    eq += (x == e);
+    lt += (x < e);
   }
+  int incl = eq;                       // inclusive scan of eq over the wave
+#pragma unroll
+  for (int o = 1; o < WAVE; o <<= 1) {
+    const int u = __shfl_up(incl, o, 64);
+    if (lane >= o) incl += u;
+  }
+  int lts = lt;                        // wave total of lt
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) lts += __shfl_xor(lts, o, 64);
+  if (lane == WAVE - 1) { w_eq[wave] = incl; w_lt[wave] = lts; }
+  __syncthreads();
+  int before = 0, base = 0, total = 0;
+  for (int w = 0; w < 16; ++w) {
+    if (w < wave) before += w_eq[w];
+    total += w_eq[w];
+    base += w_lt[w];
+  }
+  if (tid == 0) {
+    off[e] = base;
+    if (e == E - 1) off[E] = base + total;
+  }
+  int row = base + before + incl - eq;
+  for (int64_t a = a0; a < a1; ++a)
+    if (experts[a] == e) {
+      pos[a] = row;
+      perm_tok[row] = (int32_t)(a / K);
+      ++row;
+    }
 }
 
 __global__ void moe_gather_rows_kernel(const uint4* __restrict__ x, const int32_t* __restrict__ src, int64_t rows,
@@ -132,7 +137,7 @@ __global__ void moe_gather_rows_kernel(const uint4* __restrict__ x, const int32_
 }
 
 // One wavefront per token, 8 columns per lane and pass.
-__global__ __launch_bounds__(256) void moe_combine_kernel(const bf16* __restrict__ y, const int32_t* __restrict__ pos,
+__global__ __launch_bounds__(256) void moe_combine_kernel(const float* __restrict__ y, const int32_t* __restrict__ pos,
                                                           const float* __restrict__ gates,
                                                           const bf16* __restrict__ res, int64_t M, int D, int K,
                                                           bf16* __restrict__ out) {
@@ -146,9 +151,11 @@ __global__ __launch_bounds__(256) void moe_combine_kernel(const bf16* __restrict
     for (int e = 0; e < 8; ++e) v[e] = (float)r8[e];
     for (int s = 0; s < K; ++s) {
       const float g = gates[t * K + s];
-      const bf16x8 y8 = *(const bf16x8*)(y + (int64_t)pos[t * K + s] * D + c * 8);
+      const float* yr = y + (int64_t)pos[t * K + s] * D + c * 8;
+      const float4 y0 = *(const float4*)yr, y1 = *(const float4*)(yr + 4);
+      const float y8[8] = {y0.x, y0.y, y0.z, y0.w, y1.x, y1.y, y1.z, y1.w};
 #pragma unroll
-      for (int e = 0; e < 8; ++e) v[e] = fmaf(g, (float)y8[e], v[e]);
+      for (int e = 0; e < 8; ++e) v[e] = fmaf(g, y8[e], v[e]);
     }
     bf16x8 o;
 #pragma unroll
@@ -157,7 +164,7 @@ __global__ __launch_bounds__(256) void moe_combine_kernel(const bf16* __restrict
   }
 }
 
-__global__ __launch_bounds__(256) void moe_combine_bwd_kernel(const bf16* __restrict__ dx, const bf16* __restrict__ y,
+__global__ __launch_bounds__(256) void moe_combine_bwd_kernel(const bf16* __restrict__ dx, const float* __restrict__ y,
                                                               const int32_t* __restrict__ pos,
                                                               const int32_t* __restrict__ experts,
                                                               const float* __restrict__ gates, int64_t M, int D, int E,
@@ -172,12 +179,14 @@ __global__ __launch_bounds__(256) void moe_combine_bwd_kernel(const bf16* __rest
     for (int s = 0; s < K; ++s) {
       const int64_t row = pos[t * K + s];
       const float g = gates[t * K + s];
-      const bf16x8 y8 = *(const bf16x8*)(y + row * D + c * 8);
+      const float* yr = y + row * D + c * 8;
+      const float4 y0 = *(const float4*)yr, y1 = *(const float4*)(yr + 4);
+      const float y8[8] = {y0.x, y0.y, y0.z, y0.w, y1.x, y1.y, y1.z, y1.w};
       bf16x8 o;
       float a = 0.f;
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
-        a = fmaf((float)d8[e], (float)y8[e], a);
+        a = fmaf((float)d8[e], y8[e], a);
         o[e] = (bf16)(g * (float)d8[e]);
       }
       *(bf16x8*)(dy + row * D + c * 8) = o;
@@ -231,16 +240,22 @@ __global__ __launch_bounds__(256) void moe_unpermute_bwd_kernel(const bf16* __re
 
 }  // namespace
 
-void moe_route(const void* h, int64_t M, int D, const float* w_router, int E, int K, const int32_t* forced,
-               float* logits, int32_t* experts, float* gates, hipStream_t s) {
+void moe_topk(const float* logits, int64_t M, int E, int K, const int32_t* forced, int32_t* experts, float* gates,
+              hipStream_t s) {
   if (M <= 0) return;
-  moe_route_kernel<<<(unsigned)((M + 3) / 4), 256, 0, s>>>((const bf16*)h, M, D, w_router, E, K, forced, logits, experts,
-                                                         gates);
+  const unsigned grid = (unsigned)((M + 255) / 256);
+  if (E <= 8) moe_topk_kernel<8><<<grid, 256, 0, s>>>(logits, M, E, K, forced, experts, gates);
+  else if (E <= 16) moe_topk_kernel<16><<<grid, 256, 0, s>>>(logits, M, E, K, forced, experts, gates);
+  else moe_topk_kernel<32><<<grid, 256, 0, s>>>(logits, M, E, K, forced, experts, gates);
+}
+
+void moe_router_copy(const float* w_router, int D, int E, void* t_router, hipStream_t s) {
+  moe_router_copy_kernel<<<(D * E + 255) / 256, 256, 0, s>>>(w_router, D, E, (bf16*)t_router);
 }
 
 void moe_sort(const int32_t* experts, int64_t M, int E, int K, int32_t* off, int32_t* pos, int32_t* perm_tok,
               hipStream_t s) {
-  moe_sort_kernel<<<1, 1024, 0, s>>>(experts, M * K, E, K, off, pos, perm_tok);
+  moe_sort_kernel<<<E, 1024, 0, s>>>(experts, M * K, E, K, off, pos, perm_tok);
 }
 
 void moe_gather_rows(const void* x, const int32_t* src, int64_t rows, int D, void* y, hipStream_t s) {
@@ -252,14 +267,14 @@ void moe_gather_rows(const void* x, const int32_t* src, int64_t rows, int D, voi
 void moe_combine(const void* y, const int32_t* pos, const float* gates, const void* res, int64_t M, int D, int K,
                  void* x_out, hipStream_t s) {
   if (M <= 0) return;
-  moe_combine_kernel<<<(unsigned)((M + 3) / 4), 256, 0, s>>>((const bf16*)y, pos, gates, (const bf16*)res, M, D, K,
+  moe_combine_kernel<<<(unsigned)((M + 3) / 4), 256, 0, s>>>((const float*)y, pos, gates, (const bf16*)res, M, D, K,
                                                            (bf16*)x_out);
 }
 
 void moe_combine_bwd(const void* dx, const void* y, const int32_t* pos, const int32_t* experts, const float* gates,
                      int64_t M, int D, int E, int K, void* dy, float* dsel, void* dlogits, hipStream_t s) {
   if (M <= 0) return;
-  moe_combine_bwd_kernel<<<(unsigned)((M + 3) / 4), 256, 0, s>>>((const bf16*)dx, (const bf16*)y, pos, experts, gates, M,
+  moe_combine_bwd_kernel<<<(unsigned)((M + 3) / 4), 256, 0, s>>>((const bf16*)dx, (const float*)y, pos, experts, gates, M,
                                                                D, E, K, (bf16*)dy, dsel, (bf16*)dlogits);
 }
 

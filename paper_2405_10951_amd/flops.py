@@ -5,11 +5,16 @@ from __future__ import annotations
 
 
 def step_flops(dim: int, mlp_hidden: int, num_classes: int, patch_dim: int, n_patches: int,
-               tokens_attn: list[int], tokens_mlp: list[int], first_trainable: int, batch: int) -> dict:
+               tokens_attn: list[int], tokens_mlp: list[int], first_trainable: int, batch: int,
+               moe_blocks=(), n_experts: int = 0, moe_top_k: int = 0) -> dict:
+    """A mixture-of-experts block (Sec. 5.3) runs moe_top_k expert FFNs per token plus the router."""
     D, F = dim, mlp_hidden
     fwd_gemm = fwd_attn = bwd_gemm = bwd_attn = 0.0
     for l, (Ta, Tm) in enumerate(zip(tokens_attn, tokens_mlp)):
-        g = 2.0 * (4 * Ta * D * D + 2 * Tm * D * F)      # QKV + proj + fc1 + fc2
+        ffn = 2 * Tm * D * F
+        if l in moe_blocks:
+            ffn = moe_top_k * ffn + Tm * D * n_experts
+        g = 2.0 * (4 * Ta * D * D + ffn)                 # QKV + proj + fc1 + fc2 (or experts + router)
         a = 4.0 * Ta * Ta * D                            # Q K^T and P V over all heads
         fwd_gemm += g
         fwd_attn += a

@@ -23,6 +23,10 @@ def hip():
 
 
 def setup(name, std=0.05, **over):
+    # batch 16 for the small model: in the last block only the CLS rows carry gradient, and with a
+    # handful of rows the LayerNorm parameter gradients sit at the bf16 noise floor
+    if name == "mini_moe":
+        over.setdefault("batch", 16)
     cfg = S.get_config(name, dtype="bf16", **over)
     p = S.make_params(cfg, std=std, bf16_exact=True)
     x, y = S.make_inputs(cfg, bf16_exact=True)
