@@ -62,6 +62,16 @@ CONFIGS = {
                          drop_blocks=[3, 6, 9], keep_ratio=0.7, first_trainable=8,
                          n_experts=16, moe_top_k=2, moe_blocks=[1, 3, 5, 7, 9, 11],
                          dtype="bf16", loss=LOSS_CE, batch=32),
+    # the paper's default layout (Sec. 5, Table 7): every fourth block trained, the blocks between
+    # them frozen but in the gradient path (input gradients only, Eq. 2 / Eq. 3), drop rate 0.5
+    "c6_vit_b_interleaved": dict(image_size=224, patch_size=16, in_chans=3, tokens_in=0,
+                                 dim=768, heads=12, mlp_hidden=3072, depth=12, num_classes=100,
+                                 drop_blocks=[3, 6, 9], keep_ratio=0.5, first_trainable=3,
+                                 trainable_blocks=[3, 7, 11], dtype="bf16", loss=LOSS_CE, batch=32),
+    "mini_interleaved": dict(image_size=64, patch_size=8, in_chans=3, tokens_in=0,
+                             dim=128, heads=2, mlp_hidden=256, depth=6, num_classes=10,
+                             drop_blocks=[1, 3], keep_ratio=0.6, first_trainable=1,
+                             trainable_blocks=[1, 3, 5], dtype="fp32", loss=LOSS_CE, batch=5),
     # small mixture-of-experts models
     "tiny_moe": dict(image_size=16, patch_size=4, in_chans=3, tokens_in=0,
                      dim=32, heads=2, mlp_hidden=48, depth=3, num_classes=5,
@@ -81,6 +91,12 @@ def get_config(name: str, **overrides) -> dict:
     cfg.update(overrides)
     cfg["name"] = name
     return cfg
+
+
+def is_trainable_block(cfg: dict, l: int) -> bool:
+    """Blocks listed in trainable_blocks, or (no list) every block from first_trainable on."""
+    tb = cfg.get("trainable_blocks")
+    return (l in tb) if tb else (l >= cfg["first_trainable"])
 
 
 def tokens_at_input(cfg: dict) -> int:

@@ -176,8 +176,10 @@ class Oracle:
         gp = None
         if want_grads:
             for name, a in params.items():
+                tb = cfg.get("trainable_blocks")
                 trainable = name in ("lnf_g", "lnf_b", "w_head", "b_head") or (
-                    name.startswith("blocks.") and int(name.split(".")[1]) >= ft)
+                    name.startswith("blocks.") and
+                    ((int(name.split(".")[1]) in tb) if tb else int(name.split(".")[1]) >= ft))
                 if trainable:
                     grads[name] = np.zeros(a.shape, dtype=self.dtype)
             gp = self._params(grads, keepalive)

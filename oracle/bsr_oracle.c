@@ -573,7 +573,10 @@ static void free_saved(saved_block* s) {
  * logits       out, may be NULL: [B,num_classes]
  * loss         out: scalar
  * grads        NULL (forward only) or a table whose non-NULL entries receive dL/dparam of the
- *              trainable tensors (overwritten)
+ *              trainable tensors (overwritten).  A block at or after first_trainable whose entries
+ *              are all NULL is frozen but in the gradient path (the paper's default layout trains
+ *              every fourth block): it keeps its activations and only passes the input gradient
+ *              on (Eq. 2, Eq. 3), no weight gradient is formed for it
  * dx_trainable out, may be NULL: dL/d(x_trainable), computed only on request (tests); the method
  *              itself never propagates this far (Fig. 2)
  * forced_experts  NULL, or the expert choice to use in the mixture-of-experts blocks (concatenated

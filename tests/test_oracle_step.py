@@ -206,3 +206,31 @@ def test_bad_configuration_is_rejected(orc64):
         orc64.step(dict(cfg, drop_blocks=[1, 0]), p, x, y, keep_k=[5, 3])
     with pytest.raises(ValueError):
         orc64.step(cfg, p, x, y, keep_k=[99])
+
+
+# ------------------------------------------------------------------ interleaved trainable layout
+
+def test_interleaved_layout_against_torch_and_finite_differences(orc64):
+    """Trainable blocks {1,3,5} with frozen blocks between them (the paper's default layout, Sec. 5):
+    the frozen blocks in the path pass the input gradient on and get no weight gradient."""
+    cfg, p, x, y = setup("mini_interleaved")
+    r = orc64.step(cfg, p, x, y, want_dx=True)
+    t = torch_reference.run(cfg, p, x, y, r["kept_idx"])
+    assert abs(r["loss"] - t["loss"]) < 1e-10
+    names = set(r["grads"])
+    assert names == set(t["grads"])
+    assert not any(n.startswith(("blocks.0.", "blocks.2.", "blocks.4.")) for n in names)
+    assert any(n.startswith("blocks.1.") for n in names) and any(n.startswith("blocks.5.") for n in names)
+    for n in names:
+        assert rel(r["grads"][n], t["grads"][n]) < 1e-8, n
+    assert rel(r["dx_trainable"], t["dx_trainable"]) < 1e-8
+    # central differences through the frozen blocks 2 and 4 into block 1
+    eps = 1e-6
+    for name, ix in (("blocks.1.w_fc1", (3, 5)), ("blocks.1.ln1_g", (7,)), ("blocks.3.w_qkv", (2, 9))):
+        pp, pm = dict(p), dict(p)
+        pp[name] = p[name].astype(np.float64).copy(); pp[name][ix] += eps
+        pm[name] = p[name].astype(np.float64).copy(); pm[name][ix] -= eps
+        lp = orc64.step(cfg, pp, x, y, forced_idx=r["kept_idx"], want_grads=False)["loss"]
+        lm = orc64.step(cfg, pm, x, y, forced_idx=r["kept_idx"], want_grads=False)["loss"]
+        fd = (lp - lm) / (2 * eps)
+        assert abs(fd - r["grads"][name][ix]) < 1e-6 * max(1.0, abs(fd)), (name, fd, r["grads"][name][ix])

@@ -35,9 +35,10 @@ def run(cfg, params, x, labels, kept_idx, dtype=torch.float64, eps=1e-6, experts
     P = {k: torch.tensor(v, dtype=dtype) for k, v in params.items()}
     ft, L, D, H = cfg["first_trainable"], cfg["depth"], cfg["dim"], cfg["heads"]
     d = D // H
+    tb = cfg.get("trainable_blocks")
     for name, t in P.items():
-        tr = name in ("lnf_g", "lnf_b", "w_head", "b_head") or (
-            name.startswith("blocks.") and int(name.split(".")[1]) >= ft)
+        blk = int(name.split(".")[1]) if name.startswith("blocks.") else -1
+        tr = name in ("lnf_g", "lnf_b", "w_head", "b_head") or (blk >= 0 and ((blk in tb) if tb else blk >= ft))
         t.requires_grad_(tr)
     x = torch.tensor(x, dtype=dtype)
     B = x.shape[0]
