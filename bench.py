@@ -142,7 +142,7 @@ def main():
         return step_flops(c["dim"], c["mlp_hidden"], c["num_classes"], pd, ctx.tokens_attn[0] - 1,
                           ctx.tokens_attn, ctx.tokens_mlp, c["first_trainable"], batch,
                           moe_blocks=tuple(c.get("moe_blocks", ())), n_experts=c.get("n_experts", 0),
-                          moe_top_k=c.get("moe_top_k", 0))
+                          moe_top_k=c.get("moe_top_k", 0), trainable_blocks=c.get("trainable_blocks"))
 
     ctx = build_context(cfg, batch)
     r = time_steps(ctx, cfg, batch, args.steps, args.warmup, profile_steps=min(args.steps, 10))
@@ -159,7 +159,8 @@ def main():
         "vs_baseline": None, "dtype": cfg["dtype"], "data": "synthetic",
         "config": {"workload": f"{args.workload}: ViT dim {cfg['dim']} depth {cfg['depth']} batch {batch}, "
                                f"keep {cfg['keep_ratio']} at blocks {cfg['drop_blocks']}, "
-                               f"trainable blocks {cfg['first_trainable']}..{cfg['depth'] - 1} + head, "
+                               + (f"trainable blocks {cfg['trainable_blocks']} + head, " if cfg.get("trainable_blocks")
+                                  else f"trainable blocks {cfg['first_trainable']}..{cfg['depth'] - 1} + head, ")
                                + (f"{cfg['n_experts']}-expert top-{cfg['moe_top_k']} FFN in blocks {cfg['moe_blocks']}, "
                                   if cfg.get("moe_blocks") else "")
                                + "SGD momentum 0.9",

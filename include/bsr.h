@@ -76,6 +76,14 @@ typedef struct {
   int32_t moe_top_k;                        /* K experts active per token, 1..4                    */
   int32_t n_moe;                            /* number of mixture-of-experts blocks                 */
   int32_t moe_blocks[BSR_MAX_BLOCKS];       /* their block indices, strictly ascending             */
+  /* Trainable set as a list (the paper's default layout trains every fourth block, Sec. 5 /
+   * Table 7).  n_trainable == 0: blocks [first_trainable_block, depth) are trained.  Otherwise
+   * first_trainable_block is ignored and taken as trainable_blocks[0]; a block after it that is not
+   * listed is frozen but lies in the gradient path: it keeps the inputs of its non-linear layers and
+   * only passes the input gradient on (Eq. 2, Eq. 3), it gets no weight gradient and its entries in
+   * the gradient / momentum tables may be NULL. */
+  int32_t n_trainable;
+  int32_t trainable_blocks[BSR_MAX_BLOCKS]; /* strictly ascending block indices                    */
 } bsr_config;
 
 /* Tables of device pointers, one per tensor (fp32).  The same struct describes parameters,

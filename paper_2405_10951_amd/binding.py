@@ -32,7 +32,8 @@ class bsr_config(C.Structure):
                 ("keep_ratio", C.c_float), ("first_trainable_block", C.c_int32),
                 ("dtype", C.c_int32), ("loss", C.c_int32), ("ln_eps", C.c_float),
                 ("n_experts", C.c_int32), ("moe_top_k", C.c_int32), ("n_moe", C.c_int32),
-                ("moe_blocks", C.c_int32 * MAX_BLOCKS)]
+                ("moe_blocks", C.c_int32 * MAX_BLOCKS),
+                ("n_trainable", C.c_int32), ("trainable_blocks", C.c_int32 * MAX_BLOCKS)]
 
 
 class bsr_block_params(C.Structure):
@@ -130,6 +131,12 @@ def make_config(cfg: dict, max_batch: int, keep_k=None) -> bsr_config:
         c.moe_blocks[i] = int(b)
     c.n_experts = int(cfg.get("n_experts", 0))
     c.moe_top_k = int(cfg.get("moe_top_k", 0))
+    tb = list(cfg.get("trainable_blocks") or [])
+    c.n_trainable = len(tb)
+    for i, b in enumerate(tb):
+        c.trainable_blocks[i] = int(b)
+    if tb:
+        c.first_trainable_block = int(tb[0])
     return c
 
 
@@ -272,8 +279,10 @@ class Context:
         self.T_last = self.tokens_mlp[L - 1]
         self.frozen_drops = [i for i in range(self.c.n_drop) if self.c.drop_blocks[i] < ft]
         self.train_drops = [i for i in range(self.c.n_drop) if self.c.drop_blocks[i] >= ft]
+        tb = [self.c.trainable_blocks[i] for i in range(self.c.n_trainable)]
         self.trainable_names = [n for n in self.params if n in HEAD_FIELDS or
-                                (n.startswith("blocks.") and int(n.split(".")[1]) >= ft)]
+                                (n.startswith("blocks.") and
+                                 ((int(n.split(".")[1]) in tb) if tb else int(n.split(".")[1]) >= ft))]
 
     def _stream(self):
         return C.c_void_p(self.torch.cuda.current_stream(self.device).cuda_stream)

@@ -26,6 +26,8 @@ struct Schedule {
   int Tm[BSR_MAX_BLOCKS] = {};      // tokens seen by FFN of block l
   int drop_of[BSR_MAX_BLOCKS];      // drop index of block l, or -1
   int T_last = 0;
+  int ft = 0;                       // first trainable block: blocks before it are the frozen prefix
+  bool trainable[BSR_MAX_BLOCKS] = {};  // block l is trained (others at or after ft: frozen, in the gradient path)
   bool moe[BSR_MAX_BLOCKS] = {};    // block l has a mixture-of-experts FFN
   int moe_row0[BSR_MAX_BLOCKS] = {};// per image: tokens of the mixture blocks before l (routing I/O layout)
 };
@@ -165,6 +167,19 @@ int make_schedule(const bsr_config* c, Schedule* s, char* why, size_t whyn) {
     s->Tm[l] = T;
   }
   s->T_last = T;
+  if (c->n_trainable < 0 || c->n_trainable > BSR_MAX_BLOCKS) BAD("n_trainable %d out of range", c->n_trainable);
+  if (c->n_trainable == 0) {
+    s->ft = c->first_trainable_block;
+    for (int l = s->ft; l < c->depth; ++l) s->trainable[l] = true;
+  } else {
+    for (int i = 0; i < c->n_trainable; ++i) {
+      const int blk = c->trainable_blocks[i];
+      if (blk < 0 || blk >= c->depth) BAD("trainable_blocks[%d] = %d out of range", i, blk);
+      if (i && blk <= c->trainable_blocks[i - 1]) BAD("trainable_blocks must be strictly ascending");
+      s->trainable[blk] = true;
+    }
+    s->ft = c->trainable_blocks[0];
+  }
   if (c->n_moe < 0 || c->n_moe > BSR_MAX_BLOCKS) BAD("n_moe %d out of range", c->n_moe);
   if (c->n_moe > 0) {
     if (c->dtype != BSR_BF16) BAD("mixture-of-experts blocks need dtype bf16");
@@ -206,7 +221,7 @@ size_t carve(const bsr_config& c, const Schedule& s, char* base, Buffers* out) {
   const bool f32 = c.dtype == BSR_FP32;
   const size_t E = f32 ? 4 : 2;
   const size_t B = c.max_batch, D = c.dim, F = c.mlp_hidden, H = c.heads, T0 = s.T0;
-  const int ft = c.first_trainable_block, L = c.depth;
+  const int ft = s.ft, L = c.depth;
   const size_t Kp = (size_t)c.in_chans * c.patch_size * c.patch_size;
   if (!f32) {
     if (c.image_size) b.t_patch = w.take<bf16>(D * Kp);
@@ -263,15 +278,16 @@ size_t carve(const bsr_config& c, const Schedule& s, char* base, Buffers* out) {
     v.mean2 = w.take<float>(B * Tm);
     v.rstd2 = w.take<float>(B * Tm);
     v.lse = w.take<float>(B * H * Ta);
-    v.h1 = w.take<char>(B * Ta * D * E);
+    const bool keep_lin = s.trainable[l] || s.moe[l];   // inputs of the linear layers: only Eq. 4 needs them
+    v.h1 = keep_lin ? w.take<char>(B * Ta * D * E) : b.h;
     v.qkv = w.take<char>(B * Ta * 3 * D * E);
     v.o = w.take<char>(B * Ta * D * E);
     v.xmid_full = w.take<char>(B * Ta * D * E);
     v.xmid = (s.drop_of[l] >= 0) ? w.take<char>(B * Tm * D * E) : v.xmid_full;
-    v.h2 = w.take<char>(B * Tm * D * E);
+    v.h2 = keep_lin ? w.take<char>(B * Tm * D * E) : b.h;
     const size_t kf = s.moe[l] ? KE : 1;               // a mixture block keeps u and g per (token, slot)
     v.u = w.take<char>(B * Tm * kf * F * E);
-    v.g = w.take<char>(B * Tm * kf * F * E);
+    v.g = keep_lin ? w.take<char>(B * Tm * kf * F * E) : b.g;
     if (s.moe[l]) take_moe(v.moe, B * Tm);
     v.xout = w.take<char>(B * Tm * D * E);
     v.idx = w.take<int32_t>(B * Tm);
@@ -421,7 +437,7 @@ void moe_ffn_forward(bsr_ctx* c, int l, int B, const void* h, const void* x_res,
 // differentiated through the softmax over the selected logits.  Expert weights get Eq. 4 over the
 // rows routed to them (grouped wgrad), the router gets dW_r = h^T dlogits.
 void moe_ffn_backward(bsr_ctx* c, int l, const void* dx, int M2, SavedBlock& v, const bsr_block_params& gw, void* dh,
-                      hipStream_t s) {
+                      bool train, hipStream_t s) {
   const bsr_config& cf = c->cfg;
   Buffers& b = c->b;
   const int D = cf.dim, F = cf.mlp_hidden, E = cf.n_experts, K = cf.moe_top_k;
@@ -434,19 +450,23 @@ void moe_ffn_backward(bsr_ctx* c, int l, const void* dx, int M2, SavedBlock& v, 
   d1.act = ACT_GELU_BWD; d1.aux = v.u;
   d1.grp_off = m.off; d1.groups = E; d1.b_gs = (int64_t)D * F;
   gemm(c, d1, s);
-  GemmDesc w2 = wgrad_desc(c, v.g, b.moe_dy, R, F, D, gw.w_fc2);
-  w2.bsum = (float*)gw.b_fc2;
-  w2.grp_off = m.off; w2.groups = E; w2.c_gs = (int64_t)F * D; w2.bsum_gs = D;
-  gemm(c, w2, s);
+  if (train) {
+    GemmDesc w2 = wgrad_desc(c, v.g, b.moe_dy, R, F, D, gw.w_fc2);
+    w2.bsum = (float*)gw.b_fc2;
+    w2.grp_off = m.off; w2.groups = E; w2.c_gs = (int64_t)F * D; w2.bsum_gs = D;
+    gemm(c, w2, s);
+  }
   GemmDesc d2 = dgrad_desc(c, b.dgu, R, D, F, nullptr, sh.s_fc1, b.moe_dxg);     // gradient at the gathered tokens
   d2.grp_off = m.off; d2.groups = E; d2.b_gs = (int64_t)D * F;
   gemm(c, d2, s);
-  GemmDesc w1 = wgrad_desc(c, m.xg, b.dgu, R, D, F, gw.w_fc1);
-  w1.bsum = (float*)gw.b_fc1;
-  w1.grp_off = m.off; w1.groups = E; w1.c_gs = (int64_t)D * F; w1.bsum_gs = F;
-  gemm(c, w1, s);
+  if (train) {
+    GemmDesc w1 = wgrad_desc(c, m.xg, b.dgu, R, D, F, gw.w_fc1);
+    w1.bsum = (float*)gw.b_fc1;
+    w1.grp_off = m.off; w1.groups = E; w1.c_gs = (int64_t)D * F; w1.bsum_gs = F;
+    gemm(c, w1, s);
+  }
   moe_unpermute_bwd(b.moe_dxg, m.pos, m.experts, m.dsel, (const float*)w.w_router, M2, D, E, K, dh, s);
-  gemm(c, wgrad_desc(c, v.h2, b.moe_dlog, M2, D, E, gw.w_router), s);             // dW_r = h^T dlogits
+  if (train) gemm(c, wgrad_desc(c, v.h2, b.moe_dlog, M2, D, E, gw.w_router), s);  // dW_r = h^T dlogits
 }
 
 void attention_fwd(bsr_ctx* c, const void* qkv, int B, int T, void* out, float* lse, float* clsp,
@@ -517,10 +537,13 @@ void build_shadows(bsr_ctx* c, int first_block, hipStream_t s) {
     if (c->sc.moe[l]) moe_router_copy((const float*)c->p.blocks[l].w_router, D, cf.n_experts, c->b.sh[l].t_router, s);
 }
 
-int check_params(const bsr_config& cf, const bsr_params* p, int first_block, bool need_stem, const char** which) {
+// only_trainable: a table of gradients or momenta (entries of frozen blocks are not read)
+int check_params(const bsr_config& cf, const bsr_params* p, int first_block, bool need_stem, const char** which,
+                 const Schedule* only_trainable = nullptr) {
 #define NEED(ptr, name) if (!aligned16(ptr)) { *which = name; return BSR_ERR_INVALID_ARG; }
   if (need_stem && cf.image_size) { NEED(p->w_patch, "w_patch"); NEED(p->b_patch, "b_patch"); NEED(p->cls, "cls"); NEED(p->pos, "pos"); }
   for (int l = first_block; l < cf.depth; ++l) {
+    if (only_trainable && !only_trainable->trainable[l]) continue;
     const bsr_block_params& w = p->blocks[l];
     NEED(w.ln1_g, "ln1_g"); NEED(w.ln1_b, "ln1_b"); NEED(w.w_qkv, "w_qkv"); NEED(w.b_qkv, "b_qkv");
     NEED(w.w_proj, "w_proj"); NEED(w.b_proj, "b_proj"); NEED(w.ln2_g, "ln2_g"); NEED(w.ln2_b, "ln2_b");
@@ -587,6 +610,7 @@ int32_t bsr_init(const bsr_config* cfg, const bsr_params* params, void* workspac
   bsr_ctx* c = new (std::nothrow) bsr_ctx();
   if (!c) return fail(nullptr, BSR_ERR_INVALID_ARG, "out of host memory");
   c->cfg = *cfg;
+  c->cfg.first_trainable_block = s.ft;      // (from trainable_blocks[0] when a list is given)
   c->p = *params;
   c->sc = s;
   c->f32 = cfg->dtype == BSR_FP32;
@@ -705,7 +729,7 @@ int32_t bsr_train_blocks_fwd_bwd(bsr_ctx* c, const void* x_in, const int32_t* la
   if (cf.loss == BSR_LOSS_CE && !labels) return fail(c, BSR_ERR_INVALID_ARG, "labels are required for the cross-entropy loss");
   if (B < 1 || B > cf.max_batch) return fail(c, BSR_ERR_INVALID_ARG, "B = %d outside 1..max_batch (%d)", B, cf.max_batch);
   const char* which = "";
-  if (check_params(cf, grads, cf.first_trainable_block, false, &which) != BSR_OK)
+  if (check_params(cf, grads, cf.first_trainable_block, false, &which, &c->sc) != BSR_OK)
     return fail(c, BSR_ERR_INVALID_ARG, "gradient tensor %s is NULL or not 16-byte aligned", which);
   hipStream_t s = (hipStream_t)stream;
   const Schedule& sc = c->sc;
@@ -800,20 +824,25 @@ int32_t bsr_train_blocks_fwd_bwd(bsr_ctx* c, const void* x_in, const int32_t* la
     const int di = sc.drop_of[l];
     const char* xin = (l == ft) ? (const char*)x_in : b.sv[l - 1].xout;
 
+    // A frozen block in the gradient path (tr == false) only passes the input gradient on (Eq. 2, 3).
+    const bool tr = sc.trainable[l];
     // FFN branch.  du = (dx . W2^T) * GELU'(u); dW2 = g^T dx; dh2 = du . W1^T; dW1 = h2^T du
     if (sc.moe[l]) {
-      moe_ffn_backward(c, l, dx, M2, v, gw, b.dh, s);
+      moe_ffn_backward(c, l, dx, M2, v, gw, b.dh, tr, s);
     } else {
       GemmDesc d1 = dgrad_desc(c, dx, M2, F, D, w.w_fc2, sh.s_fc2, b.dgu);
       d1.act = ACT_GELU_BWD;
       d1.aux = v.u;
       gemm(c, d1, s);
-      wgrad(c, v.g, dx, M2, F, D, gw.w_fc2, gw.b_fc2, s);
+      if (tr) wgrad(c, v.g, dx, M2, F, D, gw.w_fc2, gw.b_fc2, s);
       gemm(c, dgrad_desc(c, b.dgu, M2, D, F, w.w_fc1, sh.s_fc1, b.dh), s);
-      wgrad(c, v.h2, b.dgu, M2, D, F, gw.w_fc1, gw.b_fc1, s);
+      if (tr) wgrad(c, v.h2, b.dgu, M2, D, F, gw.w_fc1, gw.b_fc1, s);
     }
-    layernorm_bwd(b.dh, v.xmid, v.mean2, v.rstd2, (const float*)w.ln2_g, dx, M2, D, f32, dx_other, b.partial,
-                  (float*)gw.ln2_g, (float*)gw.ln2_b, s);
+    if (tr)
+      layernorm_bwd(b.dh, v.xmid, v.mean2, v.rstd2, (const float*)w.ln2_g, dx, M2, D, f32, dx_other, b.partial,
+                    (float*)gw.ln2_g, (float*)gw.ln2_b, s);
+    else
+      layernorm_bwd_dx(b.dh, v.xmid, v.mean2, v.rstd2, (const float*)w.ln2_g, dx, M2, D, f32, dx_other, s);
     std::swap(dx, dx_other);   // dx: gradient at x_mid (kept tokens)
 
     // adjoint of the token drop: dropped tokens receive nothing from the FFN side
@@ -824,13 +853,16 @@ int32_t bsr_train_blocks_fwd_bwd(bsr_ctx* c, const void* x_in, const int32_t* la
 
     // MHSA branch.  dO = dx . Wproj^T; dWproj = o^T dx; attention backward; dWqkv = h1^T dqkv
     gemm(c, dgrad_desc(c, dx, M, D, D, w.w_proj, sh.s_proj, b.dh), s);
-    wgrad(c, v.o, dx, M, D, D, gw.w_proj, gw.b_proj, s);
+    if (tr) wgrad(c, v.o, dx, M, D, D, gw.w_proj, gw.b_proj, s);
     attention_bwd(c, v.qkv, v.o, b.dh, v.lse, B, Ta, b.dqkv, s);
-    wgrad(c, v.h1, b.dqkv, M, D, 3 * D, gw.w_qkv, gw.b_qkv, s);
+    if (tr) wgrad(c, v.h1, b.dqkv, M, D, 3 * D, gw.w_qkv, gw.b_qkv, s);
     gemm(c, dgrad_desc(c, b.dqkv, M, D, 3 * D, w.w_qkv, sh.s_qkv, b.dh), s);
     // the gradient is not carried below the earliest trainable block (Fig. 2): no dx there
-    layernorm_bwd(b.dh, xin, v.mean1, v.rstd1, (const float*)w.ln1_g, dx, M, D, f32, l > ft ? dx_other : nullptr,
-                  b.partial, (float*)gw.ln1_g, (float*)gw.ln1_b, s);
+    if (tr)
+      layernorm_bwd(b.dh, xin, v.mean1, v.rstd1, (const float*)w.ln1_g, dx, M, D, f32, l > ft ? dx_other : nullptr,
+                    b.partial, (float*)gw.ln1_g, (float*)gw.ln1_b, s);
+    else
+      layernorm_bwd_dx(b.dh, xin, v.mean1, v.rstd1, (const float*)w.ln1_g, dx, M, D, f32, dx_other, s);
     if (l > ft) std::swap(dx, dx_other);
   }
   return check_hip(c, "bsr_train_blocks_fwd_bwd");
@@ -856,9 +888,9 @@ int32_t bsr_sgd_step(bsr_ctx* c, const bsr_params* grads, const bsr_params* mome
   if (momentum > 0.f && !momenta) return fail(c, BSR_ERR_INVALID_ARG, "momenta is NULL but momentum > 0");
   const bsr_config& cf = c->cfg;
   const char* which = "";
-  if (check_params(cf, grads, cf.first_trainable_block, false, &which) != BSR_OK)
+  if (check_params(cf, grads, cf.first_trainable_block, false, &which, &c->sc) != BSR_OK)
     return fail(c, BSR_ERR_INVALID_ARG, "gradient tensor %s is NULL or not 16-byte aligned", which);
-  if (momentum > 0.f && check_params(cf, momenta, cf.first_trainable_block, false, &which) != BSR_OK)
+  if (momentum > 0.f && check_params(cf, momenta, cf.first_trainable_block, false, &which, &c->sc) != BSR_OK)
     return fail(c, BSR_ERR_INVALID_ARG, "momentum tensor %s is NULL or not 16-byte aligned", which);
   hipStream_t s = (hipStream_t)stream;
   const int D = cf.dim, F = cf.mlp_hidden;
@@ -876,6 +908,7 @@ int32_t bsr_sgd_step(bsr_ctx* c, const bsr_params* grads, const bsr_params* mome
     if (mats.count == MAT_TABLE_MAX) { matrix_table_run(mats, true, lr, momentum, weight_decay, s); mats = MatTable(); }
   };
   for (int l = cf.first_trainable_block; l < cf.depth; ++l) {
+    if (!c->sc.trainable[l]) continue;
     const bsr_block_params& W = c->p.blocks[l];
     const bsr_block_params& G = grads->blocks[l];
     const bsr_block_params& Mo = mom ? momenta->blocks[l] : grads->blocks[l];
@@ -910,7 +943,8 @@ int32_t bsr_sgd_step(bsr_ctx* c, const bsr_params* grads, const bsr_params* mome
   sgd_table(tab, ntab, lr, momentum, weight_decay, s);
   matrix_table_run(mats, true, lr, momentum, weight_decay, s);
   for (int l = cf.first_trainable_block; l < cf.depth; ++l)      // the routers were updated as vectors
-    if (c->sc.moe[l]) moe_router_copy((const float*)c->p.blocks[l].w_router, D, cf.n_experts, c->b.sh[l].t_router, s);
+    if (c->sc.moe[l] && c->sc.trainable[l])
+      moe_router_copy((const float*)c->p.blocks[l].w_router, D, cf.n_experts, c->b.sh[l].t_router, s);
   return check_hip(c, "bsr_sgd_step");
 }
 

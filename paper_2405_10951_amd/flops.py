@@ -6,8 +6,10 @@ from __future__ import annotations
 
 def step_flops(dim: int, mlp_hidden: int, num_classes: int, patch_dim: int, n_patches: int,
                tokens_attn: list[int], tokens_mlp: list[int], first_trainable: int, batch: int,
-               moe_blocks=(), n_experts: int = 0, moe_top_k: int = 0) -> dict:
-    """A mixture-of-experts block (Sec. 5.3) runs moe_top_k expert FFNs per token plus the router."""
+               moe_blocks=(), n_experts: int = 0, moe_top_k: int = 0, trainable_blocks=None) -> dict:
+    """A mixture-of-experts block (Sec. 5.3) runs moe_top_k expert FFNs per token plus the router.
+    trainable_blocks (a list): blocks at or after first_trainable that are not in it are frozen in the
+    gradient path and run the input gradients only."""
     D, F = dim, mlp_hidden
     fwd_gemm = fwd_attn = bwd_gemm = bwd_attn = 0.0
     for l, (Ta, Tm) in enumerate(zip(tokens_attn, tokens_mlp)):
@@ -19,7 +21,8 @@ def step_flops(dim: int, mlp_hidden: int, num_classes: int, patch_dim: int, n_pa
         fwd_gemm += g
         fwd_attn += a
         if l >= first_trainable:
-            bwd_gemm += 2.0 * g                          # dgrad + wgrad of every linear (Eq. 2, 4)
+            trained = (l in trainable_blocks) if trainable_blocks else True
+            bwd_gemm += (2.0 if trained else 1.0) * g    # dgrad + wgrad of every linear (Eq. 2, 4), or dgrad only
             bwd_attn += 2.5 * a                          # dV, dP, dQ, dK and the recomputed Q K^T
     stem = 2.0 * n_patches * patch_dim * D
     head = 3 * 2.0 * D * num_classes

@@ -250,3 +250,43 @@ def test_headline_workload_full_size(hip, orc32):
     for b in range(32):
         assert np.array_equal(free["kept_idx"][0][b], orc32.topk(free["scores"][0][b], 137))
         assert len(set(free["kept_idx"][0][b]) & set(ref["kept_idx"][0][b])) >= 130
+
+
+# ------------------------------------------------------------------ interleaved trainable layout
+
+def test_interleaved_layout_fp32(hip, orc64):
+    """Trainable blocks {1,3,5}, frozen blocks 2 and 4 in the gradient path (the paper's default
+    layout, Sec. 5): same loss and gradients as the oracle, and no gradient tensors for frozen blocks."""
+    cfg = S.get_config("mini_interleaved", dtype="fp32")
+    p = S.make_params(cfg, std=0.05)
+    x, y = S.make_inputs(cfg)
+    got, ref, ok = check_step(hip, orc64, cfg, p, x, y, TOL_FP32, free_running=True)
+    assert ok
+    assert not any(n.startswith(("blocks.0.", "blocks.2.", "blocks.4.")) for n in got["grads"])
+
+
+def test_interleaved_layout_bf16_and_sgd(hip, orc64):
+    cfg = S.get_config("mini_interleaved", dtype="bf16", batch=16)
+    p = S.make_params(cfg, std=0.05)
+    x, y = S.make_inputs(cfg)
+    got, ref, ok = check_step(hip, orc64, cfg, p, x, y, TOL_BF16, free_running=False)
+    assert ok
+    # SGD touches the trained blocks only
+    lr = 0.1
+    got = hip.run_hip_step(cfg, p, x, y, forced_idx=ref["kept_idx"], sgd=dict(lr=lr, momentum=0.0, weight_decay=0.0, momenta=None))
+    for n in got["new_params"]:
+        want = p[n] - lr * got["grads"][n]
+        assert np.abs(got["new_params"][n] - want).max() <= 1e-6 * max(1.0, np.abs(want).max()), n
+    ctx = got["ctx"]
+    for n in ("blocks.2.w_fc1", "blocks.4.w_qkv", "blocks.0.w_proj"):
+        assert np.array_equal(ctx.params[n].cpu().numpy(), p[n]), n
+
+
+def test_paper_default_layout_full_size(hip, orc32):
+    """ViT-B/16, trainable {3,7,11}, drops at {3,6,9}, keep 0.5 (batch 4 here; the oracle is fp32)."""
+    cfg = S.get_config("c6_vit_b_interleaved", batch=4)
+    p = S.make_params(cfg)
+    x, y = S.make_inputs(cfg)
+    got, ref, ok = check_step(hip, orc32, cfg, p, x, y, TOL_BF16, free_running=False)
+    assert ok
+    assert got["keep_k"] == [98, 49, 24]
