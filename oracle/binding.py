@@ -20,14 +20,16 @@ BLOCK_FIELDS = ("ln1_g", "ln1_b", "w_qkv", "b_qkv", "w_proj", "b_proj",
                 "ln2_g", "ln2_b", "w_fc1", "b_fc1", "w_fc2", "b_fc2")
 
 
-def token_schedule(n0: int, keep_ratio: float, n_drop: int) -> list[int]:
+def token_schedule(n0: int, keep_ratio: float, n_drop: int, fuse: bool = False) -> list[int]:
     """Patch tokens kept after each drop location: K = floor(r * n) on the current patch count
     (Sec. 4.3, Discussion 3: N/2, N/4, N/8 at drop rate 0.5).  The 1e-9 guards products such as
-    0.29 * 100 that land a hair below an integer in binary floating point."""
+    0.29 * 100 that land a hair below an integer in binary floating point.  With fuse, the dropped
+    tokens of a location become one more patch token of the following blocks."""
     ks, n = [], n0
     for _ in range(n_drop):
-        n = int(math.floor(float(keep_ratio) * n + 1e-9))
-        ks.append(n)
+        k = int(math.floor(float(keep_ratio) * n + 1e-9))
+        ks.append(k)
+        n = k + (1 if fuse and n - k > 0 else 0)
     return ks
 
 
@@ -53,7 +55,8 @@ class _Config(C.Structure):
                 ("n_drop", C.c_int32), ("drop_blocks", C.c_int32 * MAX_BLOCKS),
                 ("keep_k", C.c_int32 * MAX_BLOCKS), ("first_trainable", C.c_int32),
                 ("loss", C.c_int32), ("ln_eps", C.c_double),
-                ("n_experts", C.c_int32), ("moe_top_k", C.c_int32), ("moe_block", C.c_int32 * MAX_BLOCKS)]
+                ("n_experts", C.c_int32), ("moe_top_k", C.c_int32), ("moe_block", C.c_int32 * MAX_BLOCKS),
+                ("fuse_dropped", C.c_int32)]
 
 
 class _Block(C.Structure):
@@ -97,10 +100,12 @@ class Oracle:
         c.n_drop = len(drops)
         n0 = (cfg["image_size"] // cfg["patch_size"]) ** 2 if cfg["image_size"] else cfg["tokens_in"] - 1
         if keep_k is None:
-            keep_k = cfg.get("keep_k") or token_schedule(n0, cfg["keep_ratio"], len(drops))
+            keep_k = cfg.get("keep_k") or token_schedule(n0, cfg["keep_ratio"], len(drops),
+                                                         bool(cfg.get("fuse_dropped")))
         for i, (b, k) in enumerate(zip(drops, keep_k)):
             c.drop_blocks[i] = b
             c.keep_k[i] = k
+        c.fuse_dropped = int(bool(cfg.get("fuse_dropped")))
         c.n_experts = int(cfg.get("n_experts", 0))
         c.moe_top_k = int(cfg.get("moe_top_k", 0))
         for l in cfg.get("moe_blocks", ()):
@@ -144,7 +149,7 @@ class Oracle:
             T_at_block.append(T)
             if di < c.n_drop and c.drop_blocks[di] == l:
                 ns.append(T - 1)
-                T = ks[di] + 1
+                T = ks[di] + 1 + (1 if c.fuse_dropped and T - 1 - ks[di] > 0 else 0)
                 di += 1
         T_last = T
         moe = sorted(cfg.get("moe_blocks", ()))

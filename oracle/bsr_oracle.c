@@ -56,6 +56,8 @@ typedef struct {
   double ln_eps;
   int32_t n_experts, moe_top_k;             /* mixture-of-experts FFN: E experts, K active per token */
   int32_t moe_block[ORC_MAX_BLOCKS];        /* 1: the FFN of this block is a mixture of experts     */
+  int32_t fuse_dropped;                     /* 1: the dropped tokens of a drop location are fused into
+                                               one extra token instead of being discarded (Sec. 4.1) */
 } orc_config;
 
 typedef struct {
@@ -194,6 +196,29 @@ void orc_gather(const real* x, int32_t B, int32_t T, int32_t D, const int32_t* i
     for (int32_t i = 0; i < k; ++i)
       memcpy(y + ((int64_t)b * (k + 1) + 1 + i) * D,
              x + ((int64_t)b * T + 1 + idx[(int64_t)b * k + i]) * D, sizeof(real) * D);
+  }
+}
+
+/* Fusion of the dropped tokens (Sec. 4.1: the unimportant tokens "are fused and passed onto the
+ * subsequent FFN layer"; the rule is the importance-weighted average of the method the paper follows):
+ *   f[b] = sum_{j not kept} a[b,j] x[b,1+j] / sum_{j not kept} a[b,j],   a = importance scores [B,n].
+ * wts [B,n] receives the normalised weight of every dropped token (0 for kept ones); the weights are
+ * constants of the backward pass, like the kept indices. */
+void orc_fuse_dropped(const real* x, const real* a, int32_t B, int32_t T, int32_t D, const int32_t* idx,
+                      int32_t k, real* wts, real* f) {
+  const int32_t n = T - 1;
+  for (int32_t b = 0; b < B; ++b) {
+    real* w = wts + (int64_t)b * n;
+    for (int32_t j = 0; j < n; ++j) w[j] = a[(int64_t)b * n + j];
+    for (int32_t i = 0; i < k; ++i) w[idx[(int64_t)b * k + i]] = 0;
+    real sum = 0;
+    for (int32_t j = 0; j < n; ++j) sum += w[j];
+    for (int32_t j = 0; j < n; ++j) w[j] /= sum;
+    for (int32_t c = 0; c < D; ++c) {
+      real v = 0;
+      for (int32_t j = 0; j < n; ++j) v += w[j] * x[((int64_t)b * T + 1 + j) * D + c];
+      f[(int64_t)b * D + c] = v;
+    }
   }
 }
 
@@ -547,6 +572,7 @@ typedef struct {         /* what a trainable block keeps for its backward pass (
   real *xhat1, *rstd1, *h1, *qkv, *P, *o;
   real *xhat2, *rstd2, *h2, *u, *g;
   int32_t* idx;
+  real* fw;              /* [B, Ta-1] weights of the fused token (NULL: nothing was fused) */
   /* mixture-of-experts FFN: u and g are [M,K,F]; router logits, chosen experts, gates, expert outputs */
   real *rlogits, *gates, *ye;
   int32_t* experts;
@@ -555,7 +581,7 @@ typedef struct {         /* what a trainable block keeps for its backward pass (
 static void free_saved(saved_block* s) {
   free(s->xhat1); free(s->rstd1); free(s->h1); free(s->qkv); free(s->P); free(s->o);
   free(s->xhat2); free(s->rstd2); free(s->h2); free(s->u); free(s->g); free(s->idx);
-  free(s->rlogits); free(s->gates); free(s->ye); free(s->experts);
+  free(s->rlogits); free(s->gates); free(s->ye); free(s->experts); free(s->fw);
   memset(s, 0, sizeof(*s));
 }
 
@@ -607,7 +633,7 @@ int32_t orc_step_moe(const orc_config* c, const orc_params* p, const real* input
       if (c->drop_blocks[i] < 0 || c->drop_blocks[i] >= L) return -2;
       if (i && c->drop_blocks[i] <= c->drop_blocks[i - 1]) return -2;
       if (c->keep_k[i] < 0 || c->keep_k[i] > n) return -2;
-      n = c->keep_k[i];
+      n = c->keep_k[i] + ((c->fuse_dropped && n - c->keep_k[i] > 0) ? 1 : 0); /* the fused token is a patch token from here on */
     }
   }
 
@@ -659,14 +685,27 @@ int32_t orc_step_moe(const orc_config* c, const orc_params* p, const real* input
       else
         for (int32_t b = 0; b < B; ++b) orc_topk(a + (int64_t)b * n, n, k, s.idx + (int64_t)b * k);
       if (kept_idx) memcpy(kept_idx + idx_off, s.idx, sizeof(int32_t) * (size_t)B * k);
-      free(a);
+      const int32_t fused = (c->fuse_dropped && n - k > 0) ? 1 : 0;
       real* xk = ralloc((int64_t)B * (k + 1) * D);
       orc_gather(x, B, T, D, s.idx, k, xk);
+      if (fused) {   /* [CLS; kept tokens; fused token] */
+        real* f = ralloc((int64_t)B * D);
+        s.fw = ralloc((int64_t)B * n);
+        orc_fuse_dropped(x, a, B, T, D, s.idx, k, s.fw, f);
+        real* xf = ralloc((int64_t)B * (k + 2) * D);
+        for (int32_t b = 0; b < B; ++b) {
+          memcpy(xf + (int64_t)b * (k + 2) * D, xk + (int64_t)b * (k + 1) * D, sizeof(real) * (size_t)(k + 1) * D);
+          memcpy(xf + ((int64_t)b * (k + 2) + k + 1) * D, f + (int64_t)b * D, sizeof(real) * D);
+        }
+        free(f); free(xk);
+        xk = xf;
+      }
+      free(a);
       free(x);
       x = xk;
       s.dropped = 1;
       s.k = k;
-      T = k + 1;
+      T = k + 1 + fused;
       idx_off += (int64_t)B * k;
       score_off += (int64_t)B * n;
       ++drop_i;
@@ -773,7 +812,23 @@ int32_t orc_step_moe(const orc_config* c, const orc_params* p, const real* input
       /* adjoint of the token drop: dropped tokens get no gradient from the FFN side */
       if (s->dropped) {
         real* full = ralloc(M * D);
-        orc_gather_bwd(dxm, B, s->Ta, D, s->idx, s->k, full);
+        if (s->fw) {   /* rows [CLS; kept; fused]: the fused token's gradient goes to the dropped tokens by weight */
+          const int32_t k = s->k, n = s->Ta - 1;
+          real* dk = ralloc((int64_t)B * (k + 1) * D);
+          for (int32_t b = 0; b < B; ++b)
+            memcpy(dk + (int64_t)b * (k + 1) * D, dxm + (int64_t)b * (k + 2) * D, sizeof(real) * (size_t)(k + 1) * D);
+          orc_gather_bwd(dk, B, s->Ta, D, s->idx, k, full);
+          free(dk);
+          for (int32_t b = 0; b < B; ++b)
+            for (int32_t j = 0; j < n; ++j) {
+              const real wj = s->fw[(int64_t)b * n + j];
+              if (wj == 0) continue;
+              for (int32_t cc = 0; cc < D; ++cc)
+                full[((int64_t)b * s->Ta + 1 + j) * D + cc] += wj * dxm[((int64_t)b * (k + 2) + k + 1) * D + cc];
+            }
+        } else {
+          orc_gather_bwd(dxm, B, s->Ta, D, s->idx, s->k, full);
+        }
         free(dxm);
         dxm = full;
       }

@@ -234,3 +234,68 @@ def test_interleaved_layout_against_torch_and_finite_differences(orc64):
         lm = orc64.step(cfg, pm, x, y, forced_idx=r["kept_idx"], want_grads=False)["loss"]
         fd = (lp - lm) / (2 * eps)
         assert abs(fd - r["grads"][name][ix]) < 1e-6 * max(1.0, abs(fd)), (name, fd, r["grads"][name][ix])
+
+
+# ------------------------------------------------------------------ fused inattentive token
+
+@pytest.mark.parametrize("name", ["tiny_2blk", "mini_4blk", "mini_interleaved"])
+def test_fused_token_against_torch_and_properties(orc64, name):
+    """Sec. 4.1: the dropped tokens are fused into one token (importance-weighted average) that follows
+    the kept ones; weights and indices are constants of the backward pass."""
+    cfg, p, x, y = setup(name, fuse_dropped=1)
+    r = orc64.step(cfg, p, x, y, want_dx=True)
+    t = torch_reference.run(cfg, p, x, y, r["kept_idx"])
+    assert abs(r["loss"] - t["loss"]) < 1e-10
+    for n in r["grads"]:
+        assert rel(r["grads"][n], t["grads"][n]) < 1e-8, n
+    assert rel(r["dx_trainable"], t["dx_trainable"]) < 1e-8
+    plain = orc64.step(S.get_config(name), p, x, y, want_grads=False)
+    assert r["T_last"] > plain["T_last"]
+    if max(cfg["drop_blocks"]) < cfg["depth"] - 1:       # a later attention sees the fused token
+        assert abs(r["loss"] - plain["loss"]) > 1e-12
+    # token schedule: one extra patch token after every drop that drops something
+    n0 = r["tokens_per_block"][0] - 1
+    assert r["keep_k"] == token_schedule(n0, cfg["keep_ratio"], len(cfg["drop_blocks"]), fuse=True)
+    # keep ratio 1.0: nothing is dropped, nothing is fused, identical to the plain model
+    a = orc64.step(S.get_config(name, fuse_dropped=1, keep_ratio=1.0), p, x, y, want_grads=False)
+    b = orc64.step(S.get_config(name, keep_ratio=1.0), p, x, y, want_grads=False)
+    assert a["loss"] == b["loss"] and a["T_last"] == b["T_last"]
+
+
+def test_fused_token_is_the_weighted_mean(orc64):
+    rng = np.random.default_rng(0)
+    B, T, D, k = 2, 9, 5, 3
+    x = rng.standard_normal((B, T, D)); a = rng.random((B, T - 1)) + 0.1
+    idx = np.stack([np.sort(rng.choice(T - 1, k, replace=False)) for _ in range(B)]).astype(np.int32)
+    wts = np.zeros((B, T - 1)); f = np.zeros((B, D))
+    import ctypes as C
+    orc64.lib.orc_fuse_dropped(x.ctypes.data_as(C.c_void_p), a.ctypes.data_as(C.c_void_p), B, T, D,
+                               idx.ctypes.data_as(C.c_void_p), k, wts.ctypes.data_as(C.c_void_p),
+                               f.ctypes.data_as(C.c_void_p))
+    for b in range(B):
+        drop = [j for j in range(T - 1) if j not in idx[b]]
+        want = np.average(x[b, 1:][drop], axis=0, weights=a[b, drop])       # numpy's weighted mean
+        assert np.allclose(f[b], want, rtol=1e-12)
+        assert np.allclose(wts[b].sum(), 1.0) and (wts[b, idx[b]] == 0).all()
+    # equal dropped tokens fuse to that token, whatever the scores
+    x[:, 1:] = x[:, 1:2]
+    orc64.lib.orc_fuse_dropped(x.ctypes.data_as(C.c_void_p), a.ctypes.data_as(C.c_void_p), B, T, D,
+                               idx.ctypes.data_as(C.c_void_p), k, wts.ctypes.data_as(C.c_void_p),
+                               f.ctypes.data_as(C.c_void_p))
+    assert np.allclose(f, x[:, 1], rtol=1e-12)
+
+
+def test_fused_token_finite_differences(orc64):
+    """Central differences for parameters downstream of the fusion (the fusion weights are constants
+    of the method's backward pass, so parameters that move the scores are not probed)."""
+    cfg, p, x, y = setup("mini_4blk", fuse_dropped=1)      # drops at blocks 1 and 2, trainable 2 and 3
+    r = orc64.step(cfg, p, x, y)
+    eps = 1e-6
+    for name, ix in (("blocks.3.w_qkv", (2, 9)), ("blocks.3.w_fc1", (3, 5)), ("blocks.2.w_fc2", (4, 4))):
+        pp, pm = dict(p), dict(p)
+        pp[name] = p[name].astype(np.float64).copy(); pp[name][ix] += eps
+        pm[name] = p[name].astype(np.float64).copy(); pm[name][ix] -= eps
+        lp = orc64.step(cfg, pp, x, y, forced_idx=r["kept_idx"], want_grads=False)["loss"]
+        lm = orc64.step(cfg, pm, x, y, forced_idx=r["kept_idx"], want_grads=False)["loss"]
+        fd = (lp - lm) / (2 * eps)
+        assert abs(fd - r["grads"][name][ix]) < 1e-6 * max(1.0, abs(fd)), (name, fd, r["grads"][name][ix])

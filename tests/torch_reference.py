@@ -65,7 +65,15 @@ def run(cfg, params, x, labels, kept_idx, dtype=torch.float64, eps=1e-6, experts
             scores.append(att[:, :, 0, 1:].mean(dim=1).detach().numpy())
             idx = torch.tensor(kept_idx[di], dtype=torch.long)
             full = torch.cat([torch.zeros(B, 1, dtype=torch.long), idx + 1], dim=1)
-            x = torch.gather(x, 1, full[:, :, None].expand(B, full.shape[1], D))
+            xk = torch.gather(x, 1, full[:, :, None].expand(B, full.shape[1], D))
+            if cfg.get("fuse_dropped") and idx.shape[1] < T - 1:
+                # importance-weighted average of the dropped tokens, weights detached (constants)
+                a = att[:, :, 0, 1:].mean(dim=1).detach()
+                wts = a.scatter(1, idx, 0.0)
+                wts = wts / wts.sum(dim=1, keepdim=True)
+                fused = torch.einsum("bn,bnd->bd", wts, x[:, 1:])
+                xk = torch.cat([xk, fused[:, None, :]], dim=1)
+            x = xk
             di += 1
         h2 = F.layer_norm(x, (D,), g("ln2_g"), g("ln2_b"), eps)
         if l in cfg.get("moe_blocks", ()):
