@@ -84,6 +84,13 @@ typedef struct {
    * the gradient / momentum tables may be NULL. */
   int32_t n_trainable;
   int32_t trainable_blocks[BSR_MAX_BLOCKS]; /* strictly ascending block indices                    */
+  /* Sec. 4.1: "the unimportant ones are fused and passed onto the subsequent FFN layer".  1: a drop
+   * location that drops at least one token appends one more token after the kept ones, the
+   * importance-weighted average of the dropped tokens (weights = their scores divided by the sum of
+   * the dropped scores; constants of the backward pass, like the kept indices).  It is a patch token
+   * of the following blocks: the next drop location ranks it with the others, so the schedule becomes
+   * n -> K + 1 patch tokens per drop.  0: dropped tokens are discarded. */
+  int32_t fuse_dropped;
 } bsr_config;
 
 /* Tables of device pointers, one per tensor (fp32).  The same struct describes parameters,

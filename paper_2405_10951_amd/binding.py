@@ -33,7 +33,8 @@ class bsr_config(C.Structure):
                 ("dtype", C.c_int32), ("loss", C.c_int32), ("ln_eps", C.c_float),
                 ("n_experts", C.c_int32), ("moe_top_k", C.c_int32), ("n_moe", C.c_int32),
                 ("moe_blocks", C.c_int32 * MAX_BLOCKS),
-                ("n_trainable", C.c_int32), ("trainable_blocks", C.c_int32 * MAX_BLOCKS)]
+                ("n_trainable", C.c_int32), ("trainable_blocks", C.c_int32 * MAX_BLOCKS),
+                ("fuse_dropped", C.c_int32)]
 
 
 class bsr_block_params(C.Structure):
@@ -131,6 +132,7 @@ def make_config(cfg: dict, max_batch: int, keep_k=None) -> bsr_config:
         c.moe_blocks[i] = int(b)
     c.n_experts = int(cfg.get("n_experts", 0))
     c.moe_top_k = int(cfg.get("moe_top_k", 0))
+    c.fuse_dropped = int(bool(cfg.get("fuse_dropped", 0)))
     tb = list(cfg.get("trainable_blocks") or [])
     c.n_trainable = len(tb)
     for i, b in enumerate(tb):

@@ -25,6 +25,7 @@ struct Schedule {
   int Ta[BSR_MAX_BLOCKS] = {};      // tokens seen by MHSA of block l
   int Tm[BSR_MAX_BLOCKS] = {};      // tokens seen by FFN of block l
   int drop_of[BSR_MAX_BLOCKS];      // drop index of block l, or -1
+  int fused[BSR_MAX_BLOCKS] = {};   // per drop: 1 when the dropped tokens are fused into one more token
   int T_last = 0;
   int ft = 0;                       // first trainable block: blocks before it are the frozen prefix
   bool trainable[BSR_MAX_BLOCKS] = {};  // block l is trained (others at or after ft: frozen, in the gradient path)
@@ -43,6 +44,7 @@ struct SavedBlock {  // what a trainable block keeps for its backward pass (Sec.
   float *mean1, *rstd1, *mean2, *rstd2, *lse;
   char *h1, *qkv, *o, *xmid_full, *xmid, *h2, *u, *g, *xout;
   int32_t* idx;
+  float* fw;         // [B, Ta-1] weights of the fused token (drop locations with fusion)
   MoeBuf moe;        // used when the block's FFN is a mixture of experts (u, g then have K rows per token)
 };
 
@@ -56,7 +58,7 @@ struct Buffers {
   bf16* t_patch = nullptr;
   Shadow sh[BSR_MAX_BLOCKS] = {};
   char *patches = nullptr, *x0 = nullptr, *x1 = nullptr, *h = nullptr, *qkv = nullptr, *o = nullptr, *g = nullptr;
-  float *clsp = nullptr, *scores = nullptr;
+  float *clsp = nullptr, *scores = nullptr, *fw = nullptr;   // fw: fusion weights of a frozen drop location
   int32_t* idx_tmp = nullptr;
   SavedBlock sv[BSR_MAX_BLOCKS] = {};
   MoeBuf moe = {};                      // frozen mixture blocks share this one
@@ -158,12 +160,13 @@ int make_schedule(const bsr_config* c, Schedule* s, char* why, size_t whyn) {
     if (k < 0 || k > n) BAD("keep_k[%d] = %d must lie in 0..%d", i, k, n);
     s->keep_k[i] = k;
     s->drop_of[blk] = i;
-    n = k;
+    s->fused[i] = (c->fuse_dropped && n - k > 0) ? 1 : 0;
+    n = k + s->fused[i];        // the fused token is a patch token of the following blocks
   }
   int T = s->T0;
   for (int l = 0; l < c->depth; ++l) {
     s->Ta[l] = T;
-    if (s->drop_of[l] >= 0) T = s->keep_k[s->drop_of[l]] + 1;
+    if (s->drop_of[l] >= 0) T = s->keep_k[s->drop_of[l]] + 1 + s->fused[s->drop_of[l]];
     s->Tm[l] = T;
   }
   s->T_last = T;
@@ -249,6 +252,7 @@ size_t carve(const bsr_config& c, const Schedule& s, char* base, Buffers* out) {
   b.g = w.take<char>(B * T0 * F * E);
   b.clsp = w.take<float>(B * H * T0);
   b.scores = w.take<float>(B * T0);
+  b.fw = w.take<float>(B * T0);
   b.idx_tmp = w.take<int32_t>(B * T0);
   const size_t KE = c.n_moe > 0 ? (size_t)c.moe_top_k : 1, NE = c.n_moe > 0 ? (size_t)c.n_experts : 0;
   auto take_moe = [&](MoeBuf& m, size_t rows) {      // rows = tokens of the FFN
@@ -291,6 +295,7 @@ size_t carve(const bsr_config& c, const Schedule& s, char* base, Buffers* out) {
     if (s.moe[l]) take_moe(v.moe, B * Tm);
     v.xout = w.take<char>(B * Tm * D * E);
     v.idx = w.take<int32_t>(B * Tm);
+    v.fw = (s.drop_of[l] >= 0 && s.fused[s.drop_of[l]]) ? w.take<float>(B * Ta) : nullptr;
   }
   b.dxa = w.take<char>(B * Tmax * D * E);
   b.dxb = w.take<char>(B * Tmax * D * E);
@@ -487,21 +492,24 @@ void attention_bwd(bsr_ctx* c, const void* qkv, const void* out, const void* dou
 
 // Rank the patch tokens of a drop location and hand CLS + the K best to the FFN (Sec. 4.1).
 // Returns the device pointer holding the kept indices.
+// fw != null: the dropped tokens are fused into one more token (row k+1 of x_kept, pitch k+2) and
+// fw receives the fusion weights.
 const int32_t* drop_tokens(bsr_ctx* c, int B, int T, int k, const void* x_full, void* x_kept,
                            int32_t* idx_own, const int32_t* forced, int32_t* idx_out, float* scores_out,
-                           hipStream_t s) {
-  const int n = T - 1, H = c->cfg.heads, D = c->cfg.dim;
+                           float* fw, hipStream_t s) {
+  const int H = c->cfg.heads, D = c->cfg.dim;
   float* scores = scores_out ? scores_out : c->b.scores;
   const int32_t* idx = forced;
   if (!forced) {
     topk_select_from_cls(c->b.clsp, B, H, T, k, scores, idx_own, s);
     idx = idx_own;
-  } else if (scores_out) {
+  } else if (scores_out || fw) {
     cls_head_mean(c->b.clsp, B, H, T, scores, s);
   }
   if (idx_out && k > 0)
     (void)hipMemcpyAsync(idx_out, idx, sizeof(int32_t) * (size_t)B * k, hipMemcpyDeviceToDevice, s);
-  gather_tokens(x_full, idx, B, T, k, D, c->f32, x_kept, s);
+  gather_tokens(x_full, idx, B, T, k, D, c->f32, x_kept, s, fw ? k + 2 : k + 1);
+  if (fw) fuse_dropped(x_full, scores, idx, B, T, k, D, c->f32, fw, x_kept, s);
   return idx;
 }
 
@@ -682,7 +690,8 @@ int32_t bsr_forward_frozen(bsr_ctx* c, const void* input, int32_t B, void* x_out
     if (di >= 0) {
       const int k = sc.keep_k[di];
       drop_tokens(c, B, Ta, k, x, xalt, b.idx_tmp, forced_idx ? forced_idx + idx_off : nullptr,
-                  kept_idx_out ? kept_idx_out + idx_off : nullptr, scores_out ? scores_out + sc_off : nullptr, s);
+                  kept_idx_out ? kept_idx_out + idx_off : nullptr, scores_out ? scores_out + sc_off : nullptr,
+                  sc.fused[di] ? b.fw : nullptr, s);
       std::swap(x, xalt);
       idx_off += (size_t)B * k;
       sc_off += (size_t)B * (Ta - 1);
@@ -761,7 +770,7 @@ int32_t bsr_train_blocks_fwd_bwd(bsr_ctx* c, const void* x_in, const int32_t* la
       const int k = sc.keep_k[di];
       idx_used[l] = drop_tokens(c, B, Ta, k, v.xmid_full, v.xmid, v.idx, forced_idx ? forced_idx + idx_off : nullptr,
                                 kept_idx_out ? kept_idx_out + idx_off : nullptr,
-                                scores_out ? scores_out + sc_off : nullptr, s);
+                                scores_out ? scores_out + sc_off : nullptr, sc.fused[di] ? v.fw : nullptr, s);
       idx_off += (size_t)B * k;
       sc_off += (size_t)B * (Ta - 1);
     }
@@ -847,7 +856,7 @@ int32_t bsr_train_blocks_fwd_bwd(bsr_ctx* c, const void* x_in, const int32_t* la
 
     // adjoint of the token drop: dropped tokens receive nothing from the FFN side
     if (di >= 0) {
-      scatter_tokens(dx, idx_used[l], B, Ta, sc.keep_k[di], D, f32, dx_other, s);
+      scatter_tokens(dx, idx_used[l], B, Ta, sc.keep_k[di], D, f32, dx_other, s, sc.fused[di] ? v.fw : nullptr);
       std::swap(dx, dx_other);
     }
 

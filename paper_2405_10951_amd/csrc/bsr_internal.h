@@ -83,10 +83,16 @@ void topk_select(const float* scores, int B, int n, int k, int32_t* idx, hipStre
 // head mean of the CLS softmax rows [B,H,T] -> scores [B,T-1], then the selection, in one launch
 void topk_select_from_cls(const float* cls_prob, int B, int H, int T, int k, float* scores, int32_t* idx,
                           hipStream_t s);
+// y rows [CLS; kept] per image; T_out: rows per image of y (0: k + 1)
 void gather_tokens(const void* x, const int32_t* idx, int B, int T, int k, int D, bool f32, void* y,
-                   hipStream_t s);
+                   hipStream_t s, int T_out = 0);
+// Sec. 4.1: row k+1 of y (pitch k+2) = importance-weighted average of the dropped tokens; fw [B,T-1]
+// receives the weights (0 for kept tokens)
+void fuse_dropped(const void* x, const float* scores, const int32_t* idx, int B, int T, int k, int D, bool f32,
+                  float* fw, void* y, hipStream_t s);
+// fw != null: dy has rows [CLS; kept; fused] and dropped tokens get fw times the fused token's gradient
 void scatter_tokens(const void* dy, const int32_t* idx, int B, int T, int k, int D, bool f32,
-                    void* dx, hipStream_t s);
+                    void* dx, hipStream_t s, const float* fw = nullptr);
 void extract_cls(const void* x, int B, int T, int D, bool f32, float* out, hipStream_t s);
 void place_cls_grad(const float* dxc, int B, int T, int D, bool f32, void* dx, hipStream_t s);
 void cross_entropy(const float* logits, const int32_t* labels, int B, int C, float* loss_rows,

@@ -471,12 +471,83 @@ __global__ __launch_bounds__(256) void topk_select_kernel(float* __restrict__ sc
 
 // y[b,0] = x[b,0]; y[b,1+i] = x[b,1+idx[b,i]].  One block per output row, 16-byte accesses.
 __global__ void gather_rows_kernel(const uint4* __restrict__ x, const int32_t* __restrict__ idx,
-                                   int T_, int k, int row_vecs, uint4* __restrict__ y) {
+                                   int T_, int k, int T_out, int row_vecs, uint4* __restrict__ y) {
   const int i = blockIdx.x, b = blockIdx.y;
   const int src = (i == 0) ? 0 : 1 + idx[(int64_t)b * k + i - 1];
   const uint4* s = x + ((int64_t)b * T_ + src) * row_vecs;
-  uint4* d = y + ((int64_t)b * (k + 1) + i) * row_vecs;
+  uint4* d = y + ((int64_t)b * T_out + i) * row_vecs;
   for (int v = threadIdx.x; v < row_vecs; v += blockDim.x) d[v] = s[v];
+}
+
+// Fusion of the dropped tokens of one image (Sec. 4.1): the importance-weighted average
+// f = sum_j w_j x[1+j], w_j = a_j / sum over the dropped j of a_j, written as row k+1 of y (pitch k+2).
+// fw [B,n] receives the weights (0 for kept tokens), the backward pass reuses them as constants.
+// One workgroup per image; every thread owns columns and adds the tokens in ascending order.
+template <typename T>
+__global__ __launch_bounds__(256) void fuse_dropped_kernel(const T* __restrict__ x, const float* __restrict__ scores,
+                                                           const int32_t* __restrict__ idx, int T_, int k, int D,
+                                                           float* __restrict__ fw, T* __restrict__ y) {
+  __shared__ float w[1024];
+  __shared__ float red[256];
+  const int b = blockIdx.x, n = T_ - 1, tid = threadIdx.x;
+  for (int j = tid; j < n; j += 256) w[j] = scores[(int64_t)b * n + j];
+  __syncthreads();
+  for (int i = tid; i < k; i += 256) w[idx[(int64_t)b * k + i]] = 0.f;
+  __syncthreads();
+  float part = 0.f;
+  for (int j = tid; j < n; j += 256) part += w[j];
+  red[tid] = part;
+  __syncthreads();
+  if (tid == 0) {
+    float tot = 0.f;
+    for (int i = 0; i < 256; ++i) tot += red[i];     // fixed order
+    red[0] = 1.0f / tot;
+  }
+  __syncthreads();
+  const float inv = red[0];
+  for (int j = tid; j < n; j += 256) {
+    const float v = w[j] * inv;
+    fw[(int64_t)b * n + j] = v;
+  }
+  const T* xb = x + ((int64_t)b * T_ + 1) * D;
+  for (int c = tid; c < D; c += 256) {
+    float acc = 0.f;
+    for (int j = 0; j < n; ++j) {
+      const float wj = w[j];
+      if (wj != 0.f) acc = fmaf(wj * inv, (float)xb[(int64_t)j * D + c], acc);
+    }
+    y[((int64_t)b * (k + 2) + k + 1) * D + c] = (T)acc;
+  }
+}
+
+// Adjoint of gather + fusion: rows [CLS; kept; fused] of dy (pitch k+2) -> dx [B,T,D]; a dropped
+// token j receives fw[j] times the gradient of the fused token.  Every row is written exactly once.
+template <typename T>
+__global__ void scatter_fused_kernel(const T* __restrict__ dy, const int32_t* __restrict__ idx,
+                                     const float* __restrict__ fw, int T_, int k, int D, T* __restrict__ dx) {
+  const int t = blockIdx.x, b = blockIdx.y;
+  int src = -1;
+  if (t == 0) {
+    src = 0;
+  } else {
+    const int32_t* row = idx + (int64_t)b * k;
+    int lo = 0, hi = k - 1;
+    while (lo <= hi) {
+      int mid = (lo + hi) >> 1;
+      int v = row[mid];
+      if (v == t - 1) { src = 1 + mid; break; }
+      if (v < t - 1) lo = mid + 1; else hi = mid - 1;
+    }
+  }
+  T* d = dx + ((int64_t)b * T_ + t) * D;
+  if (src >= 0) {
+    const T* s = dy + ((int64_t)b * (k + 2) + src) * D;
+    for (int c = threadIdx.x; c < D; c += blockDim.x) d[c] = s[c];
+  } else {
+    const float wj = fw[(int64_t)b * (T_ - 1) + t - 1];
+    const T* s = dy + ((int64_t)b * (k + 2) + k + 1) * D;
+    for (int c = threadIdx.x; c < D; c += blockDim.x) d[c] = (T)(wj * (float)s[c]);
+  }
 }
 
 // Adjoint of the gather: every row of dx is written exactly once (kept rows copied, dropped rows
@@ -757,13 +828,25 @@ void topk_select_from_cls(const float* cls_prob, int B, int H, int T, int k, flo
 }
 
 void gather_tokens(const void* x, const int32_t* idx, int B, int T, int k, int D, bool f32, void* y,
-                   hipStream_t s) {
+                   hipStream_t s, int T_out) {
   const int row_vecs = D * (f32 ? 4 : 2) / 16;
-  gather_rows_kernel<<<dim3(k + 1, B), 64, 0, s>>>((const uint4*)x, idx, T, k, row_vecs, (uint4*)y);
+  gather_rows_kernel<<<dim3(k + 1, B), 64, 0, s>>>((const uint4*)x, idx, T, k, T_out > 0 ? T_out : k + 1, row_vecs,
+                                                  (uint4*)y);
+}
+
+void fuse_dropped(const void* x, const float* scores, const int32_t* idx, int B, int T, int k, int D, bool f32,
+                  float* fw, void* y, hipStream_t s) {
+  if (f32) fuse_dropped_kernel<float><<<B, 256, 0, s>>>((const float*)x, scores, idx, T, k, D, fw, (float*)y);
+  else fuse_dropped_kernel<bf16><<<B, 256, 0, s>>>((const bf16*)x, scores, idx, T, k, D, fw, (bf16*)y);
 }
 
 void scatter_tokens(const void* dy, const int32_t* idx, int B, int T, int k, int D, bool f32,
-                    void* dx, hipStream_t s) {
+                    void* dx, hipStream_t s, const float* fw) {
+  if (fw) {   // rows of dy are [CLS; kept; fused]
+    if (f32) scatter_fused_kernel<float><<<dim3(T, B), 128, 0, s>>>((const float*)dy, idx, fw, T, k, D, (float*)dx);
+    else scatter_fused_kernel<bf16><<<dim3(T, B), 128, 0, s>>>((const bf16*)dy, idx, fw, T, k, D, (bf16*)dx);
+    return;
+  }
   const int row_vecs = D * (f32 ? 4 : 2) / 16;
   scatter_rows_kernel<<<dim3(T, B), 64, 0, s>>>((const uint4*)dy, idx, T, k, row_vecs, (uint4*)dx);
 }

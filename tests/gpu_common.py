@@ -12,6 +12,12 @@ def rel(a, b):
     return float(np.max(np.abs(a - b)) / max(float(np.max(np.abs(b))), 1e-30))
 
 
+def rel_rms(a, b):
+    """rms(a-b) / rms(b)"""
+    a, b = np.asarray(a, np.float64), np.asarray(b, np.float64)
+    return float(np.sqrt(np.mean((a - b) ** 2)) / max(float(np.sqrt(np.mean(b ** 2))), 1e-30))
+
+
 def run_hip_step(cfg, params, x, labels, forced_idx=None, max_batch=None, sgd=None, ctx=None,
                  forced_experts=None):
     """One BSR step on cuda:0.  forced_idx: list per drop of [B,k] arrays (or None).
