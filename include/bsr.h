@@ -224,6 +224,20 @@ int32_t bsr_sgd_step(bsr_ctx* ctx, const bsr_params* grads, const bsr_params* mo
                      float momentum, float weight_decay, void* stream);
 
 /*
+ * AdamW update of the trainable tensors (the optimiser of the paper's DeiT-S runs, Sec. 5), in place:
+ *   m = beta1 m + (1-beta1) g;  v = beta2 v + (1-beta2) g^2;
+ *   w -= lr * ( (m / (1-beta1^step)) / (sqrt(v / (1-beta2^step)) + eps) + weight_decay * w )
+ * (decoupled weight decay).  Also refreshes the bf16 copies the kernels read.
+ *   grads, exp_avg, exp_avg_sq   host structs of device fp32 pointers (layout of bsr_params); the two
+ *                                moment tables are updated in place and start at zero
+ *   step                         1 for the first update
+ * Errors: INVALID_ARG, HIP.
+ */
+int32_t bsr_adamw_step(bsr_ctx* ctx, const bsr_params* grads, const bsr_params* exp_avg,
+                       const bsr_params* exp_avg_sq, float lr, float beta1, float beta2, float eps,
+                       float weight_decay, int32_t step, void* stream);
+
+/*
  * Single layers in bf16, as the step runs them (for kernel-level parity tests and benchmarks; no
  * context needed).  All pointers are device pointers, 16-byte aligned; bf16 tensors unless noted.
  * *used_mfma (host, may be NULL) is set to 1 when the MFMA kernel took the shape, 0 when the

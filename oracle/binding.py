@@ -212,6 +212,13 @@ class Oracle:
                     dx_trainable=dx_tr, keep_k=ks, tokens_per_block=T_at_block, T_last=T_last,
                     experts=experts, router_logits=router_logits)
 
+    def adamw(self, w, g, m, v, lr, b1, b2, eps, wd, t):
+        """In place on copies; returns (w, m, v)."""
+        w, g, m, v = (self.arr(a).copy() for a in (w, g, m, v))
+        self.lib.orc_adamw(_ptr(w), _ptr(g), _ptr(m), _ptr(v), C.c_int64(w.size), C.c_double(lr), C.c_double(b1),
+                           C.c_double(b2), C.c_double(eps), C.c_double(wd), C.c_int32(t))
+        return w, m, v
+
     # ---- mixture-of-experts FFN, for pins ----------------------------------------------
     def moe_route(self, logits, K, forced=None):
         logits = self.arr(logits); M, E = logits.shape

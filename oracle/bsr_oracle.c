@@ -435,6 +435,22 @@ void orc_sgd(real* w, const real* g, real* m, int64_t n, double lr, double mu, d
   }
 }
 
+/* AdamW (the optimiser of the paper's DeiT-S runs, Sec. 5), step t = 1, 2, ...:
+ *   m = b1 m + (1-b1) g;  v = b2 v + (1-b2) g^2;  mhat = m / (1-b1^t);  vhat = v / (1-b2^t);
+ *   w = w - lr (mhat / (sqrt(vhat) + eps) + wd w)          (decoupled weight decay) */
+void orc_adamw(real* w, const real* g, real* m, real* v, int64_t n, double lr, double b1, double b2,
+               double eps, double wd, int32_t t) {
+  const double c1 = 1.0 - pow(b1, (double)t), c2 = 1.0 - pow(b2, (double)t);
+  for (int64_t i = 0; i < n; ++i) {
+    const double gi = (double)g[i];
+    const double mi = b1 * (double)m[i] + (1.0 - b1) * gi;
+    const double vi = b2 * (double)v[i] + (1.0 - b2) * gi * gi;
+    m[i] = (real)mi;
+    v[i] = (real)vi;
+    w[i] = (real)((double)w[i] - lr * ((mi / c1) / (sqrt(vi / c2) + eps) + wd * (double)w[i]));
+  }
+}
+
 /* ---------------------------------------------------------------- mixture-of-experts FFN (Sec. 5.3) */
 
 /* Routing of one token: the K experts with the largest router logits (ties: lower expert index

@@ -67,7 +67,8 @@ def load_library():
     lib.bsr_last_error.argtypes = [C.c_void_p]
     for name in ("bsr_token_schedule", "bsr_workspace_bytes", "bsr_init", "bsr_refresh_weights",
                  "bsr_forward_frozen", "bsr_select_tokens", "bsr_train_blocks_fwd_bwd",
-                 "bsr_sgd_step", "bsr_destroy", "bsr_profile_begin", "bsr_profile_end", "bsr_moe_routing_io"):
+                 "bsr_sgd_step", "bsr_destroy", "bsr_profile_begin", "bsr_profile_end", "bsr_moe_routing_io",
+                 "bsr_adamw_step"):
         getattr(lib, name).restype = C.c_int32
     lib.bsr_token_schedule.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
     lib.bsr_workspace_bytes.argtypes = [C.c_void_p, C.POINTER(C.c_size_t)]
@@ -83,6 +84,8 @@ def load_library():
     lib.bsr_sgd_step.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_float, C.c_float, C.c_float, C.c_void_p]
     lib.bsr_destroy.argtypes = [C.c_void_p]
     lib.bsr_moe_routing_io.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.bsr_adamw_step.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_float, C.c_float, C.c_float,
+                                   C.c_float, C.c_float, C.c_int32, C.c_void_p]
     lib.bsr_linear_forward.restype = C.c_int32
     lib.bsr_linear_forward.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
                                        C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
@@ -354,6 +357,13 @@ class Context:
         self._chk(self.lib.bsr_sgd_step(self.ctx, C.byref(gs), C.byref(ms) if ms is not None else None,
                                         C.c_float(lr), C.c_float(momentum), C.c_float(weight_decay),
                                         self._stream()))
+
+    def bsr_adamw_step(self, grads: dict, exp_avg: dict, exp_avg_sq: dict, lr: float, beta1: float = 0.9,
+                       beta2: float = 0.999, eps: float = 1e-8, weight_decay: float = 0.01, step: int = 1):
+        gs, ms, vs = _params_struct(grads), _params_struct(exp_avg), _params_struct(exp_avg_sq)
+        self._chk(self.lib.bsr_adamw_step(self.ctx, C.byref(gs), C.byref(ms), C.byref(vs), C.c_float(lr),
+                                          C.c_float(beta1), C.c_float(beta2), C.c_float(eps),
+                                          C.c_float(weight_decay), C.c_int32(step), self._stream()))
 
     def bsr_profile_begin(self):
         self._chk(self.lib.bsr_profile_begin(self.ctx))

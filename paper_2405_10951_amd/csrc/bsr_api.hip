@@ -519,8 +519,8 @@ void build_shadows(bsr_ctx* c, int first_block, hipStream_t s) {
   const int D = cf.dim, F = cf.mlp_hidden;
   MatTable tab;
   auto add = [&](const void* w, int rows, int cols, bf16* sp, bf16* tp) {
-    matrix_table_add(tab, (float*)const_cast<void*>(w), nullptr, nullptr, rows, cols, sp, tp);
-    if (tab.count == MAT_TABLE_MAX) { matrix_table_run(tab, false, 0.f, 0.f, 0.f, s); tab = MatTable(); }
+    matrix_table_add(tab, (float*)const_cast<void*>(w), nullptr, nullptr, nullptr, rows, cols, sp, tp);
+    if (tab.count == MAT_TABLE_MAX) { matrix_table_run(tab, false, OptArgs(), s); tab = MatTable(); }
   };
   if (first_block == 0 && cf.image_size)
     add(c->p.w_patch, cf.in_chans * cf.patch_size * cf.patch_size, D, nullptr, c->b.t_patch);
@@ -540,7 +540,7 @@ void build_shadows(bsr_ctx* c, int first_block, hipStream_t s) {
     add(w.w_fc1, D, F, sh.s_fc1, sh.t_fc1);
     add(w.w_fc2, F, D, sh.s_fc2, sh.t_fc2);
   }
-  matrix_table_run(tab, false, 0.f, 0.f, 0.f, s);
+  matrix_table_run(tab, false, OptArgs(), s);
   for (int l = first_block; l < cf.depth; ++l)
     if (c->sc.moe[l]) moe_router_copy((const float*)c->p.blocks[l].w_router, D, cf.n_experts, c->b.sh[l].t_router, s);
 }
@@ -889,6 +889,72 @@ int32_t bsr_moe_routing_io(bsr_ctx* c, const int32_t* forced_experts, int32_t* e
   return BSR_OK;
 }
 
+// One optimiser step over the trainable tensors: vectors through sgd_table, matrices through the
+// matrix table (which also rewrites their bf16 copies).  m1 / m2: first / second moment tables (null
+// when the rule does not use them).
+static int32_t optimizer_step(bsr_ctx* c, const bsr_params* grads, const bsr_params* m1, const bsr_params* m2,
+                              const OptArgs& o, hipStream_t s, const char* where) {
+  const bsr_config& cf = c->cfg;
+  const int D = cf.dim, F = cf.mlp_hidden;
+  SgdTable tab;
+  int ntab = 0;
+  auto vec = [&](void* w, const void* g, void* a, void* b2, int64_t n) {
+    tab.e[ntab++] = SgdEntry{(float*)w, (const float*)g, m1 ? (float*)a : nullptr, m2 ? (float*)b2 : nullptr, n};
+    if (ntab == SGD_TABLE_MAX) { sgd_table(tab, ntab, o, s); ntab = 0; }
+  };
+  MatTable mats;
+  auto mat = [&](void* w, const void* g, void* a, void* b2, size_t off, int rows, int cols, bf16* sp, bf16* tp) {
+    float* wp = (float*)w + off;
+    const float* gp = (const float*)g + off;
+    float* ap = m1 ? (float*)a + off : nullptr;
+    float* bp = m2 ? (float*)b2 + off : nullptr;
+    matrix_table_add(mats, wp, gp, ap, bp, rows, cols, sp, tp);
+    if (mats.count == MAT_TABLE_MAX) { matrix_table_run(mats, true, o, s); mats = MatTable(); }
+  };
+  for (int l = cf.first_trainable_block; l < cf.depth; ++l) {
+    if (!c->sc.trainable[l]) continue;
+    const bsr_block_params& W = c->p.blocks[l];
+    const bsr_block_params& G = grads->blocks[l];
+    const bsr_block_params& A = m1 ? m1->blocks[l] : grads->blocks[l];
+    const bsr_block_params& V = m2 ? m2->blocks[l] : grads->blocks[l];
+    const Shadow& sh = c->b.sh[l];
+    vec(W.ln1_g, G.ln1_g, A.ln1_g, V.ln1_g, D); vec(W.ln1_b, G.ln1_b, A.ln1_b, V.ln1_b, D);
+    vec(W.b_qkv, G.b_qkv, A.b_qkv, V.b_qkv, 3 * D); vec(W.b_proj, G.b_proj, A.b_proj, V.b_proj, D);
+    vec(W.ln2_g, G.ln2_g, A.ln2_g, V.ln2_g, D); vec(W.ln2_b, G.ln2_b, A.ln2_b, V.ln2_b, D);
+    mat(W.w_qkv, G.w_qkv, A.w_qkv, V.w_qkv, 0, D, 3 * D, sh.s_qkv, sh.t_qkv);
+    mat(W.w_proj, G.w_proj, A.w_proj, V.w_proj, 0, D, D, sh.s_proj, sh.t_proj);
+    if (c->sc.moe[l]) {   // router, E bias vectors each, E matrices each
+      const int E = cf.n_experts;
+      vec(W.w_router, G.w_router, A.w_router, V.w_router, (int64_t)D * E);
+      vec(W.b_fc1, G.b_fc1, A.b_fc1, V.b_fc1, (int64_t)E * F); vec(W.b_fc2, G.b_fc2, A.b_fc2, V.b_fc2, (int64_t)E * D);
+      for (int e = 0; e < E; ++e) {
+        const size_t off = (size_t)e * D * F;
+        mat(W.w_fc1, G.w_fc1, A.w_fc1, V.w_fc1, off, D, F, sh.s_fc1 + off, sh.t_fc1 + off);
+        mat(W.w_fc2, G.w_fc2, A.w_fc2, V.w_fc2, off, F, D, sh.s_fc2 + off, sh.t_fc2 + off);
+      }
+      continue;
+    }
+    vec(W.b_fc1, G.b_fc1, A.b_fc1, V.b_fc1, F); vec(W.b_fc2, G.b_fc2, A.b_fc2, V.b_fc2, D);
+    mat(W.w_fc1, G.w_fc1, A.w_fc1, V.w_fc1, 0, D, F, sh.s_fc1, sh.t_fc1);
+    mat(W.w_fc2, G.w_fc2, A.w_fc2, V.w_fc2, 0, F, D, sh.s_fc2, sh.t_fc2);
+  }
+  if (cf.num_classes > 0) {
+    const bsr_params& W = c->p;
+    const bsr_params& G = *grads;
+    const bsr_params& A = m1 ? *m1 : *grads;
+    const bsr_params& V = m2 ? *m2 : *grads;
+    vec(W.lnf_g, G.lnf_g, A.lnf_g, V.lnf_g, D); vec(W.lnf_b, G.lnf_b, A.lnf_b, V.lnf_b, D);
+    vec(W.w_head, G.w_head, A.w_head, V.w_head, (int64_t)D * cf.num_classes);
+    vec(W.b_head, G.b_head, A.b_head, V.b_head, cf.num_classes);
+  }
+  sgd_table(tab, ntab, o, s);
+  matrix_table_run(mats, true, o, s);
+  for (int l = cf.first_trainable_block; l < cf.depth; ++l)      // the routers were updated as vectors
+    if (c->sc.moe[l] && c->sc.trainable[l])
+      moe_router_copy((const float*)c->p.blocks[l].w_router, D, cf.n_experts, c->b.sh[l].t_router, s);
+  return check_hip(c, where);
+}
+
 int32_t bsr_sgd_step(bsr_ctx* c, const bsr_params* grads, const bsr_params* momenta, float lr,
                      float momentum, float weight_decay, void* stream) {
   if (!c) return fail(nullptr, BSR_ERR_INVALID_ARG, "ctx is NULL");
@@ -901,60 +967,29 @@ int32_t bsr_sgd_step(bsr_ctx* c, const bsr_params* grads, const bsr_params* mome
     return fail(c, BSR_ERR_INVALID_ARG, "gradient tensor %s is NULL or not 16-byte aligned", which);
   if (momentum > 0.f && check_params(cf, momenta, cf.first_trainable_block, false, &which, &c->sc) != BSR_OK)
     return fail(c, BSR_ERR_INVALID_ARG, "momentum tensor %s is NULL or not 16-byte aligned", which);
-  hipStream_t s = (hipStream_t)stream;
-  const int D = cf.dim, F = cf.mlp_hidden;
-  const bool mom = momentum > 0.f;
-  SgdTable tab;
-  int ntab = 0;
-  auto vec = [&](void* w, const void* g, void* m, int64_t n) {
-    tab.e[ntab++] = SgdEntry{(float*)w, (const float*)g, mom ? (float*)m : nullptr, n};
-    if (ntab == SGD_TABLE_MAX) { sgd_table(tab, ntab, lr, momentum, weight_decay, s); ntab = 0; }
-  };
-  MatTable mats;
-  auto mat = [&](void* w, const void* g, void* m, int rows, int cols, bf16* sp, bf16* tp) {
-    if (!sp && !tp) { vec(w, g, m, (int64_t)rows * cols); return; }
-    matrix_table_add(mats, (float*)w, (const float*)g, mom ? (float*)m : nullptr, rows, cols, sp, tp);
-    if (mats.count == MAT_TABLE_MAX) { matrix_table_run(mats, true, lr, momentum, weight_decay, s); mats = MatTable(); }
-  };
-  for (int l = cf.first_trainable_block; l < cf.depth; ++l) {
-    if (!c->sc.trainable[l]) continue;
-    const bsr_block_params& W = c->p.blocks[l];
-    const bsr_block_params& G = grads->blocks[l];
-    const bsr_block_params& Mo = mom ? momenta->blocks[l] : grads->blocks[l];
-    const Shadow& sh = c->b.sh[l];
-    vec(W.ln1_g, G.ln1_g, Mo.ln1_g, D); vec(W.ln1_b, G.ln1_b, Mo.ln1_b, D);
-    vec(W.b_qkv, G.b_qkv, Mo.b_qkv, 3 * D); vec(W.b_proj, G.b_proj, Mo.b_proj, D);
-    vec(W.ln2_g, G.ln2_g, Mo.ln2_g, D); vec(W.ln2_b, G.ln2_b, Mo.ln2_b, D);
-    mat(W.w_qkv, G.w_qkv, Mo.w_qkv, D, 3 * D, sh.s_qkv, sh.t_qkv);
-    mat(W.w_proj, G.w_proj, Mo.w_proj, D, D, sh.s_proj, sh.t_proj);
-    if (c->sc.moe[l]) {   // router, E bias vectors each, E matrices each
-      const int E = cf.n_experts;
-      vec(W.w_router, G.w_router, Mo.w_router, (int64_t)D * E);
-      vec(W.b_fc1, G.b_fc1, Mo.b_fc1, (int64_t)E * F); vec(W.b_fc2, G.b_fc2, Mo.b_fc2, (int64_t)E * D);
-      for (int e = 0; e < E; ++e) {
-        const size_t o = (size_t)e * D * F;
-        mat((float*)W.w_fc1 + o, (const float*)G.w_fc1 + o, (float*)Mo.w_fc1 + o, D, F, sh.s_fc1 + o, sh.t_fc1 + o);
-        mat((float*)W.w_fc2 + o, (const float*)G.w_fc2 + o, (float*)Mo.w_fc2 + o, F, D, sh.s_fc2 + o, sh.t_fc2 + o);
-      }
-      continue;
-    }
-    vec(W.b_fc1, G.b_fc1, Mo.b_fc1, F); vec(W.b_fc2, G.b_fc2, Mo.b_fc2, D);
-    mat(W.w_fc1, G.w_fc1, Mo.w_fc1, D, F, sh.s_fc1, sh.t_fc1);
-    mat(W.w_fc2, G.w_fc2, Mo.w_fc2, F, D, sh.s_fc2, sh.t_fc2);
-  }
-  if (cf.num_classes > 0) {
-    const bsr_params& W = c->p;
-    const bsr_params& G = *grads;
-    const bsr_params& Mo = mom ? *momenta : *grads;
-    vec(W.lnf_g, G.lnf_g, Mo.lnf_g, D); vec(W.lnf_b, G.lnf_b, Mo.lnf_b, D);
-    vec(W.w_head, G.w_head, Mo.w_head, (int64_t)D * cf.num_classes); vec(W.b_head, G.b_head, Mo.b_head, cf.num_classes);
-  }
-  sgd_table(tab, ntab, lr, momentum, weight_decay, s);
-  matrix_table_run(mats, true, lr, momentum, weight_decay, s);
-  for (int l = cf.first_trainable_block; l < cf.depth; ++l)      // the routers were updated as vectors
-    if (c->sc.moe[l] && c->sc.trainable[l])
-      moe_router_copy((const float*)c->p.blocks[l].w_router, D, cf.n_experts, c->b.sh[l].t_router, s);
-  return check_hip(c, "bsr_sgd_step");
+  OptArgs o;
+  o.kind = OPT_SGD; o.lr = lr; o.mu = momentum; o.wd = weight_decay;
+  return optimizer_step(c, grads, momentum > 0.f ? momenta : nullptr, nullptr, o, (hipStream_t)stream, "bsr_sgd_step");
+}
+
+int32_t bsr_adamw_step(bsr_ctx* c, const bsr_params* grads, const bsr_params* exp_avg, const bsr_params* exp_avg_sq,
+                       float lr, float beta1, float beta2, float eps, float weight_decay, int32_t step,
+                       void* stream) {
+  if (!c) return fail(nullptr, BSR_ERR_INVALID_ARG, "ctx is NULL");
+  if (!grads || !exp_avg || !exp_avg_sq) return fail(c, BSR_ERR_INVALID_ARG, "grads, exp_avg or exp_avg_sq is NULL");
+  if (step < 1) return fail(c, BSR_ERR_INVALID_ARG, "step counts from 1");
+  if (!(beta1 >= 0.f && beta1 < 1.f && beta2 >= 0.f && beta2 < 1.f && eps > 0.f))
+    return fail(c, BSR_ERR_INVALID_ARG, "need 0 <= beta1, beta2 < 1 and eps > 0");
+  const bsr_config& cf = c->cfg;
+  const char* which = "";
+  for (const bsr_params* t : {grads, exp_avg, exp_avg_sq})
+    if (check_params(cf, t, cf.first_trainable_block, false, &which, &c->sc) != BSR_OK)
+      return fail(c, BSR_ERR_INVALID_ARG, "tensor %s of a table is NULL or not 16-byte aligned", which);
+  OptArgs o;
+  o.kind = OPT_ADAMW; o.lr = lr; o.wd = weight_decay; o.b1 = beta1; o.b2 = beta2; o.eps = eps;
+  o.bc1 = (float)(1.0 - pow((double)beta1, (double)step));
+  o.bc2 = (float)(1.0 - pow((double)beta2, (double)step));
+  return optimizer_step(c, grads, exp_avg, exp_avg_sq, o, (hipStream_t)stream, "bsr_adamw_step");
 }
 
 static int32_t run_layer(const GemmDesc& g, int32_t* used_mfma, void* stream, const char* where,

@@ -127,21 +127,26 @@ void moe_combine_bwd(const void* dx, const void* y, const int32_t* pos, const in
 void moe_unpermute_bwd(const void* dxg, const int32_t* pos, const int32_t* experts, const float* dsel,
                        const float* w_router, int64_t M, int D, int E, int K, void* dh, hipStream_t s);
 
-// A table of weight matrices handled by one launch: bf16 copies (straight and / or transposed) of
-// each, optionally after an SGD update.  The table travels as a kernel argument.
-constexpr int MAT_TABLE_MAX = 64;
-struct MatEntry { float* w; const float* g; float* m; bf16* s; bf16* t; int rows, cols, tile_start; };
-struct MatTable { MatEntry e[MAT_TABLE_MAX]; int count = 0; int total_tiles = 0; };
-void matrix_table_add(MatTable& t, float* w, const float* g, float* m, int rows, int cols, bf16* straight,
-                      bf16* transposed);
-void matrix_table_run(const MatTable& t, bool update, float lr, float mu, float wd, hipStream_t s);
+// Update rule of the optimiser kernels.  SGD: g' = g + wd w; mu > 0: m = mu m + g', w -= lr m; else
+// w -= lr g'.  AdamW: m = b1 m + (1-b1) g; v = b2 v + (1-b2) g^2; w -= lr ((m/bc1) / (sqrt(v/bc2) + eps)
+// + wd w) with bc = 1 - b^t computed on the host.
+enum { OPT_SGD = 0, OPT_ADAMW = 1 };
+struct OptArgs { int kind = OPT_SGD; float lr = 0.f, mu = 0.f, wd = 0.f, b1 = 0.f, b2 = 0.f, eps = 0.f, bc1 = 1.f, bc2 = 1.f; };
 
-// SGD on up to SGD_TABLE_MAX tensors without bf16 copies in one launch (the table travels as a
-// kernel argument)
+// A table of weight matrices handled by one launch: bf16 copies (straight and / or transposed) of
+// each, optionally after an optimiser update.  The table travels as a kernel argument (< 4 KB).
+constexpr int MAT_TABLE_MAX = 56;
+struct MatEntry { float* w; const float* g; float* m; float* v2; bf16* s; bf16* t; int rows, cols, tile_start; };
+struct MatTable { MatEntry e[MAT_TABLE_MAX]; int count = 0; int total_tiles = 0; };
+void matrix_table_add(MatTable& t, float* w, const float* g, float* m, float* v2, int rows, int cols, bf16* straight,
+                      bf16* transposed);
+void matrix_table_run(const MatTable& t, bool update, const OptArgs& o, hipStream_t s);
+
+// The same update on up to SGD_TABLE_MAX tensors without bf16 copies in one launch
 constexpr int SGD_TABLE_MAX = 96;
-struct SgdEntry { float* w; const float* g; float* m; int64_t n; };
+struct SgdEntry { float* w; const float* g; float* m; float* v2; int64_t n; };
 struct SgdTable { SgdEntry e[SGD_TABLE_MAX]; };
-void sgd_table(const SgdTable& t, int count, float lr, float mu, float wd, hipStream_t s);
+void sgd_table(const SgdTable& t, int count, const OptArgs& o, hipStream_t s);
 // fp32 C[M,N] = A.B (+bias) for tiny problems (the classification head)
 void gemm_small_f32(const GemmDesc& g, hipStream_t s);
 

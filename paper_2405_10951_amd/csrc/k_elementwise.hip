@@ -646,8 +646,25 @@ __global__ __launch_bounds__(256) void mean_sq_kernel(const T* __restrict__ x, i
 // rows and cols are multiples of 4.
 typedef __bf16 bf16x4_t __attribute__((ext_vector_type(4)));
 
+// one element of the optimiser update; m / v2 are read and written only by the rules that use them
+__device__ inline float opt_update(const OptArgs& o, float w, float g, float* m, float* v2, int64_t i) {
+  if (o.kind == OPT_ADAMW) {
+    const float mi = o.b1 * m[i] + (1.0f - o.b1) * g;
+    const float vi = o.b2 * v2[i] + (1.0f - o.b2) * g * g;
+    m[i] = mi;
+    v2[i] = vi;
+    return w - o.lr * ((mi / o.bc1) / (sqrtf(vi / o.bc2) + o.eps) + o.wd * w);
+  }
+  float gp = g + o.wd * w;
+  if (o.mu > 0.f) {
+    gp = o.mu * m[i] + gp;
+    m[i] = gp;
+  }
+  return w - o.lr * gp;
+}
+
 template <bool UPDATE>
-__global__ __launch_bounds__(256) void matrix_table_kernel(MatTable t, float lr, float mu, float wd) {
+__global__ __launch_bounds__(256) void matrix_table_kernel(MatTable t, OptArgs o) {
   __shared__ float tile[64][65];
   int ei = 0;
   while (ei + 1 < t.count && (int)blockIdx.x >= t.e[ei + 1].tile_start) ++ei;
@@ -664,13 +681,10 @@ __global__ __launch_bounds__(256) void matrix_table_kernel(MatTable t, float lr,
       v = *(const float4*)(e.w + off);
       if (UPDATE) {
         const float4 g = *(const float4*)(e.g + off);
-        float4 gp = make_float4(g.x + wd * v.x, g.y + wd * v.y, g.z + wd * v.z, g.w + wd * v.w);
-        if (mu > 0.f) {
-          const float4 m0 = *(const float4*)(e.m + off);
-          gp = make_float4(mu * m0.x + gp.x, mu * m0.y + gp.y, mu * m0.z + gp.z, mu * m0.w + gp.w);
-          *(float4*)(e.m + off) = gp;
-        }
-        v = make_float4(v.x - lr * gp.x, v.y - lr * gp.y, v.z - lr * gp.z, v.w - lr * gp.w);
+        v.x = opt_update(o, v.x, g.x, e.m, e.v2, off);
+        v.y = opt_update(o, v.y, g.y, e.m, e.v2, off + 1);
+        v.z = opt_update(o, v.z, g.z, e.m, e.v2, off + 2);
+        v.w = opt_update(o, v.w, g.w, e.m, e.v2, off + 3);
         *(float4*)(e.w + off) = v;
       }
       if (e.s) {
@@ -698,23 +712,14 @@ __global__ __launch_bounds__(256) void matrix_table_kernel(MatTable t, float lr,
 
 // SGD on a table of small tensors (biases, LayerNorm parameters, the head) in one launch:
 // blockIdx.y picks the tensor, blockIdx.x a slice of 1024 elements.
-__global__ __launch_bounds__(256) void sgd_table_kernel(SgdTable t, float lr, float mu, float wd) {
+__global__ __launch_bounds__(256) void sgd_table_kernel(SgdTable t, OptArgs o) {
   const SgdEntry e = t.e[blockIdx.y];
   const int64_t i0 = (int64_t)blockIdx.x * 1024 + threadIdx.x;
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
     const int64_t i = i0 + 256 * j;
     if (i >= e.n) break;
-    float v = e.w[i];
-    float gp = e.g[i] + wd * v;
-    if (mu > 0.f) {
-      float m = mu * e.m[i] + gp;
-      e.m[i] = m;
-      v -= lr * m;
-    } else {
-      v -= lr * gp;
-    }
-    e.w[i] = v;
+    e.w[i] = opt_update(o, e.w[i], e.g[i], e.m, e.v2, i);
   }
 }
 
@@ -876,26 +881,26 @@ void mean_sq_loss(const void* x, int64_t n, bool f32, float* partial, float* los
   mean_of_rows_kernel<<<1, 64, 0, s>>>(partial, MSQ_BLOCKS, 1.0f / (float)n, loss);
 }
 
-void matrix_table_add(MatTable& t, float* w, const float* g, float* m, int rows, int cols, bf16* straight,
+void matrix_table_add(MatTable& t, float* w, const float* g, float* m, float* v2, int rows, int cols, bf16* straight,
                       bf16* transposed) {
   MatEntry& e = t.e[t.count];
-  e.w = w; e.g = g; e.m = m; e.s = straight; e.t = transposed; e.rows = rows; e.cols = cols;
+  e.w = w; e.g = g; e.m = m; e.v2 = v2; e.s = straight; e.t = transposed; e.rows = rows; e.cols = cols;
   e.tile_start = t.total_tiles;
   t.total_tiles += ((rows + 63) / 64) * ((cols + 63) / 64);
   ++t.count;
 }
 
-void matrix_table_run(const MatTable& t, bool update, float lr, float mu, float wd, hipStream_t s) {
+void matrix_table_run(const MatTable& t, bool update, const OptArgs& o, hipStream_t s) {
   if (t.count == 0) return;
-  if (update) matrix_table_kernel<true><<<t.total_tiles, 256, 0, s>>>(t, lr, mu, wd);
-  else matrix_table_kernel<false><<<t.total_tiles, 256, 0, s>>>(t, 0.f, 0.f, 0.f);
+  if (update) matrix_table_kernel<true><<<t.total_tiles, 256, 0, s>>>(t, o);
+  else matrix_table_kernel<false><<<t.total_tiles, 256, 0, s>>>(t, OptArgs());
 }
 
-void sgd_table(const SgdTable& t, int count, float lr, float mu, float wd, hipStream_t s) {
+void sgd_table(const SgdTable& t, int count, const OptArgs& o, hipStream_t s) {
   if (count <= 0) return;
   int64_t nmax = 0;
   for (int i = 0; i < count; ++i) nmax = std::max(nmax, t.e[i].n);
-  sgd_table_kernel<<<dim3((unsigned)((nmax + 1023) / 1024), count), 256, 0, s>>>(t, lr, mu, wd);
+  sgd_table_kernel<<<dim3((unsigned)((nmax + 1023) / 1024), count), 256, 0, s>>>(t, o);
 }
 
 }  // namespace bsr

@@ -19,10 +19,12 @@ def rel_rms(a, b):
 
 
 def run_hip_step(cfg, params, x, labels, forced_idx=None, max_batch=None, sgd=None, ctx=None,
-                 forced_experts=None):
+                 forced_experts=None, adamw=None):
     """One BSR step on cuda:0.  forced_idx: list per drop of [B,k] arrays (or None).
     forced_experts: dict block -> [rows,K] expert choice for the mixture-of-experts blocks (or None).
-    sgd: None or dict(lr=, momentum=, weight_decay=, momenta=dict|None).  Returns a dict."""
+    sgd: None or dict(lr=, momentum=, weight_decay=, momenta=dict|None).
+    adamw: None or dict(lr=, beta1=, beta2=, eps=, weight_decay=, step=, exp_avg=dict, exp_avg_sq=dict).
+    Returns a dict."""
     dev = torch.device("cuda:0")
     B = x.shape[0]
     own = ctx is None
@@ -69,6 +71,10 @@ def run_hip_step(cfg, params, x, labels, forced_idx=None, max_batch=None, sgd=No
     if sgd is not None:
         mom = sgd.get("momenta")
         ctx.bsr_sgd_step(grads, mom, sgd["lr"], sgd.get("momentum", 0.0), sgd.get("weight_decay", 0.0))
+        new_params = {n: ctx.params[n].detach().cpu().numpy().copy() for n in ctx.trainable_names}
+    if adamw is not None:
+        ctx.bsr_adamw_step(grads, adamw["exp_avg"], adamw["exp_avg_sq"], adamw["lr"], adamw["beta1"],
+                           adamw["beta2"], adamw["eps"], adamw["weight_decay"], adamw["step"])
         new_params = {n: ctx.params[n].detach().cpu().numpy().copy() for n in ctx.trainable_names}
     torch.cuda.synchronize()
 

@@ -229,6 +229,53 @@ def test_sgd_update_and_second_step(hip, orc64, dtype, mu, wd):
             assert np.array_equal(t.cpu().numpy(), p[n].astype(np.float32)), n
 
 
+@pytest.mark.parametrize("name,dtype", [("mini_4blk", "fp32"), ("mini_4blk", "bf16"), ("mini_moe", "bf16"),
+                                        ("mini_interleaved", "fp32")])
+def test_adamw_update_and_next_step(hip, orc64, name, dtype):
+    # AdamW divides by sqrt(v): a first step moves every weight by about lr whatever the size of its
+    # gradient, so the update rule is checked on the GPU's own gradients (their parity is the other
+    # tests' business); the step after it is checked against the oracle on the GPU's new weights.
+    import torch
+    cfg = S.get_config(name, dtype=dtype)
+    p = S.make_params(cfg, std=0.05)
+    x, y = S.make_inputs(cfg)
+    hp = dict(lr=2e-3, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.05)
+    ref1 = orc64.step(cfg, p, x, y)
+    fex = ref1.get("experts") or None
+    p_ref = {n: p[n].astype(np.float32).astype(np.float64) for n in ref1["grads"]}
+    m_ref = {n: np.zeros(v.size) for n, v in p_ref.items()}
+    v_ref = {n: np.zeros(v.size) for n, v in p_ref.items()}
+    got = hip.run_hip_step(cfg, p, x, y, forced_idx=ref1["kept_idx"], forced_experts=fex)
+    ctx = got["ctx"]
+    ea = {n: torch.zeros_like(t) for n, t in ctx.new_grads().items()}
+    ev = {n: torch.zeros_like(t) for n, t in ctx.new_grads().items()}
+    for t in (1, 2):
+        got = hip.run_hip_step(cfg, p, x, y, forced_idx=ref1["kept_idx"], forced_experts=fex, ctx=ctx,
+                               adamw=dict(step=t, exp_avg=ea, exp_avg_sq=ev, **hp))
+        for n in p_ref:
+            w, m, v = orc64.adamw(p_ref[n].reshape(-1), got["grads"][n].reshape(-1).astype(np.float64), m_ref[n],
+                                  v_ref[n], hp["lr"], hp["beta1"], hp["beta2"], hp["eps"], hp["weight_decay"], t)
+            moved = np.abs(w - p_ref[n].reshape(-1)).max()
+            assert moved > 0.1 * hp["lr"], n
+            # fp32 state on the GPU: the error allowed is a few ulps of the weight plus 1e-4 of the move
+            err = np.abs(got["new_params"][n].reshape(-1) - w).max()
+            assert err < 1e-4 * moved + 4e-7 * np.abs(w).max(), (n, t, err, moved)
+            assert hip.rel(ea[n].cpu().numpy().reshape(-1), m) < 1e-5, n
+            assert hip.rel(ev[n].cpu().numpy().reshape(-1), v) < 1e-5, n
+            p_ref[n], m_ref[n], v_ref[n] = got["new_params"][n].astype(np.float64), m, v
+    # the next step on the updated weights (in bf16 mode through the refreshed bf16 copies)
+    p2 = dict(p)
+    p2.update({n: v.reshape(p[n].shape) for n, v in p_ref.items()})
+    ref = orc64.step(cfg, p2, x, y, forced_idx=ref1["kept_idx"], forced_experts=fex)
+    got3 = hip.run_hip_step(cfg, p, x, y, forced_idx=ref1["kept_idx"], forced_experts=fex, ctx=ctx)
+    tol = TOL_FP32 if dtype == "fp32" else TOL_BF16
+    assert abs(got3["loss"] - ref["loss"]) < tol * max(1.0, abs(ref["loss"]))
+    assert hip.rel(got3["logits"], ref["logits"]) < tol
+    for n, t_ in ctx.params.items():
+        if n not in ctx.trainable_names:
+            assert np.array_equal(t_.cpu().numpy(), p[n].astype(np.float32)), n
+
+
 # ------------------------------------------------------------------ the benchmark's own workload
 
 def test_headline_workload_full_size(hip, orc32):

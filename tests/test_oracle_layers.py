@@ -203,3 +203,20 @@ def test_sgd_closed_form(orc64):
         opt.step()
         w, m = orc64.sgd(w, np.array(g), m, lr=0.05, mu=0.9, wd=1e-2)
     assert close(w, wt.detach().numpy(), 1e-14)
+
+
+def test_adamw_against_torch_optimizer(orc64):
+    """orc_adamw against torch.optim.AdamW (decoupled weight decay), three steps."""
+    import torch
+    rng = np.random.default_rng(4)
+    w0 = rng.standard_normal(257); gs = [rng.standard_normal(257) for _ in range(3)]
+    lr, b1, b2, eps, wd = 3e-3, 0.9, 0.98, 1e-8, 0.05
+    p = torch.tensor(w0, dtype=torch.float64, requires_grad=True)
+    opt = torch.optim.AdamW([p], lr=lr, betas=(b1, b2), eps=eps, weight_decay=wd)
+    w, m, v = w0.copy(), np.zeros_like(w0), np.zeros_like(w0)
+    for t, g in enumerate(gs, 1):
+        p.grad = torch.tensor(g, dtype=torch.float64)
+        opt.step()
+        w, m, v = orc64.adamw(w, g, m, v, lr, b1, b2, eps, wd, t)
+        assert np.allclose(w, p.detach().numpy(), rtol=1e-12, atol=1e-14), t
+    assert np.abs(w - w0).max() > 1e-3
