@@ -127,6 +127,34 @@ int32_t bsr_token_schedule(const bsr_config* cfg, int32_t* keep_k_out, int32_t* 
 int32_t bsr_workspace_bytes(const bsr_config* cfg, size_t* bytes_out);
 
 /*
+ * Bytes of activations the blocks in the gradient path keep between their forward and backward
+ * pass (host only, touches no GPU), per block and by kind, for `batch` images.  The counts are the
+ * unpadded sizes of the very buffers the workspace layout reserves, so the report cannot drift
+ * from what the library stores.  Sec. 3.2 / Table 1 list what the non-linear layers of a block
+ * need (Q, K, V, the softmax input, the GELU input); a block whose weights are trained also keeps
+ * the inputs of its linear layers (Eq. 4).  This library keeps one log-sum-exp per attention row
+ * in place of the [H,T,T] softmax input and recomputes the probabilities in the backward pass.
+ *   qkv        Q, K, V                               [B,T,3D]  act
+ *   softmax    per-row log-sum-exp                   [B,H,T]   fp32
+ *   attn_out   attention output O (softmax backward reads rowsum(dO*O); the projection's input)
+ *   gelu_in    FFN hidden pre-activation u           [B,T',F]  act  (x top-k in a mixture block)
+ *   linear_in  LN1 output, LN2 output, GELU output: inputs of linears whose weights are trained
+ *   residual   the tensors LayerNorm backward reads: x after MHSA (gathered at a drop location)
+ *              and the block output (which is the next block's input)
+ *   stats      LayerNorm mean / rstd, kept-token indices, fused-token weights
+ *   moe        router logits, gates, expert choice, expert-major row copies and expert outputs
+ *   total      sum of the above
+ * Blocks before the first one in the gradient path report zeros: they store nothing.
+ *   per_block  host [depth], may be NULL;  sum  host, one entry, may be NULL.
+ * Errors: INVALID_ARG (cfg NULL, batch < 1 or > max_batch), BAD_CONFIG.
+ */
+typedef struct {
+  uint64_t qkv, softmax, attn_out, gelu_in, linear_in, residual, stats, moe, total;
+} bsr_saved_bytes;
+int32_t bsr_saved_activation_bytes(const bsr_config* cfg, int32_t batch, bsr_saved_bytes* per_block,
+                                   bsr_saved_bytes* sum);
+
+/*
  * Create a context (the problem statement of Sec. 4.1: a pre-trained ViT, drop locations, drop
  * rate, trainable set).
  *   params     host struct of device fp32 pointers: the master weights.  The struct is copied; the

@@ -68,10 +68,11 @@ def load_library():
     for name in ("bsr_token_schedule", "bsr_workspace_bytes", "bsr_init", "bsr_refresh_weights",
                  "bsr_forward_frozen", "bsr_select_tokens", "bsr_train_blocks_fwd_bwd",
                  "bsr_sgd_step", "bsr_destroy", "bsr_profile_begin", "bsr_profile_end", "bsr_moe_routing_io",
-                 "bsr_adamw_step"):
+                 "bsr_adamw_step", "bsr_saved_activation_bytes"):
         getattr(lib, name).restype = C.c_int32
     lib.bsr_token_schedule.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
     lib.bsr_workspace_bytes.argtypes = [C.c_void_p, C.POINTER(C.c_size_t)]
+    lib.bsr_saved_activation_bytes.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]
     lib.bsr_init.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p, C.POINTER(C.c_void_p)]
     lib.bsr_refresh_weights.argtypes = [C.c_void_p, C.c_void_p]
     lib.bsr_forward_frozen.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p,
@@ -164,6 +165,20 @@ def bsr_workspace_bytes(cfg: bsr_config) -> int:
     n = C.c_size_t(0)
     _check(load_library().bsr_workspace_bytes(C.byref(cfg), C.byref(n)))
     return int(n.value)
+
+
+class bsr_saved_bytes(C.Structure):
+    _fields_ = [(n, C.c_uint64) for n in ("qkv", "softmax", "attn_out", "gelu_in", "linear_in", "residual",
+                                          "stats", "moe", "total")]
+
+
+def bsr_saved_activation_bytes(cfg: bsr_config, batch: int):
+    """-> (list per block of dict kind -> bytes, dict of sums) for `batch` images."""
+    per = (bsr_saved_bytes * MAX_BLOCKS)()
+    tot = bsr_saved_bytes()
+    _check(load_library().bsr_saved_activation_bytes(C.byref(cfg), C.c_int32(batch), per, C.byref(tot)))
+    as_dict = lambda r: {n: int(getattr(r, n)) for n, _ in bsr_saved_bytes._fields_}
+    return [as_dict(per[l]) for l in range(cfg.depth)], as_dict(tot)
 
 
 def _cur_stream(t):

@@ -209,7 +209,8 @@ struct Carver {
   char* base;
   size_t off = 0;
   template <typename T>
-  T* take(size_t count) {
+  T* take(size_t count, uint64_t* tally = nullptr) {   // tally: unpadded bytes, for the saved-activation report
+    if (tally) *tally += count * sizeof(T);
     size_t bytes = (count * sizeof(T) + 255) & ~(size_t)255;
     T* p = base ? (T*)(base + off) : nullptr;
     off += bytes;
@@ -218,7 +219,7 @@ struct Carver {
 };
 
 // One function lays out the workspace; with base == nullptr it only measures.
-size_t carve(const bsr_config& c, const Schedule& s, char* base, Buffers* out) {
+size_t carve(const bsr_config& c, const Schedule& s, char* base, Buffers* out, bsr_saved_bytes* saved = nullptr) {
   Carver w{base};
   Buffers b;
   const bool f32 = c.dtype == BSR_FP32;
@@ -255,16 +256,16 @@ size_t carve(const bsr_config& c, const Schedule& s, char* base, Buffers* out) {
   b.fw = w.take<float>(B * T0);
   b.idx_tmp = w.take<int32_t>(B * T0);
   const size_t KE = c.n_moe > 0 ? (size_t)c.moe_top_k : 1, NE = c.n_moe > 0 ? (size_t)c.n_experts : 0;
-  auto take_moe = [&](MoeBuf& m, size_t rows) {      // rows = tokens of the FFN
-    m.logits = w.take<float>(rows * NE);
-    m.gates = w.take<float>(rows * KE);
-    m.dsel = w.take<float>(rows * KE);
-    m.experts = w.take<int32_t>(rows * KE);
-    m.pos = w.take<int32_t>(rows * KE);
-    m.perm_tok = w.take<int32_t>(rows * KE);
-    m.off = w.take<int32_t>(NE + 1);
-    m.xg = w.take<char>(rows * KE * D * E);
-    m.y = w.take<float>(rows * KE * D);
+  auto take_moe = [&](MoeBuf& m, size_t rows, uint64_t* t = nullptr) {      // rows = tokens of the FFN
+    m.logits = w.take<float>(rows * NE, t);
+    m.gates = w.take<float>(rows * KE, t);
+    m.dsel = w.take<float>(rows * KE, t);
+    m.experts = w.take<int32_t>(rows * KE, t);
+    m.pos = w.take<int32_t>(rows * KE, t);
+    m.perm_tok = w.take<int32_t>(rows * KE, t);
+    m.off = w.take<int32_t>(NE + 1, t);
+    m.xg = w.take<char>(rows * KE * D * E, t);
+    m.y = w.take<float>(rows * KE * D, t);
   };
   bool frozen_moe = false;
   for (int l = 0; l < ft && l < L; ++l) frozen_moe |= s.moe[l];
@@ -277,25 +278,30 @@ size_t carve(const bsr_config& c, const Schedule& s, char* base, Buffers* out) {
     const size_t Ta = s.Ta[l], Tm = s.Tm[l];
     Tmax = std::max(Tmax, Ta);
     SavedBlock& v = b.sv[l];
-    v.mean1 = w.take<float>(B * Ta);
-    v.rstd1 = w.take<float>(B * Ta);
-    v.mean2 = w.take<float>(B * Tm);
-    v.rstd2 = w.take<float>(B * Tm);
-    v.lse = w.take<float>(B * H * Ta);
+    bsr_saved_bytes none = {};
+    bsr_saved_bytes& r = saved ? saved[l] : none;
+    v.mean1 = w.take<float>(B * Ta, &r.stats);
+    v.rstd1 = w.take<float>(B * Ta, &r.stats);
+    v.mean2 = w.take<float>(B * Tm, &r.stats);
+    v.rstd2 = w.take<float>(B * Tm, &r.stats);
+    v.lse = w.take<float>(B * H * Ta, &r.softmax);
     const bool keep_lin = s.trainable[l] || s.moe[l];   // inputs of the linear layers: only Eq. 4 needs them
-    v.h1 = keep_lin ? w.take<char>(B * Ta * D * E) : b.h;
-    v.qkv = w.take<char>(B * Ta * 3 * D * E);
-    v.o = w.take<char>(B * Ta * D * E);
-    v.xmid_full = w.take<char>(B * Ta * D * E);
-    v.xmid = (s.drop_of[l] >= 0) ? w.take<char>(B * Tm * D * E) : v.xmid_full;
-    v.h2 = keep_lin ? w.take<char>(B * Tm * D * E) : b.h;
+    v.h1 = keep_lin ? w.take<char>(B * Ta * D * E, &r.linear_in) : b.h;
+    v.qkv = w.take<char>(B * Ta * 3 * D * E, &r.qkv);
+    v.o = w.take<char>(B * Ta * D * E, &r.attn_out);
+    // x after MHSA: at a drop location only its gathered rows are read again, the full tensor is scratch
+    const bool drop = s.drop_of[l] >= 0;
+    v.xmid_full = drop ? b.o : w.take<char>(B * Ta * D * E, &r.residual);
+    v.xmid = drop ? w.take<char>(B * Tm * D * E, &r.residual) : v.xmid_full;
+    v.h2 = keep_lin ? w.take<char>(B * Tm * D * E, &r.linear_in) : b.h;
     const size_t kf = s.moe[l] ? KE : 1;               // a mixture block keeps u and g per (token, slot)
-    v.u = w.take<char>(B * Tm * kf * F * E);
-    v.g = keep_lin ? w.take<char>(B * Tm * kf * F * E) : b.g;
-    if (s.moe[l]) take_moe(v.moe, B * Tm);
-    v.xout = w.take<char>(B * Tm * D * E);
-    v.idx = w.take<int32_t>(B * Tm);
-    v.fw = (s.drop_of[l] >= 0 && s.fused[s.drop_of[l]]) ? w.take<float>(B * Ta) : nullptr;
+    v.u = w.take<char>(B * Tm * kf * F * E, &r.gelu_in);
+    v.g = keep_lin ? w.take<char>(B * Tm * kf * F * E, &r.linear_in) : b.g;
+    if (s.moe[l]) take_moe(v.moe, B * Tm, &r.moe);
+    v.xout = w.take<char>(B * Tm * D * E, &r.residual);
+    v.idx = w.take<int32_t>(drop ? B * Tm : 0, &r.stats);
+    v.fw = (drop && s.fused[s.drop_of[l]]) ? w.take<float>(B * Ta, &r.stats) : nullptr;
+    r.total = r.qkv + r.softmax + r.attn_out + r.gelu_in + r.linear_in + r.residual + r.stats + r.moe;
   }
   b.dxa = w.take<char>(B * Tmax * D * E);
   b.dxb = w.take<char>(B * Tmax * D * E);
@@ -592,6 +598,29 @@ int32_t bsr_workspace_bytes(const bsr_config* cfg, size_t* bytes_out) {
   int rc = make_schedule(cfg, &s, why, sizeof(why));
   if (rc != BSR_OK) return fail(nullptr, rc, "%s", why);
   *bytes_out = carve(*cfg, s, nullptr, nullptr);
+  return BSR_OK;
+}
+
+int32_t bsr_saved_activation_bytes(const bsr_config* cfg, int32_t batch, bsr_saved_bytes* per_block,
+                                   bsr_saved_bytes* sum) {
+  if (!cfg) return fail(nullptr, BSR_ERR_INVALID_ARG, "cfg is NULL");
+  Schedule s;
+  char why[256];
+  int rc = make_schedule(cfg, &s, why, sizeof(why));
+  if (rc != BSR_OK) return fail(nullptr, rc, "%s", why);
+  if (batch < 1 || batch > cfg->max_batch) return fail(nullptr, BSR_ERR_INVALID_ARG, "batch %d outside 1..max_batch %d", batch, cfg->max_batch);
+  bsr_config c = *cfg;
+  c.max_batch = batch;
+  bsr_saved_bytes rep[BSR_MAX_BLOCKS] = {};
+  carve(c, s, nullptr, nullptr, rep);
+  bsr_saved_bytes t = {};
+  for (int l = 0; l < cfg->depth; ++l) {
+    if (per_block) per_block[l] = rep[l];
+    t.qkv += rep[l].qkv; t.softmax += rep[l].softmax; t.attn_out += rep[l].attn_out; t.gelu_in += rep[l].gelu_in;
+    t.linear_in += rep[l].linear_in; t.residual += rep[l].residual; t.stats += rep[l].stats; t.moe += rep[l].moe;
+    t.total += rep[l].total;
+  }
+  if (sum) *sum = t;
   return BSR_OK;
 }
 

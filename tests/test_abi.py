@@ -97,3 +97,77 @@ def test_step_flop_count_matches_the_closed_form():
     c3 = step_flops(768, 3072, 100, 768, 196, [197, 197, 197, 197, 138, 138, 138, 96, 96, 96, 67, 67],
                     [197, 197, 197, 138, 138, 138, 96, 96, 96, 67, 67, 67], 8, 32)
     assert abs(c3["total"] / 1e9 - 1012.8) < 0.5
+
+
+# ---------------------------------------------------------------- saved-activation byte report (host only)
+
+def _deit_s(**over):
+    return dict(S.get_config("c2_deit_s", dtype="fp32", keep_ratio=1.0, drop_blocks=[], first_trainable=0), **over)
+
+
+def test_saved_bytes_match_table_1_categories():
+    # Table 1: DeiT-S, one image, fp32, 197 tokens: Q,K,V 0.87 MB, softmax input 0.89 MB, GELU input 1.15 MB
+    from oracle import accounting as acc
+    per, tot = P.bsr_saved_activation_bytes(P.make_config(_deit_s(), 4), 1)
+    nl = acc.saved_bytes_nonlinear(T=197, D=384, H=6, F=1536)
+    MB = 2.0 ** 20
+    for r in per:
+        assert r["qkv"] == nl["qkv"] and abs(r["qkv"] / MB - 0.87) < 0.005
+        assert r["gelu_in"] == nl["gelu_in"] and abs(r["gelu_in"] / MB - 1.15) < 0.005
+        # one log-sum-exp per row stands in for the row itself
+        assert r["softmax"] * 197 == nl["softmax_in"] and abs(r["softmax"] * 197 / MB - 0.89) < 0.005
+        # a trained block stays below the paper's 5.5 MB (it keeps no [H,T,T] tensor)
+        assert r["total"] < acc.saved_bytes_trainable(197, 384, 6, 1536) and r["total"] / MB < 5.5
+        assert r == dict(acc.saved_bytes_lse_design(197, 197, 384, 6, 1536, 4, trained=True, drop=False), moe=0)
+    assert tot["total"] == sum(r["total"] for r in per) == 12 * per[0]["total"]
+
+
+def test_saved_bytes_follow_the_token_schedule_and_the_trainable_set():
+    from oracle import accounting as acc
+    cfg = S.get_config("c6_vit_b_interleaved")          # bf16, trainable {3,7,11}, drops {3,6,9} at 0.5
+    c = P.make_config(cfg, 8)
+    _, ta, tm = P.bsr_token_schedule(c)
+    per, tot = P.bsr_saved_activation_bytes(c, 1)
+    for l, r in enumerate(per):
+        if l < 3:
+            assert all(v == 0 for v in r.values()), l    # the frozen prefix stores nothing
+            continue
+        want = acc.saved_bytes_lse_design(ta[l], tm[l], 768, 12, 3072, 2, trained=l in (3, 7, 11),
+                                          drop=l in (3, 6, 9))
+        assert r == dict(want, moe=0), l
+    assert per[4]["linear_in"] == 0 and per[7]["linear_in"] > 0
+    # frozen in the gradient path: below Table 1's three tensors at the same token count, fp32
+    cfg32 = _deit_s(trainable_blocks=[11], first_trainable=0)
+    per32, _ = P.bsr_saved_activation_bytes(P.make_config(cfg32, 2), 1)
+    assert per32[5]["total"] <= sum(acc.saved_bytes_nonlinear(197, 384, 6, 1536).values())
+    assert per32[5]["total"] < per32[11]["total"]
+
+
+def test_saved_bytes_scale_with_batch_dtype_and_fit_the_workspace():
+    cfg = S.get_config("c3_vit_b")
+    c = P.make_config(cfg, 32)
+    p1, t1 = P.bsr_saved_activation_bytes(c, 1)
+    p32, t32 = P.bsr_saved_activation_bytes(c, 32)
+    assert all(t32[k] == 32 * t1[k] for k in t1)
+    assert 0 < t32["total"] < P.bsr_workspace_bytes(c)
+    _, t1f = P.bsr_saved_activation_bytes(P.make_config(dict(cfg, dtype="fp32"), 32), 1)
+    for k in ("qkv", "attn_out", "gelu_in", "linear_in", "residual"):
+        assert t1f[k] == 2 * t1[k], k
+    assert t1f["softmax"] == t1["softmax"] and t1f["stats"] == t1["stats"]
+    # token dropping shrinks what the trained suffix keeps (Sec. 4.3 Discussion 2)
+    _, full = P.bsr_saved_activation_bytes(P.make_config(dict(cfg, keep_ratio=1.0), 32), 1)
+    assert t1["total"] < 0.5 * full["total"]
+    # fused inattentive token: one more row per drop and the fusion weights
+    _, fu = P.bsr_saved_activation_bytes(P.make_config(dict(cfg, fuse_dropped=True), 32), 1)
+    assert fu["total"] > t1["total"] and fu["stats"] > t1["stats"]
+    # mixture-of-experts blocks report their routing state
+    pm, tmoe = P.bsr_saved_activation_bytes(P.make_config(S.get_config("c5_vit_s_moe"), 8), 1)
+    assert tmoe["moe"] > 0 and all((r["moe"] > 0) == (l in (9, 11)) for l, r in enumerate(pm) if r["total"])
+
+
+def test_saved_bytes_errors():
+    c = P.make_config(S.get_config("mini_4blk"), 4)
+    for bad in (0, 5):
+        with pytest.raises(P.BsrError):
+            P.bsr_saved_activation_bytes(c, bad)
+    assert P.load_library().bsr_saved_activation_bytes(None, 1, None, None) == -1
