@@ -29,7 +29,7 @@ def build_context(cfg, batch, seed=0):
     return ctx
 
 
-def time_steps(ctx, cfg, batch, steps, warmup, profile_steps=0):
+def time_steps(ctx, cfg, batch, steps, warmup, profile_steps=0, autotune=True):
     import torch
     import bsr_synth as S
     dev = ctx.device
@@ -40,6 +40,7 @@ def time_steps(ctx, cfg, batch, steps, warmup, profile_steps=0):
     mom = {n: torch.zeros_like(g) for n, g in grads.items()}
     x_f = torch.empty((batch, ctx.T_f, cfg["dim"]), dtype=ctx.act_dtype, device=dev)
     loss = torch.zeros(4, dtype=torch.float32, device=dev)
+    tuned = ctx.bsr_autotune(xin, lab, x_f, loss, grads) if autotune else None      # set-up, untimed
 
     def step():
         ctx.bsr_forward_frozen(xin, x_out=x_f)
@@ -66,7 +67,7 @@ def time_steps(ctx, cfg, batch, steps, warmup, profile_steps=0):
         prof = ctx.bsr_profile_end()
         prof = {k: (v[0] / profile_steps, v[1] / profile_steps, v[2] // profile_steps) for k, v in prof.items()}
     return dict(wall_s=wall, ms_per_step=1e3 * wall / steps, ms_per_step_events=ms_events / steps,
-                loss=float(loss[0].item()), prof=prof)
+                loss=float(loss[0].item()), prof=prof, tuned=tuned)
 
 
 def cpu_baseline(cfg, sample_batch):
@@ -113,6 +114,7 @@ def main():
     ap.add_argument("--keep-ratio", type=float, default=None)
     ap.add_argument("--trainable", type=int, default=None, help="number of trainable blocks (suffix)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--no-autotune", action="store_true", help="keep the cost model's tile choices")
     ap.add_argument("--no-compare", action="store_true", help="skip the keep-1.0 / full-fine-tuning legs")
     ap.add_argument("--cpu-sample", type=int, default=16)
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -145,7 +147,8 @@ def main():
                           moe_top_k=c.get("moe_top_k", 0), trainable_blocks=c.get("trainable_blocks"))
 
     ctx = build_context(cfg, batch)
-    r = time_steps(ctx, cfg, batch, args.steps, args.warmup, profile_steps=min(args.steps, 10))
+    r = time_steps(ctx, cfg, batch, args.steps, args.warmup, profile_steps=min(args.steps, 10),
+                   autotune=not args.no_autotune)
     fl = flops_of(cfg, ctx)
     ips = batch * args.steps / r["wall_s"]
     gemm_ms, gemm_flops, gemm_n = r["prof"]["gemm"]
@@ -169,6 +172,7 @@ def main():
         "step_pct_of_bf16_mfma_peak": 100.0 * fl["total"] / (r["ms_per_step"] * 1e-3) / (peak * 1e12),
         "ms_per_step_hip_events": r["ms_per_step_events"],
         "loss": r["loss"],
+        "tile_autotune": None if r["tuned"] is None else {"launches": r["tuned"][0], "differ_from_cost_model": r["tuned"][1]},
         "roofline": {"bound": "mfma", "kernel": "GEMM launches of the step (forward, dgrad, wgrad)",
                      "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak,
                      "traffic": None, "launches_per_step": gemm_n, "ms_per_step": gemm_ms,

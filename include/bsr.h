@@ -224,6 +224,25 @@ int32_t bsr_train_blocks_fwd_bwd(bsr_ctx* ctx, const void* x_in, const int32_t* 
                                  const int32_t* forced_idx, void* stream);
 
 /*
+ * Measured tile choice (set-up, not part of a step).  The tiled matrix-multiply kernel behind the
+ * linear layers comes in several block-tile shapes; which one is fastest for a launch depends on how
+ * its tile count divides over the 256 compute units and on what surrounds it in the step.  This call
+ * runs bsr_forward_frozen + bsr_train_blocks_fwd_bwd on the given batch once per shape (twice over),
+ * times every such launch with HIP events in its place in the step, and from then on gives each
+ * launch of a batch of the same size B its fastest shape; other batch sizes keep the built-in cost
+ * model.  Every shape adds up an output element in the same order, so results do not change by a
+ * bit.  Arguments as for the two entry points (x_frozen is the x_out of the first and the x_in of
+ * the second; loss_out and grads are overwritten as by a normal step).
+ *   launches_out  host, may be NULL: number of launches that now have a measured choice
+ *   changed_out   host, may be NULL: how many of them differ from the cost model's choice
+ * BLOCKS until the stream has drained (it reads event times).  Not capturable into a graph.
+ * Errors: as the two entry points; HIP.
+ */
+int32_t bsr_autotune(bsr_ctx* ctx, const void* input, const int32_t* labels, int32_t B, void* x_frozen,
+                     float* loss_out, const bsr_params* grads, int32_t* launches_out, int32_t* changed_out,
+                     void* stream);
+
+/*
  * Routing of the mixture-of-experts blocks (Sec. 5.3), for tests and inspection.  Per token the K
  * experts with the largest router logits (logits = LN2(x) . w_router; ties: lower expert index) are
  * active, ordered by descending logit, and weighted by the softmax over those K logits; the choice

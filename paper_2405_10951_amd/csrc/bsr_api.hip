@@ -79,7 +79,22 @@ struct ProfRec {
   double flops;
 };
 
+// Tile choice per NT GEMM launch, measured on the context's own launches (bsr_autotune).  A launch is
+// identified by the entry point it belongs to and its position in that call's launch order.
+struct TunePick { int M, N, K, tile; };
+struct TuneRec { int kind, cand; size_t site; int M, N, K; hipEvent_t start, stop; };
+struct Tune {
+  int batch = 0;                       // the picks hold for this batch size (0: none)
+  std::vector<TunePick> pick[2];       // [0] bsr_forward_frozen, [1] bsr_train_blocks_fwd_bwd
+  int kind = 0;                        // entry point running now
+  size_t site = 0;                     // NT launches it has issued so far
+  int cur_batch = 0;
+  int cand = -1;                       // >= 0 while tuning: index of the shape every launch is forced to
+  std::vector<TuneRec> recs;
+};
+
 struct bsr_ctx {
+  Tune tune;
   std::vector<ProfRec> prof;   // event pairs of the profiling mode (bsr_profile_begin / _end)
   size_t prof_used = 0;
   bool prof_on = false;
@@ -392,6 +407,28 @@ struct ProfScope {
 
 void gemm(bsr_ctx* c, const GemmDesc& g, hipStream_t s) {
   ProfScope ps(c, BSR_PROF_GEMM, 2.0 * g.M * g.N * g.K, s);
+  if (gemm_nt_tile_is_free(g)) {
+    Tune& t = c->tune;
+    const size_t site = t.site++;
+    if (t.cand >= 0) {                 // tuning pass: force the candidate and bracket the launch with events
+      TuneRec r{t.kind, t.cand, site, g.M, g.N, g.K, nullptr, nullptr};
+      const bool ev = hipEventCreate(&r.start) == hipSuccess && hipEventCreate(&r.stop) == hipSuccess;
+      if (ev) (void)hipEventRecord(r.start, s);
+      gemm_mfma(g, c->b.splitk, c->b.splitk_floats, s, gemm_nt_tile_id(t.cand));
+      if (ev) {
+        (void)hipEventRecord(r.stop, s);
+        t.recs.push_back(r);
+      }
+      return;
+    }
+    int tile = 0;
+    if (t.batch == t.cur_batch && site < t.pick[t.kind].size()) {
+      const TunePick& p = t.pick[t.kind][site];
+      if (p.M == g.M && p.N == g.N && p.K == g.K) tile = p.tile;
+    }
+    gemm_mfma(g, c->b.splitk, c->b.splitk_floats, s, tile);
+    return;
+  }
   if (gemm_mfma_supported(g)) gemm_mfma(g, c->b.splitk, c->b.splitk_floats, s);
   else if (g.grp_off) fail(c, BSR_ERR_BAD_CONFIG, "grouped GEMM %d x %d x %d is not an MFMA shape", g.M, g.N, g.K);
   else gemm_generic(g, s);
@@ -676,6 +713,7 @@ int32_t bsr_forward_frozen(bsr_ctx* c, const void* input, int32_t B, void* x_out
   if (!c) return fail(nullptr, BSR_ERR_INVALID_ARG, "ctx is NULL");
   if (!aligned16(input) || !aligned16(x_out)) return fail(c, BSR_ERR_INVALID_ARG, "input / x_out is NULL or not 16-byte aligned");
   if (B < 1 || B > c->cfg.max_batch) return fail(c, BSR_ERR_INVALID_ARG, "B = %d outside 1..max_batch (%d)", B, c->cfg.max_batch);
+  c->tune.kind = 0; c->tune.site = 0; c->tune.cur_batch = B;
   hipStream_t s = (hipStream_t)stream;
   const bsr_config& cf = c->cfg;
   const Schedule& sc = c->sc;
@@ -769,6 +807,7 @@ int32_t bsr_train_blocks_fwd_bwd(bsr_ctx* c, const void* x_in, const int32_t* la
   const char* which = "";
   if (check_params(cf, grads, cf.first_trainable_block, false, &which, &c->sc) != BSR_OK)
     return fail(c, BSR_ERR_INVALID_ARG, "gradient tensor %s is NULL or not 16-byte aligned", which);
+  c->tune.kind = 1; c->tune.site = 0; c->tune.cur_batch = B;
   hipStream_t s = (hipStream_t)stream;
   const Schedule& sc = c->sc;
   Buffers& b = c->b;
@@ -982,6 +1021,70 @@ static int32_t optimizer_step(bsr_ctx* c, const bsr_params* grads, const bsr_par
     if (c->sc.moe[l] && c->sc.trainable[l])
       moe_router_copy((const float*)c->p.blocks[l].w_router, D, cf.n_experts, c->b.sh[l].t_router, s);
   return check_hip(c, where);
+}
+
+int32_t bsr_autotune(bsr_ctx* c, const void* input, const int32_t* labels, int32_t B, void* x_frozen,
+                     float* loss_out, const bsr_params* grads, int32_t* launches_out, int32_t* changed_out,
+                     void* stream) {
+  if (!c) return fail(nullptr, BSR_ERR_INVALID_ARG, "ctx is NULL");
+  hipStream_t s = (hipStream_t)stream;
+  Tune& t = c->tune;
+  t.batch = 0;
+  t.pick[0].clear();
+  t.pick[1].clear();
+  const int n = gemm_nt_tile_count();
+  constexpr int ROUNDS = 2;
+  int rc = BSR_OK;
+  // pass -1 is untimed (first-use set-up of the kernels); then every shape, ROUNDS times
+  for (int pass = -1; pass < ROUNDS * n && rc == BSR_OK; ++pass) {
+    t.cand = pass < 0 ? -1 : pass % n;
+    rc = bsr_forward_frozen(c, input, B, x_frozen, nullptr, nullptr, nullptr, stream);
+    if (rc == BSR_OK) rc = bsr_train_blocks_fwd_bwd(c, x_frozen, labels, B, loss_out, nullptr, nullptr, grads, nullptr, nullptr, nullptr, stream);
+  }
+  t.cand = -1;
+  const bool synced = hipStreamSynchronize(s) == hipSuccess;
+  int launches = 0;
+  if (rc == BSR_OK && synced) {
+    size_t sites[2] = {0, 0};
+    for (const TuneRec& r : t.recs) sites[r.kind] = std::max(sites[r.kind], r.site + 1);
+    for (int k = 0; k < 2; ++k) {
+      std::vector<float> best(sites[k] * n, -1.f);          // min over the rounds, per (site, shape)
+      t.pick[k].assign(sites[k], TunePick{0, 0, 0, 0});
+      for (const TuneRec& r : t.recs) {
+        if (r.kind != k) continue;
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, r.start, r.stop) != hipSuccess) continue;
+        float& b = best[r.site * n + r.cand];
+        if (b < 0.f || ms < b) b = ms;
+        TunePick& p = t.pick[k][r.site];
+        p.M = r.M; p.N = r.N; p.K = r.K;
+      }
+      for (size_t i = 0; i < sites[k]; ++i) {
+        int arg = -1;
+        for (int j = 0; j < n; ++j)
+          if (best[i * n + j] >= 0.f && (arg < 0 || best[i * n + j] < best[i * n + arg])) arg = j;
+        t.pick[k][i].tile = arg < 0 ? 0 : gemm_nt_tile_id(arg);
+        ++launches;
+      }
+    }
+    t.batch = B;
+  }
+  for (TuneRec& r : t.recs) {
+    (void)hipEventDestroy(r.start);
+    (void)hipEventDestroy(r.stop);
+  }
+  t.recs.clear();
+  if (rc != BSR_OK) return rc;
+  if (!synced) return fail(c, BSR_ERR_HIP, "bsr_autotune: stream synchronisation failed");
+  if (launches_out) *launches_out = launches;
+  if (changed_out) {
+    // how many launches now take another shape than the built-in model would give them
+    int diff = 0;
+    for (int k = 0; k < 2; ++k)
+      for (const TunePick& p : t.pick[k]) diff += p.tile != 0 && p.tile != gemm_nt_model_tile(p.M, p.N, p.K);
+    *changed_out = diff;
+  }
+  return check_hip(c, "bsr_autotune");
 }
 
 int32_t bsr_sgd_step(bsr_ctx* c, const bsr_params* grads, const bsr_params* momenta, float lr,

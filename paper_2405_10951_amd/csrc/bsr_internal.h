@@ -47,7 +47,13 @@ void attn_bwd_generic(const void* qkv, const void* out, const void* dout, const 
 // ---- bf16 MFMA paths --------------------------------------------------------------------------
 bool gemm_mfma_supported(const GemmDesc& g);
 // splitk_ws: fp32 scratch for the partial sums of split-K weight gradients (may be null: no split)
-void gemm_mfma(const GemmDesc& g, float* splitk_ws, size_t splitk_ws_floats, hipStream_t s);
+// tile: one of gemm_nt_tile_id() for the NT kernel (ignored by the others), 0 = the built-in model chooses
+void gemm_mfma(const GemmDesc& g, float* splitk_ws, size_t splitk_ws_floats, hipStream_t s, int tile = 0);
+// the block-tile shapes the NT kernel is instantiated for, and whether a GEMM is free to take any of them
+int gemm_nt_tile_count();
+int gemm_nt_model_tile(int M, int N, int K);   // the built-in model's choice
+int gemm_nt_tile_id(int i);
+bool gemm_nt_tile_is_free(const GemmDesc& g);
 size_t gemm_splitk_ws_floats(int dim, int mlp_hidden);
 
 bool attn_mfma_supported(int T, int d);

@@ -602,35 +602,57 @@ bool gemm_mfma_supported(const GemmDesc& g) { return is_nt(g) || is_tn(g); }
 // without a tile, so each launch takes the shape that a two-parameter model predicts to be fastest:
 //   time = ceil(tiles / 256 CUs) * (fixed + per_ktile * K / 64)
 // with (fixed, per_ktile) in microseconds fitted per tile shape to the durations of the step's own
-// GEMMs (N and K in {768, 2304, 3072}, epilogues included) with every shape forced in turn; the
-// model's picks cost 0.3 % more than the per-launch best of those runs.  The large tiles pay a long
-// fixed part because their single workgroup per CU cannot hide its prologue and epilogue.
+// GEMMs (N and K in {768, 2304, 3072}, epilogues included) with every shape forced in turn.  The
+// model's picks cost 2.5 % more than the per-launch best of those runs (its residual is 3 - 5 us per
+// launch), which is why a context can instead time every shape on its own launches and keep the
+// fastest (bsr_autotune).  The large tiles pay a long fixed part because their single workgroup per
+// CU cannot hide its prologue and epilogue.  Every shape accumulates an output element over k in the
+// same order, so the choice never changes a result.
 struct NtShape { int id, bm, bn; float fixed_us, per_ktile_us; };
 static const NtShape kNtShapes[] = {
-    {256128, 256, 128, 11.23f, 0.714f}, {128128, 128, 128, 3.22f, 0.620f}, {192128, 192, 128, 8.03f, 0.689f},
-    {160256, 160, 256, 12.81f, 1.007f}, {256256, 256, 256, 18.17f, 1.303f},
+    {256128, 256, 128, 9.77f, 0.714f},  {128128, 128, 128, 2.78f, 0.577f}, {192128, 192, 128, 4.17f, 0.734f},
+    {160256, 160, 256, 11.85f, 0.975f}, {256256, 256, 256, 17.70f, 1.300f},
+    {128064, 128, 64, 1.39f, 0.351f},   {96128, 96, 128, 2.38f, 0.507f},
+    // offered to the measured choice only (no fitted constants: fixed_us < 0 keeps them out of the model)
+    {64128, 64, 128, -1.f, 0.f},        {128256, 128, 256, -1.f, 0.f},     {192256, 192, 256, -1.f, 0.f},
+    {256064, 256, 64, -1.f, 0.f},       {96256, 96, 256, -1.f, 0.f},
 };
 
-void gemm_mfma(const GemmDesc& g, float* splitk_ws, size_t splitk_ws_floats, hipStream_t s) {
+int gemm_nt_model_tile(int M, int N, int K) {
+  int pick = 0;
+  float best = 0.f;
+  for (const NtShape& t : kNtShapes) {
+    if (t.fixed_us < 0.f) continue;
+    const int64_t tiles = (int64_t)((M + t.bm - 1) / t.bm) * ((N + t.bn - 1) / t.bn);
+    const float us = (float)((tiles + 255) / 256) * (t.fixed_us + t.per_ktile_us * (float)((K + BK - 1) / BK));
+    if (!pick || us < best) { pick = t.id; best = us; }
+  }
+  return pick;
+}
+int gemm_nt_tile_count() { return (int)(sizeof(kNtShapes) / sizeof(kNtShapes[0])); }
+int gemm_nt_tile_id(int i) { return kNtShapes[i].id; }
+bool gemm_nt_tile_is_free(const GemmDesc& g) { return is_nt(g) && !g.grp_off; }
+
+void gemm_mfma(const GemmDesc& g, float* splitk_ws, size_t splitk_ws_floats, hipStream_t s, int tile) {
   if (is_tn(g)) {
     launch_tn(g, splitk_ws, splitk_ws_floats, s);
     return;
   }
   static const int forced = [] { const char* e = getenv("BSR_NT_TILE"); return e ? atoi(e) : 0; }();
-  int pick = g.grp_off ? 128128 : forced;     // groups are a few hundred rows: small tiles
-  if (!pick) {
-    float best = 0.f;
-    for (const NtShape& t : kNtShapes) {
-      const int64_t tiles = (int64_t)((g.M + t.bm - 1) / t.bm) * ((g.N + t.bn - 1) / t.bn);
-      const float us = (float)((tiles + 255) / 256) * (t.fixed_us + t.per_ktile_us * (float)((g.K + BK - 1) / BK));
-      if (!pick || us < best) { pick = t.id; best = us; }
-    }
-  }
+  int pick = g.grp_off ? 128128 : (tile ? tile : forced);     // groups are a few hundred rows: small tiles
+  if (!pick) pick = gemm_nt_model_tile(g.M, g.N, g.K);
   switch (pick) {
     case 256256: launch_nt<256, 256, 2, 4>(g, s); break;
     case 256128: launch_nt<256, 128, 4, 4>(g, s); break;
     case 192128: launch_nt<192, 128, 2, 4>(g, s); break;
     case 160256: launch_nt<160, 256, 1, 8>(g, s); break;
+    case 128064: launch_nt<128, 64, 4, 2>(g, s); break;
+    case 96128: launch_nt<96, 128, 1, 4>(g, s); break;
+    case 64128: launch_nt<64, 128, 2, 4>(g, s); break;
+    case 128256: launch_nt<128, 256, 2, 4>(g, s); break;
+    case 192256: launch_nt<192, 256, 2, 4>(g, s); break;
+    case 256064: launch_nt<256, 64, 4, 2>(g, s); break;
+    case 96256: launch_nt<96, 256, 1, 8>(g, s); break;
     default: launch_nt<128, 128, 4, 2>(g, s); break;
   }
 }
