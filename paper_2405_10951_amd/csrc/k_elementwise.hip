@@ -646,21 +646,34 @@ __global__ __launch_bounds__(256) void mean_sq_kernel(const T* __restrict__ x, i
 // rows and cols are multiples of 4.
 typedef __bf16 bf16x4_t __attribute__((ext_vector_type(4)));
 
-// one element of the optimiser update; m / v2 are read and written only by the rules that use them
-__device__ inline float opt_update(const OptArgs& o, float w, float g, float* m, float* v2, int64_t i) {
+// one element of the optimiser update; m / v2 are the element's moments, used and rewritten only by
+// the rules that have them
+__device__ inline float opt_update(const OptArgs& o, float w, float g, float& m, float& v2) {
   if (o.kind == OPT_ADAMW) {
-    const float mi = o.b1 * m[i] + (1.0f - o.b1) * g;
-    const float vi = o.b2 * v2[i] + (1.0f - o.b2) * g * g;
-    m[i] = mi;
-    v2[i] = vi;
-    return w - o.lr * ((mi / o.bc1) / (sqrtf(vi / o.bc2) + o.eps) + o.wd * w);
+    m = o.b1 * m + (1.0f - o.b1) * g;
+    v2 = o.b2 * v2 + (1.0f - o.b2) * g * g;
+    return w - o.lr * ((m / o.bc1) / (sqrtf(v2 / o.bc2) + o.eps) + o.wd * w);
   }
   float gp = g + o.wd * w;
   if (o.mu > 0.f) {
-    gp = o.mu * m[i] + gp;
-    m[i] = gp;
+    gp = o.mu * m + gp;
+    m = gp;
   }
   return w - o.lr * gp;
+}
+
+// four consecutive elements at offset off (16-byte accesses)
+__device__ inline float4 opt_update4(const OptArgs& o, float4 w, float4 g, float* m, float* v2, int64_t off) {
+  const bool use_m = o.kind == OPT_ADAMW || o.mu > 0.f, use_v = o.kind == OPT_ADAMW;
+  float4 mm = use_m ? *(const float4*)(m + off) : make_float4(0.f, 0.f, 0.f, 0.f);
+  float4 vv = use_v ? *(const float4*)(v2 + off) : make_float4(0.f, 0.f, 0.f, 0.f);
+  w.x = opt_update(o, w.x, g.x, mm.x, vv.x);
+  w.y = opt_update(o, w.y, g.y, mm.y, vv.y);
+  w.z = opt_update(o, w.z, g.z, mm.z, vv.z);
+  w.w = opt_update(o, w.w, g.w, mm.w, vv.w);
+  if (use_m) *(float4*)(m + off) = mm;
+  if (use_v) *(float4*)(v2 + off) = vv;
+  return w;
 }
 
 template <bool UPDATE>
@@ -681,10 +694,7 @@ __global__ __launch_bounds__(256) void matrix_table_kernel(MatTable t, OptArgs o
       v = *(const float4*)(e.w + off);
       if (UPDATE) {
         const float4 g = *(const float4*)(e.g + off);
-        v.x = opt_update(o, v.x, g.x, e.m, e.v2, off);
-        v.y = opt_update(o, v.y, g.y, e.m, e.v2, off + 1);
-        v.z = opt_update(o, v.z, g.z, e.m, e.v2, off + 2);
-        v.w = opt_update(o, v.w, g.w, e.m, e.v2, off + 3);
+        v = opt_update4(o, v, g, e.m, e.v2, off);
         *(float4*)(e.w + off) = v;
       }
       if (e.s) {
@@ -719,7 +729,11 @@ __global__ __launch_bounds__(256) void sgd_table_kernel(SgdTable t, OptArgs o) {
   for (int j = 0; j < 4; ++j) {
     const int64_t i = i0 + 256 * j;
     if (i >= e.n) break;
-    e.w[i] = opt_update(o, e.w[i], e.g[i], e.m, e.v2, i);
+    const bool use_m = o.kind == OPT_ADAMW || o.mu > 0.f, use_v = o.kind == OPT_ADAMW;
+    float mm = use_m ? e.m[i] : 0.f, vv = use_v ? e.v2[i] : 0.f;
+    e.w[i] = opt_update(o, e.w[i], e.g[i], mm, vv);
+    if (use_m) e.m[i] = mm;
+    if (use_v) e.v2[i] = vv;
   }
 }
 

@@ -333,33 +333,35 @@ void launch_nt(const GemmDesc& g, hipStream_t s) {
 
 // ------------------------------------------------------------------------------------------ TN
 // Weight gradient dW[Mo,No] = sum_t X[t,Mo]^T dY[t,No] (Eq. 4): both operands have the contraction
-// index t (tokens) as their row index, so a fragment (8 consecutive t for one column) is strided in
-// memory.  Each thread loads 4 token rows x 8 columns (16-byte chunks), transposes them in
-// registers with v_perm_b32 and stores, per column, 4 consecutive tokens as one 8-byte unit:
-//   LDS[kq = t/4][column][t%4].  A fragment is then two 8-byte reads (kq, kq+1).
-// The 16-byte slots (column pairs) of a row are permuted inside each 32-column block b by
-// slot ^ b, which keeps the reads of 32 consecutive columns conflict-free and spreads the 16
-// writers of a row over all banks.
+// index t (tokens) as their row index, so an MFMA fragment (8 consecutive t for one column) is
+// strided in memory.  The tiles are staged in LDS as they lie in memory - 64 token rows of 16-byte
+// chunks, plain 16-byte writes - and the fragments are read with the LDS transpose read
+// (ds_read_b64_tr_b16): within every 16 lanes, lane 4e+q passes the address of 4 columns of token
+// row e, and lane j receives column j of the four rows, i.e. 4 consecutive tokens of one column.
+// A fragment is two such reads (token rows r..r+3 and r+4..r+7).  One half-wave reads 4 rows x 64
+// bytes; the 64-byte segments of a row are permuted by segment ^ (row & 3) so that those four land
+// in four different bank groups (a row of 128 columns spans all 64 banks exactly once).
 // Split-K: workgroup z handles k-tiles [z*kt_per, (z+1)*kt_per) and writes its own fp32 partial;
 // a second kernel adds the partials in a fixed order (bit-reproducible, no atomics).
 // Bias gradient: the workgroups of the first row of tiles also multiply every dY fragment by an
 // all-ones A fragment, which leaves the column sums of dY (db = 1^T dY) in one more accumulator per
 // 32 columns; they travel through the same partial / reduce path as dW.
-__device__ inline int tn_unit(int col) {       // 8-byte unit index of a column inside its LDS row
-  const int b = col >> 5, slot = (col >> 1) & 15;
-  return ((b << 4) + (slot ^ b)) * 2 + (col & 1);
-}
+#define BSR_LDS_PTR(T, p) ((T __attribute__((address_space(3)))*)(p))
 
-template <int BM, int BN>
-__global__ __launch_bounds__(256) void gemm_tn_kernel(GemmDesc g, float* partial, float* bpartial, int kt_per) {
-  constexpr int TM = BM / 2, TN = BN / 2, MI = TM / 32, NI = TN / 32;
-  constexpr int ACH = BM * 8 / 256 / 4, BCH = BN * 8 / 256 / 4;   // 4-token groups per thread per tile
-  static_assert(BM == 128 && BN == 128, "thread mapping below assumes 16 column chunks per row");
+template <int BM, int BN, int WM, int WN>
+__global__ __launch_bounds__(WM * WN * 64) void gemm_tn_kernel(GemmDesc g, float* partial, float* bpartial, int kt_per) {
+  constexpr int NT = WM * WN * 64;
+  constexpr int TM = BM / WM, TN = BN / WN, MI = TM / 32, NI = TN / 32;
+  constexpr int ACPR = BM / 8, BCPR = BN / 8;                  // 16-byte chunks per token row
+  constexpr int ACH = BK * ACPR / NT, BCH = BK * BCPR / NT;    // chunks per thread per k-tile
+  static_assert(BM % 128 == 0 && BN % 128 == 0, "the segment permutation needs a multiple of 4 segments per row");
+  static_assert(ACH >= 1 && BCH >= 1 && (BK * ACPR) % NT == 0 && (BK * BCPR) % NT == 0 && MI >= 1 && NI >= 1, "");
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  uint2* As = (uint2*)smem;                    // [2][16 kq][BM] 8-byte units
-  uint2* Bs = As + 2 * 16 * BM;                // [2][16 kq][BN]
+  unsigned char* As = smem;                            // [2][64 token rows][BM columns] bf16
+  unsigned char* Bs = smem + 2 * BK * BM * 2;          // [2][64 token rows][BN columns] bf16
+  constexpr int ABUF = BK * BM * 2, BBUF = BK * BN * 2;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
+  const int wm = wave / WN, wn = wave % WN;
   const int ntn = (g.N + BN - 1) / BN;
   const int ntiles = gridDim.x;
   const int tile = xcd_remap(blockIdx.x, ntiles);
@@ -380,47 +382,45 @@ __global__ __launch_bounds__(256) void gemm_tn_kernel(GemmDesc g, float* partial
   const int kt0 = g.grp_off ? 0 : blockIdx.y * kt_per, kt1 = min(kt0 + kt_per, nk_all);
   const bf16* __restrict__ X = (const bf16*)g.A;     // [K tokens, Mo], row stride a_cs
   const bf16* __restrict__ Y = (const bf16*)g.B;     // [K tokens, No], row stride b_rs
-  const int fc = tid & 15, tg = tid >> 4;            // column chunk (8 columns), token group (4 tokens)
-  const int colA = min(m0 + fc * 8, g.M - 8), colB = min(n0 + fc * 8, g.N - 8);
 
-  u32x4 ra[ACH][4], rb[BCH][4];
-  auto fetch = [&](int kt) {
+  // chunk c of a tile: token row c / chunks-per-row, chunk position c % chunks-per-row
+  int ar[ACH], br[BCH], sa[ACH], sb[BCH];
+  const bf16* pa[ACH];
+  const bf16* pb[BCH];
 #pragma unroll
-    for (int i = 0; i < ACH; ++i)
+  for (int i = 0; i < ACH; ++i) {
+    const int c = tid + NT * i, r = c / ACPR, q = c % ACPR;
+    ar[i] = r;
+    pa[i] = X + min(m0 + q * 8, g.M - 8);              // columns past Mo repeat valid ones: never stored
+    sa[i] = r * (BM * 2) + ((((q >> 2) ^ (r & 3)) << 2) + (q & 3)) * 16;
+  }
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const int t = kt * BK + (tg + 16 * i) * 4 + j;
-        ra[i][j] = *(const u32x4*)(X + (int64_t)min(t, g.K - 1) * g.a_cs + colA);
-        if (t >= g.K) ra[i][j] = u32x4{0u, 0u, 0u, 0u};
-      }
+  for (int i = 0; i < BCH; ++i) {
+    const int c = tid + NT * i, r = c / BCPR, q = c % BCPR;
+    br[i] = r;
+    pb[i] = Y + min(n0 + q * 8, g.N - 8);
+    sb[i] = r * (BN * 2) + ((((q >> 2) ^ (r & 3)) << 2) + (q & 3)) * 16;
+  }
+  u32x4 ra[ACH], rb[BCH];
+  auto fetch = [&](int kt) {                           // token rows past K are zero
 #pragma unroll
-    for (int i = 0; i < BCH; ++i)
+    for (int i = 0; i < ACH; ++i) {
+      const int t = kt * BK + ar[i];
+      ra[i] = *(const u32x4*)(pa[i] + (int64_t)min(t, g.K - 1) * g.a_cs);
+      if (t >= g.K) ra[i] = u32x4{0u, 0u, 0u, 0u};
+    }
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const int t = kt * BK + (tg + 16 * i) * 4 + j;
-        rb[i][j] = *(const u32x4*)(Y + (int64_t)min(t, g.K - 1) * g.b_rs + colB);
-        if (t >= g.K) rb[i][j] = u32x4{0u, 0u, 0u, 0u};
-      }
-  };
-  // 16-byte slot d of this thread's 8 columns: columns (8fc+2d, 8fc+2d+1) x 4 tokens
-  const int wb = fc >> 2;
-  auto stash_one = [&](uint2* dst_row, const u32x4 (&r)[4]) {
-#pragma unroll
-    for (int d = 0; d < 4; ++d) {
-      u32x4 w;
-      w[0] = __builtin_amdgcn_perm(r[1][d], r[0][d], 0x05040100u);
-      w[1] = __builtin_amdgcn_perm(r[3][d], r[2][d], 0x05040100u);
-      w[2] = __builtin_amdgcn_perm(r[1][d], r[0][d], 0x07060302u);
-      w[3] = __builtin_amdgcn_perm(r[3][d], r[2][d], 0x07060302u);
-      const int slot = ((fc & 3) << 2) + d;
-      *(u32x4*)(dst_row + ((wb << 4) + (slot ^ wb)) * 2) = w;
+    for (int i = 0; i < BCH; ++i) {
+      const int t = kt * BK + br[i];
+      rb[i] = *(const u32x4*)(pb[i] + (int64_t)min(t, g.K - 1) * g.b_rs);
+      if (t >= g.K) rb[i] = u32x4{0u, 0u, 0u, 0u};
     }
   };
   auto stash = [&](int buf) {
 #pragma unroll
-    for (int i = 0; i < ACH; ++i) stash_one(As + (buf * 16 + tg + 16 * i) * BM, ra[i]);
+    for (int i = 0; i < ACH; ++i) *(u32x4*)(As + buf * ABUF + sa[i]) = ra[i];
 #pragma unroll
-    for (int i = 0; i < BCH; ++i) stash_one(Bs + (buf * 16 + tg + 16 * i) * BN, rb[i]);
+    for (int i = 0; i < BCH; ++i) *(u32x4*)(Bs + buf * BBUF + sb[i]) = rb[i];
   };
 
   f32x16 acc[MI][NI];
@@ -431,12 +431,22 @@ __global__ __launch_bounds__(256) void gemm_tn_kernel(GemmDesc g, float* partial
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.f;
 
+  // transpose-read coordinates of this lane: j = lane % 16 inside its block of 16 lanes, the block
+  // covers columns cb*16 .. +16 of the 32-column fragment for k-group kg (tokens kg*8 .. +8 of a k-step)
   const int lr = lane & 31, lh = lane >> 5;
-  int ua[MI], ub[NI];
+  const int j = lane & 15, cb = (lane >> 4) & 1, kg = lh;
+  const int rj = j >> 2;                               // token row inside a group of four (= row & 3)
+  int oa[MI], ob[NI];                                  // byte offset inside a token row, segment-permuted
 #pragma unroll
-  for (int mi = 0; mi < MI; ++mi) ua[mi] = tn_unit(wm * TM + mi * 32 + lr);
+  for (int mi = 0; mi < MI; ++mi) {
+    const int off = (wm * TM + mi * 32 + cb * 16 + (j & 3) * 4) * 2, q = off >> 4;
+    oa[mi] = ((((q >> 2) ^ rj) << 2) + (q & 3)) * 16 + (off & 15);
+  }
 #pragma unroll
-  for (int ni = 0; ni < NI; ++ni) ub[ni] = tn_unit(wn * TN + ni * 32 + lr);
+  for (int ni = 0; ni < NI; ++ni) {
+    const int off = (wn * TN + ni * 32 + cb * 16 + (j & 3) * 4) * 2, q = off >> 4;
+    ob[ni] = ((((q >> 2) ^ rj) << 2) + (q & 3)) * 16 + (off & 15);
+  }
 
   const bool do_bsum = g.bsum && m0 == 0 && wm == 0;     // uniform over the wavefront
   f32x16 accb[NI];
@@ -448,19 +458,22 @@ __global__ __launch_bounds__(256) void gemm_tn_kernel(GemmDesc g, float* partial
 #pragma unroll
     for (int r = 0; r < 16; ++r) accb[ni][r] = 0.f;
 
-  union Frag { bf16x8 v; uint2 h[2]; };
+  typedef short s16x4 __attribute__((ext_vector_type(4)));
+  union Frag { bf16x8 v; s16x4 h[2]; };
   Frag fa[2][MI], fb[2][NI];
-  auto load_frags = [&](int set, const uint2* Ab, const uint2* Bb, int ks) {
-    const int kq = ks * 4 + lh * 2;
+  auto load_frags = [&](int set, const unsigned char* Ab, const unsigned char* Bb, int ks) {
+    const int row = ks * 16 + kg * 8 + rj;             // and row + 4: both have (row & 3) == rj
 #pragma unroll
     for (int mi = 0; mi < MI; ++mi) {
-      fa[set][mi].h[0] = Ab[kq * BM + ua[mi]];
-      fa[set][mi].h[1] = Ab[(kq + 1) * BM + ua[mi]];
+      const unsigned char* a = Ab + row * (BM * 2) + oa[mi];
+      fa[set][mi].h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(BSR_LDS_PTR(s16x4, a));
+      fa[set][mi].h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(BSR_LDS_PTR(s16x4, a + 4 * BM * 2));
     }
 #pragma unroll
     for (int ni = 0; ni < NI; ++ni) {
-      fb[set][ni].h[0] = Bb[kq * BN + ub[ni]];
-      fb[set][ni].h[1] = Bb[(kq + 1) * BN + ub[ni]];
+      const unsigned char* bp = Bb + row * (BN * 2) + ob[ni];
+      fb[set][ni].h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(BSR_LDS_PTR(s16x4, bp));
+      fb[set][ni].h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(BSR_LDS_PTR(s16x4, bp + 4 * BN * 2));
     }
   };
   auto mma = [&](int set) {
@@ -485,8 +498,8 @@ __global__ __launch_bounds__(256) void gemm_tn_kernel(GemmDesc g, float* partial
     load_frags(0, As, Bs, 0);
     for (int kt = 0; kt < nk; ++kt) {
       const int buf = kt & 1;
-      const uint2* Ab = As + buf * 16 * BM;
-      const uint2* Bb = Bs + buf * 16 * BN;
+      const unsigned char* Ab = As + buf * ABUF;
+      const unsigned char* Bb = Bs + buf * BBUF;
       load_frags(1, Ab, Bb, 1);
       mma(0);
       load_frags(0, Ab, Bb, 2);
@@ -496,7 +509,7 @@ __global__ __launch_bounds__(256) void gemm_tn_kernel(GemmDesc g, float* partial
       if (kt + 2 < nk) fetch(kt0 + kt + 2);
       mma(0);
       __syncthreads();
-      if (kt + 1 < nk) load_frags(0, As + (buf ^ 1) * 16 * BM, Bs + (buf ^ 1) * 16 * BN, 0);
+      if (kt + 1 < nk) load_frags(0, As + (buf ^ 1) * ABUF, Bs + (buf ^ 1) * BBUF, 0);
       mma(1);
     }
     __syncthreads();
@@ -545,16 +558,19 @@ bool is_tn(const GemmDesc& g) {
 }
 
 void launch_tn(const GemmDesc& g, float* ws, size_t ws_floats, hipStream_t s) {
-  constexpr int BM = 128, BN = 128;
+  constexpr int BM = 128, BN = 128, WM = 4, WN = 2, NTHR = WM * WN * 64;
   static bool attr_set = false;
-  constexpr size_t lds = (size_t)2 * (BM + BN) * BK * sizeof(bf16);
+  constexpr size_t lds_tiles = (size_t)2 * (BM + BN) * BK * sizeof(bf16);
+  constexpr size_t lds_patch = (size_t)WM * WN * 32 * (BN / WN + 4) * sizeof(float);   // epilogue patches
+  constexpr size_t lds = lds_tiles > lds_patch ? lds_tiles : lds_patch;
+  auto kern = gemm_tn_kernel<BM, BN, WM, WN>;
   if (!attr_set) {
-    (void)hipFuncSetAttribute((const void*)gemm_tn_kernel<BM, BN>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     attr_set = true;
   }
   const int tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
   if (g.grp_off) {   // one grid row per group, no split: tiles x groups already fills the machine
-    gemm_tn_kernel<BM, BN><<<dim3(tiles, g.groups), 256, lds, s>>>(g, nullptr, nullptr, 0);
+    kern<<<dim3(tiles, g.groups), NTHR, lds, s>>>(g, nullptr, nullptr, 0);
     return;
   }
   const int nk = (g.K + BK - 1) / BK;
@@ -564,15 +580,17 @@ void launch_tn(const GemmDesc& g, float* ws, size_t ws_floats, hipStream_t s) {
   const size_t per_split = mn + (g.bsum ? (size_t)g.N : 0);   // partial dW, then partial column sums
   if (ws && mn % 4 == 0) {
     splits = std::max(1, std::min({512 / tiles, nk / 4, (int)(ws_floats / per_split), 16}));
+    static const int forced = [] { const char* e = getenv("BSR_TN_SPLITS"); return e ? atoi(e) : 0; }();
+    if (forced > 0) splits = std::max(1, std::min({forced, nk, (int)(ws_floats / per_split)}));
   }
   int kt_per = (nk + splits - 1) / splits;
   splits = (nk + kt_per - 1) / kt_per;
   if (splits <= 1) {
-    gemm_tn_kernel<BM, BN><<<dim3(tiles, 1), 256, lds, s>>>(g, nullptr, nullptr, nk);
+    kern<<<dim3(tiles, 1), NTHR, lds, s>>>(g, nullptr, nullptr, nk);
   } else {
     float* bws = g.bsum ? ws + (size_t)splits * mn : nullptr;
     const int nb = g.bsum ? g.N : 0;
-    gemm_tn_kernel<BM, BN><<<dim3(tiles, splits), 256, lds, s>>>(g, ws, bws, kt_per);
+    kern<<<dim3(tiles, splits), NTHR, lds, s>>>(g, ws, bws, kt_per);
     splitk_reduce_kernel<<<(unsigned)((mn / 4 + (nb + 3) / 4 + 255) / 256), 256, 0, s>>>(ws, (int64_t)mn, splits, (float*)g.C,
                                                                                bws, nb, g.bsum);
   }
