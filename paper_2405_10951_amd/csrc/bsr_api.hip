@@ -66,6 +66,7 @@ struct Buffers {
   char *moe_dy = nullptr, *moe_dxg = nullptr, *moe_dlog = nullptr;   // backward scratch
   char *dxa = nullptr, *dxb = nullptr, *dgu = nullptr, *dh = nullptr, *dqkv = nullptr;
   float *delta = nullptr, *partial = nullptr, *splitk = nullptr;
+  float *ln_partial = nullptr;          // one slot per LayerNorm of the trained blocks (deferred dgamma / dbeta sums)
   size_t splitk_floats = 0;
   float *xc = nullptr, *z = nullptr, *dz = nullptr, *dxc = nullptr, *meanf = nullptr, *rstdf = nullptr;
   float *logits = nullptr, *dlogits = nullptr, *loss_rows = nullptr;
@@ -332,6 +333,9 @@ size_t carve(const bsr_config& c, const Schedule& s, char* base, Buffers* out, b
   b.dqkv = w.take<char>(B * Tmax * 3 * D * E);
   b.delta = w.take<float>(B * H * Tmax);
   b.partial = w.take<float>(std::max(colsum_partial_floats(0, (int)std::max(3 * D, F)), mean_sq_partial_floats()));
+  int n_ln = 0;
+  for (int l = ft; l < L; ++l) n_ln += s.trainable[l] ? 2 : 0;
+  if (!f32 && n_ln > 0 && n_ln <= LN_DEFER_MAX) b.ln_partial = w.take<float>((size_t)n_ln * ln_deferred_partial_floats((int)D));
   b.splitk_floats = f32 ? 0 : gemm_splitk_ws_floats((int)D, (int)F);
   if (ft < L && b.splitk_floats) b.splitk = w.take<float>(b.splitk_floats);
   const size_t C = std::max(c.num_classes, 1);
@@ -866,6 +870,12 @@ int32_t bsr_train_blocks_fwd_bwd(bsr_ctx* c, const void* x_in, const int32_t* la
   char* dx_other = b.dxb;
   if (cf.loss == BSR_LOSS_CE) {
     const int C = cf.num_classes;
+    if (head_lds_bytes(D, C) <= 64 * 1024) {
+      head_fwd_bwd(x, B, Tl, D, C, f32, (const float*)c->p.lnf_g, (const float*)c->p.lnf_b, c->eps, (const float*)c->p.w_head,
+                   (const float*)c->p.b_head, labels, b.xc, b.z, b.logits, b.dlogits, b.dz, b.loss_rows, dx,
+                   (float*)grads->w_head, (float*)grads->b_head, (float*)grads->lnf_g, (float*)grads->lnf_b, loss_out, s);
+      if (logits_out) (void)hipMemcpyAsync(logits_out, b.logits, sizeof(float) * (size_t)B * C, hipMemcpyDeviceToDevice, s);
+    } else {
     extract_cls(x, B, Tl, D, f32, b.xc, s);
     layernorm_fwd(b.xc, B, D, (const float*)c->p.lnf_g, (const float*)c->p.lnf_b, c->eps, true, b.z, b.meanf, b.rstdf, s);
     GemmDesc gl;   // logits = z . W_h + b_h (fp32)
@@ -887,11 +897,14 @@ int32_t bsr_train_blocks_fwd_bwd(bsr_ctx* c, const void* x_in, const int32_t* la
     layernorm_bwd_params(b.dz, b.xc, b.meanf, b.rstdf, B, D, true, b.partial, (float*)grads->lnf_g, (float*)grads->lnf_b, s);
     layernorm_bwd_dx(b.dz, b.xc, b.meanf, b.rstdf, (const float*)c->p.lnf_g, nullptr, B, D, true, b.dxc, s);
     place_cls_grad(b.dxc, B, Tl, D, f32, dx, s);
+    }
   } else {
     mean_sq_loss(x, (int64_t)B * Tl * D, f32, b.partial, loss_out, dx, s);
   }
 
   // ---------------------------------------------------------------- backward (Eq. 2-5), last block first
+  LnDeferTable ln_tab;          // dgamma / dbeta of all trained LayerNorms are summed in one launch at the end
+  int ln_slot = 0;
   for (int l = L - 1; l >= ft; --l) {
     const bsr_block_params& w = c->p.blocks[l];
     const bsr_block_params& gw = grads->blocks[l];
@@ -915,9 +928,13 @@ int32_t bsr_train_blocks_fwd_bwd(bsr_ctx* c, const void* x_in, const int32_t* la
       gemm(c, dgrad_desc(c, b.dgu, M2, D, F, w.w_fc1, sh.s_fc1, b.dh), s);
       if (tr) wgrad(c, v.h2, b.dgu, M2, D, F, gw.w_fc1, gw.b_fc1, s);
     }
-    if (tr)
-      layernorm_bwd(b.dh, v.xmid, v.mean2, v.rstd2, (const float*)w.ln2_g, dx, M2, D, f32, dx_other, b.partial,
-                    (float*)gw.ln2_g, (float*)gw.ln2_b, s);
+    if (tr) {
+      float* slot = b.ln_partial ? b.ln_partial + (size_t)(ln_slot++) * ln_deferred_partial_floats(D) : nullptr;
+      if (!layernorm_bwd_deferred(b.dh, v.xmid, v.mean2, v.rstd2, (const float*)w.ln2_g, dx, M2, D, f32, dx_other, slot,
+                                  (float*)gw.ln2_g, (float*)gw.ln2_b, ln_tab, s))
+        layernorm_bwd(b.dh, v.xmid, v.mean2, v.rstd2, (const float*)w.ln2_g, dx, M2, D, f32, dx_other, b.partial,
+                      (float*)gw.ln2_g, (float*)gw.ln2_b, s);
+    }
     else
       layernorm_bwd_dx(b.dh, v.xmid, v.mean2, v.rstd2, (const float*)w.ln2_g, dx, M2, D, f32, dx_other, s);
     std::swap(dx, dx_other);   // dx: gradient at x_mid (kept tokens)
@@ -935,13 +952,18 @@ int32_t bsr_train_blocks_fwd_bwd(bsr_ctx* c, const void* x_in, const int32_t* la
     if (tr) wgrad(c, v.h1, b.dqkv, M, D, 3 * D, gw.w_qkv, gw.b_qkv, s);
     gemm(c, dgrad_desc(c, b.dqkv, M, D, 3 * D, w.w_qkv, sh.s_qkv, b.dh), s);
     // the gradient is not carried below the earliest trainable block (Fig. 2): no dx there
-    if (tr)
-      layernorm_bwd(b.dh, xin, v.mean1, v.rstd1, (const float*)w.ln1_g, dx, M, D, f32, l > ft ? dx_other : nullptr,
-                    b.partial, (float*)gw.ln1_g, (float*)gw.ln1_b, s);
+    if (tr) {
+      float* slot = b.ln_partial ? b.ln_partial + (size_t)(ln_slot++) * ln_deferred_partial_floats(D) : nullptr;
+      if (!layernorm_bwd_deferred(b.dh, xin, v.mean1, v.rstd1, (const float*)w.ln1_g, dx, M, D, f32,
+                                  l > ft ? dx_other : nullptr, slot, (float*)gw.ln1_g, (float*)gw.ln1_b, ln_tab, s))
+        layernorm_bwd(b.dh, xin, v.mean1, v.rstd1, (const float*)w.ln1_g, dx, M, D, f32, l > ft ? dx_other : nullptr,
+                      b.partial, (float*)gw.ln1_g, (float*)gw.ln1_b, s);
+    }
     else
       layernorm_bwd_dx(b.dh, xin, v.mean1, v.rstd1, (const float*)w.ln1_g, dx, M, D, f32, dx_other, s);
     if (l > ft) std::swap(dx, dx_other);
   }
+  ln_deferred_finish(ln_tab, s);
   return check_hip(c, "bsr_train_blocks_fwd_bwd");
 }
 

@@ -80,6 +80,19 @@ void layernorm_bwd(const void* dy, const void* x, const float* mean, const float
 void colsum(const void* a, int64_t M, int N, int64_t ld, bool f32, float* partial, float* out,
             hipStream_t s);
 size_t colsum_partial_floats(int64_t M, int N);
+// The LayerNorm backward of several layers with one final reduction for all of them: each call of
+// layernorm_bwd_deferred writes dx and its workgroup partials of dgamma / dbeta into `partial` (its own
+// buffer of ln_deferred_partial_floats(D) floats, kept until the reduction) and adds an entry to the
+// table; ln_deferred_finish adds the partials of every entry in one launch.  Returns false (nothing
+// done) when the shape is not one the one-pass kernel takes: then use layernorm_bwd.
+constexpr int LN_DEFER_MAX = 32;
+struct LnDeferEntry { const float* partial; float* dgamma; float* dbeta; int blocks; };
+struct LnDeferTable { LnDeferEntry e[LN_DEFER_MAX]; int count = 0; int D = 0; };
+size_t ln_deferred_partial_floats(int D);
+bool layernorm_bwd_deferred(const void* dy, const void* x, const float* mean, const float* rstd, const float* gamma,
+                            const void* res, int64_t M, int D, bool f32, void* dx, float* partial, float* dgamma,
+                            float* dbeta, LnDeferTable& t, hipStream_t s);
+void ln_deferred_finish(LnDeferTable& t, hipStream_t s);
 
 void patchify(const void* img, int B, int C, int S, int P, bool f32, void* out, hipStream_t s);
 void write_cls_rows(const float* cls, const float* pos, int B, int T, int D, bool f32, void* x,
@@ -99,6 +112,15 @@ void fuse_dropped(const void* x, const float* scores, const int32_t* idx, int B,
 // fw != null: dy has rows [CLS; kept; fused] and dropped tokens get fw times the fused token's gradient
 void scatter_tokens(const void* dy, const int32_t* idx, int B, int T, int k, int D, bool f32,
                     void* dx, hipStream_t s, const float* fw = nullptr);
+// Classification head, forward and backward, in two launches (class-token LayerNorm, logits, mean
+// cross-entropy, and the gradients of the head, of the final LayerNorm and of the last block's output
+// dx [B,Tl,D], whose non-class rows are set to zero).  xhat, z, dz: [B,D] fp32 scratch; logits, dlogits:
+// [B,C] fp32; loss_rows [B].  Needs head_lds_bytes(D, C) of LDS per workgroup (caller checks <= 64 KB).
+size_t head_lds_bytes(int D, int C);
+void head_fwd_bwd(const void* x, int B, int Tl, int D, int C, bool f32, const float* gamma, const float* beta, float eps,
+                  const float* w_head, const float* b_head, const int32_t* labels, float* xhat, float* z, float* logits,
+                  float* dlogits, float* dz, float* loss_rows, void* dx, float* dw, float* db, float* dgamma, float* dbeta,
+                  float* loss, hipStream_t s);
 void extract_cls(const void* x, int B, int T, int D, bool f32, float* out, hipStream_t s);
 void place_cls_grad(const float* dxc, int B, int T, int D, bool f32, void* dx, hipStream_t s);
 void cross_entropy(const float* logits, const int32_t* labels, int B, int C, float* loss_rows,

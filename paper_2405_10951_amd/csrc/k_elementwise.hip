@@ -379,6 +379,32 @@ __global__ __launch_bounds__(FINAL_WAVES * WAVE) void colsum_final_kernel(const 
   }
 }
 
+// the same reduction for a table of LayerNorm backward passes: blockIdx.y picks the entry
+__global__ __launch_bounds__(FINAL_WAVES * WAVE) void ln_deferred_final_kernel(LnDeferTable t) {
+  __shared__ float red[2][FINAL_WAVES][WAVE];
+  const LnDeferEntry e = t.e[blockIdx.y];
+  const int lane = threadIdx.x % WAVE, w = threadIdx.x / WAVE, N = t.D;
+  const int col = blockIdx.x * WAVE + lane;
+  float s = 0.f, u = 0.f;
+  if (col < N) {
+#pragma unroll 4
+    for (int r = w; r < e.blocks; r += FINAL_WAVES) {
+      s += e.partial[(int64_t)r * N + col];
+      u += e.partial[(int64_t)(LN_BWD_BLOCKS + r) * N + col];
+    }
+  }
+  red[0][w][lane] = s;
+  red[1][w][lane] = u;
+  __syncthreads();
+  if (w == 0 && col < N) {
+    float a0 = red[0][0][lane], a1 = red[1][0][lane];
+#pragma unroll
+    for (int i = 1; i < FINAL_WAVES; ++i) { a0 += red[0][i][lane]; a1 += red[1][i][lane]; }
+    e.dgamma[col] = a0;
+    e.dbeta[col] = a1;
+  }
+}
+
 // ---------------------------------------------------------------- stem helpers
 // out[(b*N + p), (c*P + r)*P + q] = img[b, c, gy*P + r, gx*P + q],  p = gy*G + gx
 template <typename T>
@@ -787,6 +813,28 @@ void layernorm_bwd(const void* dy, const void* x, const float* mean, const float
   }
   layernorm_bwd_params(dy, x, mean, rstd, M, D, f32, partial, dgamma, dbeta, s);
   layernorm_bwd_dx(dy, x, mean, rstd, gamma, res, M, D, f32, dx, s);
+}
+
+size_t ln_deferred_partial_floats(int D) { return (size_t)2 * LN_BWD_BLOCKS * (size_t)D; }
+
+bool layernorm_bwd_deferred(const void* dy, const void* x, const float* mean, const float* rstd, const float* gamma,
+                            const void* res, int64_t M, int D, bool f32, void* dx, float* partial, float* dgamma,
+                            float* dbeta, LnDeferTable& t, hipStream_t s) {
+  if (M <= 0 || f32 || D % 8 != 0 || D > 8 * WAVE * LN_MAXC || !partial || t.count >= LN_DEFER_MAX ||
+      (t.count > 0 && t.D != D))
+    return false;
+  const int blocks = (int)std::min<int64_t>(LN_BWD_BLOCKS, (M + 3) / 4);
+  ln_bwd_fused_vec_kernel<<<blocks, 256, 0, s>>>((const bf16*)dy, (const bf16*)x, mean, rstd, gamma,
+                                                 (const bf16*)res, M, D, (bf16*)dx, partial);
+  t.D = D;
+  t.e[t.count++] = LnDeferEntry{partial, dgamma, dbeta, blocks};
+  return true;
+}
+
+void ln_deferred_finish(LnDeferTable& t, hipStream_t s) {
+  if (t.count == 0) return;
+  ln_deferred_final_kernel<<<dim3((t.D + WAVE - 1) / WAVE, t.count), FINAL_WAVES * WAVE, 0, s>>>(t);
+  t.count = 0;
 }
 
 size_t colsum_partial_floats(int64_t, int N) { return (size_t)2 * std::max(COLSUM_R, LN_BWD_BLOCKS) * (size_t)N; }
