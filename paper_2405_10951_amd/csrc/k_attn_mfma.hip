@@ -3,8 +3,8 @@
 // Eq. 6 ranks tokens by, leaves the forward kernel in fp32 as a by-product.
 //
 // Forward.  One workgroup = one (image, head): K and V of the head are staged once, and each of
-// its ceil(T / 32) wavefronts owns 32 queries.  K sits in LDS row-major (swizzled 16-byte chunks),
-// V sits transposed (feature-major).  The wave computes S^T = K Q^T with 32x32x16 MFMAs, so that a
+// its ceil(T / 32) wavefronts owns 32 queries.  K and V sit in LDS row-major (swizzled 16-byte chunks);
+// V^T fragments come from the LDS transpose read.  The wave computes S^T = K Q^T with 32x32x16 MFMAs, so that a
 // lane owns one query and the softmax reductions over keys are in-register (plus one exchange between
 // the two halves of the wave).  The normalised P^T accumulators are, as they lie in registers, an
 // operand of the second product O^T = V^T P^T: MFMA contracts over a dummy index, so the key order
@@ -21,11 +21,17 @@ typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
 
 constexpr int HD = 64;          // head size
-constexpr int VP = 260;         // V^T row pitch in bf16: 520 B = 2*256 + 8, so 32 rows hit all 64 banks
 
-__device__ inline int swz(int row) { return (row & 7) ^ ((row >> 3) & 1); }
+// Chunk permutation of a row of 8 16-byte chunks (128 B, two rows per sweep of the 64 banks): chunk kc of
+// row r sits at kc ^ swz(r).  It serves two access patterns without bank conflicts:
+//   - row fragments (16 consecutive rows read the same logical chunk): the 8 rows of either parity get 8
+//     different positions;
+//   - transposed fragments (4 consecutive rows r..r+3, r % 4 == 0, 64 bytes each): bit 2 differs between
+//     rows r and r+2 (and r+1, r+3), so the four rows hit the four 64-byte bank groups.
+__device__ inline int swz(int row) { return (((row >> 1) & 1) << 2) | ((row >> 2) & 3); }
 
 // key index of accumulator element r (of key block jb) held by a lane of wave half lh
 __device__ inline int key_of(int jb, int r, int lh) { return jb * 32 + 8 * (r >> 2) + 4 * lh + (r & 3); }
@@ -41,29 +47,22 @@ __device__ inline void load_k(const bf16* base, int64_t row_stride, int T, int T
   }
 }
 
-// Rows [T,64] -> transposed LDS [64][VP]: 4 rows x 8 columns per thread, transposed in registers.
-__device__ inline void load_transposed(const bf16* base, int64_t row_stride, int T, int Tpad, bf16* Vt, int tid,
-                                       int nthreads = 256) {
-  for (int c = tid; c < (Tpad / 4) * 8; c += nthreads) {
-    const int fc = c & 7, kg = c >> 3;
-    u32x4 r[4];
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int t = kg * 4 + j;
-      r[j] = u32x4{0u, 0u, 0u, 0u};
-      if (t < T) r[j] = *(const u32x4*)(base + (int64_t)t * row_stride + fc * 8);
-    }
-#pragma unroll
-    for (int d = 0; d < 4; ++d) {
-      u32x2 lo, hi;
-      lo[0] = __builtin_amdgcn_perm(r[1][d], r[0][d], 0x05040100u);
-      lo[1] = __builtin_amdgcn_perm(r[3][d], r[2][d], 0x05040100u);
-      hi[0] = __builtin_amdgcn_perm(r[1][d], r[0][d], 0x07060302u);
-      hi[1] = __builtin_amdgcn_perm(r[3][d], r[2][d], 0x07060302u);
-      *(u32x2*)(Vt + (fc * 8 + 2 * d) * VP + kg * 4) = lo;
-      *(u32x2*)(Vt + (fc * 8 + 2 * d + 1) * VP + kg * 4) = hi;
-    }
-  }
+// Transposed fragment of a row-major LDS tile [rows][64 features] for the 32 features nb*32 .. +31:
+// lane (feature nb*32 + lane % 32, half lh = lane / 32) receives rows 16 st + 4 lh + {0..3} and
+// 16 st + 8 + 4 lh + {0..3}, the order in which a 32x32 accumulator holds its rows.  Two LDS
+// transpose reads (ds_read_b64_tr_b16): within 16 lanes, lane 4e+q passes the address of 4 features of
+// row e and lane j receives feature j of the four rows.
+__device__ inline bf16x8 lds_frag_t(const u32x4* rows, int nb, int lane, int st) {
+  const int j = lane & 15, cb = (lane >> 4) & 1, lh = lane >> 5;
+  const int chunk = nb * 4 + cb * 2 + ((j & 3) >> 1), half = j & 1;
+  const int r0 = 16 * st + 4 * lh + (j >> 2), r1 = r0 + 8;
+  const unsigned char* p = (const unsigned char*)rows;
+  union { bf16x8 v; s16x4 h[2]; } f;
+  f.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+      (s16x4 __attribute__((address_space(3)))*)(p + (r0 * 8 + (chunk ^ swz(r0))) * 16 + half * 8));
+  f.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+      (s16x4 __attribute__((address_space(3)))*)(p + (r1 * 8 + (chunk ^ swz(r1))) * 16 + half * 8));
+  return f.v;
 }
 
 template <int NJ>
@@ -73,7 +72,7 @@ __global__ __launch_bounds__(NJ * 64) void attn_fwd_mfma_kernel(const bf16* __re
   constexpr int Tpad = NJ * 32, NTH = NJ * 64;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   u32x4* Ks = (u32x4*)smem;                         // [Tpad][8 chunks]
-  bf16* Vt = (bf16*)(smem + (size_t)Tpad * 128);    // [64][VP]
+  u32x4* Vs = Ks + Tpad * 8;                        // [Tpad][8 chunks]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int lr = lane & 31, lh = lane >> 5;
   const int b = blockIdx.x / H, h = blockIdx.x % H;
@@ -90,7 +89,7 @@ __global__ __launch_bounds__(NJ * 64) void attn_fwd_mfma_kernel(const bf16* __re
     for (int ks = 0; ks < 4; ++ks) qf[ks] = *(const bf16x8*)(qrow + (2 * ks + lh) * 8);
   }
   load_k(base + D, rs, T, Tpad, Ks, tid, NTH);
-  load_transposed(base + 2 * D, rs, T, Tpad, Vt, tid, NTH);
+  load_k(base + 2 * D, rs, T, Tpad, Vs, tid, NTH);
   __syncthreads();
 
   // S^T[key, query] = K Q^T
@@ -157,14 +156,9 @@ __global__ __launch_bounds__(NJ * 64) void attn_fwd_mfma_kernel(const bf16* __re
   for (int nb = 0; nb < 2; ++nb) {
 #pragma unroll
     for (int r = 0; r < 16; ++r) o[nb][r] = 0.f;
-    const bf16* vrow = Vt + (nb * 32 + lr) * VP + 4 * lh;
 #pragma unroll
-    for (int st = 0; st < 2 * NJ; ++st) {
-      union { bf16x8 v; u32x2 hpart[2]; } vf;
-      vf.hpart[0] = *(const u32x2*)(vrow + 16 * st);
-      vf.hpart[1] = *(const u32x2*)(vrow + 16 * st + 8);
-      o[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf.v, pf[st], o[nb], 0, 0, 0);
-    }
+    for (int st = 0; st < 2 * NJ; ++st)
+      o[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_frag_t(Vs, nb, lane, st), pf[st], o[nb], 0, 0, 0);
   }
   if (qi < T) {
     bf16* orow = out + ((int64_t)b * T + qi) * D + h * HD + 4 * lh;
@@ -183,7 +177,7 @@ __global__ __launch_bounds__(NJ * 64) void attn_fwd_mfma_kernel(const bf16* __re
 template <int NJ>
 void launch_fwd(const bf16* qkv, int B, int T, int H, bf16* out, float* lse, float* cls_prob, hipStream_t s) {
   static bool attr_set = false;
-  constexpr size_t lds = (size_t)NJ * 32 * 128 + (size_t)HD * VP * sizeof(bf16);
+  constexpr size_t lds = (size_t)2 * NJ * 32 * 128;
   if (!attr_set) {
     (void)hipFuncSetAttribute((const void*)attn_fwd_mfma_kernel<NJ>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     attr_set = true;
@@ -207,14 +201,6 @@ __device__ inline bf16x8 lds_frag(const u32x4* rows, int row, int chunk) {
   return *(const bf16x8*)(rows + row * 8 + (chunk ^ swz(row)));
 }
 
-__device__ inline bf16x8 lds_frag_t(const bf16* tr, int row, int lh, int st) {
-  union { bf16x8 v; u32x2 h[2]; } f;
-  const bf16* p = tr + row * VP + 4 * lh + 16 * st;
-  f.h[0] = *(const u32x2*)p;
-  f.h[1] = *(const u32x2*)(p + 8);
-  return f.v;
-}
-
 template <int NJ>
 __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ out,
                                                           const bf16* __restrict__ dout, const float* __restrict__ lse,
@@ -224,7 +210,6 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(const bf16* __restrict
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   u32x4* Ks = (u32x4*)smem;
   u32x4* Vs = Ks + Tpad * 8;
-  bf16* Kt = (bf16*)(Vs + Tpad * 8);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int lr = lane & 31, lh = lane >> 5;
   const int b = blockIdx.y / H, h = blockIdx.y % H;
@@ -233,7 +218,6 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(const bf16* __restrict
   const bf16* base = qkv + (int64_t)b * T * rs + h * HD;
   load_k(base + D, rs, T, Tpad, Ks, tid);
   load_k(base + 2 * D, rs, T, Tpad, Vs, tid);
-  load_transposed(base + D, rs, T, Tpad, Kt, tid);
   __syncthreads();
   const int q0 = blockIdx.x * 128 + wave * 32;
   if (q0 >= T) return;
@@ -283,7 +267,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(const bf16* __restrict
     for (int nb = 0; nb < 2; ++nb)
 #pragma unroll
       for (int hf = 0; hf < 2; ++hf)
-        o[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dsf[hf], lds_frag_t(Kt, nb * 32 + lr, lh, 2 * jb + hf), o[nb], 0, 0, 0);
+        o[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dsf[hf], lds_frag_t(Ks, nb, lane, 2 * jb + hf), o[nb], 0, 0, 0);
   }
 #pragma unroll
   for (int nb = 0; nb < 2; ++nb)
@@ -302,9 +286,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(const bf16* __restric
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   u32x4* Qs = (u32x4*)smem;
   u32x4* dOs = Qs + Tpad * 8;
-  bf16* Qt = (bf16*)(dOs + Tpad * 8);
-  bf16* dOt = Qt + HD * VP;
-  float* lse_s = (float*)(dOt + HD * VP);       // [Tpad], pre-multiplied by log2(e); +inf beyond T
+  float* lse_s = (float*)(dOs + Tpad * 8);      // [Tpad], pre-multiplied by log2(e); +inf beyond T
   float* del_s = lse_s + Tpad;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int lr = lane & 31, lh = lane >> 5;
@@ -315,8 +297,6 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(const bf16* __restric
   const bf16* dobase = dout + (int64_t)b * T * D + h * HD;
   load_k(base, rs, T, Tpad, Qs, tid);
   load_k(dobase, D, T, Tpad, dOs, tid);
-  load_transposed(base, rs, T, Tpad, Qt, tid);
-  load_transposed(dobase, D, T, Tpad, dOt, tid);
   for (int i = tid; i < Tpad; i += 256) {
     lse_s[i] = (i < T) ? lse[((int64_t)b * H + h) * T + i] * 1.44269504088896341f : INFINITY;
     del_s[i] = (i < T) ? delta[((int64_t)b * H + h) * T + i] : 0.f;
@@ -369,8 +349,8 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(const bf16* __restric
     for (int nb = 0; nb < 2; ++nb)
 #pragma unroll
       for (int hf = 0; hf < 2; ++hf) {
-        ov[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pf[hf], lds_frag_t(dOt, nb * 32 + lr, lh, 2 * ib + hf), ov[nb], 0, 0, 0);
-        ok[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dsf[hf], lds_frag_t(Qt, nb * 32 + lr, lh, 2 * ib + hf), ok[nb], 0, 0, 0);
+        ov[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pf[hf], lds_frag_t(dOs, nb, lane, 2 * ib + hf), ov[nb], 0, 0, 0);
+        ok[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dsf[hf], lds_frag_t(Qs, nb, lane, 2 * ib + hf), ok[nb], 0, 0, 0);
       }
   }
 #pragma unroll
@@ -390,8 +370,8 @@ template <int NJ>
 void launch_bwd(const bf16* qkv, const bf16* out, const bf16* dout, const float* lse, int B, int T, int H,
                 float* delta, bf16* dqkv, hipStream_t s) {
   static bool attr_set = false;
-  constexpr size_t lds_q = (size_t)2 * NJ * 32 * 128 + (size_t)HD * VP * sizeof(bf16);
-  constexpr size_t lds_kv = (size_t)2 * NJ * 32 * 128 + (size_t)2 * HD * VP * sizeof(bf16) + (size_t)2 * NJ * 32 * sizeof(float);
+  constexpr size_t lds_q = (size_t)2 * NJ * 32 * 128;
+  constexpr size_t lds_kv = (size_t)2 * NJ * 32 * 128 + (size_t)2 * NJ * 32 * sizeof(float);
   if (!attr_set) {
     (void)hipFuncSetAttribute((const void*)attn_bwd_dq_kernel<NJ>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_q);
     (void)hipFuncSetAttribute((const void*)attn_bwd_dkv_kernel<NJ>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_kv);

@@ -17,6 +17,7 @@ namespace {
 constexpr int WAVE = 64, HT = 1024, HW = HT / WAVE;    // threads and wavefronts per workgroup of the row kernel
 constexpr int NPART = 8;                               // d-ranges the logits are split over
 constexpr int BT = 256;                                // threads per workgroup of the batch kernel
+constexpr int RPP = 16;                                // rows of W_h a wavefront has in flight in the dz pass
 
 __device__ inline float wave_sum_h(float v) {
 #pragma unroll
@@ -92,12 +93,12 @@ __global__ __launch_bounds__(HT) void head_rows_kernel(const T* __restrict__ x, 
         float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
         const float* wc = w_head + c;
         int d = d0;
-        for (; d + 15 < d1; d += 16) {          // 16 loads in flight
-          float wv[16];
+        for (; d + 31 < d1; d += 32) {          // 32 loads in flight
+          float wv[32];
 #pragma unroll
-          for (int u = 0; u < 16; ++u) wv[u] = wc[(int64_t)(d + u) * C];
+          for (int u = 0; u < 32; ++u) wv[u] = wc[(int64_t)(d + u) * C];
 #pragma unroll
-          for (int u = 0; u < 16; u += 4) {
+          for (int u = 0; u < 32; u += 4) {
             a0 = fmaf(zs[d + u], wv[u], a0);
             a1 = fmaf(zs[d + u + 1], wv[u + 1], a1);
             a2 = fmaf(zs[d + u + 2], wv[u + 2], a2);
@@ -137,31 +138,36 @@ __global__ __launch_bounds__(HT) void head_rows_kernel(const T* __restrict__ x, 
   // dz = dlogits . W_h^T, then the LayerNorm backward of the row:
   //   dxhat = dz * gamma;  dx = rstd * (dxhat - mean(dxhat) - xhat * mean(dxhat * xhat))
   // a wavefront per row d of W_h: lanes walk the classes (coalesced), then a wave sum
-  for (int d = w; d < D; d += 4 * HW) {                 // four rows per pass: their loads overlap
-    float a[4] = {0.f, 0.f, 0.f, 0.f};
+  for (int d = w; d < D; d += RPP * HW) {               // RPP rows per pass: their loads overlap
+    float a[RPP];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      const int dd = d + u * HW;
-      if (dd < D) {
-        const float* wr = w_head + (int64_t)dd * C;
-        for (int c = lane; c < C; c += WAVE) a[u] = fmaf(lg[c], wr[c], a[u]);
+    for (int u = 0; u < RPP; ++u) a[u] = 0.f;
+    for (int c0 = 0; c0 < C; c0 += WAVE) {               // uniform trip count, lanes past C idle
+      const int c = c0 + lane;
+      const bool in = c < C;
+      const float g = in ? lg[c] : 0.f;
+#pragma unroll
+      for (int u = 0; u < RPP; ++u) {
+        const int dd = min(d + u * HW, D - 1);           // rows past D repeat the last one and are dropped below
+        a[u] = fmaf(g, in ? w_head[(int64_t)dd * C + c] : 0.f, a[u]);
       }
     }
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
+    for (int u = 0; u < RPP; ++u) {
       const int dd = d + u * HW;
       const float t = wave_sum_h(a[u]);
-      if (lane == 0 && dd < D) {
-        dz_out[(int64_t)b * D + dd] = t;
-        zs[dd] = t * gamma[dd];               // dxhat (z is not needed any more)
-      }
+      if (lane == 0 && dd < D) zs[dd] = t;               // raw dz (z is not needed any more)
     }
   }
   __syncthreads();
   float s1 = 0.f, s2 = 0.f;
   for (int d = tid; d < D; d += HT) {
-    s1 += zs[d];
-    s2 += zs[d] * xh[d];
+    const float t = zs[d];
+    dz_out[(int64_t)b * D + d] = t;
+    const float dh = t * gamma[d];                       // dxhat
+    zs[d] = dh;
+    s1 += dh;
+    s2 += dh * xh[d];
   }
   s1 = block_sum(s1, red) / (float)D;
   s2 = block_sum(s2, red) / (float)D;
