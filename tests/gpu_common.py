@@ -19,11 +19,12 @@ def rel_rms(a, b):
 
 
 def run_hip_step(cfg, params, x, labels, forced_idx=None, max_batch=None, sgd=None, ctx=None,
-                 forced_experts=None, adamw=None):
+                 forced_experts=None, adamw=None, autotune=False):
     """One BSR step on cuda:0.  forced_idx: list per drop of [B,k] arrays (or None).
     forced_experts: dict block -> [rows,K] expert choice for the mixture-of-experts blocks (or None).
     sgd: None or dict(lr=, momentum=, weight_decay=, momenta=dict|None).
     adamw: None or dict(lr=, beta1=, beta2=, eps=, weight_decay=, step=, exp_avg=dict, exp_avg_sq=dict).
+    autotune: run the measured tile choice first (as bench.py does during set-up).
     Returns a dict."""
     dev = torch.device("cuda:0")
     B = x.shape[0]
@@ -60,6 +61,9 @@ def run_hip_step(cfg, params, x, labels, forced_idx=None, max_batch=None, sgd=No
         ctx.bsr_moe_routing_io(fex, ex_out, rl_out)
     kf, sf = bufs(ctx.frozen_drops)
     kt, st = bufs(ctx.train_drops)
+    if autotune:
+        x_t = torch.empty((B, ctx.T_f, cfg["dim"]), dtype=act, device=dev)
+        ctx.bsr_autotune(xin, lab, x_t, torch.zeros(1, dtype=torch.float32, device=dev), ctx.new_grads())
     x_f = ctx.bsr_forward_frozen(xin, kept_idx_out=kf, scores_out=sf, forced_idx=cat_idx(ctx.frozen_drops))
     grads = ctx.new_grads()
     C = max(cfg["num_classes"], 1)

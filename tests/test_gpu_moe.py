@@ -147,5 +147,5 @@ def test_c5_workload_matches_oracle(hip, orc32):
     """The ViT-S mixture-of-experts workload at full model size (batch 8 here; the oracle is fp32)."""
     cfg, p, x, y = setup("c5_vit_s_moe", std=0.02, batch=8)
     ref = orc32.step(cfg, p, x, y)
-    got = hip.run_hip_step(cfg, p, x, y, forced_idx=ref["kept_idx"], forced_experts=ref["experts"])
+    got = hip.run_hip_step(cfg, p, x, y, forced_idx=ref["kept_idx"], forced_experts=ref["experts"], autotune=True)
     compare(hip, got, ref, cfg)
