@@ -1066,6 +1066,8 @@ int32_t bsr_autotune(bsr_ctx* c, const void* input, const int32_t* labels, int32
   t.cand = -1;
   const bool synced = hipStreamSynchronize(s) == hipSuccess;
   int launches = 0;
+  const char* venv = getenv("BSR_TUNE_VERBOSE");
+  const bool verbose = venv && venv[0] == '1';
   if (rc == BSR_OK && synced) {
     size_t sites[2] = {0, 0};
     for (const TuneRec& r : t.recs) sites[r.kind] = std::max(sites[r.kind], r.site + 1);
@@ -1087,6 +1089,11 @@ int32_t bsr_autotune(bsr_ctx* c, const void* input, const int32_t* labels, int32
           if (best[i * n + j] >= 0.f && (arg < 0 || best[i * n + j] < best[i * n + arg])) arg = j;
         t.pick[k][i].tile = arg < 0 ? 0 : gemm_nt_tile_id(arg);
         ++launches;
+        if (verbose) {                 // the measured microseconds of every shape, for inspection
+          fprintf(stderr, "bsr_autotune call %d launch %zu M=%d N=%d K=%d:", k, i, t.pick[k][i].M, t.pick[k][i].N, t.pick[k][i].K);
+          for (int j = 0; j < n; ++j) fprintf(stderr, " %d=%.1f", gemm_nt_tile_id(j), best[i * n + j] * 1e3f);
+          fprintf(stderr, " -> %d\n", t.pick[k][i].tile);
+        }
       }
     }
     t.batch = B;

@@ -154,11 +154,14 @@ __device__ __forceinline__ void epilogue(const GemmDesc& g, f32x16 (&acc)[MI][NI
 // Software pipeline of one k-tile (4 MFMA steps of k = 16):
 //   step 0,1: MFMAs on fragment set s while the fragments of the next step load into set s^1
 //   step 2  : as above; the registers holding k-tile kt+1 go to the other LDS buffer and the global
-//             loads of k-tile kt+2 are issued (they have a full k-tile of matrix work to land)
+//             loads of k-tile kt+1+PF are issued into the registers just freed
 //   barrier ; step 3: MFMAs of the last fragments while the first fragments of k-tile kt+1 load.
+// PF register stages hold the k-tiles kt+1 .. kt+PF on their way from global memory (k-tile j in stage
+// j % PF): with PF = 1 a load has one k-tile of matrix work to land, which a small tile that is alone on
+// its CU finishes long before an L2 or HBM access returns; such tiles run with PF = 3.
 // Rows beyond M (or N) are clamped to the last valid row: they only feed accumulators that are
 // never stored.  KTAIL zero-fills chunks beyond K (K % 64 != 0).
-template <int BM, int BN, int WM, int WN, bool KTAIL>
+template <int BM, int BN, int WM, int WN, bool KTAIL, int PF = 1>
 __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_kernel(GemmDesc g) {
   constexpr int NT = WM * WN * 64;
   constexpr int TM = BM / WM, TN = BN / WN, MI = TM / 32, NI = TN / 32;
@@ -214,33 +217,35 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_kernel(GemmDesc g) {
     pb[i] = Bt + (int64_t)min(n0 + row, g.N - 1) * g.b_cs + kc8;
     sb[i] = row * 8 + ((tid & 7) ^ swz(row));
   }
-  u32x4 ra[ACH], rb[BCH];                // the next k-tile waits here while the current one is multiplied
-  auto fetch = [&](int k0) {
+  u32x4 ra[PF][ACH], rb[PF][BCH];        // the next PF k-tiles wait here while the current one is multiplied
+  auto fetch = [&](auto ST, int k0) {
+    constexpr int st = decltype(ST)::value;
     if (KTAIL) {
       const bool oob = k0 + kc8 >= g.K;
       const int kk = oob ? 0 : k0;
 #pragma unroll
       for (int i = 0; i < ACH; ++i) {
-        ra[i] = *(const u32x4*)(pa[i] + kk - (oob ? kc8 : 0));
-        if (oob) ra[i] = u32x4{0u, 0u, 0u, 0u};
+        ra[st][i] = *(const u32x4*)(pa[i] + kk - (oob ? kc8 : 0));
+        if (oob) ra[st][i] = u32x4{0u, 0u, 0u, 0u};
       }
 #pragma unroll
       for (int i = 0; i < BCH; ++i) {
-        rb[i] = *(const u32x4*)(pb[i] + kk - (oob ? kc8 : 0));
-        if (oob) rb[i] = u32x4{0u, 0u, 0u, 0u};
+        rb[st][i] = *(const u32x4*)(pb[i] + kk - (oob ? kc8 : 0));
+        if (oob) rb[st][i] = u32x4{0u, 0u, 0u, 0u};
       }
     } else {
 #pragma unroll
-      for (int i = 0; i < ACH; ++i) ra[i] = *(const u32x4*)(pa[i] + k0);
+      for (int i = 0; i < ACH; ++i) ra[st][i] = *(const u32x4*)(pa[i] + k0);
 #pragma unroll
-      for (int i = 0; i < BCH; ++i) rb[i] = *(const u32x4*)(pb[i] + k0);
+      for (int i = 0; i < BCH; ++i) rb[st][i] = *(const u32x4*)(pb[i] + k0);
     }
   };
-  auto stash = [&](int buf) {
+  auto stash = [&](auto ST, int buf) {
+    constexpr int st = decltype(ST)::value;
 #pragma unroll
-    for (int i = 0; i < ACH; ++i) As[buf * BM * 8 + sa[i]] = ra[i];
+    for (int i = 0; i < ACH; ++i) As[buf * BM * 8 + sa[i]] = ra[st][i];
 #pragma unroll
-    for (int i = 0; i < BCH; ++i) Bs[buf * BN * 8 + sb[i]] = rb[i];
+    for (int i = 0; i < BCH; ++i) Bs[buf * BN * 8 + sb[i]] = rb[st][i];
   };
 
   f32x16 acc[MI][NI];
@@ -276,17 +281,22 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_kernel(GemmDesc g) {
   };
 
   const int nk = (g.K + BK - 1) / BK;
-  // prologue: k-tile 0 into LDS buffer 0, k-tile 1 in flight in the registers
-  fetch(0);
-  stash(0);
-  if (nk > 1) fetch(BK);
+  // prologue: k-tile 0 into LDS buffer 0, k-tiles 1 .. PF in flight in the register stages
+  fetch(IC<0>{}, 0);
+  stash(IC<0>{}, 0);
+  auto pro = [&](auto J) {
+    constexpr int j = decltype(J)::value;
+    if (j <= PF && j < nk) fetch(IC<j % PF>{}, j * BK);
+  };
+  pro(IC<1>{}); pro(IC<2>{}); pro(IC<3>{}); pro(IC<4>{});
+  static_assert(PF >= 1 && PF <= 4, "");
   __syncthreads();
   load_frags(0, As, Bs, 0);
-  // One k-tile.  STASH: k-tile kt + 1 exists (registers -> other LDS buffer, and its first fragments
-  // are loaded after the barrier); FETCH: k-tile kt + 2 exists.  The steady-state loop has both set
-  // and no branches, so that the compiler can interleave the whole body.
-  auto ktile = [&](auto STASH, auto FETCH, int kt) {
-    constexpr bool do_stash = decltype(STASH)::value != 0, do_fetch = decltype(FETCH)::value != 0;
+  // One k-tile.  ST: the register stage of k-tile kt + 1.  do_stash: k-tile kt + 1 exists (stage -> other
+  // LDS buffer, and its first fragments are loaded after the barrier); do_fetch: k-tile kt + 1 + PF exists.
+  // The steady-state loop has both set and no branches, so that the compiler can interleave the whole body.
+  auto ktile = [&](auto ST, auto STEADY, bool do_stash, bool do_fetch, int kt) {
+    constexpr bool steady = decltype(STEADY)::value != 0;      // both flags known to be set: no branches
     const int buf = kt & 1;
     const u32x4* Ab = As + buf * BM * 8;
     const u32x4* Bb = Bs + buf * BN * 8;
@@ -295,40 +305,52 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_kernel(GemmDesc g) {
     load_frags(0, Ab, Bb, 2);
     mma(1);
     load_frags(1, Ab, Bb, 3);
-    if (do_stash) stash(buf ^ 1);
-    if (do_fetch) fetch((kt + 2) * BK);
+    if (steady || do_stash) stash(ST, buf ^ 1);
+    if (steady || do_fetch) fetch(ST, (kt + 1 + PF) * BK);
     mma(0);
     __syncthreads();
-    if (do_stash) load_frags(0, As + (buf ^ 1) * BM * 8, Bs + (buf ^ 1) * BN * 8, 0);
+    if (steady || do_stash) load_frags(0, As + (buf ^ 1) * BM * 8, Bs + (buf ^ 1) * BN * 8, 0);
     mma(1);
   };
+  // k-tile kt + j of a run that starts at a multiple of PF has k-tile kt + j + 1 in stage (j + 1) % PF
+  auto steady_one = [&](auto J, int kt) {
+    constexpr int j = decltype(J)::value;
+    if (j < PF) ktile(IC<(j + 1) % PF>{}, IC<1>{}, true, true, kt + j);
+  };
+  auto tail_one = [&](auto J, int kt) {
+    constexpr int j = decltype(J)::value;
+    if (j < 2 * PF && kt + j < nk) ktile(IC<(j + 1) % PF>{}, IC<0>{}, kt + j + 1 < nk, kt + j + 1 + PF < nk, kt + j);
+  };
   int kt = 0;
-  for (; kt + 2 < nk; ++kt) ktile(IC<1>{}, IC<1>{}, kt);
-  if (kt + 1 < nk) { ktile(IC<1>{}, IC<0>{}, kt); ++kt; }
-  ktile(IC<0>{}, IC<0>{}, kt);
+  for (; kt + 2 * PF < nk; kt += PF) {      // every k-tile of the group stashes and fetches
+    steady_one(IC<0>{}, kt); steady_one(IC<1>{}, kt); steady_one(IC<2>{}, kt); steady_one(IC<3>{}, kt);
+  }
+  // at most 2 PF k-tiles are left
+  tail_one(IC<0>{}, kt); tail_one(IC<1>{}, kt); tail_one(IC<2>{}, kt); tail_one(IC<3>{}, kt);
+  tail_one(IC<4>{}, kt); tail_one(IC<5>{}, kt); tail_one(IC<6>{}, kt); tail_one(IC<7>{}, kt);
   __syncthreads();
   // the tile buffers are free now: reuse them as per-wave epilogue patches
   float* patch = (float*)smem + wave * (32 * (TN + 4));
   epilogue<MI, NI>(g, acc, m0 + wm * TM, n0 + wn * TN, lane, patch);
 }
 
-template <int BM, int BN, int WM, int WN>
+template <int BM, int BN, int WM, int WN, int PF = 1>
 void launch_nt(const GemmDesc& g, hipStream_t s) {
   static bool attr_set = false;
   constexpr size_t lds_tiles = (size_t)2 * (BM + BN) * BK * sizeof(bf16);
   constexpr size_t lds_patch = (size_t)WM * WN * 32 * (BN / WN + 4) * sizeof(float);   // epilogue patches
   constexpr size_t lds = lds_tiles > lds_patch ? lds_tiles : lds_patch;
   if (!attr_set) {
-    (void)hipFuncSetAttribute((const void*)gemm_nt_kernel<BM, BN, WM, WN, false>,
+    (void)hipFuncSetAttribute((const void*)gemm_nt_kernel<BM, BN, WM, WN, false, PF>,
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    (void)hipFuncSetAttribute((const void*)gemm_nt_kernel<BM, BN, WM, WN, true>,
+    (void)hipFuncSetAttribute((const void*)gemm_nt_kernel<BM, BN, WM, WN, true, PF>,
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     attr_set = true;
   }
   // grouped: every group may end in one partial row tile
   const int tiles = ((g.M + BM - 1) / BM + (g.grp_off ? g.groups : 0)) * ((g.N + BN - 1) / BN);
-  if (g.K % BK == 0) gemm_nt_kernel<BM, BN, WM, WN, false><<<tiles, WM * WN * 64, lds, s>>>(g);
-  else gemm_nt_kernel<BM, BN, WM, WN, true><<<tiles, WM * WN * 64, lds, s>>>(g);
+  if (g.K % BK == 0) gemm_nt_kernel<BM, BN, WM, WN, false, PF><<<tiles, WM * WN * 64, lds, s>>>(g);
+  else gemm_nt_kernel<BM, BN, WM, WN, true, PF><<<tiles, WM * WN * 64, lds, s>>>(g);
 }
 
 // ------------------------------------------------------------------------------------------ TN
@@ -634,6 +656,9 @@ static const NtShape kNtShapes[] = {
     // offered to the measured choice only (no fitted constants: fixed_us < 0 keeps them out of the model)
     {64128, 64, 128, -1.f, 0.f},        {128256, 128, 256, -1.f, 0.f},     {192256, 192, 256, -1.f, 0.f},
     {256064, 256, 64, -1.f, 0.f},       {96256, 96, 256, -1.f, 0.f},
+    // with deeper register prefetch (id = PF * 1000000 + shape)
+    {3128064, 128, 64, -1.f, 0.f},      {3064128, 64, 128, -1.f, 0.f},     {2192128, 192, 128, -1.f, 0.f},
+    {2256128, 256, 128, -1.f, 0.f},     {2128128, 128, 128, -1.f, 0.f},
 };
 
 int gemm_nt_model_tile(int M, int N, int K) {
@@ -671,6 +696,11 @@ void gemm_mfma(const GemmDesc& g, float* splitk_ws, size_t splitk_ws_floats, hip
     case 192256: launch_nt<192, 256, 2, 4>(g, s); break;
     case 256064: launch_nt<256, 64, 4, 2>(g, s); break;
     case 96256: launch_nt<96, 256, 1, 8>(g, s); break;
+    case 3128064: launch_nt<128, 64, 4, 2, 3>(g, s); break;
+    case 3064128: launch_nt<64, 128, 2, 4, 3>(g, s); break;
+    case 2192128: launch_nt<192, 128, 2, 4, 2>(g, s); break;
+    case 2256128: launch_nt<256, 128, 4, 4, 2>(g, s); break;
+    case 2128128: launch_nt<128, 128, 4, 2, 2>(g, s); break;
     default: launch_nt<128, 128, 4, 2>(g, s); break;
   }
 }

@@ -296,20 +296,25 @@ def test_fp32_mode_at_deit_s_scale(hip, orc64, layout):
     assert t32["gelu_in"] == 2 * t16["gelu_in"] and t16["total"] < t32["total"] < P.bsr_workspace_bytes(c)
 
 
-def test_autotune_picks_tiles_without_changing_a_bit(hip):
+@pytest.mark.parametrize("name,batch,launches_expected", [("c2_deit_s", 8, 1 + 4 * 12 + 4 * 4), ("mini_4blk", 5, None),
+                                                          ("tiny_2blk", 3, None)])
+def test_autotune_picks_tiles_without_changing_a_bit(hip, name, batch, launches_expected):
     # every tile shape of the matrix-multiply kernel sums an output element in the same order, so the
-    # measured choice must leave logits, gradients and activations bit-identical
+    # measured choice must leave logits, gradients and activations bit-identical (the small models have
+    # contraction lengths of 1 - 4 k-tiles and, at dim 32, a partial k-tile: the pipeline's edge cases)
     import torch
-    cfg, p, x, y = bf16_setup("c2_deit_s", batch=8)
+    cfg, p, x, y = bf16_setup(name, batch=batch)
     before = hip.run_hip_step(cfg, p, x, y)
     ctx = before["ctx"]
     dev = torch.device("cuda:0")
     xin = torch.as_tensor(x).to(dev).to(ctx.act_dtype).contiguous()
     lab = torch.as_tensor(y, dtype=torch.int32).to(dev)
-    x_f = torch.empty((8, ctx.T_f, cfg["dim"]), dtype=ctx.act_dtype, device=dev)
+    x_f = torch.empty((batch, ctx.T_f, cfg["dim"]), dtype=ctx.act_dtype, device=dev)
     loss = torch.zeros(1, dtype=torch.float32, device=dev)
     launches, changed = ctx.bsr_autotune(xin, lab, x_f, loss, ctx.new_grads())
-    assert launches == 1 + 4 * 12 + 4 * 4 and 0 <= changed <= launches
+    assert launches > 0 and 0 <= changed <= launches
+    if launches_expected is not None:
+        assert launches == launches_expected
     assert abs(float(loss[0]) - before["loss"]) == 0.0
     after = hip.run_hip_step(cfg, p, x, y, ctx=ctx)
     assert np.array_equal(after["logits"], before["logits"]) and after["loss"] == before["loss"]
@@ -317,9 +322,9 @@ def test_autotune_picks_tiles_without_changing_a_bit(hip):
     for n, g in before["grads"].items():
         assert np.array_equal(after["grads"][n], g), n
     # another batch size falls back to the cost model and still works
-    other = hip.run_hip_step(cfg, p, x[:5], y[:5], ctx=ctx)
-    ref5 = hip.run_hip_step(cfg, p, x[:5], y[:5])
-    assert np.array_equal(other["logits"], ref5["logits"])
+    other = hip.run_hip_step(cfg, p, x[:2], y[:2], ctx=ctx)
+    ref2 = hip.run_hip_step(cfg, p, x[:2], y[:2])
+    assert np.array_equal(other["logits"], ref2["logits"])
 
 
 # ------------------------------------------------------------------ the benchmark's own workload
