@@ -424,6 +424,24 @@ __global__ void patchify_kernel(const T* __restrict__ img, int B, int C, int S, 
   }
 }
 
+// the same copy in 16-byte pieces: V elements of one patch row at a time (P % V == 0, 16-byte aligned rows)
+template <typename T, int V>
+__global__ void patchify_vec_kernel(const T* __restrict__ img, int B, int C, int S, int P, T* __restrict__ out) {
+  const int G = S / P, PV = P / V;                      // pieces per patch row
+  const int64_t total = (int64_t)B * G * G * C * P * PV;
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= total) return;
+  const int qv = (int)(i % PV);
+  int64_t t = i / PV;
+  const int r = (int)(t % P); t /= P;
+  const int c = (int)(t % C); t /= C;
+  const int p = (int)(t % (G * G));
+  const int b = (int)(t / (G * G));
+  const int gy = p / G, gx = p % G;
+  const uint4 v = *(const uint4*)(img + (((int64_t)b * C + c) * S + gy * P + r) * S + gx * P + qv * V);
+  *(uint4*)(out + i * V) = v;                           // out index = ((b*N + p) * C*P*P + (c*P + r)*P + qv*V)
+}
+
 template <typename T>
 __global__ void write_cls_rows_kernel(const float* __restrict__ cls, const float* __restrict__ pos,
                                       int B, int T_, int D, T* __restrict__ x) {
@@ -866,6 +884,13 @@ void colsum(const void* a, int64_t M, int N, int64_t ld, bool f32, float* partia
 
 void patchify(const void* img, int B, int C, int S, int P, bool f32, void* out, hipStream_t s) {
   const int64_t total = (int64_t)B * C * S * S;
+  const int V = f32 ? 4 : 8;                             // elements per 16 bytes
+  if (P % V == 0 && S % V == 0 && (((uintptr_t)img | (uintptr_t)out) & 15) == 0) {
+    const unsigned vgrid = (unsigned)((total / V + 255) / 256);
+    if (f32) patchify_vec_kernel<float, 4><<<vgrid, 256, 0, s>>>((const float*)img, B, C, S, P, (float*)out);
+    else patchify_vec_kernel<bf16, 8><<<vgrid, 256, 0, s>>>((const bf16*)img, B, C, S, P, (bf16*)out);
+    return;
+  }
   const unsigned grid = (unsigned)std::min<int64_t>((total + 255) / 256, 65536);
   if (f32) patchify_kernel<float><<<grid, 256, 0, s>>>((const float*)img, B, C, S, P, (float*)out);
   else patchify_kernel<bf16><<<grid, 256, 0, s>>>((const bf16*)img, B, C, S, P, (bf16*)out);
