@@ -171,3 +171,10 @@ def test_saved_bytes_errors():
         with pytest.raises(P.BsrError):
             P.bsr_saved_activation_bytes(c, bad)
     assert P.load_library().bsr_saved_activation_bytes(None, 1, None, None) == -1
+
+
+def test_null_context_is_rejected_before_any_gpu_work():
+    lib = P.load_library()
+    assert lib.bsr_autotune(None, None, None, 1, None, None, None, None, None, None) == -1
+    assert lib.bsr_adamw_step(None, None, None, None, 0.0, 0.9, 0.999, 1e-8, 0.0, 1, None) == -1
+    assert lib.bsr_sgd_step(None, None, None, 0.0, 0.0, 0.0, None) == -1
