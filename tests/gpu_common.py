@@ -9,6 +9,9 @@ import paper_2405_10951_amd as P
 def rel(a, b):
     """max|a-b| / max|b| per tensor (the tolerance the parity bar is stated in)."""
     a, b = np.asarray(a, np.float64), np.asarray(b, np.float64)
+    assert a.shape == b.shape, (a.shape, b.shape)
+    if b.size == 0:
+        return 0.0
     return float(np.max(np.abs(a - b)) / max(float(np.max(np.abs(b))), 1e-30))
 
 
