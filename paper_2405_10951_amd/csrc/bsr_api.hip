@@ -96,6 +96,7 @@ struct Tune {
 
 struct bsr_ctx {
   Tune tune;
+  TnChain tn_chain;            // split-K reduction of the latest weight gradient, folded into the next one's launch
   std::vector<ProfRec> prof;   // event pairs of the profiling mode (bsr_profile_begin / _end)
   size_t prof_used = 0;
   bool prof_on = false;
@@ -433,7 +434,7 @@ void gemm(bsr_ctx* c, const GemmDesc& g, hipStream_t s) {
     gemm_mfma(g, c->b.splitk, c->b.splitk_floats, s, tile);
     return;
   }
-  if (gemm_mfma_supported(g)) gemm_mfma(g, c->b.splitk, c->b.splitk_floats, s);
+  if (gemm_mfma_supported(g)) gemm_mfma(g, c->b.splitk, c->b.splitk_floats, s, 0, &c->tn_chain);
   else if (g.grp_off) fail(c, BSR_ERR_BAD_CONFIG, "grouped GEMM %d x %d x %d is not an MFMA shape", g.M, g.N, g.K);
   else gemm_generic(g, s);
 }
@@ -964,6 +965,7 @@ int32_t bsr_train_blocks_fwd_bwd(bsr_ctx* c, const void* x_in, const int32_t* la
     if (l > ft) std::swap(dx, dx_other);
   }
   ln_deferred_finish(ln_tab, s);
+  gemm_tn_flush(&c->tn_chain, s);
   return check_hip(c, "bsr_train_blocks_fwd_bwd");
 }
 

@@ -47,8 +47,27 @@ void attn_bwd_generic(const void* qkv, const void* out, const void* dout, const 
 // ---- bf16 MFMA paths --------------------------------------------------------------------------
 bool gemm_mfma_supported(const GemmDesc& g);
 // splitk_ws: fp32 scratch for the partial sums of split-K weight gradients (may be null: no split)
+// A split-K weight gradient leaves fp32 partials that one more pass has to add up.  With a chain, that
+// pass does not get a launch of its own: it rides as extra workgroups on the NEXT weight-gradient launch
+// (which works on the other half of the workspace), and gemm_tn_flush runs the last one.  The sums and
+// their order are the same either way.
+struct TnReduce {
+  const float* partial = nullptr;   // [splits][n]
+  int64_t n = 0;
+  int splits = 0;
+  float* out = nullptr;
+  const float* bpartial = nullptr;  // [splits][nb] column sums (bias gradient), may be null
+  int nb = 0;
+  float* bout = nullptr;
+};
+struct TnChain {
+  TnReduce pending;                 // pending.splits > 0: a reduction is waiting
+  int slot = 0;                     // workspace half the next split launch writes
+};
 // tile: one of gemm_nt_tile_id() for the NT kernel (ignored by the others), 0 = the built-in model chooses
-void gemm_mfma(const GemmDesc& g, float* splitk_ws, size_t splitk_ws_floats, hipStream_t s, int tile = 0);
+void gemm_mfma(const GemmDesc& g, float* splitk_ws, size_t splitk_ws_floats, hipStream_t s, int tile = 0,
+               TnChain* chain = nullptr);
+void gemm_tn_flush(TnChain* chain, hipStream_t s);
 // the block-tile shapes the NT kernel is instantiated for, and whether a GEMM is free to take any of them
 int gemm_nt_tile_count();
 int gemm_nt_model_tile(int M, int N, int K);   // the built-in model's choice

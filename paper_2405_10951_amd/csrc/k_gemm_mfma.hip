@@ -370,9 +370,41 @@ void launch_nt(const GemmDesc& g, hipStream_t s) {
 // 32 columns; they travel through the same partial / reduce path as dW.
 #define BSR_LDS_PTR(T, p) ((T __attribute__((address_space(3)))*)(p))
 
+// four elements of a split-K sum (or, past the matrix, up to four of the column sums): partials added in
+// ascending split order
+__device__ inline void splitk_reduce_item(const TnReduce& r, int64_t item) {
+  const int64_t i = item * 4;
+  if (i >= r.n) {
+    for (int64_t j = i - r.n; j < min(i - r.n + 4, (int64_t)r.nb); ++j) {
+      float s = r.bpartial[j];
+      for (int z = 1; z < r.splits; ++z) s += r.bpartial[(int64_t)z * r.nb + j];
+      r.bout[j] = s;
+    }
+    return;
+  }
+  float4 s = *(const float4*)(r.partial + i);
+  for (int z = 1; z < r.splits; ++z) {
+    const float4 v = *(const float4*)(r.partial + (int64_t)z * r.n + i);
+    s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+  }
+  *(float4*)(r.out + i) = s;
+}
+__device__ inline int64_t splitk_reduce_items(const TnReduce& r) { return r.n / 4 + (r.nb + 3) / 4; }
+inline int64_t splitk_reduce_items_host(const TnReduce& r) { return r.n / 4 + (r.nb + 3) / 4; }
+
+// Grid rows [0, tn_rows) multiply; rows past them (if any) add up the partials of the previous weight
+// gradient (red), a bandwidth-bound job that overlaps with this launch's matrix work.
 template <int BM, int BN, int WM, int WN>
-__global__ __launch_bounds__(WM * WN * 64) void gemm_tn_kernel(GemmDesc g, float* partial, float* bpartial, int kt_per) {
+__global__ __launch_bounds__(WM * WN * 64) void gemm_tn_kernel(GemmDesc g, float* partial, float* bpartial, int kt_per,
+                                                              int tn_rows, TnReduce red) {
   constexpr int NT = WM * WN * 64;
+  if ((int)blockIdx.y >= tn_rows) {
+    const int64_t nthreads = (int64_t)(gridDim.y - tn_rows) * gridDim.x * NT;
+    const int64_t first = ((int64_t)(blockIdx.y - tn_rows) * gridDim.x + blockIdx.x) * NT + threadIdx.x;
+    const int64_t items = splitk_reduce_items(red);
+    for (int64_t it = first; it < items; it += nthreads) splitk_reduce_item(red, it);
+    return;
+  }
   constexpr int TM = BM / WM, TN = BN / WN, MI = TM / 32, NI = TN / 32;
   constexpr int ACPR = BM / 8, BCPR = BN / 8;                  // 16-byte chunks per token row
   constexpr int ACH = BK * ACPR / NT, BCH = BK * BCPR / NT;    // chunks per thread per k-tile
@@ -553,24 +585,14 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_tn_kernel(GemmDesc g, float
   }
 }
 
-// out[i] = sum over splits, ascending; the threads past the matrix do the same for the nb column sums
-__global__ void splitk_reduce_kernel(const float* __restrict__ partial, int64_t n, int splits, float* __restrict__ out,
-                                     const float* __restrict__ bpartial, int nb, float* __restrict__ bout) {
-  const int64_t i = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * 4;
-  if (i >= n) {
-    for (int64_t j = i - n; j < min(i - n + 4, (int64_t)nb); ++j) {
-      float s = bpartial[j];
-      for (int z = 1; z < splits; ++z) s += bpartial[(int64_t)z * nb + j];
-      bout[j] = s;
-    }
-    return;
-  }
-  float4 s = *(const float4*)(partial + i);
-  for (int z = 1; z < splits; ++z) {
-    const float4 v = *(const float4*)(partial + (int64_t)z * n + i);
-    s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
-  }
-  *(float4*)(out + i) = s;
+// the same reduction as a launch of its own
+__global__ void splitk_reduce_kernel(TnReduce r) {
+  const int64_t it = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (it < splitk_reduce_items(r)) splitk_reduce_item(r, it);
+}
+
+void launch_reduce(const TnReduce& r, hipStream_t s) {
+  splitk_reduce_kernel<<<(unsigned)((splitk_reduce_items_host(r) + 255) / 256), 256, 0, s>>>(r);
 }
 
 bool is_tn(const GemmDesc& g) {
@@ -579,7 +601,7 @@ bool is_tn(const GemmDesc& g) {
          g.remap_np == 0 && (((uintptr_t)g.A | (uintptr_t)g.B | (uintptr_t)g.C) & 15) == 0;
 }
 
-void launch_tn(const GemmDesc& g, float* ws, size_t ws_floats, hipStream_t s) {
+void launch_tn(const GemmDesc& g, float* ws, size_t ws_floats, hipStream_t s, TnChain* chain) {
   constexpr int BM = 128, BN = 128, WM = 4, WN = 2, NTHR = WM * WN * 64;
   static bool attr_set = false;
   constexpr size_t lds_tiles = (size_t)2 * (BM + BN) * BK * sizeof(bf16);
@@ -592,8 +614,14 @@ void launch_tn(const GemmDesc& g, float* ws, size_t ws_floats, hipStream_t s) {
   }
   const int tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
   if (g.grp_off) {   // one grid row per group, no split: tiles x groups already fills the machine
-    kern<<<dim3(tiles, g.groups), NTHR, lds, s>>>(g, nullptr, nullptr, 0);
+    gemm_tn_flush(chain, s);
+    kern<<<dim3(tiles, g.groups), NTHR, lds, s>>>(g, nullptr, nullptr, 0, g.groups, TnReduce());
     return;
+  }
+  if (chain) {       // this launch takes one half of the workspace, the pending reduction reads the other
+    ws_floats /= 2;
+    ws_floats &= ~(size_t)3;
+    if (ws) ws += (size_t)chain->slot * ws_floats;
   }
   const int nk = (g.K + BK - 1) / BK;
   // enough splits to give every CU about two workgroups, each with at least 4 k-tiles
@@ -607,14 +635,30 @@ void launch_tn(const GemmDesc& g, float* ws, size_t ws_floats, hipStream_t s) {
   }
   int kt_per = (nk + splits - 1) / splits;
   splits = (nk + kt_per - 1) / kt_per;
+  // the previous weight gradient's reduction rides along: about four items per thread
+  TnReduce prev;
+  int red_rows = 0;
+  if (chain && chain->pending.splits > 0) {
+    prev = chain->pending;
+    chain->pending = TnReduce();
+    const int64_t per_row = (int64_t)tiles * NTHR * 4;
+    red_rows = (int)std::min<int64_t>(8, std::max<int64_t>(1, (splitk_reduce_items_host(prev) + per_row - 1) / per_row));
+  }
   if (splits <= 1) {
-    kern<<<dim3(tiles, 1), NTHR, lds, s>>>(g, nullptr, nullptr, nk);
+    kern<<<dim3(tiles, 1 + red_rows), NTHR, lds, s>>>(g, nullptr, nullptr, nk, 1, prev);
+    return;
+  }
+  float* bws = g.bsum ? ws + (size_t)splits * mn : nullptr;
+  const int nb = g.bsum ? g.N : 0;
+  kern<<<dim3(tiles, splits + red_rows), NTHR, lds, s>>>(g, ws, bws, kt_per, splits, prev);
+  TnReduce mine;
+  mine.partial = ws; mine.n = (int64_t)mn; mine.splits = splits; mine.out = (float*)g.C;
+  mine.bpartial = bws; mine.nb = nb; mine.bout = g.bsum;
+  if (chain) {
+    chain->pending = mine;
+    chain->slot ^= 1;
   } else {
-    float* bws = g.bsum ? ws + (size_t)splits * mn : nullptr;
-    const int nb = g.bsum ? g.N : 0;
-    kern<<<dim3(tiles, splits), NTHR, lds, s>>>(g, ws, bws, kt_per);
-    splitk_reduce_kernel<<<(unsigned)((mn / 4 + (nb + 3) / 4 + 255) / 256), 256, 0, s>>>(ws, (int64_t)mn, splits, (float*)g.C,
-                                                                               bws, nb, g.bsum);
+    launch_reduce(mine, s);
   }
 }
 
@@ -626,11 +670,12 @@ bool is_nt(const GemmDesc& g) {
 
 }  // namespace
 
-// room for 8 partial copies of the largest weight gradient of a block ([D,3D] or [D,F]) and of its
+// two halves (a launch writes one while the previous launch's partials are added up from the other), each
+// with room for 8 partial copies of the largest weight gradient of a block ([D,3D] or [D,F]) and of its
 // bias gradient (16 for the smaller matrices, which split further)
 size_t gemm_splitk_ws_floats(int dim, int mlp_hidden) {
-  return (size_t)8 * std::max((size_t)3 * dim * dim, (size_t)dim * mlp_hidden) +
-         (size_t)16 * std::max(3 * dim, mlp_hidden);
+  return 2 * ((size_t)8 * std::max((size_t)3 * dim * dim, (size_t)dim * mlp_hidden) +
+              (size_t)16 * std::max(3 * dim, mlp_hidden));
 }
 
 bool gemm_mfma_supported(const GemmDesc& g) { return is_nt(g) || is_tn(g); }
@@ -676,9 +721,15 @@ int gemm_nt_tile_count() { return (int)(sizeof(kNtShapes) / sizeof(kNtShapes[0])
 int gemm_nt_tile_id(int i) { return kNtShapes[i].id; }
 bool gemm_nt_tile_is_free(const GemmDesc& g) { return is_nt(g) && !g.grp_off; }
 
-void gemm_mfma(const GemmDesc& g, float* splitk_ws, size_t splitk_ws_floats, hipStream_t s, int tile) {
+void gemm_tn_flush(TnChain* chain, hipStream_t s) {
+  if (!chain || chain->pending.splits <= 0) return;
+  launch_reduce(chain->pending, s);
+  chain->pending = TnReduce();
+}
+
+void gemm_mfma(const GemmDesc& g, float* splitk_ws, size_t splitk_ws_floats, hipStream_t s, int tile, TnChain* chain) {
   if (is_tn(g)) {
-    launch_tn(g, splitk_ws, splitk_ws_floats, s);
+    launch_tn(g, splitk_ws, splitk_ws_floats, s, chain);
     return;
   }
   static const int forced = [] { const char* e = getenv("BSR_NT_TILE"); return e ? atoi(e) : 0; }();
