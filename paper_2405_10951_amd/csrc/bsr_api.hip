@@ -410,31 +410,42 @@ struct ProfScope {
   }
 };
 
+// Tile shape for the NT launch at this position of the running call: the shape under test while tuning
+// (the launch is then bracketed by events), the measured choice for this batch size, or 0 (cost model).
+struct TileChoice {
+  int tile = 0;
+  bool timing = false;
+  TuneRec rec{};
+};
+TileChoice choose_tile(bsr_ctx* c, const GemmDesc& g, hipStream_t s) {
+  TileChoice ch;
+  if (!gemm_nt_tile_is_free(g)) return ch;
+  Tune& t = c->tune;
+  const size_t site = t.site++;
+  if (t.cand >= 0) {
+    ch.tile = gemm_nt_tile_id(t.cand);
+    ch.rec = TuneRec{t.kind, t.cand, site, g.M, g.N, g.K, nullptr, nullptr};
+    ch.timing = hipEventCreate(&ch.rec.start) == hipSuccess && hipEventCreate(&ch.rec.stop) == hipSuccess;
+    if (ch.timing) (void)hipEventRecord(ch.rec.start, s);
+  } else if (t.batch == t.cur_batch && site < t.pick[t.kind].size()) {
+    const TunePick& p = t.pick[t.kind][site];
+    if (p.M == g.M && p.N == g.N && p.K == g.K) ch.tile = p.tile;
+  }
+  return ch;
+}
+void tile_done(bsr_ctx* c, TileChoice& ch, hipStream_t s) {
+  if (!ch.timing) return;
+  (void)hipEventRecord(ch.rec.stop, s);
+  c->tune.recs.push_back(ch.rec);
+}
+
 void gemm(bsr_ctx* c, const GemmDesc& g, hipStream_t s) {
   ProfScope ps(c, BSR_PROF_GEMM, 2.0 * g.M * g.N * g.K, s);
-  if (gemm_nt_tile_is_free(g)) {
-    Tune& t = c->tune;
-    const size_t site = t.site++;
-    if (t.cand >= 0) {                 // tuning pass: force the candidate and bracket the launch with events
-      TuneRec r{t.kind, t.cand, site, g.M, g.N, g.K, nullptr, nullptr};
-      const bool ev = hipEventCreate(&r.start) == hipSuccess && hipEventCreate(&r.stop) == hipSuccess;
-      if (ev) (void)hipEventRecord(r.start, s);
-      gemm_mfma(g, c->b.splitk, c->b.splitk_floats, s, gemm_nt_tile_id(t.cand));
-      if (ev) {
-        (void)hipEventRecord(r.stop, s);
-        t.recs.push_back(r);
-      }
-      return;
-    }
-    int tile = 0;
-    if (t.batch == t.cur_batch && site < t.pick[t.kind].size()) {
-      const TunePick& p = t.pick[t.kind][site];
-      if (p.M == g.M && p.N == g.N && p.K == g.K) tile = p.tile;
-    }
-    gemm_mfma(g, c->b.splitk, c->b.splitk_floats, s, tile);
-    return;
+  if (gemm_mfma_supported(g)) {
+    TileChoice ch = choose_tile(c, g, s);
+    gemm_mfma(g, c->b.splitk, c->b.splitk_floats, s, ch.tile, &c->tn_chain);
+    tile_done(c, ch, s);
   }
-  if (gemm_mfma_supported(g)) gemm_mfma(g, c->b.splitk, c->b.splitk_floats, s, 0, &c->tn_chain);
   else if (g.grp_off) fail(c, BSR_ERR_BAD_CONFIG, "grouped GEMM %d x %d x %d is not an MFMA shape", g.M, g.N, g.K);
   else gemm_generic(g, s);
 }
@@ -450,6 +461,24 @@ void wgrad(bsr_ctx* c, const void* x, const void* dy, int M, int in, int out, vo
     gemm(c, g, s);
     colsum(dy, M, out, out, c->f32, c->b.partial, (float*)db, s);
   }
+}
+
+// Input gradient (Eq. 2, described by dg) and weight gradient (Eq. 4) of one linear layer: both read dy and
+// neither reads what the other writes, so on the MFMA path they go out together (one launch when the tile
+// shape of the input gradient allows it).
+void dgrad_wgrad(bsr_ctx* c, const GemmDesc& dg, const void* x, const void* dy, int M, int in, int out, void* dw, void* db,
+                 hipStream_t s) {
+  GemmDesc wg = wgrad_desc(c, x, dy, M, in, out, dw);
+  if (!(gemm_nt_tile_is_free(dg) && gemm_mfma_supported(wg)) || wg.grp_off) {
+    gemm(c, dg, s);
+    wgrad(c, x, dy, M, in, out, dw, db, s);
+    return;
+  }
+  wg.bsum = (float*)db;
+  ProfScope ps(c, BSR_PROF_GEMM, 2.0 * dg.M * dg.N * dg.K + 2.0 * wg.M * wg.N * wg.K, s);
+  TileChoice ch = choose_tile(c, dg, s);
+  gemm_mfma_pair(dg, wg, c->b.splitk, c->b.splitk_floats, s, ch.tile, &c->tn_chain);
+  tile_done(c, ch, s);
 }
 
 // Mixture-of-experts FFN of block l on M2 tokens (Sec. 5.3):  x_out = x_res + sum_s gate_s FFN_{e_s}(h),
@@ -924,10 +953,11 @@ int32_t bsr_train_blocks_fwd_bwd(bsr_ctx* c, const void* x_in, const int32_t* la
       GemmDesc d1 = dgrad_desc(c, dx, M2, F, D, w.w_fc2, sh.s_fc2, b.dgu);
       d1.act = ACT_GELU_BWD;
       d1.aux = v.u;
-      gemm(c, d1, s);
-      if (tr) wgrad(c, v.g, dx, M2, F, D, gw.w_fc2, gw.b_fc2, s);
-      gemm(c, dgrad_desc(c, b.dgu, M2, D, F, w.w_fc1, sh.s_fc1, b.dh), s);
-      if (tr) wgrad(c, v.h2, b.dgu, M2, D, F, gw.w_fc1, gw.b_fc1, s);
+      if (tr) dgrad_wgrad(c, d1, v.g, dx, M2, F, D, gw.w_fc2, gw.b_fc2, s);
+      else gemm(c, d1, s);
+      const GemmDesc d2 = dgrad_desc(c, b.dgu, M2, D, F, w.w_fc1, sh.s_fc1, b.dh);
+      if (tr) dgrad_wgrad(c, d2, v.h2, b.dgu, M2, D, F, gw.w_fc1, gw.b_fc1, s);
+      else gemm(c, d2, s);
     }
     if (tr) {
       float* slot = b.ln_partial ? b.ln_partial + (size_t)(ln_slot++) * ln_deferred_partial_floats(D) : nullptr;
@@ -947,11 +977,13 @@ int32_t bsr_train_blocks_fwd_bwd(bsr_ctx* c, const void* x_in, const int32_t* la
     }
 
     // MHSA branch.  dO = dx . Wproj^T; dWproj = o^T dx; attention backward; dWqkv = h1^T dqkv
-    gemm(c, dgrad_desc(c, dx, M, D, D, w.w_proj, sh.s_proj, b.dh), s);
-    if (tr) wgrad(c, v.o, dx, M, D, D, gw.w_proj, gw.b_proj, s);
+    const GemmDesc d3 = dgrad_desc(c, dx, M, D, D, w.w_proj, sh.s_proj, b.dh);
+    if (tr) dgrad_wgrad(c, d3, v.o, dx, M, D, D, gw.w_proj, gw.b_proj, s);
+    else gemm(c, d3, s);
     attention_bwd(c, v.qkv, v.o, b.dh, v.lse, B, Ta, b.dqkv, s);
-    if (tr) wgrad(c, v.h1, b.dqkv, M, D, 3 * D, gw.w_qkv, gw.b_qkv, s);
-    gemm(c, dgrad_desc(c, b.dqkv, M, D, 3 * D, w.w_qkv, sh.s_qkv, b.dh), s);
+    const GemmDesc d4 = dgrad_desc(c, b.dqkv, M, D, 3 * D, w.w_qkv, sh.s_qkv, b.dh);
+    if (tr) dgrad_wgrad(c, d4, v.h1, b.dqkv, M, D, 3 * D, gw.w_qkv, gw.b_qkv, s);
+    else gemm(c, d4, s);
     // the gradient is not carried below the earliest trainable block (Fig. 2): no dx there
     if (tr) {
       float* slot = b.ln_partial ? b.ln_partial + (size_t)(ln_slot++) * ln_deferred_partial_floats(D) : nullptr;

@@ -68,6 +68,9 @@ struct TnChain {
 void gemm_mfma(const GemmDesc& g, float* splitk_ws, size_t splitk_ws_floats, hipStream_t s, int tile = 0,
                TnChain* chain = nullptr);
 void gemm_tn_flush(TnChain* chain, hipStream_t s);
+// input gradient (NT) + weight gradient (TN) of one layer, in one launch when the NT tile shape allows it
+void gemm_mfma_pair(const GemmDesc& nt, const GemmDesc& tn, float* splitk_ws, size_t splitk_ws_floats, hipStream_t s,
+                    int tile = 0, TnChain* chain = nullptr);
 // the block-tile shapes the NT kernel is instantiated for, and whether a GEMM is free to take any of them
 int gemm_nt_tile_count();
 int gemm_nt_model_tile(int M, int N, int K);   // the built-in model's choice

@@ -149,6 +149,21 @@ __device__ __forceinline__ void epilogue(const GemmDesc& g, f32x16 (&acc)[MI][NI
   }
 }
 
+// A weight-gradient launch folded into an input-gradient launch (both read the same dy and neither reads
+// what the other writes): workgroups past nt_tiles do the work of workgroup (i % gx, i / gx) of the
+// gx x gy weight-gradient grid.
+struct TnArgs {
+  GemmDesc g;
+  float *partial, *bpartial;
+  int kt_per, tn_rows;
+  TnReduce red;
+  int gx, gy;
+  int nt_tiles;
+};
+template <int BM, int BN, int WM, int WN>
+__device__ __forceinline__ void tn_body(GemmDesc g, float* partial, float* bpartial, int kt_per, int tn_rows,
+                                        const TnReduce& red, int bx, int by, int gx, int gy);
+
 // ------------------------------------------------------------------------------------------ NT
 // LDS tile: rows of 8 chunks (16 B each), chunk kc of row r stored at position kc ^ swz(r).
 // Software pipeline of one k-tile (4 MFMA steps of k = 16):
@@ -161,9 +176,15 @@ __device__ __forceinline__ void epilogue(const GemmDesc& g, f32x16 (&acc)[MI][NI
 // its CU finishes long before an L2 or HBM access returns; such tiles run with PF = 3.
 // Rows beyond M (or N) are clamped to the last valid row: they only feed accumulators that are
 // never stored.  KTAIL zero-fills chunks beyond K (K % 64 != 0).
-template <int BM, int BN, int WM, int WN, bool KTAIL, int PF = 1>
-__global__ __launch_bounds__(WM * WN * 64) void gemm_nt_kernel(GemmDesc g) {
+template <int BM, int BN, int WM, int WN, bool KTAIL, int PF = 1, bool FUSE = false>
+__global__ __launch_bounds__(WM * WN * 64) void gemm_nt_kernel(GemmDesc g, TnArgs tn) {
   constexpr int NT = WM * WN * 64;
+  if (FUSE && (int)blockIdx.x >= tn.nt_tiles) {          // uniform over the workgroup
+    static_assert(!FUSE || NT == 512, "the weight-gradient body runs with 8 waves");
+    const int i = blockIdx.x - tn.nt_tiles;
+    tn_body<128, 128, 4, 2>(tn.g, tn.partial, tn.bpartial, tn.kt_per, tn.tn_rows, tn.red, i % tn.gx, i / tn.gx, tn.gx, tn.gy);
+    return;
+  }
   constexpr int TM = BM / WM, TN = BN / WN, MI = TM / 32, NI = TN / 32;
   constexpr int ACH = (BM * 8 + NT - 1) / NT, BCH = (BN * 8 + NT - 1) / NT;   // 16-byte chunks per thread per tile
   constexpr bool AEVEN = (BM * 8) % NT == 0, BEVEN = (BN * 8) % NT == 0;      // else the last chunk is partial
@@ -174,7 +195,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_kernel(GemmDesc g) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WN, wn = wave % WN;
   const int ntn = (g.N + BN - 1) / BN;
-  const int tile = xcd_remap(blockIdx.x, gridDim.x);
+  const int tile = xcd_remap(blockIdx.x, FUSE ? tn.nt_tiles : (int)gridDim.x);
   int m0 = (tile / ntn) * BM;
   const int n0 = (tile % ntn) * BN;
   if (g.grp_off) {
@@ -349,8 +370,8 @@ void launch_nt(const GemmDesc& g, hipStream_t s) {
   }
   // grouped: every group may end in one partial row tile
   const int tiles = ((g.M + BM - 1) / BM + (g.grp_off ? g.groups : 0)) * ((g.N + BN - 1) / BN);
-  if (g.K % BK == 0) gemm_nt_kernel<BM, BN, WM, WN, false, PF><<<tiles, WM * WN * 64, lds, s>>>(g);
-  else gemm_nt_kernel<BM, BN, WM, WN, true, PF><<<tiles, WM * WN * 64, lds, s>>>(g);
+  if (g.K % BK == 0) gemm_nt_kernel<BM, BN, WM, WN, false, PF><<<tiles, WM * WN * 64, lds, s>>>(g, TnArgs());
+  else gemm_nt_kernel<BM, BN, WM, WN, true, PF><<<tiles, WM * WN * 64, lds, s>>>(g, TnArgs());
 }
 
 // ------------------------------------------------------------------------------------------ TN
@@ -394,13 +415,15 @@ inline int64_t splitk_reduce_items_host(const TnReduce& r) { return r.n / 4 + (r
 
 // Grid rows [0, tn_rows) multiply; rows past them (if any) add up the partials of the previous weight
 // gradient (red), a bandwidth-bound job that overlaps with this launch's matrix work.
+// The work of workgroup (bx, by) of a gx x gy grid (the kernel below passes its own block index; the fused
+// input-gradient + weight-gradient launch passes the coordinates of its extra workgroups).
 template <int BM, int BN, int WM, int WN>
-__global__ __launch_bounds__(WM * WN * 64) void gemm_tn_kernel(GemmDesc g, float* partial, float* bpartial, int kt_per,
-                                                              int tn_rows, TnReduce red) {
+__device__ __forceinline__ void tn_body(GemmDesc g, float* partial, float* bpartial, int kt_per, int tn_rows,
+                                        const TnReduce& red, int bx, int by, int gx, int gy) {
   constexpr int NT = WM * WN * 64;
-  if ((int)blockIdx.y >= tn_rows) {
-    const int64_t nthreads = (int64_t)(gridDim.y - tn_rows) * gridDim.x * NT;
-    const int64_t first = ((int64_t)(blockIdx.y - tn_rows) * gridDim.x + blockIdx.x) * NT + threadIdx.x;
+  if (by >= tn_rows) {
+    const int64_t nthreads = (int64_t)(gy - tn_rows) * gx * NT;
+    const int64_t first = ((int64_t)(by - tn_rows) * gx + bx) * NT + threadIdx.x;
     const int64_t items = splitk_reduce_items(red);
     for (int64_t it = first; it < items; it += nthreads) splitk_reduce_item(red, it);
     return;
@@ -417,12 +440,12 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_tn_kernel(GemmDesc g, float
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WN, wn = wave % WN;
   const int ntn = (g.N + BN - 1) / BN;
-  const int ntiles = gridDim.x;
-  const int tile = xcd_remap(blockIdx.x, ntiles);
+  const int ntiles = gx;
+  const int tile = xcd_remap(bx, ntiles);
   const int m0 = (tile / ntn) * BM, n0 = (tile % ntn) * BN;
   if (g.grp_off) {
-    // grouped form: blockIdx.y is the group; the contraction runs over its token rows only
-    const int e = blockIdx.y, r0 = g.grp_off[e], r1 = g.grp_off[e + 1];
+    // grouped form: by is the group; the contraction runs over its token rows only
+    const int e = by, r0 = g.grp_off[e], r1 = g.grp_off[e + 1];
     g.A = (const bf16*)g.A + (int64_t)r0 * g.a_cs;
     g.B = (const bf16*)g.B + (int64_t)r0 * g.b_rs;
     g.K = r1 - r0;
@@ -433,7 +456,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_tn_kernel(GemmDesc g, float
     kt_per = (g.K + BK - 1) / BK;
   }
   const int nk_all = (g.K + BK - 1) / BK;
-  const int kt0 = g.grp_off ? 0 : blockIdx.y * kt_per, kt1 = min(kt0 + kt_per, nk_all);
+  const int kt0 = g.grp_off ? 0 : by * kt_per, kt1 = min(kt0 + kt_per, nk_all);
   const bf16* __restrict__ X = (const bf16*)g.A;     // [K tokens, Mo], row stride a_cs
   const bf16* __restrict__ Y = (const bf16*)g.B;     // [K tokens, No], row stride b_rs
 
@@ -570,19 +593,25 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_tn_kernel(GemmDesc g, float
   }
   GemmDesc o = g;
   if (partial) {                                   // split-K: plain fp32 partial, no epilogue terms
-    o.C = partial + (int64_t)blockIdx.y * g.M * g.N;
+    o.C = partial + (int64_t)by * g.M * g.N;
     o.ldc = g.N; o.bias = nullptr; o.act = ACT_NONE; o.res = nullptr; o.remap_np = 0; o.out_f32 = true;
   }
   float* patch = (float*)smem + wave * (32 * (TN + 4));
   epilogue<MI, NI>(o, acc, m0 + wm * TM, n0 + wn * TN, lane, patch);
   if (do_bsum && lh == 0) {                        // every row of accb holds the column sums
-    float* dst = bpartial ? bpartial + (int64_t)blockIdx.y * g.N : g.bsum;
+    float* dst = bpartial ? bpartial + (int64_t)by * g.N : g.bsum;
 #pragma unroll
     for (int ni = 0; ni < NI; ++ni) {
       const int col = n0 + wn * TN + ni * 32 + lr;
       if (col < g.N) dst[col] = accb[ni][0];
     }
   }
+}
+
+template <int BM, int BN, int WM, int WN>
+__global__ __launch_bounds__(WM * WN * 64) void gemm_tn_kernel(GemmDesc g, float* partial, float* bpartial, int kt_per,
+                                                              int tn_rows, TnReduce red) {
+  tn_body<BM, BN, WM, WN>(g, partial, bpartial, kt_per, tn_rows, red, blockIdx.x, blockIdx.y, gridDim.x, gridDim.y);
 }
 
 // the same reduction as a launch of its own
@@ -601,23 +630,26 @@ bool is_tn(const GemmDesc& g) {
          g.remap_np == 0 && (((uintptr_t)g.A | (uintptr_t)g.B | (uintptr_t)g.C) & 15) == 0;
 }
 
-void launch_tn(const GemmDesc& g, float* ws, size_t ws_floats, hipStream_t s, TnChain* chain) {
-  constexpr int BM = 128, BN = 128, WM = 4, WN = 2, NTHR = WM * WN * 64;
-  static bool attr_set = false;
-  constexpr size_t lds_tiles = (size_t)2 * (BM + BN) * BK * sizeof(bf16);
-  constexpr size_t lds_patch = (size_t)WM * WN * 32 * (BN / WN + 4) * sizeof(float);   // epilogue patches
-  constexpr size_t lds = lds_tiles > lds_patch ? lds_tiles : lds_patch;
-  auto kern = gemm_tn_kernel<BM, BN, WM, WN>;
-  if (!attr_set) {
-    (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    attr_set = true;
-  }
-  const int tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
-  if (g.grp_off) {   // one grid row per group, no split: tiles x groups already fills the machine
-    gemm_tn_flush(chain, s);
-    kern<<<dim3(tiles, g.groups), NTHR, lds, s>>>(g, nullptr, nullptr, 0, g.groups, TnReduce());
-    return;
-  }
+constexpr int TN_BM = 128, TN_BN = 128, TN_WM = 4, TN_WN = 2, TN_THREADS = TN_WM * TN_WN * 64;
+constexpr size_t TN_LDS_TILES = (size_t)2 * (TN_BM + TN_BN) * BK * sizeof(bf16);
+constexpr size_t TN_LDS_PATCH = (size_t)TN_WM * TN_WN * 32 * (TN_BN / TN_WN + 4) * sizeof(float);   // epilogue patches
+constexpr size_t TN_LDS = TN_LDS_TILES > TN_LDS_PATCH ? TN_LDS_TILES : TN_LDS_PATCH;
+
+// Everything a weight-gradient launch needs beyond the kernel itself: the split, the workspace half, the
+// reduction of the previous launch that rides along (taken from the chain) and the one this launch leaves.
+struct TnPlan {
+  GemmDesc g;
+  float *partial = nullptr, *bpartial = nullptr;
+  int kt_per = 0, tn_rows = 1, grid_x = 0, grid_y = 1;
+  TnReduce prev;                 // added up by the extra grid rows of this launch
+  TnReduce mine;                 // what this launch leaves to add up (mine.splits == 0: nothing)
+};
+
+TnPlan plan_tn(const GemmDesc& g, float* ws, size_t ws_floats, TnChain* chain) {
+  TnPlan p;
+  p.g = g;
+  const int tiles = ((g.M + TN_BM - 1) / TN_BM) * ((g.N + TN_BN - 1) / TN_BN);
+  p.grid_x = tiles;
   if (chain) {       // this launch takes one half of the workspace, the pending reduction reads the other
     ws_floats /= 2;
     ws_floats &= ~(size_t)3;
@@ -633,33 +665,68 @@ void launch_tn(const GemmDesc& g, float* ws, size_t ws_floats, hipStream_t s, Tn
     static const int forced = [] { const char* e = getenv("BSR_TN_SPLITS"); return e ? atoi(e) : 0; }();
     if (forced > 0) splits = std::max(1, std::min({forced, nk, (int)(ws_floats / per_split)}));
   }
-  int kt_per = (nk + splits - 1) / splits;
-  splits = (nk + kt_per - 1) / kt_per;
+  p.kt_per = (nk + splits - 1) / splits;
+  splits = (nk + p.kt_per - 1) / p.kt_per;
+  p.tn_rows = splits;
   // the previous weight gradient's reduction rides along: about four items per thread
-  TnReduce prev;
   int red_rows = 0;
   if (chain && chain->pending.splits > 0) {
-    prev = chain->pending;
+    p.prev = chain->pending;
     chain->pending = TnReduce();
-    const int64_t per_row = (int64_t)tiles * NTHR * 4;
-    red_rows = (int)std::min<int64_t>(8, std::max<int64_t>(1, (splitk_reduce_items_host(prev) + per_row - 1) / per_row));
+    const int64_t per_row = (int64_t)tiles * TN_THREADS * 4;
+    red_rows = (int)std::min<int64_t>(8, std::max<int64_t>(1, (splitk_reduce_items_host(p.prev) + per_row - 1) / per_row));
   }
-  if (splits <= 1) {
-    kern<<<dim3(tiles, 1 + red_rows), NTHR, lds, s>>>(g, nullptr, nullptr, nk, 1, prev);
+  p.grid_y = splits + red_rows;
+  if (splits > 1) {
+    p.partial = ws;
+    p.bpartial = g.bsum ? ws + (size_t)splits * mn : nullptr;
+    p.mine.partial = ws; p.mine.n = (int64_t)mn; p.mine.splits = splits; p.mine.out = (float*)g.C;
+    p.mine.bpartial = p.bpartial; p.mine.nb = g.bsum ? g.N : 0; p.mine.bout = g.bsum;
+    if (chain) {
+      chain->pending = p.mine;
+      chain->slot ^= 1;
+    }
+  }
+  return p;
+}
+
+void launch_tn(const GemmDesc& g, float* ws, size_t ws_floats, hipStream_t s, TnChain* chain) {
+  static bool attr_set = false;
+  auto kern = gemm_tn_kernel<TN_BM, TN_BN, TN_WM, TN_WN>;
+  if (!attr_set) {
+    (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)TN_LDS);
+    attr_set = true;
+  }
+  if (g.grp_off) {   // one grid row per group, no split: tiles x groups already fills the machine
+    gemm_tn_flush(chain, s);
+    const int tiles = ((g.M + TN_BM - 1) / TN_BM) * ((g.N + TN_BN - 1) / TN_BN);
+    kern<<<dim3(tiles, g.groups), TN_THREADS, TN_LDS, s>>>(g, nullptr, nullptr, 0, g.groups, TnReduce());
     return;
   }
-  float* bws = g.bsum ? ws + (size_t)splits * mn : nullptr;
-  const int nb = g.bsum ? g.N : 0;
-  kern<<<dim3(tiles, splits + red_rows), NTHR, lds, s>>>(g, ws, bws, kt_per, splits, prev);
-  TnReduce mine;
-  mine.partial = ws; mine.n = (int64_t)mn; mine.splits = splits; mine.out = (float*)g.C;
-  mine.bpartial = bws; mine.nb = nb; mine.bout = g.bsum;
-  if (chain) {
-    chain->pending = mine;
-    chain->slot ^= 1;
-  } else {
-    launch_reduce(mine, s);
+  const TnPlan p = plan_tn(g, ws, ws_floats, chain);
+  kern<<<dim3(p.grid_x, p.grid_y), TN_THREADS, TN_LDS, s>>>(p.g, p.partial, p.bpartial, p.kt_per, p.tn_rows, p.prev);
+  if (!chain && p.mine.splits > 0) launch_reduce(p.mine, s);
+}
+
+// One launch for an input gradient (NT, tile BM x BN) and the weight gradient of the same layer.
+template <int BM, int BN, int WM, int WN, int PF>
+void launch_nt_fused(const GemmDesc& g, const TnPlan& p, hipStream_t s) {
+  static_assert(WM * WN * 64 == TN_THREADS, "");
+  static bool attr_set = false;
+  constexpr size_t lds_tiles = (size_t)2 * (BM + BN) * BK * sizeof(bf16);
+  constexpr size_t lds_patch = (size_t)WM * WN * 32 * (BN / WN + 4) * sizeof(float);
+  constexpr size_t lds_nt = lds_tiles > lds_patch ? lds_tiles : lds_patch;
+  constexpr size_t lds = lds_nt > TN_LDS ? lds_nt : TN_LDS;
+  auto kern = gemm_nt_kernel<BM, BN, WM, WN, false, PF, true>;
+  if (!attr_set) {
+    (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    attr_set = true;
   }
+  TnArgs t;
+  t.g = p.g; t.partial = p.partial; t.bpartial = p.bpartial; t.kt_per = p.kt_per; t.tn_rows = p.tn_rows;
+  t.red = p.prev; t.gx = p.grid_x; t.gy = p.grid_y;
+  t.nt_tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
+  kern<<<t.nt_tiles + p.grid_x * p.grid_y, TN_THREADS, lds, s>>>(g, t);
 }
 
 bool is_nt(const GemmDesc& g) {
@@ -754,6 +821,33 @@ void gemm_mfma(const GemmDesc& g, float* splitk_ws, size_t splitk_ws_floats, hip
     case 2128128: launch_nt<128, 128, 4, 2, 2>(g, s); break;
     default: launch_nt<128, 128, 4, 2>(g, s); break;
   }
+}
+
+// The input gradient (NT) and the weight gradient (TN) of one layer.  When the tile shape chosen for the
+// NT part runs with 8 waves they go out as one launch (the weight-gradient workgroups fill the machine
+// behind the input-gradient tiles), otherwise as two.
+void gemm_mfma_pair(const GemmDesc& nt, const GemmDesc& tn, float* splitk_ws, size_t splitk_ws_floats, hipStream_t s,
+                    int tile, TnChain* chain) {
+  static const int forced = [] { const char* e = getenv("BSR_NT_TILE"); return e ? atoi(e) : 0; }();
+  static const bool no_fuse = [] { const char* e = getenv("BSR_NO_PAIR_FUSION"); return e && e[0] == '1'; }();
+  int pick = tile ? tile : forced;
+  if (!pick) pick = gemm_nt_model_tile(nt.M, nt.N, nt.K);
+  const bool can = !no_fuse && is_nt(nt) && is_tn(tn) && !nt.grp_off && !tn.grp_off && nt.K % BK == 0;
+  if (can) {
+    switch (pick) {
+      case 128064: { const TnPlan p = plan_tn(tn, splitk_ws, splitk_ws_floats, chain); launch_nt_fused<128, 64, 4, 2, 1>(nt, p, s); if (!chain && p.mine.splits > 0) launch_reduce(p.mine, s); return; }
+      case 64128: { const TnPlan p = plan_tn(tn, splitk_ws, splitk_ws_floats, chain); launch_nt_fused<64, 128, 2, 4, 1>(nt, p, s); if (!chain && p.mine.splits > 0) launch_reduce(p.mine, s); return; }
+      case 192128: { const TnPlan p = plan_tn(tn, splitk_ws, splitk_ws_floats, chain); launch_nt_fused<192, 128, 2, 4, 1>(nt, p, s); if (!chain && p.mine.splits > 0) launch_reduce(p.mine, s); return; }
+      case 128128: { const TnPlan p = plan_tn(tn, splitk_ws, splitk_ws_floats, chain); launch_nt_fused<128, 128, 4, 2, 1>(nt, p, s); if (!chain && p.mine.splits > 0) launch_reduce(p.mine, s); return; }
+      case 3128064: { const TnPlan p = plan_tn(tn, splitk_ws, splitk_ws_floats, chain); launch_nt_fused<128, 64, 4, 2, 3>(nt, p, s); if (!chain && p.mine.splits > 0) launch_reduce(p.mine, s); return; }
+      case 3064128: { const TnPlan p = plan_tn(tn, splitk_ws, splitk_ws_floats, chain); launch_nt_fused<64, 128, 2, 4, 3>(nt, p, s); if (!chain && p.mine.splits > 0) launch_reduce(p.mine, s); return; }
+      case 2192128: { const TnPlan p = plan_tn(tn, splitk_ws, splitk_ws_floats, chain); launch_nt_fused<192, 128, 2, 4, 2>(nt, p, s); if (!chain && p.mine.splits > 0) launch_reduce(p.mine, s); return; }
+      case 2128128: { const TnPlan p = plan_tn(tn, splitk_ws, splitk_ws_floats, chain); launch_nt_fused<128, 128, 4, 2, 2>(nt, p, s); if (!chain && p.mine.splits > 0) launch_reduce(p.mine, s); return; }
+      default: break;
+    }
+  }
+  gemm_mfma(nt, splitk_ws, splitk_ws_floats, s, pick, chain);
+  gemm_mfma(tn, splitk_ws, splitk_ws_floats, s, 0, chain);
 }
 
 }  // namespace bsr
