@@ -571,9 +571,18 @@ void attention_bwd(bsr_ctx* c, const void* qkv, const void* out, const void* dou
 // Returns the device pointer holding the kept indices.
 // fw != null: the dropped tokens are fused into one more token (row k+1 of x_kept, pitch k+2) and
 // fw receives the fusion weights.
+// LayerNorm that follows the token drop (LN2 of the drop location): when given, and when the one-pass kernel
+// takes the shape, gather and LayerNorm are one launch and done is set.
+struct LnAfterDrop {
+  const float *gamma, *beta;
+  void* y;
+  float *mean, *rstd;
+  bool done;
+};
+
 const int32_t* drop_tokens(bsr_ctx* c, int B, int T, int k, const void* x_full, void* x_kept,
                            int32_t* idx_own, const int32_t* forced, int32_t* idx_out, float* scores_out,
-                           float* fw, hipStream_t s) {
+                           float* fw, hipStream_t s, LnAfterDrop* ln = nullptr) {
   const int H = c->cfg.heads, D = c->cfg.dim;
   float* scores = scores_out ? scores_out : c->b.scores;
   const int32_t* idx = forced;
@@ -585,6 +594,11 @@ const int32_t* drop_tokens(bsr_ctx* c, int B, int T, int k, const void* x_full, 
   }
   if (idx_out && k > 0)
     (void)hipMemcpyAsync(idx_out, idx, sizeof(int32_t) * (size_t)B * k, hipMemcpyDeviceToDevice, s);
+  if (ln && !fw) {
+    ln->done = gather_layernorm_fwd(x_full, idx, B, T, k, D, ln->gamma, ln->beta, c->eps, c->f32, x_kept, ln->y, ln->mean,
+                                    ln->rstd, s);
+    if (ln->done) return idx;
+  }
   gather_tokens(x_full, idx, B, T, k, D, c->f32, x_kept, s, fw ? k + 2 : k + 1);
   if (fw) fuse_dropped(x_full, scores, idx, B, T, k, D, c->f32, fw, x_kept, s);
   return idx;
@@ -788,17 +802,19 @@ int32_t bsr_forward_frozen(bsr_ctx* c, const void* input, int32_t B, void* x_out
     g2.bias = (const float*)w.b_proj;
     g2.res = x;
     gemm(c, g2, s);
+    LnAfterDrop ln2{(const float*)w.ln2_g, (const float*)w.ln2_b, b.h, nullptr, nullptr, false};
     if (di >= 0) {
       const int k = sc.keep_k[di];
       drop_tokens(c, B, Ta, k, x, xalt, b.idx_tmp, forced_idx ? forced_idx + idx_off : nullptr,
                   kept_idx_out ? kept_idx_out + idx_off : nullptr, scores_out ? scores_out + sc_off : nullptr,
-                  sc.fused[di] ? b.fw : nullptr, s);
+                  sc.fused[di] ? b.fw : nullptr, s, &ln2);
       std::swap(x, xalt);
       idx_off += (size_t)B * k;
       sc_off += (size_t)B * (Ta - 1);
     }
     // FFN: x <- x + fc2(GELU(fc1(LN2(x)))), or the mixture of expert FFNs
-    layernorm_fwd(x, M2, D, (const float*)w.ln2_g, (const float*)w.ln2_b, c->eps, f32, b.h, nullptr, nullptr, s);
+    if (!ln2.done)
+      layernorm_fwd(x, M2, D, (const float*)w.ln2_g, (const float*)w.ln2_b, c->eps, f32, b.h, nullptr, nullptr, s);
     char* dest = (l == ft - 1) ? (char*)x_out : x;
     if (sc.moe[l]) {
       moe_ffn_forward(c, l, B, b.h, x, M2, b.moe, nullptr, b.moe_u, dest, s);
@@ -868,15 +884,17 @@ int32_t bsr_train_blocks_fwd_bwd(bsr_ctx* c, const void* x_in, const int32_t* la
     g2.bias = (const float*)w.b_proj;
     g2.res = x;
     gemm(c, g2, s);
+    LnAfterDrop ln2{(const float*)w.ln2_g, (const float*)w.ln2_b, v.h2, v.mean2, v.rstd2, false};
     if (di >= 0) {
       const int k = sc.keep_k[di];
       idx_used[l] = drop_tokens(c, B, Ta, k, v.xmid_full, v.xmid, v.idx, forced_idx ? forced_idx + idx_off : nullptr,
                                 kept_idx_out ? kept_idx_out + idx_off : nullptr,
-                                scores_out ? scores_out + sc_off : nullptr, sc.fused[di] ? v.fw : nullptr, s);
+                                scores_out ? scores_out + sc_off : nullptr, sc.fused[di] ? v.fw : nullptr, s, &ln2);
       idx_off += (size_t)B * k;
       sc_off += (size_t)B * (Ta - 1);
     }
-    layernorm_fwd(v.xmid, M2, D, (const float*)w.ln2_g, (const float*)w.ln2_b, c->eps, f32, v.h2, v.mean2, v.rstd2, s);
+    if (!ln2.done)
+      layernorm_fwd(v.xmid, M2, D, (const float*)w.ln2_g, (const float*)w.ln2_b, c->eps, f32, v.h2, v.mean2, v.rstd2, s);
     if (sc.moe[l]) {
       moe_ffn_forward(c, l, B, v.h2, v.xmid, M2, v.moe, v.u, v.g, v.xout, s);
     } else {

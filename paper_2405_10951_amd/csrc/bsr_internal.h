@@ -87,6 +87,11 @@ void attn_bwd_mfma(const void* qkv, const void* out, const void* dout, const flo
 void layernorm_fwd(const void* x, int64_t M, int D, const float* gamma, const float* beta, float eps,
                    bool f32, void* y, float* mean, float* rstd, hipStream_t s);
 // dx = res + LN'(dy) (res may be null; dx may be null to skip it)
+// Token gather (x_kept[b,0] = x[b,0], x_kept[b,1+i] = x[b,1+idx[b,i]]; x is [B,T,D]) and the LayerNorm of the
+// gathered rows in one pass.  Returns false (nothing done) for shapes the one-pass kernel does not take.
+bool gather_layernorm_fwd(const void* x, const int32_t* idx, int B, int T, int k, int D, const float* gamma,
+                          const float* beta, float eps, bool f32, void* x_kept, void* y, float* mean, float* rstd,
+                          hipStream_t s);
 void layernorm_bwd_dx(const void* dy, const void* x, const float* mean, const float* rstd,
                       const float* gamma, const void* res, int64_t M, int D, bool f32, void* dx,
                       hipStream_t s);

@@ -88,16 +88,26 @@ __global__ __launch_bounds__(256) void ln_bwd_dx_kernel(const T* __restrict__ dy
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 constexpr int LN_MAXC = 4;
 
+// With idx (token selection fused in, Sec. 4.1): output row m = b * (k + 1) + i reads token 0 (i == 0) or
+// token 1 + idx[b, i - 1] of image b of x [B, T_in, D], and the row itself is also copied to xcopy[m].
 __global__ __launch_bounds__(256) void ln_fwd_vec_kernel(const bf16* __restrict__ x, int64_t M, int D,
                                                          const float* __restrict__ gamma,
                                                          const float* __restrict__ beta, float eps,
                                                          bf16* __restrict__ y, float* __restrict__ mean,
-                                                         float* __restrict__ rstd) {
+                                                         float* __restrict__ rstd, const int32_t* __restrict__ idx,
+                                                         int T_in, int k, bf16* __restrict__ xcopy) {
   const int lane = threadIdx.x % WAVE;
   const int64_t m = (int64_t)blockIdx.x * 4 + threadIdx.x / WAVE;
   if (m >= M) return;
   const int nch = D / 8;
-  const bf16x8_t* xr = (const bf16x8_t*)(x + m * D);
+  int64_t src = m;
+  if (idx) {
+    const int64_t b = m / (k + 1);
+    const int i = (int)(m % (k + 1));
+    src = b * T_in + (i == 0 ? 0 : 1 + idx[b * k + i - 1]);
+  }
+  const bf16x8_t* xr = (const bf16x8_t*)(x + src * D);
+  bf16x8_t* cr = xcopy ? (bf16x8_t*)(xcopy + m * D) : nullptr;
   float v[LN_MAXC][8];
   float s = 0.f;
 #pragma unroll
@@ -105,6 +115,7 @@ __global__ __launch_bounds__(256) void ln_fwd_vec_kernel(const bf16* __restrict_
     const int c = lane + i * WAVE;
     if (c < nch) {
       const bf16x8_t t = xr[c];
+      if (cr) cr[c] = t;
 #pragma unroll
       for (int e = 0; e < 8; ++e) { v[i][e] = (float)t[e]; s += v[i][e]; }
     }
@@ -797,8 +808,20 @@ void layernorm_fwd(const void* x, int64_t M, int D, const float* gamma, const fl
   dim3 grid((unsigned)((M + 3) / 4));
   if (f32) ln_fwd_kernel<float><<<grid, 256, 0, s>>>((const float*)x, M, D, gamma, beta, eps, (float*)y, mean, rstd);
   else if (D % 8 == 0 && D <= 8 * WAVE * LN_MAXC)
-    ln_fwd_vec_kernel<<<grid, 256, 0, s>>>((const bf16*)x, M, D, gamma, beta, eps, (bf16*)y, mean, rstd);
+    ln_fwd_vec_kernel<<<grid, 256, 0, s>>>((const bf16*)x, M, D, gamma, beta, eps, (bf16*)y, mean, rstd, nullptr, 0, 0, nullptr);
   else ln_fwd_kernel<bf16><<<grid, 256, 0, s>>>((const bf16*)x, M, D, gamma, beta, eps, (bf16*)y, mean, rstd);
+}
+
+bool gather_layernorm_fwd(const void* x, const int32_t* idx, int B, int T, int k, int D, const float* gamma,
+                          const float* beta, float eps, bool f32, void* x_kept, void* y, float* mean, float* rstd,
+                          hipStream_t s) {
+  if (f32 || D % 8 != 0 || D > 8 * WAVE * LN_MAXC || B <= 0) return false;
+  const int64_t M = (int64_t)B * (k + 1);
+  // k == 0: only the class tokens; the kernel then never reads idx, which may be null: give it any non-null value
+  const int32_t* ip = idx ? idx : (const int32_t*)x;
+  ln_fwd_vec_kernel<<<(unsigned)((M + 3) / 4), 256, 0, s>>>((const bf16*)x, M, D, gamma, beta, eps, (bf16*)y, mean, rstd, ip, T, k,
+                                                           (bf16*)x_kept);
+  return true;
 }
 
 void layernorm_bwd_dx(const void* dy, const void* x, const float* mean, const float* rstd,
