@@ -39,11 +39,21 @@ __device__ inline int key_of(int jb, int r, int lh) { return jb * 32 + 8 * (r >>
 // K rows [T,64] of one head -> LDS chunks; rows >= T are zero.
 __device__ inline void load_k(const bf16* base, int64_t row_stride, int T, int Tpad, u32x4* Ks, int tid,
                               int nthreads = 256) {
-  for (int c = tid; c < Tpad * 8; c += nthreads) {
-    const int row = c >> 3, kc = c & 7;
-    u32x4 v = {0u, 0u, 0u, 0u};
-    if (row < T) v = *(const u32x4*)(base + (int64_t)row * row_stride + kc * 8);
-    Ks[row * 8 + (kc ^ swz(row))] = v;
+  // four loads in flight per thread before the first LDS write: one trip to memory instead of four
+  const int total = Tpad * 8;
+  for (int c0 = tid; c0 < total; c0 += 4 * nthreads) {
+    u32x4 v[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int c = c0 + u * nthreads, row = c >> 3, kc = c & 7;
+      v[u] = u32x4{0u, 0u, 0u, 0u};
+      if (c < total && row < T) v[u] = *(const u32x4*)(base + (int64_t)row * row_stride + kc * 8);
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int c = c0 + u * nthreads, row = c >> 3, kc = c & 7;
+      if (c < total) Ks[row * 8 + (kc ^ swz(row))] = v[u];
+    }
   }
 }
 
@@ -105,38 +115,38 @@ __global__ __launch_bounds__(NJ * 64) void attn_fwd_mfma_kernel(const bf16* __re
       s[jb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], s[jb], 0, 0, 0);
     }
   }
-  // softmax over keys: this lane holds, for query q0 + lr, the keys key_of(jb, r, lh)
+  // softmax over keys: this lane holds, for query q0 + lr, the keys key_of(jb, r, lh).  The probabilities
+  // stay unnormalised (p = exp(s - max) in (0, 1]) on their way through the second product; 1 / sum is
+  // applied to the 32 output values instead of the 32 NJ probabilities.
   const float c = 0.125f * 1.44269504088896341f;    // 1/sqrt(64) * log2(e)
   float mx = -INFINITY;
 #pragma unroll
-  for (int jb = 0; jb < NJ; ++jb)
+  for (int jb = 0; jb < NJ; ++jb) {
+    if (jb * 32 + 32 > T) {                         // only the last key block can hold keys past T (uniform)
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      if (key_of(jb, r, lh) >= T) s[jb][r] = -INFINITY;
-      mx = fmaxf(mx, s[jb][r]);
+      for (int r = 0; r < 16; ++r)
+        if (key_of(jb, r, lh) >= T) s[jb][r] = -INFINITY;
     }
+#pragma unroll
+    for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[jb][r]);
+  }
   mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+  const float mc = mx * c;
   float sum = 0.f;
-#pragma unroll
-  for (int jb = 0; jb < NJ; ++jb)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      s[jb][r] = __builtin_amdgcn_exp2f((s[jb][r] - mx) * c);
-      sum += s[jb][r];
-    }
-  sum += __shfl_xor(sum, 32, 64);
-  const float inv = 1.0f / sum;
-  const int qi = q0 + lr;
-  if (lse && lh == 0 && qi < T) lse[((int64_t)b * H + h) * T + qi] = mx * 0.125f + __logf(sum);
   bf16x8 pf[2 * NJ];
 #pragma unroll
   for (int jb = 0; jb < NJ; ++jb)
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
-      const float p = s[jb][r] * inv;
+      const float p = __builtin_amdgcn_exp2f(fmaf(s[jb][r], c, -mc));
       s[jb][r] = p;
+      sum += p;
       pf[2 * jb + (r >> 3)][r & 7] = (bf16)p;
     }
+  sum += __shfl_xor(sum, 32, 64);
+  const float inv = 1.0f / sum;
+  const int qi = q0 + lr;
+  if (lse && lh == 0 && qi < T) lse[((int64_t)b * H + h) * T + qi] = mx * 0.125f + __logf(sum);
   if (cls_prob && qi == 0) {   // the CLS query: its softmax row in fp32 (Eq. 6)
     float* dst = cls_prob + ((int64_t)b * H + h) * T;
 #pragma unroll
@@ -144,7 +154,7 @@ __global__ __launch_bounds__(NJ * 64) void attn_fwd_mfma_kernel(const bf16* __re
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int j = key_of(jb, r, lh);
-        if (j < T) dst[j] = s[jb][r];
+        if (j < T) dst[j] = s[jb][r] * inv;
       }
   }
   // O^T = V^T P^T, contraction over keys in the order the accumulators hold them:
@@ -168,7 +178,7 @@ __global__ __launch_bounds__(NJ * 64) void attn_fwd_mfma_kernel(const bf16* __re
       for (int rq = 0; rq < 4; ++rq) {
         bf16x4 v4;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) v4[e] = (bf16)o[nb][4 * rq + e];
+        for (int e = 0; e < 4; ++e) v4[e] = (bf16)(o[nb][4 * rq + e] * inv);
         *(bf16x4*)(orow + nb * 32 + 8 * rq) = v4;
       }
   }
