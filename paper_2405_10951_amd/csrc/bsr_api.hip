@@ -31,6 +31,9 @@ struct Schedule {
   bool trainable[BSR_MAX_BLOCKS] = {};  // block l is trained (others at or after ft: frozen, in the gradient path)
   bool moe[BSR_MAX_BLOCKS] = {};    // block l has a mixture-of-experts FFN
   int moe_row0[BSR_MAX_BLOCKS] = {};// per image: tokens of the mixture blocks before l (routing I/O layout)
+  // frozen prefix, bf16: LN1 / LN2 of block l is folded into the qkv / fc1 product behind it (no launch, no
+  // normalised copy): that product takes the row statistics itself, the folded weights are built once
+  bool fold1[BSR_MAX_BLOCKS] = {}, fold2[BSR_MAX_BLOCKS] = {};
 };
 
 struct MoeBuf {      // routing and the expert-ordered tensors of one mixture-of-experts FFN
@@ -52,6 +55,8 @@ struct Shadow {  // bf16 copies of a block's matrices: transposed [out,in] and, 
   bf16 *t_qkv, *t_proj, *t_fc1, *t_fc2;     // (a mixture-of-experts block: E matrices each, expert-major)
   bf16 *s_qkv, *s_proj, *s_fc1, *s_fc2;
   bf16 *t_router;                           // [E,D], mixture-of-experts blocks only
+  // folded LayerNorm (then t_qkv / t_fc1 hold W diag(gamma)): column sums of that matrix, b + W beta
+  float *cs_qkv, *fb_qkv, *cs_fc1, *fb_fc1;
 };
 
 struct Buffers {
@@ -218,6 +223,14 @@ int make_schedule(const bsr_config* c, Schedule* s, char* why, size_t whyn) {
       if (s->moe[l]) rows += s->Tm[l];
     }
   }
+  // A LayerNorm of the frozen prefix is folded when its output goes into a dense product only (after a
+  // token drop the LayerNorm kernel also does the gather; a mixture block routes on the normalised tokens).
+  static const bool no_fold = getenv("BSR_NO_LN_FOLD") != nullptr;
+  if (c->dtype == BSR_BF16 && c->dim % 64 == 0 && !no_fold)
+    for (int l = 0; l < s->ft && l < c->depth; ++l) {
+      s->fold1[l] = true;
+      s->fold2[l] = s->drop_of[l] < 0 && !s->moe[l];
+    }
   return BSR_OK;
 #undef BAD
 }
@@ -253,6 +266,8 @@ size_t carve(const bsr_config& c, const Schedule& s, char* base, Buffers* out, b
       b.sh[l].t_fc1 = w.take<bf16>(ne * D * F);
       b.sh[l].t_fc2 = w.take<bf16>(ne * D * F);
       if (s.moe[l]) b.sh[l].t_router = w.take<bf16>((size_t)c.n_experts * D);
+      if (s.fold1[l]) { b.sh[l].cs_qkv = w.take<float>(3 * D); b.sh[l].fb_qkv = w.take<float>(3 * D); }
+      if (s.fold2[l]) { b.sh[l].cs_fc1 = w.take<float>(F); b.sh[l].fb_fc1 = w.take<float>(F); }
       if (l >= ft) {
         b.sh[l].s_qkv = w.take<bf16>(3 * D * D);
         b.sh[l].s_proj = w.take<bf16>(D * D);
@@ -440,6 +455,10 @@ void tile_done(bsr_ctx* c, TileChoice& ch, hipStream_t s) {
 }
 
 void gemm(bsr_ctx* c, const GemmDesc& g, hipStream_t s) {
+  if (g.ln_colsum && (g.K % 64 || g.grp_off || !gemm_mfma_supported(g))) {
+    fail(c, BSR_ERR_BAD_CONFIG, "folded LayerNorm on a product of %d x %d x %d that cannot carry it", g.M, g.N, g.K);
+    return;
+  }
   ProfScope ps(c, BSR_PROF_GEMM, 2.0 * g.M * g.N * g.K, s);
   if (gemm_mfma_supported(g)) {
     TileChoice ch = choose_tile(c, g, s);
@@ -618,7 +637,11 @@ void build_shadows(bsr_ctx* c, int first_block, hipStream_t s) {
   for (int l = first_block; l < cf.depth; ++l) {
     const bsr_block_params& w = c->p.blocks[l];
     Shadow& sh = c->b.sh[l];
-    add(w.w_qkv, D, 3 * D, sh.s_qkv, sh.t_qkv);
+    if (c->sc.fold1[l])
+      ln_fold_weights((const float*)w.w_qkv, (const float*)w.b_qkv, (const float*)w.ln1_g, (const float*)w.ln1_b, D, 3 * D,
+                      sh.t_qkv, sh.cs_qkv, sh.fb_qkv, s);
+    else
+      add(w.w_qkv, D, 3 * D, sh.s_qkv, sh.t_qkv);
     add(w.w_proj, D, D, sh.s_proj, sh.t_proj);
     if (c->sc.moe[l]) {   // one entry per expert matrix
       for (int e = 0; e < cf.n_experts; ++e) {
@@ -628,7 +651,11 @@ void build_shadows(bsr_ctx* c, int first_block, hipStream_t s) {
       }
       continue;
     }
-    add(w.w_fc1, D, F, sh.s_fc1, sh.t_fc1);
+    if (c->sc.fold2[l])
+      ln_fold_weights((const float*)w.w_fc1, (const float*)w.b_fc1, (const float*)w.ln2_g, (const float*)w.ln2_b, D, F,
+                      sh.t_fc1, sh.cs_fc1, sh.fb_fc1, s);
+    else
+      add(w.w_fc1, D, F, sh.s_fc1, sh.t_fc1);
     add(w.w_fc2, F, D, sh.s_fc2, sh.t_fc2);
   }
   matrix_table_run(tab, false, OptArgs(), s);
@@ -793,9 +820,11 @@ int32_t bsr_forward_frozen(bsr_ctx* c, const void* input, int32_t B, void* x_out
     const int Ta = sc.Ta[l], Tm = sc.Tm[l], M = B * Ta, M2 = B * Tm;
     const int di = sc.drop_of[l];
     // MHSA: x <- x + proj(Attention(LN1(x)))
-    layernorm_fwd(x, M, D, (const float*)w.ln1_g, (const float*)w.ln1_b, c->eps, f32, b.h, nullptr, nullptr, s);
-    GemmDesc g1 = fwd_desc(c, b.h, M, D, 3 * D, w.w_qkv, sh.t_qkv, b.qkv);
-    g1.bias = (const float*)w.b_qkv;
+    const bool f1 = sc.fold1[l], f2 = sc.fold2[l];
+    if (!f1) layernorm_fwd(x, M, D, (const float*)w.ln1_g, (const float*)w.ln1_b, c->eps, f32, b.h, nullptr, nullptr, s);
+    GemmDesc g1 = fwd_desc(c, f1 ? x : b.h, M, D, 3 * D, w.w_qkv, sh.t_qkv, b.qkv);
+    g1.bias = f1 ? sh.fb_qkv : (const float*)w.b_qkv;
+    if (f1) { g1.ln_colsum = sh.cs_qkv; g1.ln_eps = c->eps; }
     gemm(c, g1, s);
     attention_fwd(c, b.qkv, B, Ta, b.o, nullptr, di >= 0 ? b.clsp : nullptr, s);
     GemmDesc g2 = fwd_desc(c, b.o, M, D, D, w.w_proj, sh.t_proj, x);
@@ -813,16 +842,17 @@ int32_t bsr_forward_frozen(bsr_ctx* c, const void* input, int32_t B, void* x_out
       sc_off += (size_t)B * (Ta - 1);
     }
     // FFN: x <- x + fc2(GELU(fc1(LN2(x)))), or the mixture of expert FFNs
-    if (!ln2.done)
+    if (!ln2.done && !f2)
       layernorm_fwd(x, M2, D, (const float*)w.ln2_g, (const float*)w.ln2_b, c->eps, f32, b.h, nullptr, nullptr, s);
     char* dest = (l == ft - 1) ? (char*)x_out : x;
     if (sc.moe[l]) {
       moe_ffn_forward(c, l, B, b.h, x, M2, b.moe, nullptr, b.moe_u, dest, s);
       continue;
     }
-    GemmDesc g3 = fwd_desc(c, b.h, M2, D, F, w.w_fc1, sh.t_fc1, b.g);
-    g3.bias = (const float*)w.b_fc1;
+    GemmDesc g3 = fwd_desc(c, f2 ? x : b.h, M2, D, F, w.w_fc1, sh.t_fc1, b.g);
+    g3.bias = f2 ? sh.fb_fc1 : (const float*)w.b_fc1;
     g3.act = ACT_GELU;
+    if (f2) { g3.ln_colsum = sh.cs_fc1; g3.ln_eps = c->eps; }
     gemm(c, g3, s);
     GemmDesc g4 = fwd_desc(c, b.g, M2, F, D, w.w_fc2, sh.t_fc2, dest);
     g4.bias = (const float*)w.b_fc2;

@@ -35,6 +35,12 @@ struct GemmDesc {
   const int32_t* grp_off = nullptr;
   int groups = 0;
   int64_t b_gs = 0, bias_gs = 0, c_gs = 0, bsum_gs = 0;
+  // LayerNorm folded into the linear layer that follows it (frozen weights; NT form, K a multiple of 64):
+  //   LN(x) W^T + b = rstd (x W'^T - mean colsum(W')) + b',   W' = W diag(gamma),  b' = b + W beta.
+  // With ln_colsum set ([N], sum_k W'(n,k)), A is the raw x, B is W', bias is b'; the kernel takes mean and
+  // 1/std of every row of A from the tiles it streams anyway and applies the formula in its epilogue.
+  const float* ln_colsum = nullptr;
+  float ln_eps = 0.f;
 };
 
 // ---- generic (any shape, fp32 or bf16 storage, fp32 arithmetic) ---------------------------------
@@ -43,6 +49,11 @@ void attn_fwd_generic(const void* qkv, int B, int T, int H, int d, bool f32, voi
                       float* cls_prob, hipStream_t s);
 void attn_bwd_generic(const void* qkv, const void* out, const void* dout, const float* lse, int B,
                       int T, int H, int d, bool f32, float* delta, void* dqkv, hipStream_t s);
+
+// W'(n,k) = bf16(w[k,n] gamma[k]) as [out][in], colsum[n] = sum_k W'(n,k), bias_out[n] = bias[n] + sum_k beta[k] w[k,n]
+// (w is the fp32 master matrix [in][out]; in a multiple of 8)
+void ln_fold_weights(const float* w, const float* bias, const float* gamma, const float* beta, int in, int out,
+                     bf16* w_t, float* colsum, float* bias_out, hipStream_t s);
 
 // ---- bf16 MFMA paths --------------------------------------------------------------------------
 bool gemm_mfma_supported(const GemmDesc& g);

@@ -798,6 +798,31 @@ inline int chunks_of(int64_t M) {
   return (int)((M + rpc - 1) / rpc);
 }
 
+// LayerNorm folded into the frozen linear layer behind it: one thread per output column n walks k in
+// ascending order, so the column sum is the sum of exactly the rounded values the matrix cores will see.
+__global__ __launch_bounds__(128) void ln_fold_kernel(const float* __restrict__ w, const float* __restrict__ bias,
+                                                     const float* __restrict__ gamma, const float* __restrict__ beta,
+                                                     int in, int out, bf16* __restrict__ w_t, float* __restrict__ colsum,
+                                                     float* __restrict__ bias_out) {
+  const int n = blockIdx.x * blockDim.x + threadIdx.x;
+  if (n >= out) return;
+  float cs = 0.f, bb = bias[n];
+  for (int k0 = 0; k0 < in; k0 += 8) {
+    bf16x8_t o;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const float wv = w[(int64_t)(k0 + j) * out + n];
+      const bf16 r = (bf16)(wv * gamma[k0 + j]);
+      o[j] = r;
+      cs += (float)r;
+      bb = fmaf(beta[k0 + j], wv, bb);
+    }
+    *(bf16x8_t*)(w_t + (int64_t)n * in + k0) = o;
+  }
+  colsum[n] = cs;
+  bias_out[n] = bb;
+}
+
 }  // namespace
 
 // ---------------------------------------------------------------- launchers
@@ -989,6 +1014,11 @@ void mean_sq_loss(const void* x, int64_t n, bool f32, float* partial, float* los
   if (f32) mean_sq_kernel<float><<<MSQ_BLOCKS, 256, 0, s>>>((const float*)x, n, partial, (float*)dx);
   else mean_sq_kernel<bf16><<<MSQ_BLOCKS, 256, 0, s>>>((const bf16*)x, n, partial, (bf16*)dx);
   mean_of_rows_kernel<<<1, 64, 0, s>>>(partial, MSQ_BLOCKS, 1.0f / (float)n, loss);
+}
+
+void ln_fold_weights(const float* w, const float* bias, const float* gamma, const float* beta, int in, int out,
+                     bf16* w_t, float* colsum, float* bias_out, hipStream_t s) {
+  ln_fold_kernel<<<(out + 127) / 128, 128, 0, s>>>(w, bias, gamma, beta, in, out, w_t, colsum, bias_out);
 }
 
 void matrix_table_add(MatTable& t, float* w, const float* g, float* m, float* v2, int rows, int cols, bf16* straight,

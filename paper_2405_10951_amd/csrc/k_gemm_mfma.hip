@@ -24,6 +24,7 @@ namespace bsr {
 namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));   // a 16-byte chunk in registers
 
@@ -75,7 +76,7 @@ __device__ inline int xcd_remap(int pid, int nblocks) {
 // 16-byte stores (32 bytes for fp32 output).
 template <int MI, int NI>
 __device__ __forceinline__ void epilogue(const GemmDesc& g, f32x16 (&acc)[MI][NI], int row0, int col0, int lane,
-                                float* patch) {
+                                float* patch, const float2* rowstat = nullptr) {
   constexpr int TN = NI * 32, LDP = TN + 4;     // +4 floats: rows start in different banks
   constexpr int CPR = TN / 8;                   // 8-column chunks per row
   constexpr int RPI = 64 / CPR;                 // rows handled per pass of the wave
@@ -86,6 +87,10 @@ __device__ __forceinline__ void epilogue(const GemmDesc& g, f32x16 (&acc)[MI][NI
   float bias[8];
 #pragma unroll
   for (int j = 0; j < 8; ++j) bias[j] = (g.bias && col_ok) ? g.bias[col + j] : 0.f;
+  // folded LayerNorm: rowstat holds (mean, 1/std) of the wave tile's rows of A, cs the column sums of W'
+  float cs[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) cs[j] = (rowstat && col_ok) ? g.ln_colsum[col + j] : 0.f;
 #pragma unroll
   for (int mi = 0; mi < MI; ++mi) {
 #pragma unroll
@@ -104,6 +109,11 @@ __device__ __forceinline__ void epilogue(const GemmDesc& g, f32x16 (&acc)[MI][NI
       const float4 p0 = *(const float4*)(patch + lr * LDP + my_chunk * 8);
       const float4 p1 = *(const float4*)(patch + lr * LDP + my_chunk * 8 + 4);
       v[0] = p0.x; v[1] = p0.y; v[2] = p0.z; v[3] = p0.w; v[4] = p1.x; v[5] = p1.y; v[6] = p1.z; v[7] = p1.w;
+      if (rowstat) {
+        const float2 st = rowstat[mi * 32 + lr];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) v[j] = st.y * fmaf(-st.x, cs[j], v[j]);
+      }
 #pragma unroll
       for (int j = 0; j < 8; ++j) v[j] += bias[j];
       int64_t row = m;
@@ -176,8 +186,9 @@ __device__ __forceinline__ void tn_body(GemmDesc g, float* partial, float* bpart
 // its CU finishes long before an L2 or HBM access returns; such tiles run with PF = 3.
 // Rows beyond M (or N) are clamped to the last valid row: they only feed accumulators that are
 // never stored.  KTAIL zero-fills chunks beyond K (K % 64 != 0).
-template <int BM, int BN, int WM, int WN, bool KTAIL, int PF = 1, bool FUSE = false>
+template <int BM, int BN, int WM, int WN, bool KTAIL, int PF = 1, bool FUSE = false, bool LNF = false>
 __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_kernel(GemmDesc g, TnArgs tn) {
+  static_assert(!LNF || (!FUSE && !KTAIL), "the folded LayerNorm reads whole rows of A in whole k-tiles");
   constexpr int NT = WM * WN * 64;
   if (FUSE && (int)blockIdx.x >= tn.nt_tiles) {          // uniform over the workgroup
     static_assert(!FUSE || NT == 512, "the weight-gradient body runs with 8 waves");
@@ -239,7 +250,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_kernel(GemmDesc g, TnArg
     sb[i] = row * 8 + ((tid & 7) ^ swz(row));
   }
   u32x4 ra[PF][ACH], rb[PF][BCH];        // the next PF k-tiles wait here while the current one is multiplied
-  auto fetch = [&](auto ST, int k0) {
+  auto fetch = [&](auto ST, int k0) __attribute__((always_inline)) {
     constexpr int st = decltype(ST)::value;
     if (KTAIL) {
       const bool oob = k0 + kc8 >= g.K;
@@ -261,12 +272,34 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_kernel(GemmDesc g, TnArg
       for (int i = 0; i < BCH; ++i) rb[st][i] = *(const u32x4*)(pb[i] + k0);
     }
   };
-  auto stash = [&](auto ST, int buf) {
+  // Folded LayerNorm (LNF): the workgroup sees every element of its rows of A on the way to LDS, so it
+  // takes their mean and variance itself: each thread adds up its chunks (always the same 8 of the 64
+  // columns of a k-tile, k-tiles in ascending order; two bf16 per dot instruction), and the 8 threads of a
+  // row are combined after the last k-tile.  The order does not depend on the tile shape.
+  float rsum[LNF ? ACH : 1], rsq[LNF ? ACH : 1];
+#pragma unroll
+  for (int i = 0; i < (LNF ? ACH : 1); ++i) rsum[i] = rsq[i] = 0.f;
+  auto stash = [&](auto ST, int buf) __attribute__((always_inline)) {
     constexpr int st = decltype(ST)::value;
 #pragma unroll
     for (int i = 0; i < ACH; ++i) As[buf * BM * 8 + sa[i]] = ra[st][i];
 #pragma unroll
     for (int i = 0; i < BCH; ++i) Bs[buf * BN * 8 + sb[i]] = rb[st][i];
+    if constexpr (LNF) {
+      const bf16x2 ones = __builtin_bit_cast(bf16x2, 0x3f803f80u);
+#pragma unroll
+      for (int i = 0; i < ACH; ++i)
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+          // (the empty asm pins the word in a register of its own: without it the compiler folds the
+          // extract-and-cast of all four words of a chunk onto word 0)
+          unsigned word = ra[st][i][w];
+          asm("" : "+v"(word));
+          const bf16x2 pr = __builtin_bit_cast(bf16x2, word);
+          rsum[i] = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, rsum[i], false);
+          rsq[i] = __builtin_amdgcn_fdot2_f32_bf16(pr, pr, rsq[i], false);
+        }
+    }
   };
 
   f32x16 acc[MI][NI];
@@ -286,14 +319,14 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_kernel(GemmDesc g, TnArg
   const int sw = swz(lr);
 
   bf16x8 fa[2][MI], fb[2][NI];
-  auto load_frags = [&](int set, const u32x4* Ab, const u32x4* Bb, int ks) {
+  auto load_frags = [&](int set, const u32x4* Ab, const u32x4* Bb, int ks) __attribute__((always_inline)) {
     const int kc = (ks * 2 + lh) ^ sw;
 #pragma unroll
     for (int mi = 0; mi < MI; ++mi) fa[set][mi] = *(const bf16x8*)(Ab + offa[mi] + kc);
 #pragma unroll
     for (int ni = 0; ni < NI; ++ni) fb[set][ni] = *(const bf16x8*)(Bb + offb[ni] + kc);
   };
-  auto mma = [&](int set) {
+  auto mma = [&](int set) __attribute__((always_inline)) {
 #pragma unroll
     for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
@@ -305,7 +338,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_kernel(GemmDesc g, TnArg
   // prologue: k-tile 0 into LDS buffer 0, k-tiles 1 .. PF in flight in the register stages
   fetch(IC<0>{}, 0);
   stash(IC<0>{}, 0);
-  auto pro = [&](auto J) {
+  auto pro = [&](auto J) __attribute__((always_inline)) {
     constexpr int j = decltype(J)::value;
     if (j <= PF && j < nk) fetch(IC<j % PF>{}, j * BK);
   };
@@ -316,7 +349,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_kernel(GemmDesc g, TnArg
   // One k-tile.  ST: the register stage of k-tile kt + 1.  do_stash: k-tile kt + 1 exists (stage -> other
   // LDS buffer, and its first fragments are loaded after the barrier); do_fetch: k-tile kt + 1 + PF exists.
   // The steady-state loop has both set and no branches, so that the compiler can interleave the whole body.
-  auto ktile = [&](auto ST, auto STEADY, bool do_stash, bool do_fetch, int kt) {
+  auto ktile = [&](auto ST, auto STEADY, bool do_stash, bool do_fetch, int kt) __attribute__((always_inline)) {
     constexpr bool steady = decltype(STEADY)::value != 0;      // both flags known to be set: no branches
     const int buf = kt & 1;
     const u32x4* Ab = As + buf * BM * 8;
@@ -334,11 +367,11 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_kernel(GemmDesc g, TnArg
     mma(1);
   };
   // k-tile kt + j of a run that starts at a multiple of PF has k-tile kt + j + 1 in stage (j + 1) % PF
-  auto steady_one = [&](auto J, int kt) {
+  auto steady_one = [&](auto J, int kt) __attribute__((always_inline)) {
     constexpr int j = decltype(J)::value;
     if (j < PF) ktile(IC<(j + 1) % PF>{}, IC<1>{}, true, true, kt + j);
   };
-  auto tail_one = [&](auto J, int kt) {
+  auto tail_one = [&](auto J, int kt) __attribute__((always_inline)) {
     constexpr int j = decltype(J)::value;
     if (j < 2 * PF && kt + j < nk) ktile(IC<(j + 1) % PF>{}, IC<0>{}, kt + j + 1 < nk, kt + j + 1 + PF < nk, kt + j);
   };
@@ -352,7 +385,24 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_kernel(GemmDesc g, TnArg
   __syncthreads();
   // the tile buffers are free now: reuse them as per-wave epilogue patches
   float* patch = (float*)smem + wave * (32 * (TN + 4));
-  epilogue<MI, NI>(g, acc, m0 + wm * TM, n0 + wn * TN, lane, patch);
+  // folded LayerNorm: (mean, 1/std) of the tile's rows go behind the tile buffers for the epilogue
+  constexpr size_t LDS_TILES = (size_t)2 * (BM + BN) * BK * sizeof(bf16), LDS_PATCH = (size_t)WM * WN * 32 * (TN + 4) * sizeof(float);
+  float2* rowstat = (float2*)(smem + (LDS_TILES > LDS_PATCH ? LDS_TILES : LDS_PATCH));
+  if constexpr (LNF) {
+#pragma unroll
+    for (int i = 0; i < ACH; ++i) {
+      float sm = rsum[i], sq = rsq[i];
+      sm += __shfl_xor(sm, 1); sq += __shfl_xor(sq, 1);
+      sm += __shfl_xor(sm, 2); sq += __shfl_xor(sq, 2);
+      sm += __shfl_xor(sm, 4); sq += __shfl_xor(sq, 4);
+      const float mean = sm / (float)g.K;
+      const float var = fmaxf(sq / (float)g.K - mean * mean, 0.f);
+      const int row = AEVEN ? (tid + NT * i) >> 3 : min((tid + NT * i) >> 3, BM - 1);
+      if ((tid & 7) == 0) rowstat[row] = make_float2(mean, rsqrtf(var + g.ln_eps));
+    }
+    __syncthreads();
+  }
+  epilogue<MI, NI>(g, acc, m0 + wm * TM, n0 + wn * TN, lane, patch, LNF ? rowstat + wm * TM : nullptr);
 }
 
 template <int BM, int BN, int WM, int WN, int PF = 1>
@@ -361,16 +411,20 @@ void launch_nt(const GemmDesc& g, hipStream_t s) {
   constexpr size_t lds_tiles = (size_t)2 * (BM + BN) * BK * sizeof(bf16);
   constexpr size_t lds_patch = (size_t)WM * WN * 32 * (BN / WN + 4) * sizeof(float);   // epilogue patches
   constexpr size_t lds = lds_tiles > lds_patch ? lds_tiles : lds_patch;
+  constexpr size_t lds_lnf = lds + BM * sizeof(float2);                  // + (mean, 1/std) of the tile's rows
   if (!attr_set) {
     (void)hipFuncSetAttribute((const void*)gemm_nt_kernel<BM, BN, WM, WN, false, PF>,
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     (void)hipFuncSetAttribute((const void*)gemm_nt_kernel<BM, BN, WM, WN, true, PF>,
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    (void)hipFuncSetAttribute((const void*)gemm_nt_kernel<BM, BN, WM, WN, false, PF, false, true>,
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_lnf);
     attr_set = true;
   }
   // grouped: every group may end in one partial row tile
   const int tiles = ((g.M + BM - 1) / BM + (g.grp_off ? g.groups : 0)) * ((g.N + BN - 1) / BN);
-  if (g.K % BK == 0) gemm_nt_kernel<BM, BN, WM, WN, false, PF><<<tiles, WM * WN * 64, lds, s>>>(g, TnArgs());
+  if (g.ln_colsum) gemm_nt_kernel<BM, BN, WM, WN, false, PF, false, true><<<tiles, WM * WN * 64, lds_lnf, s>>>(g, TnArgs());
+  else if (g.K % BK == 0) gemm_nt_kernel<BM, BN, WM, WN, false, PF><<<tiles, WM * WN * 64, lds, s>>>(g, TnArgs());
   else gemm_nt_kernel<BM, BN, WM, WN, true, PF><<<tiles, WM * WN * 64, lds, s>>>(g, TnArgs());
 }
 
