@@ -710,13 +710,17 @@ TnPlan plan_tn(const GemmDesc& g, float* ws, size_t ws_floats, TnChain* chain) {
     if (ws) ws += (size_t)chain->slot * ws_floats;
   }
   const int nk = (g.K + BK - 1) / BK;
-  // enough splits for about 1.5 workgroups per CU (measured: 384 beats 512 and 320 by 1 % of the step when
-  // the launch shares the chip with an input-gradient product), each with at least 4 k-tiles
+  // enough splits for about 1.5 workgroups per CU, each with at least 4 k-tiles (measured with the launch
+  // sharing the chip with an input-gradient product: at 35 - 49 k-tiles of tokens, 384 workgroups beat 512
+  // and 320 by 1 % of the step); two per CU once the token dimension is long (at 138 - 194 k-tiles 512 beat
+  // 384 by 3 % and 256 by 12 %)
   int splits = 1;
   const size_t mn = (size_t)g.M * g.N;
   const size_t per_split = mn + (g.bsum ? (size_t)g.N : 0);   // partial dW, then partial column sums
   if (ws && mn % 4 == 0) {
-    splits = std::max(1, std::min({384 / tiles, nk / 4, (int)(ws_floats / per_split), 16}));
+    static const int forced_target = [] { const char* e = getenv("BSR_TN_TARGET"); return e ? atoi(e) : 0; }();
+    const int target = forced_target > 0 ? forced_target : (nk >= 96 ? 512 : 384);
+    splits = std::max(1, std::min({target / tiles, nk / 4, (int)(ws_floats / per_split), 16}));
     static const int forced = [] { const char* e = getenv("BSR_TN_SPLITS"); return e ? atoi(e) : 0; }();
     if (forced > 0) splits = std::max(1, std::min({forced, nk, (int)(ws_floats / per_split)}));
   }
