@@ -312,6 +312,31 @@ int32_t bsr_linear_wgrad(const void* x, const void* dy, int32_t M, int32_t in, i
                          float* db, float* workspace, size_t workspace_floats, int32_t* used_mfma, void* stream);
 
 /*
+ * LayerNorm followed by a linear layer (the LN -> qkv and LN -> fc1 pairs of the pre-norm block, Sec. 3.1),
+ * as the frozen prefix runs them in bf16: the LayerNorm is folded into the product,
+ *   LN(x) W + b = rstd (x W' - mean c) + b',   W' = diag(gamma) W,   c = column sums of W',   b' = b + beta W,
+ * and the product takes mean and 1/std of every row of x from the tiles it reads anyway.
+ * bsr_ln_linear_fold (once per weight matrix):
+ *   w [in,out] fp32 (the master layout), bias [out], gamma [in], beta [in]: device fp32, 16-byte aligned
+ *   w_folded    device bf16 [out,in]: W' transposed, rounded once
+ *   colsum      device fp32 [out]: sums of the rounded W' over `in`
+ *   bias_folded device fp32 [out]
+ * bsr_ln_linear_forward: y[M,out] (bf16) = act(LN(x) W + b) from x [M,in] bf16 and the three folded tensors.
+ *   act   0: none, 1: exact-erf GELU
+ *   tile  0: the library chooses the block-tile shape; otherwise one of the ids bsr_gemm_tile_shapes
+ *         lists.  Every shape gives the same bits.
+ * bsr_gemm_tile_shapes: writes up to `max` shape ids to ids (host) and returns how many there are.
+ * Errors: INVALID_ARG (NULL / misaligned pointer, M < 1, `in` not a multiple of 64, `out` not a multiple of
+ * 8, unknown tile id), HIP.
+ */
+int32_t bsr_ln_linear_fold(const float* w, const float* bias, const float* gamma, const float* beta, int32_t in,
+                           int32_t out, void* w_folded, float* colsum, float* bias_folded, void* stream);
+int32_t bsr_ln_linear_forward(const void* x, int32_t M, int32_t in, int32_t out, const void* w_folded,
+                              const float* colsum, const float* bias_folded, float eps, int32_t act, void* y,
+                              int32_t tile, void* stream);
+int32_t bsr_gemm_tile_shapes(int32_t* ids, int32_t max);
+
+/*
  * Multi-head softmax attention in bf16 (Eq. 1), as the step runs it.  qkv is [B,T,3*H*d] with
  * columns [q|k|v], head h owning columns h*d .. h*d+d-1 of each third.
  * bsr_attention_forward:

@@ -92,6 +92,14 @@ def load_library():
     lib.bsr_linear_forward.restype = C.c_int32
     lib.bsr_linear_forward.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
                                        C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.bsr_gemm_tile_shapes.restype = C.c_int32
+    lib.bsr_gemm_tile_shapes.argtypes = [C.c_void_p, C.c_int32]
+    lib.bsr_ln_linear_fold.restype = C.c_int32
+    lib.bsr_ln_linear_fold.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p,
+                                       C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.bsr_ln_linear_forward.restype = C.c_int32
+    lib.bsr_ln_linear_forward.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
+                                          C.c_float, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p]
     lib.bsr_linear_dgrad.restype = C.c_int32
     lib.bsr_linear_dgrad.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
                                      C.c_void_p, C.c_void_p, C.c_void_p]
@@ -199,6 +207,39 @@ def bsr_linear_forward(x, w_t, bias=None, act=0, u_out=None, res=None, y=None):
     _check(load_library().bsr_linear_forward(_dp(x), M, kin, out, _dp(w_t), _dp(bias), act, _dp(u_out),
                                              _dp(res), _dp(y), C.byref(used), _cur_stream(x)))
     return y, used.value
+
+
+def bsr_gemm_tile_shapes():
+    """Ids of the block-tile shapes of the bf16 product kernel."""
+    lib = load_library()
+    n = lib.bsr_gemm_tile_shapes(None, 0)
+    ids = (C.c_int32 * n)()
+    lib.bsr_gemm_tile_shapes(ids, n)
+    return list(ids)
+
+
+def bsr_ln_linear_fold(w, bias, gamma, beta):
+    """w [in,out], bias [out], gamma [in], beta [in] fp32 -> (w_folded [out,in] bf16, colsum [out], bias_folded [out])."""
+    import torch
+    kin, out = w.shape
+    wf = torch.empty((out, kin), dtype=torch.bfloat16, device=w.device)
+    cs = torch.empty(out, dtype=torch.float32, device=w.device)
+    bf = torch.empty(out, dtype=torch.float32, device=w.device)
+    _check(load_library().bsr_ln_linear_fold(_dp(w), _dp(bias), _dp(gamma), _dp(beta), kin, out, _dp(wf), _dp(cs),
+                                             _dp(bf), _cur_stream(w)))
+    return wf, cs, bf
+
+
+def bsr_ln_linear_forward(x, w_folded, colsum, bias_folded, eps=1e-6, act=0, tile=0, y=None):
+    """x [M,in] bf16 and the folded tensors -> y [M,out] bf16 = act(LN(x) W + b)."""
+    import torch
+    M, kin = x.shape
+    out = w_folded.shape[0]
+    if y is None:
+        y = torch.empty((M, out), dtype=torch.bfloat16, device=x.device)
+    _check(load_library().bsr_ln_linear_forward(_dp(x), M, kin, out, _dp(w_folded), _dp(colsum), _dp(bias_folded),
+                                                C.c_float(eps), act, _dp(y), tile, _cur_stream(x)))
+    return y
 
 
 def bsr_linear_dgrad(dy, w_s, u=None, dx=None):

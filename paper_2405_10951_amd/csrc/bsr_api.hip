@@ -1260,6 +1260,40 @@ int32_t bsr_linear_forward(const void* x, int32_t M, int32_t in, int32_t out, co
   return run_layer(g, used_mfma, stream, "bsr_linear_forward");
 }
 
+int32_t bsr_gemm_tile_shapes(int32_t* ids, int32_t max) {
+  const int n = gemm_nt_tile_count();
+  for (int i = 0; ids && i < n && i < max; ++i) ids[i] = gemm_nt_tile_id(i);
+  return n;
+}
+
+int32_t bsr_ln_linear_fold(const float* w, const float* bias, const float* gamma, const float* beta, int32_t in,
+                           int32_t out, void* w_folded, float* colsum, float* bias_folded, void* stream) {
+  if (!aligned16(w) || !aligned16(bias) || !aligned16(gamma) || !aligned16(beta) || !aligned16(w_folded) ||
+      !aligned16(colsum) || !aligned16(bias_folded) || in < 8 || in % 8 || out < 1)
+    return fail(nullptr, BSR_ERR_INVALID_ARG, "bsr_ln_linear_fold: bad argument");
+  ln_fold_weights(w, bias, gamma, beta, in, out, (bf16*)w_folded, colsum, bias_folded, (hipStream_t)stream);
+  return check_hip(nullptr, "bsr_ln_linear_fold");
+}
+
+int32_t bsr_ln_linear_forward(const void* x, int32_t M, int32_t in, int32_t out, const void* w_folded,
+                              const float* colsum, const float* bias_folded, float eps, int32_t act, void* y,
+                              int32_t tile, void* stream) {
+  if (!aligned16(x) || !aligned16(w_folded) || !aligned16(colsum) || !aligned16(bias_folded) || !aligned16(y) || M < 1 ||
+      in < 64 || in % 64 || out < 8 || out % 8 || (act != 0 && act != 1))
+    return fail(nullptr, BSR_ERR_INVALID_ARG, "bsr_ln_linear_forward: bad argument");
+  bool known = tile == 0;
+  for (int i = 0; i < gemm_nt_tile_count(); ++i) known |= gemm_nt_tile_id(i) == tile;
+  if (!known) return fail(nullptr, BSR_ERR_INVALID_ARG, "bsr_ln_linear_forward: %d is not a tile shape id", tile);
+  GemmDesc g;
+  g.A = x; g.a_rs = in; g.a_cs = 1; g.B = w_folded; g.b_rs = 1; g.b_cs = in;
+  g.C = y; g.ldc = out; g.M = M; g.N = out; g.K = in;
+  g.bias = bias_folded; g.act = act ? ACT_GELU : ACT_NONE;
+  g.ln_colsum = colsum; g.ln_eps = eps;
+  if (!gemm_mfma_supported(g)) return fail(nullptr, BSR_ERR_INVALID_ARG, "bsr_ln_linear_forward: shape not taken by the MFMA kernel");
+  gemm_mfma(g, nullptr, 0, (hipStream_t)stream, tile);
+  return check_hip(nullptr, "bsr_ln_linear_forward");
+}
+
 int32_t bsr_linear_dgrad(const void* dy, int32_t M, int32_t in, int32_t out, const void* w_s,
                          const void* u, void* dx, int32_t* used_mfma, void* stream) {
   if (!aligned16(dy) || !aligned16(w_s) || !aligned16(dx) || M < 1 || in < 1 || out < 1)

@@ -33,7 +33,8 @@ def test_python_binding_has_the_entry_points_names():
     for n in ("bsr_forward_frozen", "bsr_select_tokens", "bsr_train_blocks_fwd_bwd", "bsr_sgd_step",
               "bsr_refresh_weights", "bsr_profile_begin", "bsr_profile_end", "bsr_destroy"):
         assert hasattr(P.Context, n)
-    for n in ("bsr_token_schedule", "bsr_workspace_bytes", "bsr_linear_forward", "bsr_linear_dgrad",
+    for n in ("bsr_token_schedule", "bsr_workspace_bytes", "bsr_linear_forward", "bsr_linear_dgrad", "bsr_ln_linear_fold",
+              "bsr_ln_linear_forward", "bsr_gemm_tile_shapes",
               "bsr_linear_wgrad", "bsr_attention_forward", "bsr_attention_backward"):
         assert hasattr(P, n)
 

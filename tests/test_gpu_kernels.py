@@ -66,6 +66,52 @@ def test_linear_forward(env, orc64, M, kin, out):
     assert_close(r.float().cpu().numpy()[rows], ref + res[rows], "residual")
 
 
+LN_SHAPES = [(6304, 768, 2304), (4416, 768, 3072), (2144, 768, 2304), (333, 128, 72), (1, 64, 8), (130, 768, 136)]
+
+
+@pytest.mark.parametrize("M,kin,out", LN_SHAPES)
+def test_layernorm_folded_into_linear(env, orc64, M, kin, out):
+    """LayerNorm then linear (the LN -> qkv / LN -> fc1 pairs of the pre-norm block) as the frozen prefix runs
+    them: one product on the raw rows with folded weights, statistics taken inside the kernel.  Against the
+    oracle's LayerNorm followed by its linear layer on sampled rows; rows get different means and spreads."""
+    torch, P = env
+    rng = np.random.default_rng(11 * M + kin + out)
+    x = S.round_to_bf16((rng.standard_normal((M, kin)) * rng.uniform(0.3, 3.0, (M, 1)) + rng.normal(0, 1.0, (M, 1))).astype(np.float32))
+    w = (rng.standard_normal((kin, out)) * 0.05).astype(np.float32); b = rng.standard_normal(out).astype(np.float32)
+    gamma = (1 + 0.2 * rng.standard_normal(kin)).astype(np.float32); beta = (0.1 * rng.standard_normal(kin)).astype(np.float32)
+    rows = np.unique(np.concatenate([rng.choice(M, min(M, 192), replace=False), np.arange(max(0, M - 40), M)]))
+    wf, cs, bf = P.bsr_ln_linear_fold(to_dev(torch, w), to_dev(torch, b), to_dev(torch, gamma), to_dev(torch, beta))
+    xt = to_dev(torch, x, torch.bfloat16)
+    y = P.bsr_ln_linear_forward(xt, wf, cs, bf, eps=1e-6)
+    g = P.bsr_ln_linear_forward(xt, wf, cs, bf, eps=1e-6, act=1)
+    torch.cuda.synchronize()
+    ref = orc64.linear(orc64.layernorm(x[rows], gamma, beta, 1e-6)[0], w, b)
+    assert_close(y.float().cpu().numpy()[rows], ref, "LayerNorm + linear")
+    assert_close(g.float().cpu().numpy()[rows], orc64.gelu(ref), "LayerNorm + linear + GELU")
+    # the folded tensors themselves: W' = diag(gamma) W rounded to bf16, its column sums, b' = b + beta W
+    wp = S.round_to_bf16((w * gamma[:, None]).astype(np.float32))
+    assert np.array_equal(wf.float().cpu().numpy(), wp.T)
+    assert np.abs(cs.cpu().numpy() - wp.sum(0, dtype=np.float64)).max() <= 1e-5 * np.abs(wp).sum(0).max()
+    assert np.abs(bf.cpu().numpy() - (b + beta.astype(np.float64) @ w)).max() <= 1e-5 * (np.abs(b).max() + 1)
+    # every block-tile shape gives the same bits (the statistics are summed in an order of their own)
+    y0 = y.view(torch.int16).cpu().numpy()
+    for tile in P.bsr_gemm_tile_shapes():
+        yt = P.bsr_ln_linear_forward(xt, wf, cs, bf, eps=1e-6, tile=tile)
+        torch.cuda.synchronize()
+        assert np.array_equal(yt.view(torch.int16).cpu().numpy(), y0), f"tile shape {tile} changes the result"
+
+
+def test_layernorm_folded_refuses_what_it_cannot_take(env):
+    torch, P = env
+    x = torch.zeros((8, 96), dtype=torch.bfloat16, device="cuda")          # 96 is not a multiple of 64
+    wf = torch.zeros((16, 96), dtype=torch.bfloat16, device="cuda"); v = torch.zeros(16, device="cuda")
+    with pytest.raises(P.BsrError):
+        P.bsr_ln_linear_forward(x, wf, v, v)
+    x = torch.zeros((8, 64), dtype=torch.bfloat16, device="cuda"); wf = torch.zeros((16, 64), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(P.BsrError):
+        P.bsr_ln_linear_forward(x, wf, v, v, tile=12345)
+
+
 @pytest.mark.parametrize("M,kin,out", SHAPES)
 def test_linear_dgrad(env, orc64, M, kin, out):
     torch, P = env
