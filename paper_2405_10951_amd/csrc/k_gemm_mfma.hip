@@ -186,8 +186,11 @@ __device__ __forceinline__ void tn_body(GemmDesc g, float* partial, float* bpart
 // its CU finishes long before an L2 or HBM access returns; such tiles run with PF = 3.
 // Rows beyond M (or N) are clamped to the last valid row: they only feed accumulators that are
 // never stored.  KTAIL zero-fills chunks beyond K (K % 64 != 0).
+// (A folded 8-wave kernel whose tiles leave room for two workgroups per CU is held to the 128 registers that
+// two workgroups need: the row sums would otherwise push the 192 x 128 shape to 132 and halve its occupancy.)
 template <int BM, int BN, int WM, int WN, bool KTAIL, int PF = 1, bool FUSE = false, bool LNF = false>
-__global__ __launch_bounds__(WM * WN * 64) void gemm_nt_kernel(GemmDesc g, TnArgs tn) {
+__global__ __launch_bounds__(WM * WN * 64, (LNF && PF == 1 && WM * WN == 8 && (BM + BN) * 256 <= 80 * 1024) ? 4 : 1)
+void gemm_nt_kernel(GemmDesc g, TnArgs tn) {
   static_assert(!LNF || (!FUSE && !KTAIL), "the folded LayerNorm reads whole rows of A in whole k-tiles");
   constexpr int NT = WM * WN * 64;
   if (FUSE && (int)blockIdx.x >= tn.nt_tiles) {          // uniform over the workgroup
@@ -385,9 +388,10 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_kernel(GemmDesc g, TnArg
   __syncthreads();
   // the tile buffers are free now: reuse them as per-wave epilogue patches
   float* patch = (float*)smem + wave * (32 * (TN + 4));
-  // folded LayerNorm: (mean, 1/std) of the tile's rows go behind the tile buffers for the epilogue
-  constexpr size_t LDS_TILES = (size_t)2 * (BM + BN) * BK * sizeof(bf16), LDS_PATCH = (size_t)WM * WN * 32 * (TN + 4) * sizeof(float);
-  float2* rowstat = (float2*)(smem + (LDS_TILES > LDS_PATCH ? LDS_TILES : LDS_PATCH));
+  // folded LayerNorm: (mean, 1/std) of the tile's rows go behind the epilogue patches (inside the tile
+  // buffers, which are free by now, whenever those are the larger of the two)
+  constexpr size_t LDS_PATCH = (size_t)WM * WN * 32 * (TN + 4) * sizeof(float);
+  float2* rowstat = (float2*)(smem + LDS_PATCH);
   if constexpr (LNF) {
 #pragma unroll
     for (int i = 0; i < ACH; ++i) {
@@ -411,7 +415,8 @@ void launch_nt(const GemmDesc& g, hipStream_t s) {
   constexpr size_t lds_tiles = (size_t)2 * (BM + BN) * BK * sizeof(bf16);
   constexpr size_t lds_patch = (size_t)WM * WN * 32 * (BN / WN + 4) * sizeof(float);   // epilogue patches
   constexpr size_t lds = lds_tiles > lds_patch ? lds_tiles : lds_patch;
-  constexpr size_t lds_lnf = lds + BM * sizeof(float2);                  // + (mean, 1/std) of the tile's rows
+  constexpr size_t lds_stat = lds_patch + BM * sizeof(float2);           // (mean, 1/std) of the tile's rows behind the patches
+  constexpr size_t lds_lnf = lds > lds_stat ? lds : lds_stat;
   if (!attr_set) {
     (void)hipFuncSetAttribute((const void*)gemm_nt_kernel<BM, BN, WM, WN, false, PF>,
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
