@@ -805,13 +805,13 @@ int32_t bsr_forward_frozen(bsr_ctx* c, const void* input, int32_t B, void* x_out
   char* xalt = b.x1;
   if (cf.image_size) {
     const int np = sc.T0 - 1, Kp = cf.in_chans * cf.patch_size * cf.patch_size;
-    patchify(input, B, cf.in_chans, cf.image_size, cf.patch_size, f32, b.patches, s);
+    patchify(input, B, cf.in_chans, cf.image_size, cf.patch_size, f32, b.patches, s, (const float*)c->p.cls,
+             (const float*)c->p.pos, sc.T0, D, x);
     GemmDesc g = fwd_desc(c, b.patches, B * np, Kp, D, c->p.w_patch, b.t_patch, x);
     g.bias = (const float*)c->p.b_patch;
     g.remap_np = np;
     g.pos = (const float*)c->p.pos;
     gemm(c, g, s);
-    write_cls_rows((const float*)c->p.cls, (const float*)c->p.pos, B, sc.T0, D, f32, x, s);
   } else {
     (void)hipMemcpyAsync(x, input, (size_t)B * sc.T0 * D * E, hipMemcpyDeviceToDevice, s);
   }

@@ -132,7 +132,10 @@ bool layernorm_bwd_deferred(const void* dy, const void* x, const float* mean, co
                             float* dbeta, LnDeferTable& t, hipStream_t s);
 void ln_deferred_finish(LnDeferTable& t, hipStream_t s);
 
-void patchify(const void* img, int B, int C, int S, int P, bool f32, void* out, hipStream_t s);
+// cls given: also writes the class-token rows x[b, 0, :] = cls + pos[0] of the token tensor x [B, T, D] (same launch
+// on the 16-byte path)
+void patchify(const void* img, int B, int C, int S, int P, bool f32, void* out, hipStream_t s,
+              const float* cls = nullptr, const float* pos = nullptr, int T = 0, int D = 0, void* x = nullptr);
 void write_cls_rows(const float* cls, const float* pos, int B, int T, int D, bool f32, void* x,
                     hipStream_t s);
 void cls_head_mean(const float* cls_prob, int B, int H, int T, float* scores, hipStream_t s);

@@ -436,8 +436,17 @@ __global__ void patchify_kernel(const T* __restrict__ img, int B, int C, int S, 
 }
 
 // the same copy in 16-byte pieces: V elements of one patch row at a time (P % V == 0, 16-byte aligned rows)
+// Workgroups past the copy (cls_blocks of them, one per image) write the class-token rows of the token tensor,
+// x[b, 0, :] = cls + pos[0] (Sec. 3.1): the same launch, since nothing else has to run before the embedding product.
 template <typename T, int V>
-__global__ void patchify_vec_kernel(const T* __restrict__ img, int B, int C, int S, int P, T* __restrict__ out) {
+__global__ void patchify_vec_kernel(const T* __restrict__ img, int B, int C, int S, int P, T* __restrict__ out,
+                                    int copy_blocks, const float* __restrict__ cls, const float* __restrict__ pos,
+                                    int T_, int D, T* __restrict__ x) {
+  if ((int)blockIdx.x >= copy_blocks) {
+    const int b = blockIdx.x - copy_blocks;
+    for (int j = threadIdx.x; j < D; j += blockDim.x) x[(int64_t)b * T_ * D + j] = (T)(cls[j] + pos[j]);
+    return;
+  }
   const int G = S / P, PV = P / V;                      // pieces per patch row
   const int64_t total = (int64_t)B * G * G * C * P * PV;
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -930,18 +939,20 @@ void colsum(const void* a, int64_t M, int N, int64_t ld, bool f32, float* partia
   colsum_final_kernel<<<(N + WAVE - 1) / WAVE, FINAL_WAVES * WAVE, 0, s>>>(partial, N, ch, 0, out, nullptr);
 }
 
-void patchify(const void* img, int B, int C, int S, int P, bool f32, void* out, hipStream_t s) {
+void patchify(const void* img, int B, int C, int S, int P, bool f32, void* out, hipStream_t s, const float* cls,
+              const float* pos, int T, int D, void* x) {
   const int64_t total = (int64_t)B * C * S * S;
   const int V = f32 ? 4 : 8;                             // elements per 16 bytes
   if (P % V == 0 && S % V == 0 && (((uintptr_t)img | (uintptr_t)out) & 15) == 0) {
-    const unsigned vgrid = (unsigned)((total / V + 255) / 256);
-    if (f32) patchify_vec_kernel<float, 4><<<vgrid, 256, 0, s>>>((const float*)img, B, C, S, P, (float*)out);
-    else patchify_vec_kernel<bf16, 8><<<vgrid, 256, 0, s>>>((const bf16*)img, B, C, S, P, (bf16*)out);
+    const unsigned vgrid = (unsigned)((total / V + 255) / 256), extra = cls ? (unsigned)B : 0u;
+    if (f32) patchify_vec_kernel<float, 4><<<vgrid + extra, 256, 0, s>>>((const float*)img, B, C, S, P, (float*)out, (int)vgrid, cls, pos, T, D, (float*)x);
+    else patchify_vec_kernel<bf16, 8><<<vgrid + extra, 256, 0, s>>>((const bf16*)img, B, C, S, P, (bf16*)out, (int)vgrid, cls, pos, T, D, (bf16*)x);
     return;
   }
   const unsigned grid = (unsigned)std::min<int64_t>((total + 255) / 256, 65536);
   if (f32) patchify_kernel<float><<<grid, 256, 0, s>>>((const float*)img, B, C, S, P, (float*)out);
   else patchify_kernel<bf16><<<grid, 256, 0, s>>>((const bf16*)img, B, C, S, P, (bf16*)out);
+  if (cls) write_cls_rows(cls, pos, B, T, D, f32, x, s);
 }
 
 void write_cls_rows(const float* cls, const float* pos, int B, int T, int D, bool f32, void* x,
