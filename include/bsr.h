@@ -17,8 +17,12 @@
  *   - Activations ("act" below) have the configured compute dtype: bf16 (2 bytes) or fp32.
  *     Parameters, gradients and momenta are always fp32.  Linear weights are row-major [in, out].
  *   - Block and drop indices are 0-based.  Token tensors are row-major [B, T, D], token 0 = CLS.
- *   - Calls on one context are not thread-safe and must be issued on one stream (or be ordered by
- *     the caller); different contexts are independent.
+ *   - Calls on one context are not thread-safe (one host thread at a time) and must be issued on one
+ *     stream or be ordered by the caller, with one exception made for pipelining: bsr_forward_frozen of
+ *     the next batch may run on a second stream beside bsr_train_blocks_fwd_bwd and the optimizer step
+ *     of the current batch.  The frozen prefix reads only frozen weights (Fig. 2) and shares no device
+ *     scratch with the other two; the caller orders the producer and the consumer of each x_out buffer
+ *     with events (two such buffers make a pipeline).  Different contexts are independent.
  */
 #ifndef BSR_H_
 #define BSR_H_

@@ -64,6 +64,10 @@ struct Buffers {
   Shadow sh[BSR_MAX_BLOCKS] = {};
   char *patches = nullptr, *x0 = nullptr, *x1 = nullptr, *h = nullptr, *qkv = nullptr, *o = nullptr, *g = nullptr;
   float *clsp = nullptr, *scores = nullptr, *fw = nullptr;   // fw: fusion weights of a frozen drop location
+  // Scratch of the trainable part that is not kept for backward.  It has buffers of its own because the
+  // frozen prefix of the next batch may run beside it on another stream.
+  float *clsp_t = nullptr, *scores_t = nullptr;
+  char *h_t = nullptr, *o_t = nullptr, *g_t = nullptr;
   int32_t* idx_tmp = nullptr;
   SavedBlock sv[BSR_MAX_BLOCKS] = {};
   MoeBuf moe = {};                      // frozen mixture blocks share this one
@@ -288,6 +292,8 @@ size_t carve(const bsr_config& c, const Schedule& s, char* base, Buffers* out, b
   b.g = w.take<char>(B * T0 * F * E);
   b.clsp = w.take<float>(B * H * T0);
   b.scores = w.take<float>(B * T0);
+  b.clsp_t = w.take<float>(B * H * T0);
+  b.scores_t = w.take<float>(B * T0);
   b.fw = w.take<float>(B * T0);
   b.idx_tmp = w.take<int32_t>(B * T0);
   const size_t KE = c.n_moe > 0 ? (size_t)c.moe_top_k : 1, NE = c.n_moe > 0 ? (size_t)c.n_experts : 0;
@@ -309,6 +315,16 @@ size_t carve(const bsr_config& c, const Schedule& s, char* base, Buffers* out, b
     b.moe_u = w.take<char>(B * T0 * KE * F * E);
   }
   size_t Tmax = s.T_last;
+  bool any_drop = false, any_dgrad_only = false;
+  for (int l = ft; l < L; ++l) {
+    any_drop |= s.drop_of[l] >= 0;
+    any_dgrad_only |= !(s.trainable[l] || s.moe[l]);
+  }
+  if (any_drop) b.o_t = w.take<char>(B * T0 * D * E);
+  if (any_dgrad_only) {
+    b.h_t = w.take<char>(B * T0 * D * E);
+    b.g_t = w.take<char>(B * T0 * F * E);
+  }
   for (int l = ft; l < L; ++l) {
     const size_t Ta = s.Ta[l], Tm = s.Tm[l];
     Tmax = std::max(Tmax, Ta);
@@ -321,17 +337,17 @@ size_t carve(const bsr_config& c, const Schedule& s, char* base, Buffers* out, b
     v.rstd2 = w.take<float>(B * Tm, &r.stats);
     v.lse = w.take<float>(B * H * Ta, &r.softmax);
     const bool keep_lin = s.trainable[l] || s.moe[l];   // inputs of the linear layers: only Eq. 4 needs them
-    v.h1 = keep_lin ? w.take<char>(B * Ta * D * E, &r.linear_in) : b.h;
+    v.h1 = keep_lin ? w.take<char>(B * Ta * D * E, &r.linear_in) : b.h_t;
     v.qkv = w.take<char>(B * Ta * 3 * D * E, &r.qkv);
     v.o = w.take<char>(B * Ta * D * E, &r.attn_out);
     // x after MHSA: at a drop location only its gathered rows are read again, the full tensor is scratch
     const bool drop = s.drop_of[l] >= 0;
-    v.xmid_full = drop ? b.o : w.take<char>(B * Ta * D * E, &r.residual);
+    v.xmid_full = drop ? b.o_t : w.take<char>(B * Ta * D * E, &r.residual);
     v.xmid = drop ? w.take<char>(B * Tm * D * E, &r.residual) : v.xmid_full;
-    v.h2 = keep_lin ? w.take<char>(B * Tm * D * E, &r.linear_in) : b.h;
+    v.h2 = keep_lin ? w.take<char>(B * Tm * D * E, &r.linear_in) : b.h_t;
     const size_t kf = s.moe[l] ? KE : 1;               // a mixture block keeps u and g per (token, slot)
     v.u = w.take<char>(B * Tm * kf * F * E, &r.gelu_in);
-    v.g = keep_lin ? w.take<char>(B * Tm * kf * F * E, &r.linear_in) : b.g;
+    v.g = keep_lin ? w.take<char>(B * Tm * kf * F * E, &r.linear_in) : b.g_t;
     if (s.moe[l]) take_moe(v.moe, B * Tm, &r.moe);
     v.xout = w.take<char>(B * Tm * D * E, &r.residual);
     v.idx = w.take<int32_t>(drop ? B * Tm : 0, &r.stats);
@@ -604,15 +620,16 @@ struct LnAfterDrop {
 
 const int32_t* drop_tokens(bsr_ctx* c, int B, int T, int k, const void* x_full, void* x_kept,
                            int32_t* idx_own, const int32_t* forced, int32_t* idx_out, float* scores_out,
-                           float* fw, hipStream_t s, LnAfterDrop* ln = nullptr) {
+                           float* fw, hipStream_t s, LnAfterDrop* ln = nullptr, bool trainable_part = false) {
   const int H = c->cfg.heads, D = c->cfg.dim;
-  float* scores = scores_out ? scores_out : c->b.scores;
+  const float* clsp = trainable_part ? c->b.clsp_t : c->b.clsp;
+  float* scores = scores_out ? scores_out : (trainable_part ? c->b.scores_t : c->b.scores);
   const int32_t* idx = forced;
   if (!forced) {
-    topk_select_from_cls(c->b.clsp, B, H, T, k, scores, idx_own, s);
+    topk_select_from_cls(clsp, B, H, T, k, scores, idx_own, s);
     idx = idx_own;
   } else if (scores_out || fw) {
-    cls_head_mean(c->b.clsp, B, H, T, scores, s);
+    cls_head_mean(clsp, B, H, T, scores, s);
   }
   if (idx_out && k > 0)
     (void)hipMemcpyAsync(idx_out, idx, sizeof(int32_t) * (size_t)B * k, hipMemcpyDeviceToDevice, s);
@@ -912,7 +929,7 @@ int32_t bsr_train_blocks_fwd_bwd(bsr_ctx* c, const void* x_in, const int32_t* la
     GemmDesc g1 = fwd_desc(c, v.h1, M, D, 3 * D, w.w_qkv, sh.t_qkv, v.qkv);
     g1.bias = (const float*)w.b_qkv;
     gemm(c, g1, s);
-    attention_fwd(c, v.qkv, B, Ta, v.o, v.lse, di >= 0 ? b.clsp : nullptr, s);
+    attention_fwd(c, v.qkv, B, Ta, v.o, v.lse, di >= 0 ? b.clsp_t : nullptr, s);
     GemmDesc g2 = fwd_desc(c, v.o, M, D, D, w.w_proj, sh.t_proj, v.xmid_full);
     g2.bias = (const float*)w.b_proj;
     g2.res = x;
@@ -922,7 +939,7 @@ int32_t bsr_train_blocks_fwd_bwd(bsr_ctx* c, const void* x_in, const int32_t* la
       const int k = sc.keep_k[di];
       idx_used[l] = drop_tokens(c, B, Ta, k, v.xmid_full, v.xmid, v.idx, forced_idx ? forced_idx + idx_off : nullptr,
                                 kept_idx_out ? kept_idx_out + idx_off : nullptr,
-                                scores_out ? scores_out + sc_off : nullptr, sc.fused[di] ? v.fw : nullptr, s, &ln2);
+                                scores_out ? scores_out + sc_off : nullptr, sc.fused[di] ? v.fw : nullptr, s, &ln2, true);
       idx_off += (size_t)B * k;
       sc_off += (size_t)B * (Ta - 1);
     }

@@ -229,6 +229,71 @@ def test_sgd_update_and_second_step(hip, orc64, dtype, mu, wd):
             assert np.array_equal(t.cpu().numpy(), p[n].astype(np.float32)), n
 
 
+@pytest.mark.parametrize("name,over", [("c2_deit_s", dict(batch=8)), ("mini_4blk", {}), ("mini_moe", {}),
+                                       ("c2_deit_s", dict(batch=8, fuse_dropped=True))])
+def test_pipelined_steps_give_the_same_bits(hip, name, over):
+    """The frozen prefix reads frozen weights only (Fig. 2), so the frozen forward of batch i+1 may run on a second
+    stream beside the trainable part and the SGD step of batch i.  Five steps over three different batches, one
+    step after the other and pipelined over two streams with two x buffers: the same losses and the same
+    weights, bit for bit."""
+    import torch
+    import paper_2405_10951_amd as P
+    cfg = S.get_config(name, dtype="bf16", **over)
+    batch = cfg["batch"]
+    params = S.make_params(cfg, std=0.05)
+    data = []
+    for seed in (1, 2, 3):
+        x, y = S.make_inputs(cfg, seed=seed)
+        data.append((torch.as_tensor(x).cuda().to(torch.bfloat16).contiguous(), torch.as_tensor(y, dtype=torch.int32).cuda()))
+    steps = 5
+
+    def run(pipelined):
+        ctx = P.Context(cfg, params, batch)
+        grads = ctx.new_grads()
+        mom = {n: torch.zeros_like(g) for n, g in grads.items()}
+        xf = [torch.empty((batch, ctx.T_f, cfg["dim"]), dtype=torch.bfloat16, device="cuda") for _ in range(2)]
+        losses = torch.zeros((steps, 4), dtype=torch.float32, device="cuda")
+
+        def train(i):
+            ctx.bsr_train_blocks_fwd_bwd(xf[i % 2], data[i % 3][1], grads, loss_out=losses[i])
+            ctx.bsr_sgd_step(grads, mom, lr=0.05, momentum=0.9, weight_decay=1e-4)
+
+        if not pipelined:
+            for i in range(steps):
+                ctx.bsr_forward_frozen(data[i % 3][0], x_out=xf[i % 2])
+                train(i)
+        else:
+            cur = torch.cuda.current_stream()
+            sa, sb = torch.cuda.Stream(), torch.cuda.Stream()
+            sa.wait_stream(cur); sb.wait_stream(cur)
+            ready, free = [None, None], [None, None]
+            with torch.cuda.stream(sa):
+                ctx.bsr_forward_frozen(data[0][0], x_out=xf[0])
+                ready[0] = sa.record_event()
+            for i in range(steps):
+                j = (i + 1) % 2
+                if i + 1 < steps:
+                    with torch.cuda.stream(sa):
+                        if free[j] is not None:
+                            sa.wait_event(free[j])
+                        ctx.bsr_forward_frozen(data[(i + 1) % 3][0], x_out=xf[j])
+                        ready[j] = sa.record_event()
+                with torch.cuda.stream(sb):
+                    sb.wait_event(ready[i % 2])
+                    train(i)
+                    free[i % 2] = sb.record_event()
+            cur.wait_stream(sa); cur.wait_stream(sb)
+        torch.cuda.synchronize()
+        return losses[:, 0].cpu().numpy(), {n: t.cpu().numpy().copy() for n, t in ctx.params.items()}
+
+    l_seq, p_seq = run(False)
+    l_pipe, p_pipe = run(True)
+    assert np.all(np.isfinite(l_seq)) and len(set(l_seq.tolist())) > 1
+    assert np.array_equal(l_seq, l_pipe), (l_seq, l_pipe)
+    for n in p_seq:
+        assert np.array_equal(p_seq[n], p_pipe[n]), n
+
+
 @pytest.mark.parametrize("name,dtype", [("mini_4blk", "fp32"), ("mini_4blk", "bf16"), ("mini_moe", "bf16"),
                                         ("mini_interleaved", "fp32")])
 def test_adamw_update_and_next_step(hip, orc64, name, dtype):
