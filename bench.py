@@ -95,15 +95,23 @@ def time_steps(ctx, cfg, batch, steps, warmup, profile_steps=0, autotune=True, p
         return dict(wall_s=wall, ms_per_step=1e3 * wall / steps, ms_per_step_events=e0.elapsed_time(e1) / steps)
 
     seq = timed(run_sequential)
-    has_prefix = (cfg.get("trainable_blocks") or [cfg["first_trainable"]])[0] > 0
-    best = timed(run_pipelined) if pipeline and has_prefix else seq
     prof = None
-    if profile_steps:          # per-launch event brackets, one step after the other (alone on the GPU)
+    if profile_steps:          # per-launch event brackets, one step after the other (a launch alone on the GPU)
         ctx.bsr_profile_begin()
         run_sequential(profile_steps)
         prof = ctx.bsr_profile_end()
         prof = {k: (v[0] / profile_steps, v[1] / profile_steps, v[2] // profile_steps) for k, v in prof.items()}
-    return dict(best, pipelined=best is not seq, sequential=seq, loss=float(loss[0].item()), prof=prof, tuned=tuned)
+    has_prefix = (cfg.get("trainable_blocks") or [cfg["first_trainable"]])[0] > 0
+    best, tuned_overlapped = seq, None
+    if pipeline and has_prefix:
+        if autotune:           # tile shapes chosen again, now with the two parts of the step side by side
+            torch.cuda.synchronize()
+            with torch.cuda.stream(s_frozen):
+                tuned_overlapped = ctx.bsr_autotune_overlapped(xin, lab, x_f[0], x_f[1], loss, grads, s_train)
+            torch.cuda.synchronize()
+        best = timed(run_pipelined)
+    return dict(best, pipelined=best is not seq, sequential=seq, loss=float(loss[0].item()), prof=prof, tuned=tuned,
+                tuned_overlapped=tuned_overlapped)
 
 
 def cpu_baseline(cfg, sample_batch):
@@ -216,6 +224,8 @@ def main():
         "images_per_sec_sequential": batch * args.steps / r["sequential"]["wall_s"],
         "loss": r["loss"],
         "tile_autotune": None if r["tuned"] is None else {"launches": r["tuned"][0], "differ_from_cost_model": r["tuned"][1]},
+        "tile_autotune_overlapped": None if r["tuned_overlapped"] is None else
+        {"launches": r["tuned_overlapped"][0], "differ_from_cost_model": r["tuned_overlapped"][1]},
         "roofline": {"bound": "mfma", "kernel": "GEMM launches of the step (forward, dgrad, wgrad)",
                      "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak,
                      "traffic": None, "launches_per_step": gemm_n, "ms_per_step": gemm_ms,

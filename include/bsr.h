@@ -245,6 +245,21 @@ int32_t bsr_train_blocks_fwd_bwd(bsr_ctx* ctx, const void* x_in, const int32_t* 
 int32_t bsr_autotune(bsr_ctx* ctx, const void* input, const int32_t* labels, int32_t B, void* x_frozen,
                      float* loss_out, const bsr_params* grads, int32_t* launches_out, int32_t* changed_out,
                      void* stream);
+/*
+ * The tile choice for the two-stream schedule (see the rule on concurrent calls at the top).  Shapes
+ * that are fastest alone on the GPU are not the ones that share it best, and side by side a launch
+ * cannot be judged by its own time, so this call times whole passes: the frozen prefix on `stream`,
+ * writing x_side (device act [B,T_f,D], a second buffer), beside the trainable part on `side_stream`,
+ * reading x_frozen, all launches with the shape under test; three passes per shape, over the shapes
+ * whose workgroups leave room for a second one on a compute unit.  The fastest shape is then used for
+ * every launch of a batch of size B.  The choice replaces the one of bsr_autotune (a context holds
+ * one).  BLOCKS until both streams have drained.
+ * Errors: as bsr_autotune; INVALID_ARG for a missing second buffer or stream; BAD_CONFIG when the
+ * model has no frozen prefix.
+ */
+int32_t bsr_autotune_overlapped(bsr_ctx* ctx, const void* input, const int32_t* labels, int32_t B, void* x_frozen,
+                                void* x_side, float* loss_out, const bsr_params* grads, int32_t* launches_out,
+                                int32_t* changed_out, void* stream, void* side_stream);
 
 /*
  * Routing of the mixture-of-experts blocks (Sec. 5.3), for tests and inspection.  Per token the K

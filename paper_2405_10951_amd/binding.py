@@ -68,7 +68,7 @@ def load_library():
     for name in ("bsr_token_schedule", "bsr_workspace_bytes", "bsr_init", "bsr_refresh_weights",
                  "bsr_forward_frozen", "bsr_select_tokens", "bsr_train_blocks_fwd_bwd",
                  "bsr_sgd_step", "bsr_destroy", "bsr_profile_begin", "bsr_profile_end", "bsr_moe_routing_io",
-                 "bsr_adamw_step", "bsr_saved_activation_bytes", "bsr_autotune"):
+                 "bsr_adamw_step", "bsr_saved_activation_bytes", "bsr_autotune", "bsr_autotune_overlapped"):
         getattr(lib, name).restype = C.c_int32
     lib.bsr_token_schedule.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
     lib.bsr_workspace_bytes.argtypes = [C.c_void_p, C.POINTER(C.c_size_t)]
@@ -89,6 +89,8 @@ def load_library():
                                    C.c_float, C.c_float, C.c_int32, C.c_void_p]
     lib.bsr_autotune.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
                                  C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.bsr_autotune_overlapped.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
+                                            C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
     lib.bsr_linear_forward.restype = C.c_int32
     lib.bsr_linear_forward.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
                                        C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
@@ -422,6 +424,16 @@ class Context:
         n, ch = C.c_int32(0), C.c_int32(0)
         self._chk(self.lib.bsr_autotune(self.ctx, _dp(inp), _dp(labels), C.c_int32(inp.shape[0]), _dp(x_frozen),
                                         _dp(loss_out), C.byref(gs), C.byref(n), C.byref(ch), self._stream()))
+        return int(n.value), int(ch.value)
+
+    def bsr_autotune_overlapped(self, inp, labels, x_frozen, x_side, loss_out, grads: dict, side_stream):
+        """Tile choice timed with the frozen prefix (current stream) beside the trainable part (side_stream, a
+        torch stream); -> (launches with a measured tile choice, how many differ from the cost model's)."""
+        gs = _params_struct(grads)
+        n, ch = C.c_int32(0), C.c_int32(0)
+        self._chk(self.lib.bsr_autotune_overlapped(self.ctx, _dp(inp), _dp(labels), C.c_int32(inp.shape[0]), _dp(x_frozen),
+                                                   _dp(x_side), _dp(loss_out), C.byref(gs), C.byref(n), C.byref(ch),
+                                                   self._stream(), C.c_void_p(side_stream.cuda_stream)))
         return int(n.value), int(ch.value)
 
     def bsr_adamw_step(self, grads: dict, exp_avg: dict, exp_avg_sq: dict, lr: float, beta1: float = 0.9,

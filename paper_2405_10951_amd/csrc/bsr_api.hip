@@ -100,6 +100,7 @@ struct Tune {
   size_t site = 0;                     // NT launches it has issued so far
   int cur_batch = 0;
   int cand = -1;                       // >= 0 while tuning: index of the shape every launch is forced to
+  int cand_train = -1;                 // >= 0: the trainable part is forced to this shape instead (two-stream tuning)
   std::vector<TuneRec> recs;
 };
 
@@ -457,8 +458,9 @@ TileChoice choose_tile(bsr_ctx* c, const GemmDesc& g, hipStream_t s) {
   Tune& t = c->tune;
   const size_t site = t.site++;
   if (t.cand >= 0) {
-    ch.tile = gemm_nt_tile_id(t.cand);
-    ch.rec = TuneRec{t.kind, t.cand, site, g.M, g.N, g.K, nullptr, nullptr};
+    const int cand = (t.kind == 1 && t.cand_train >= 0) ? t.cand_train : t.cand;
+    ch.tile = gemm_nt_tile_id(cand);
+    ch.rec = TuneRec{t.kind, cand, site, g.M, g.N, g.K, nullptr, nullptr};
     ch.timing = hipEventCreate(&ch.rec.start) == hipSuccess && hipEventCreate(&ch.rec.stop) == hipSuccess;
     if (ch.timing) (void)hipEventRecord(ch.rec.start, s);
   } else if (t.batch == t.cur_batch && site < t.pick[t.kind].size()) {
@@ -1147,10 +1149,122 @@ static int32_t optimizer_step(bsr_ctx* c, const bsr_params* grads, const bsr_par
   return check_hip(c, where);
 }
 
-int32_t bsr_autotune(bsr_ctx* c, const void* input, const int32_t* labels, int32_t B, void* x_frozen,
-                     float* loss_out, const bsr_params* grads, int32_t* launches_out, int32_t* changed_out,
-                     void* stream) {
-  if (!c) return fail(nullptr, BSR_ERR_INVALID_ARG, "ctx is NULL");
+// The two-stream schedule is not tuned launch by launch.  Side by side, a launch cannot be judged by its own
+// time: a shape whose workgroup fills the LDS of a CU is quick by itself and stalls whatever runs on the other
+// stream, and with the GPU always full it is the work per CU-second that counts, not how evenly one launch
+// alone fills the chip.  (Measured on the headline step: the per-launch best of all shapes timed alone gives
+// 2.13 ms pipelined, 192 x 128 forced everywhere 2.03 ms; per-launch event times taken side by side chose
+// worse than that, too.)  So the choice is one shape for all launches, among the shapes that leave room for a
+// second workgroup on a CU (two tile buffers of at most 80 KB; the shape id is [prefetch depth] BM BN in
+// decimal), and what is timed is a whole side-by-side pass.
+static bool shares_a_cu(int tile_id) {
+  const int bm = tile_id % 1000000 / 1000, bn = tile_id % 1000;
+  return (size_t)2 * (bm + bn) * 64 * sizeof(bf16) <= 80 * 1024;
+}
+
+static int32_t autotune_overlapped(bsr_ctx* c, const void* input, const int32_t* labels, int32_t B, void* x_frozen,
+                                   void* x_side, float* loss_out, const bsr_params* grads, int32_t* launches_out,
+                                   int32_t* changed_out, void* stream, void* side) {
+  hipStream_t s = (hipStream_t)stream, s2 = (hipStream_t)side;
+  Tune& t = c->tune;
+  t.batch = 0;
+  t.pick[0].clear();
+  t.pick[1].clear();
+  const int n = gemm_nt_tile_count();
+  hipEvent_t e0 = nullptr, e1 = nullptr, ej = nullptr;
+  if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess ||
+      hipEventCreateWithFlags(&ej, hipEventDisableTiming) != hipSuccess)
+    return fail(c, BSR_ERR_HIP, "bsr_autotune_overlapped: cannot create events");
+  int rc = BSR_OK;
+  // one pass: frozen prefix (shape f) on s beside the trainable part (shape tr) on s2; < 0: one after the other, untimed
+  auto pass = [&](int f, int tr, float* ms) {
+    t.cand = f;
+    t.cand_train = tr;
+    const bool side_by_side = f >= 0;
+    if (side_by_side) {
+      (void)hipEventRecord(e0, s);
+      (void)hipStreamWaitEvent(s2, e0, 0);
+    }
+    // side by side: three of each back to back, so that the two streams run next to each other for a while
+    // and the start and the end of the pass weigh less
+    for (int rep = 0; rep < (side_by_side ? 3 : 1) && rc == BSR_OK; ++rep) {
+      rc = bsr_forward_frozen(c, input, B, side_by_side ? x_side : x_frozen, nullptr, nullptr, nullptr, stream);
+      if (rc == BSR_OK)
+        rc = bsr_train_blocks_fwd_bwd(c, x_frozen, labels, B, loss_out, nullptr, nullptr, grads, nullptr, nullptr, nullptr,
+                                      side_by_side ? side : stream);
+    }
+    if (rc != BSR_OK) return;
+    if (!side_by_side) return;
+    (void)hipEventRecord(ej, s2);
+    (void)hipStreamWaitEvent(s, ej, 0);
+    (void)hipEventRecord(e1, s);
+    if (hipEventSynchronize(e1) != hipSuccess || hipEventElapsedTime(ms, e0, e1) != hipSuccess) rc = BSR_ERR_HIP;
+  };
+  float dummy = 0.f;
+  pass(-1, -1, &dummy);                                   // set-up; leaves a valid x_frozen
+  (void)hipStreamSynchronize(s);
+  std::vector<int> cands;
+  for (int j = 0; j < n; ++j)
+    if (shares_a_cu(gemm_nt_tile_id(j))) cands.push_back(j);
+  // the shape with the shortest pass, three tries each.  (Refining it into one shape for the prefix and another
+  // for the trainable part was tried: the passes differ by less than they scatter, and the refined pairs ran
+  // 4 - 6 % slower in the pipeline than the single shape.)
+  int both = -1;
+  float best = 0.f;
+  for (int round = 0; round < 3 && rc == BSR_OK; ++round)
+    for (int j : cands) {
+      float ms = 0.f;
+      pass(j, j, &ms);
+      if (rc != BSR_OK) break;
+      if (both < 0 || ms < best) { both = j; best = ms; }
+    }
+  const int fz = both, tr = both;
+  t.cand = -1;
+  t.cand_train = -1;
+  const bool synced = hipStreamSynchronize(s) == hipSuccess && hipStreamSynchronize(s2) == hipSuccess;
+  (void)hipEventDestroy(e0); (void)hipEventDestroy(e1); (void)hipEventDestroy(ej);
+  int launches = 0;
+  if (rc == BSR_OK && synced && fz >= 0 && tr >= 0) {
+    // the launch sites and their dimensions come from the records of the passes; their times are not used
+    size_t sites[2] = {0, 0};
+    for (const TuneRec& r : t.recs) sites[r.kind] = std::max(sites[r.kind], r.site + 1);
+    for (int k = 0; k < 2; ++k) {
+      t.pick[k].assign(sites[k], TunePick{0, 0, 0, 0});
+      for (const TuneRec& r : t.recs) {
+        if (r.kind != k) continue;
+        TunePick& p = t.pick[k][r.site];
+        p.M = r.M; p.N = r.N; p.K = r.K;
+        p.tile = gemm_nt_tile_id(k == 0 ? fz : tr);
+      }
+      launches += (int)sites[k];
+    }
+    t.batch = B;
+    const char* venv = getenv("BSR_TUNE_VERBOSE");
+    if (venv && venv[0] == '1')
+      fprintf(stderr, "bsr_autotune_overlapped: shape %d (%.3f ms per side-by-side pass of three)\n", gemm_nt_tile_id(both), best);
+  }
+  for (TuneRec& r : t.recs) {
+    (void)hipEventDestroy(r.start);
+    (void)hipEventDestroy(r.stop);
+  }
+  t.recs.clear();
+  if (rc != BSR_OK) return rc == BSR_ERR_HIP ? fail(c, BSR_ERR_HIP, "bsr_autotune_overlapped: event timing failed") : rc;
+  if (!synced) return fail(c, BSR_ERR_HIP, "bsr_autotune_overlapped: stream synchronisation failed");
+  if (launches_out) *launches_out = launches;
+  if (changed_out) {
+    int diff = 0;
+    for (int k = 0; k < 2; ++k)
+      for (const TunePick& p : t.pick[k]) diff += p.tile != 0 && p.tile != gemm_nt_model_tile(p.M, p.N, p.K);
+    *changed_out = diff;
+  }
+  return check_hip(c, "bsr_autotune_overlapped");
+}
+
+// Measured tile choice, launch by launch: the two calls follow each other on `stream`, once per shape (twice
+// over), every NT launch bracketed by events in its place in the step.
+static int32_t autotune(bsr_ctx* c, const void* input, const int32_t* labels, int32_t B, void* x_frozen,
+                        float* loss_out, const bsr_params* grads, int32_t* launches_out, int32_t* changed_out,
+                        void* stream) {
   hipStream_t s = (hipStream_t)stream;
   Tune& t = c->tune;
   t.batch = 0;
@@ -1216,6 +1330,24 @@ int32_t bsr_autotune(bsr_ctx* c, const void* input, const int32_t* labels, int32
     *changed_out = diff;
   }
   return check_hip(c, "bsr_autotune");
+}
+
+int32_t bsr_autotune(bsr_ctx* c, const void* input, const int32_t* labels, int32_t B, void* x_frozen,
+                     float* loss_out, const bsr_params* grads, int32_t* launches_out, int32_t* changed_out,
+                     void* stream) {
+  if (!c) return fail(nullptr, BSR_ERR_INVALID_ARG, "ctx is NULL");
+  return autotune(c, input, labels, B, x_frozen, loss_out, grads, launches_out, changed_out, stream);
+}
+
+int32_t bsr_autotune_overlapped(bsr_ctx* c, const void* input, const int32_t* labels, int32_t B, void* x_frozen,
+                                void* x_side, float* loss_out, const bsr_params* grads, int32_t* launches_out,
+                                int32_t* changed_out, void* stream, void* side_stream) {
+  if (!c) return fail(nullptr, BSR_ERR_INVALID_ARG, "ctx is NULL");
+  if (!aligned16(x_side) || x_side == x_frozen) return fail(c, BSR_ERR_INVALID_ARG, "x_side is NULL, misaligned or x_frozen itself");
+  if (!side_stream || side_stream == stream) return fail(c, BSR_ERR_INVALID_ARG, "side_stream must be a second stream");
+  if (c->sc.ft == 0)
+    return fail(c, BSR_ERR_BAD_CONFIG, "there is no frozen prefix to run beside the trainable part");
+  return autotune_overlapped(c, input, labels, B, x_frozen, x_side, loss_out, grads, launches_out, changed_out, stream, side_stream);
 }
 
 int32_t bsr_sgd_step(bsr_ctx* c, const bsr_params* grads, const bsr_params* momenta, float lr,

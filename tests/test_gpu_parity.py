@@ -392,6 +392,43 @@ def test_autotune_picks_tiles_without_changing_a_bit(hip, name, batch, launches_
     assert np.array_equal(other["logits"], ref2["logits"])
 
 
+def test_two_stream_tile_choice_changes_no_bit(hip):
+    """The tile choice of the two-stream schedule (whole side-by-side passes timed, one shape for every launch)
+    leaves the step's results as they were, and refuses what it cannot do."""
+    import torch
+    import paper_2405_10951_amd as P
+    cfg, p, x, y = bf16_setup("c2_deit_s", batch=8)
+    before = hip.run_hip_step(cfg, p, x, y)
+    ctx = before["ctx"]
+    dev = torch.device("cuda:0")
+    xin = torch.as_tensor(x).to(dev).to(ctx.act_dtype).contiguous()
+    lab = torch.as_tensor(y, dtype=torch.int32).to(dev)
+    x_f = [torch.empty((8, ctx.T_f, cfg["dim"]), dtype=ctx.act_dtype, device=dev) for _ in range(2)]
+    loss = torch.zeros(1, dtype=torch.float32, device=dev)
+    side = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    launches, changed = ctx.bsr_autotune_overlapped(xin, lab, x_f[0], x_f[1], loss, ctx.new_grads(), side)
+    assert launches > 0 and 0 <= changed <= launches
+    assert float(loss[0]) == before["loss"]
+    assert torch.equal(x_f[0], x_f[1])                       # both passes computed the same frozen prefix
+    after = hip.run_hip_step(cfg, p, x, y, ctx=ctx)
+    assert np.array_equal(after["logits"], before["logits"]) and after["loss"] == before["loss"]
+    for n, g in before["grads"].items():
+        assert np.array_equal(after["grads"][n], g), n
+    with pytest.raises(P.BsrError):                          # the second buffer must be another one
+        ctx.bsr_autotune_overlapped(xin, lab, x_f[0], x_f[0], loss, ctx.new_grads(), side)
+    with pytest.raises(P.BsrError):                          # and the second stream too
+        ctx.bsr_autotune_overlapped(xin, lab, x_f[0], x_f[1], loss, ctx.new_grads(), torch.cuda.current_stream())
+    full = S.get_config("mini_4blk", dtype="bf16", first_trainable=0)
+    pf = S.make_params(full)
+    c2 = P.Context(full, pf, full["batch"])
+    xi, yi = S.make_inputs(full)
+    xf2 = [torch.empty((full["batch"], c2.T_f, full["dim"]), dtype=c2.act_dtype, device=dev) for _ in range(2)]
+    with pytest.raises(P.BsrError):                          # no frozen prefix, nothing to overlap
+        c2.bsr_autotune_overlapped(torch.as_tensor(xi).to(dev).to(c2.act_dtype).contiguous(),
+                                   torch.as_tensor(yi, dtype=torch.int32).to(dev), xf2[0], xf2[1], loss, c2.new_grads(), side)
+
+
 # ------------------------------------------------------------------ the benchmark's own workload
 
 def test_headline_workload_full_size(hip, orc32):
