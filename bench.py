@@ -64,23 +64,11 @@ def time_steps(ctx, cfg, batch, steps, warmup, profile_steps=0, autotune=True, p
         cur = torch.cuda.current_stream()
         s_frozen.wait_stream(cur)
         s_train.wait_stream(cur)
-        ready = [None, None]        # x_f[j] holds the frozen output of a batch
-        free = [None, None]         # x_f[j] has been consumed
-        with torch.cuda.stream(s_frozen):
-            ctx.bsr_forward_frozen(xin, x_out=x_f[0])
-            ready[0] = s_frozen.record_event()
+        step = lambda inp, xn, xc: ctx.bsr_pipeline_step(inp, xn, xc, lab, loss, grads, mom, 1e-3, 0.9, 1e-4, s_frozen, s_train)
+        step(xin, x_f[0], None)                                    # prime: the frozen prefix of batch 0
         for i in range(n):
-            j = (i + 1) % 2
-            if i + 1 < n:
-                with torch.cuda.stream(s_frozen):
-                    if free[j] is not None:
-                        s_frozen.wait_event(free[j])
-                    ctx.bsr_forward_frozen(xin, x_out=x_f[j])
-                    ready[j] = s_frozen.record_event()
-            with torch.cuda.stream(s_train):
-                s_train.wait_event(ready[i % 2])
-                train(x_f[i % 2])
-                free[i % 2] = s_train.record_event()
+            last = i + 1 == n
+            step(None if last else xin, None if last else x_f[(i + 1) % 2], x_f[i % 2])
         cur.wait_stream(s_frozen)
         cur.wait_stream(s_train)
 

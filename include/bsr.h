@@ -290,6 +290,29 @@ int32_t bsr_sgd_step(bsr_ctx* ctx, const bsr_params* grads, const bsr_params* mo
                      float momentum, float weight_decay, void* stream);
 
 /*
+ * One step of the two-stream pipeline (see the rule on concurrent calls at the top; Fig. 2: the frozen
+ * prefix depends on frozen weights only).  Enqueues
+ *   on stream_frozen: bsr_forward_frozen(input_next) -> x_next            (the NEXT batch)
+ *   on stream_train:  bsr_train_blocks_fwd_bwd(x_cur, labels_cur) and bsr_sgd_step   (the CURRENT batch)
+ * and the events that order them: the trainable part waits until the call that named its x_cur as
+ * x_next has filled it, and a frozen prefix waits until the trainable part that last read its x_next
+ * is done.  The context owns these events (one pair per x buffer it has seen, at most 8 buffers).
+ *   input_next, x_next  as input / x_out of bsr_forward_frozen; both NULL on the last step
+ *   x_cur               the x_next of an earlier call; NULL on the first call (which only primes)
+ *   the other arguments as for bsr_train_blocks_fwd_bwd and bsr_sgd_step
+ * A loop over batches 0..n-1 with two buffers x[2] is: step(in[0], x[0], NULL); then for i = 0..n-1:
+ * step(i+1 < n ? in[i+1] : NULL, i+1 < n ? x[(i+1)%2] : NULL, x[i%2], labels[i]).  The results are
+ * those of the three calls issued one after the other, bit for bit.  The caller joins both streams
+ * before it reads loss, gradients or weights.
+ * Errors: INVALID_ARG (x_cur never filled, one stream given twice, x_next == x_cur, ...), BAD_CONFIG
+ * (no frozen prefix), HIP, and those of the three entry points.
+ */
+int32_t bsr_pipeline_step(bsr_ctx* ctx, const void* input_next, void* x_next, const void* x_cur,
+                          const int32_t* labels_cur, int32_t B, float* loss_out, const bsr_params* grads,
+                          const bsr_params* momenta, float lr, float momentum, float weight_decay,
+                          void* stream_frozen, void* stream_train);
+
+/*
  * AdamW update of the trainable tensors (the optimiser of the paper's DeiT-S runs, Sec. 5), in place:
  *   m = beta1 m + (1-beta1) g;  v = beta2 v + (1-beta2) g^2;
  *   w -= lr * ( (m / (1-beta1^step)) / (sqrt(v / (1-beta2^step)) + eps) + weight_decay * w )

@@ -68,7 +68,8 @@ def load_library():
     for name in ("bsr_token_schedule", "bsr_workspace_bytes", "bsr_init", "bsr_refresh_weights",
                  "bsr_forward_frozen", "bsr_select_tokens", "bsr_train_blocks_fwd_bwd",
                  "bsr_sgd_step", "bsr_destroy", "bsr_profile_begin", "bsr_profile_end", "bsr_moe_routing_io",
-                 "bsr_adamw_step", "bsr_saved_activation_bytes", "bsr_autotune", "bsr_autotune_overlapped"):
+                 "bsr_adamw_step", "bsr_saved_activation_bytes", "bsr_autotune", "bsr_autotune_overlapped",
+                 "bsr_pipeline_step"):
         getattr(lib, name).restype = C.c_int32
     lib.bsr_token_schedule.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
     lib.bsr_workspace_bytes.argtypes = [C.c_void_p, C.POINTER(C.c_size_t)]
@@ -91,6 +92,8 @@ def load_library():
                                  C.c_void_p, C.c_void_p, C.c_void_p]
     lib.bsr_autotune_overlapped.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
                                             C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.bsr_pipeline_step.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p,
+                                      C.c_void_p, C.c_void_p, C.c_float, C.c_float, C.c_float, C.c_void_p, C.c_void_p]
     lib.bsr_linear_forward.restype = C.c_int32
     lib.bsr_linear_forward.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
                                        C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
@@ -425,6 +428,19 @@ class Context:
         self._chk(self.lib.bsr_autotune(self.ctx, _dp(inp), _dp(labels), C.c_int32(inp.shape[0]), _dp(x_frozen),
                                         _dp(loss_out), C.byref(gs), C.byref(n), C.byref(ch), self._stream()))
         return int(n.value), int(ch.value)
+
+    def bsr_pipeline_step(self, inp_next, x_next, x_cur, labels_cur, loss_out, grads: dict, momenta: dict | None, lr: float,
+                          momentum: float, weight_decay: float, stream_frozen, stream_train):
+        """Frozen prefix of the next batch (inp_next -> x_next, both None on the last step) on stream_frozen beside
+        the trainable part + SGD step of the current batch (x_cur, None on the first call) on stream_train
+        (two torch streams)."""
+        gs = _params_struct(grads)
+        ms = _params_struct(momenta) if momenta is not None else None
+        B = (inp_next if inp_next is not None else x_cur).shape[0]
+        self._chk(self.lib.bsr_pipeline_step(self.ctx, _dp(inp_next), _dp(x_next), _dp(x_cur), _dp(labels_cur), C.c_int32(B),
+                                             _dp(loss_out), C.byref(gs), C.byref(ms) if ms is not None else None,
+                                             C.c_float(lr), C.c_float(momentum), C.c_float(weight_decay),
+                                             C.c_void_p(stream_frozen.cuda_stream), C.c_void_p(stream_train.cuda_stream)))
 
     def bsr_autotune_overlapped(self, inp, labels, x_frozen, x_side, loss_out, grads: dict, side_stream):
         """Tile choice timed with the frozen prefix (current stream) beside the trainable part (side_stream, a

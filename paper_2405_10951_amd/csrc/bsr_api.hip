@@ -108,6 +108,9 @@ struct bsr_ctx {
   Tune tune;
   TnChain tn_chain;            // split-K reduction of the latest weight gradient, folded into the next one's launch
   std::vector<ProfRec> prof;   // event pairs of the profiling mode (bsr_profile_begin / _end)
+  // bsr_pipeline_step: per x buffer, "the frozen prefix has filled it" and "the trainable part has read it"
+  struct PipeSlot { const void* x; hipEvent_t ready, free; bool has_ready, has_free; };
+  std::vector<PipeSlot> pipe;
   size_t prof_used = 0;
   bool prof_on = false;
   bsr_config cfg;
@@ -1367,6 +1370,60 @@ int32_t bsr_sgd_step(bsr_ctx* c, const bsr_params* grads, const bsr_params* mome
   return optimizer_step(c, grads, momentum > 0.f ? momenta : nullptr, nullptr, o, (hipStream_t)stream, "bsr_sgd_step");
 }
 
+// One step of the two-stream pipeline (the rule on concurrent calls in the header): the frozen prefix of the
+// next batch on stream_frozen, the trainable part and the SGD step of the current batch on stream_train, and
+// the events that order the producer and the consumer of every x buffer.
+int32_t bsr_pipeline_step(bsr_ctx* c, const void* input_next, void* x_next, const void* x_cur, const int32_t* labels_cur,
+                          int32_t B, float* loss_out, const bsr_params* grads, const bsr_params* momenta, float lr,
+                          float momentum, float weight_decay, void* stream_frozen, void* stream_train) {
+  if (!c) return fail(nullptr, BSR_ERR_INVALID_ARG, "ctx is NULL");
+  if ((input_next == nullptr) != (x_next == nullptr)) return fail(c, BSR_ERR_INVALID_ARG, "input_next and x_next go together");
+  if (!x_next && !x_cur) return fail(c, BSR_ERR_INVALID_ARG, "nothing to do: neither a next batch nor a current one");
+  if (x_next && x_next == x_cur) return fail(c, BSR_ERR_INVALID_ARG, "x_next and x_cur must be two buffers");
+  if (stream_frozen == stream_train) return fail(c, BSR_ERR_INVALID_ARG, "the pipeline needs two streams");
+  if (c->sc.ft == 0) return fail(c, BSR_ERR_BAD_CONFIG, "there is no frozen prefix to run ahead");
+  auto slot_of = [&](const void* x) -> bsr_ctx::PipeSlot* {
+    for (auto& p : c->pipe)
+      if (p.x == x) return &p;
+    if (c->pipe.size() >= 8) return nullptr;
+    bsr_ctx::PipeSlot p{x, nullptr, nullptr, false, false};
+    if (hipEventCreateWithFlags(&p.ready, hipEventDisableTiming) != hipSuccess) return nullptr;
+    if (hipEventCreateWithFlags(&p.free, hipEventDisableTiming) != hipSuccess) { (void)hipEventDestroy(p.ready); return nullptr; }
+    c->pipe.push_back(p);
+    return &c->pipe.back();
+  };
+  hipStream_t sf = (hipStream_t)stream_frozen, st = (hipStream_t)stream_train;
+  bsr_ctx::PipeSlot* cur = nullptr;
+  if (x_cur) {
+    for (auto& p : c->pipe)
+      if (p.x == x_cur) cur = &p;
+    if (!cur || !cur->has_ready) return fail(c, BSR_ERR_INVALID_ARG, "x_cur has not been filled by an earlier bsr_pipeline_step");
+  }
+  int32_t rc = BSR_OK;
+  if (x_next) {
+    const size_t cur_index = cur ? (size_t)(cur - c->pipe.data()) : 0;
+    bsr_ctx::PipeSlot* nx = slot_of(x_next);
+    if (!nx) return fail(c, BSR_ERR_HIP, "bsr_pipeline_step: more than 8 x buffers, or no event to be had");
+    if (cur) cur = &c->pipe[cur_index];                   // the table may have moved
+    if (nx->has_free) (void)hipStreamWaitEvent(sf, nx->free, 0);     // its previous reader is done
+    rc = bsr_forward_frozen(c, input_next, B, x_next, nullptr, nullptr, nullptr, stream_frozen);
+    if (rc != BSR_OK) return rc;
+    (void)hipEventRecord(nx->ready, sf);
+    nx->has_ready = true;
+    nx->has_free = false;
+  }
+  if (cur) {
+    (void)hipStreamWaitEvent(st, cur->ready, 0);
+    rc = bsr_train_blocks_fwd_bwd(c, x_cur, labels_cur, B, loss_out, nullptr, nullptr, grads, nullptr, nullptr, nullptr, stream_train);
+    if (rc == BSR_OK) rc = bsr_sgd_step(c, grads, momenta, lr, momentum, weight_decay, stream_train);
+    if (rc != BSR_OK) return rc;
+    (void)hipEventRecord(cur->free, st);
+    cur->has_free = true;
+    cur->has_ready = false;
+  }
+  return check_hip(c, "bsr_pipeline_step");
+}
+
 int32_t bsr_adamw_step(bsr_ctx* c, const bsr_params* grads, const bsr_params* exp_avg, const bsr_params* exp_avg_sq,
                        float lr, float beta1, float beta2, float eps, float weight_decay, int32_t step,
                        void* stream) {
@@ -1525,6 +1582,7 @@ int32_t bsr_profile_end(bsr_ctx* c, double* ms, double* flops, int32_t* launches
 int32_t bsr_destroy(bsr_ctx* c) {
   if (c) {
     for (ProfRec& r : c->prof) { (void)hipEventDestroy(r.start); (void)hipEventDestroy(r.stop); }
+    for (auto& p : c->pipe) { (void)hipEventDestroy(p.ready); (void)hipEventDestroy(p.free); }
   }
   delete c;
   return BSR_OK;

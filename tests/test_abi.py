@@ -178,5 +178,6 @@ def test_null_context_is_rejected_before_any_gpu_work():
     lib = P.load_library()
     assert lib.bsr_autotune(None, None, None, 1, None, None, None, None, None, None) == -1
     assert lib.bsr_autotune_overlapped(None, None, None, 1, None, None, None, None, None, None, None, None) == -1
+    assert lib.bsr_pipeline_step(None, None, None, None, None, 1, None, None, None, 0.0, 0.0, 0.0, None, None) == -1
     assert lib.bsr_adamw_step(None, None, None, None, 0.0, 0.9, 0.999, 1e-8, 0.0, 1, None) == -1
     assert lib.bsr_sgd_step(None, None, None, 0.0, 0.0, 0.0, None) == -1

@@ -234,8 +234,8 @@ def test_sgd_update_and_second_step(hip, orc64, dtype, mu, wd):
 def test_pipelined_steps_give_the_same_bits(hip, name, over):
     """The frozen prefix reads frozen weights only (Fig. 2), so the frozen forward of batch i+1 may run on a second
     stream beside the trainable part and the SGD step of batch i.  Five steps over three different batches, one
-    step after the other and pipelined over two streams with two x buffers: the same losses and the same
-    weights, bit for bit."""
+    step after the other and pipelined over two streams with two x buffers (once with the caller's own events,
+    once through bsr_pipeline_step): the same losses and the same weights, bit for bit."""
     import torch
     import paper_2405_10951_amd as P
     cfg = S.get_config(name, dtype="bf16", **over)
@@ -266,32 +266,41 @@ def test_pipelined_steps_give_the_same_bits(hip, name, over):
             cur = torch.cuda.current_stream()
             sa, sb = torch.cuda.Stream(), torch.cuda.Stream()
             sa.wait_stream(cur); sb.wait_stream(cur)
-            ready, free = [None, None], [None, None]
-            with torch.cuda.stream(sa):
-                ctx.bsr_forward_frozen(data[0][0], x_out=xf[0])
-                ready[0] = sa.record_event()
-            for i in range(steps):
-                j = (i + 1) % 2
-                if i + 1 < steps:
-                    with torch.cuda.stream(sa):
-                        if free[j] is not None:
-                            sa.wait_event(free[j])
-                        ctx.bsr_forward_frozen(data[(i + 1) % 3][0], x_out=xf[j])
-                        ready[j] = sa.record_event()
-                with torch.cuda.stream(sb):
-                    sb.wait_event(ready[i % 2])
-                    train(i)
-                    free[i % 2] = sb.record_event()
+            if pipelined == "caller":          # the caller's own events
+                ready, free = [None, None], [None, None]
+                with torch.cuda.stream(sa):
+                    ctx.bsr_forward_frozen(data[0][0], x_out=xf[0])
+                    ready[0] = sa.record_event()
+                for i in range(steps):
+                    j = (i + 1) % 2
+                    if i + 1 < steps:
+                        with torch.cuda.stream(sa):
+                            if free[j] is not None:
+                                sa.wait_event(free[j])
+                            ctx.bsr_forward_frozen(data[(i + 1) % 3][0], x_out=xf[j])
+                            ready[j] = sa.record_event()
+                    with torch.cuda.stream(sb):
+                        sb.wait_event(ready[i % 2])
+                        train(i)
+                        free[i % 2] = sb.record_event()
+            else:                              # bsr_pipeline_step orders the buffers itself
+                args = dict(grads=grads, momenta=mom, lr=0.05, momentum=0.9, weight_decay=1e-4, stream_frozen=sa, stream_train=sb)
+                ctx.bsr_pipeline_step(data[0][0], xf[0], None, None, losses[0], **args)
+                for i in range(steps):
+                    last = i + 1 == steps
+                    ctx.bsr_pipeline_step(None if last else data[(i + 1) % 3][0], None if last else xf[(i + 1) % 2],
+                                          xf[i % 2], data[i % 3][1], losses[i], **args)
             cur.wait_stream(sa); cur.wait_stream(sb)
         torch.cuda.synchronize()
         return losses[:, 0].cpu().numpy(), {n: t.cpu().numpy().copy() for n, t in ctx.params.items()}
 
     l_seq, p_seq = run(False)
-    l_pipe, p_pipe = run(True)
     assert np.all(np.isfinite(l_seq)) and len(set(l_seq.tolist())) > 1
-    assert np.array_equal(l_seq, l_pipe), (l_seq, l_pipe)
-    for n in p_seq:
-        assert np.array_equal(p_seq[n], p_pipe[n]), n
+    for how in ("caller", "bsr_pipeline_step"):
+        l_pipe, p_pipe = run(how)
+        assert np.array_equal(l_seq, l_pipe), (how, l_seq, l_pipe)
+        for n in p_seq:
+            assert np.array_equal(p_seq[n], p_pipe[n]), (how, n)
 
 
 @pytest.mark.parametrize("name,dtype", [("mini_4blk", "fp32"), ("mini_4blk", "bf16"), ("mini_moe", "bf16"),
