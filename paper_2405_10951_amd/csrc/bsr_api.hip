@@ -1155,7 +1155,7 @@ static int32_t optimizer_step(bsr_ctx* c, const bsr_params* grads, const bsr_par
 // The two-stream schedule is not tuned launch by launch.  Side by side, a launch cannot be judged by its own
 // time: a shape whose workgroup fills the LDS of a CU is quick by itself and stalls whatever runs on the other
 // stream, and with the GPU always full it is the work per CU-second that counts, not how evenly one launch
-// alone fills the chip.  (Measured on the headline step: the per-launch best of all shapes timed alone gives
+// alone fills the chip.  (Measured on a ViT-B/16 step, batch 32: the per-launch best of all shapes timed alone gives
 // 2.13 ms pipelined, 192 x 128 forced everywhere 2.03 ms; per-launch event times taken side by side chose
 // worse than that, too.)  So the choice is one shape for all launches, among the shapes that leave room for a
 // second workgroup on a CU (two tile buffers of at most 80 KB; the shape id is [prefetch depth] BM BN in
