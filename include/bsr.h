@@ -248,12 +248,14 @@ int32_t bsr_autotune(bsr_ctx* ctx, const void* input, const int32_t* labels, int
 /*
  * The tile choice for the two-stream schedule (see the rule on concurrent calls at the top).  Shapes
  * that are fastest alone on the GPU are not the ones that share it best, and side by side a launch
- * cannot be judged by its own time, so this call times whole passes: the frozen prefix on `stream`,
- * writing x_side (device act [B,T_f,D], a second buffer), beside the trainable part on `side_stream`,
- * reading x_frozen, all launches with the shape under test; three passes per shape, over the shapes
- * whose workgroups leave room for a second one on a compute unit.  The fastest shape is then used for
- * every launch of a batch of size B.  The choice replaces the one of bsr_autotune (a context holds
- * one).  BLOCKS until both streams have drained.
+ * cannot be judged by its own time, so this call times short runs of the pipeline itself: six
+ * iterations, the frozen prefix on `stream` (writing x_side, device act [B,T_f,D], a second buffer) one
+ * iteration ahead of the trainable part on `side_stream` (reading x_frozen), ordered as
+ * bsr_pipeline_step orders them, every launch with the shape under test; in place of the optimizer
+ * step the bf16 copies of the trainable weights are rebuilt (no weight changes).  Three runs per shape,
+ * over the shapes whose workgroups leave room for a second one on a compute unit.  The fastest shape
+ * is then used for every launch of a batch of size B.  The choice replaces the one of bsr_autotune (a
+ * context holds one).  BLOCKS until both streams have drained.
  * Errors: as bsr_autotune; INVALID_ARG for a missing second buffer or stream; BAD_CONFIG when the
  * model has no frozen prefix.
  */

@@ -1174,30 +1174,52 @@ static int32_t autotune_overlapped(bsr_ctx* c, const void* input, const int32_t*
   t.pick[0].clear();
   t.pick[1].clear();
   const int n = gemm_nt_tile_count();
-  hipEvent_t e0 = nullptr, e1 = nullptr, ej = nullptr;
-  if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess ||
-      hipEventCreateWithFlags(&ej, hipEventDisableTiming) != hipSuccess)
-    return fail(c, BSR_ERR_HIP, "bsr_autotune_overlapped: cannot create events");
+  hipEvent_t e0 = nullptr, e1 = nullptr, ej = nullptr, ready[2] = {nullptr, nullptr}, done[2] = {nullptr, nullptr};
+  bool ok = hipEventCreate(&e0) == hipSuccess && hipEventCreate(&e1) == hipSuccess &&
+            hipEventCreateWithFlags(&ej, hipEventDisableTiming) == hipSuccess;
+  for (int i = 0; i < 2 && ok; ++i)
+    ok = hipEventCreateWithFlags(&ready[i], hipEventDisableTiming) == hipSuccess &&
+         hipEventCreateWithFlags(&done[i], hipEventDisableTiming) == hipSuccess;
+  auto drop_events = [&]() {
+    for (hipEvent_t e : {e0, e1, ej, ready[0], ready[1], done[0], done[1]})
+      if (e) (void)hipEventDestroy(e);
+  };
+  if (!ok) { drop_events(); return fail(c, BSR_ERR_HIP, "bsr_autotune_overlapped: cannot create events"); }
   int rc = BSR_OK;
-  // one pass: frozen prefix (shape f) on s beside the trainable part (shape tr) on s2; < 0: one after the other, untimed
+  // One pass.  f < 0: the two calls one after the other on `stream`, untimed.  Otherwise a short run of the
+  // pipeline itself with every launch forced to its shape: the frozen prefix (shape f) of iteration k+1 on s
+  // beside the trainable part (shape tr) of iteration k on s2, ordered as bsr_pipeline_step orders them with
+  // two x buffers (the prefix may run one iteration ahead), and in place of the optimizer step, which a
+  // tuning pass must not take, the rebuild of the trainable blocks' bf16 weight copies: the same matrices
+  // read and rewritten, bound by memory like the update.  The prefix writes x_side every time; the trainable
+  // part reads x_frozen, which the untimed pass has left.
+  constexpr int ITER = 6;
   auto pass = [&](int f, int tr, float* ms) {
     t.cand = f;
     t.cand_train = tr;
-    const bool side_by_side = f >= 0;
-    if (side_by_side) {
-      (void)hipEventRecord(e0, s);
-      (void)hipStreamWaitEvent(s2, e0, 0);
-    }
-    // side by side: three of each back to back, so that the two streams run next to each other for a while
-    // and the start and the end of the pass weigh less
-    for (int rep = 0; rep < (side_by_side ? 3 : 1) && rc == BSR_OK; ++rep) {
-      rc = bsr_forward_frozen(c, input, B, side_by_side ? x_side : x_frozen, nullptr, nullptr, nullptr, stream);
+    if (f < 0) {
+      rc = bsr_forward_frozen(c, input, B, x_frozen, nullptr, nullptr, nullptr, stream);
       if (rc == BSR_OK)
-        rc = bsr_train_blocks_fwd_bwd(c, x_frozen, labels, B, loss_out, nullptr, nullptr, grads, nullptr, nullptr, nullptr,
-                                      side_by_side ? side : stream);
+        rc = bsr_train_blocks_fwd_bwd(c, x_frozen, labels, B, loss_out, nullptr, nullptr, grads, nullptr, nullptr, nullptr, stream);
+      return;
+    }
+    (void)hipEventRecord(e0, s);
+    (void)hipStreamWaitEvent(s2, e0, 0);
+    rc = bsr_forward_frozen(c, input, B, x_side, nullptr, nullptr, nullptr, stream);           // iteration 0's prefix
+    (void)hipEventRecord(ready[0], s);
+    for (int k = 0; k < ITER && rc == BSR_OK; ++k) {
+      if (k + 1 < ITER) {
+        if (k >= 1) (void)hipStreamWaitEvent(s, done[(k + 1) % 2], 0);     // the reader of that buffer, two iterations back
+        rc = bsr_forward_frozen(c, input, B, x_side, nullptr, nullptr, nullptr, stream);
+        (void)hipEventRecord(ready[(k + 1) % 2], s);
+        if (rc != BSR_OK) break;
+      }
+      (void)hipStreamWaitEvent(s2, ready[k % 2], 0);
+      rc = bsr_train_blocks_fwd_bwd(c, x_frozen, labels, B, loss_out, nullptr, nullptr, grads, nullptr, nullptr, nullptr, side);
+      build_shadows(c, c->sc.ft, s2);
+      (void)hipEventRecord(done[k % 2], s2);
     }
     if (rc != BSR_OK) return;
-    if (!side_by_side) return;
     (void)hipEventRecord(ej, s2);
     (void)hipStreamWaitEvent(s, ej, 0);
     (void)hipEventRecord(e1, s);
@@ -1225,7 +1247,7 @@ static int32_t autotune_overlapped(bsr_ctx* c, const void* input, const int32_t*
   t.cand = -1;
   t.cand_train = -1;
   const bool synced = hipStreamSynchronize(s) == hipSuccess && hipStreamSynchronize(s2) == hipSuccess;
-  (void)hipEventDestroy(e0); (void)hipEventDestroy(e1); (void)hipEventDestroy(ej);
+  drop_events();
   int launches = 0;
   if (rc == BSR_OK && synced && fz >= 0 && tr >= 0) {
     // the launch sites and their dimensions come from the records of the passes; their times are not used
@@ -1244,7 +1266,7 @@ static int32_t autotune_overlapped(bsr_ctx* c, const void* input, const int32_t*
     t.batch = B;
     const char* venv = getenv("BSR_TUNE_VERBOSE");
     if (venv && venv[0] == '1')
-      fprintf(stderr, "bsr_autotune_overlapped: shape %d (%.3f ms per side-by-side pass of three)\n", gemm_nt_tile_id(both), best);
+      fprintf(stderr, "bsr_autotune_overlapped: shape %d (%.3f ms per pipelined pass of six)\n", gemm_nt_tile_id(both), best);
   }
   for (TuneRec& r : t.recs) {
     (void)hipEventDestroy(r.start);
