@@ -86,6 +86,7 @@ void gemm_mfma_pair(const GemmDesc& nt, const GemmDesc& tn, float* splitk_ws, si
 int gemm_nt_tile_count();
 int gemm_nt_model_tile(int M, int N, int K);   // the built-in model's choice
 int gemm_nt_tile_id(int i);
+size_t gemm_nt_tile_lds_bytes(int id);          // dynamic LDS a workgroup of that shape holds
 bool gemm_nt_tile_is_free(const GemmDesc& g);
 size_t gemm_splitk_ws_floats(int dim, int mlp_hidden);
 

@@ -16,6 +16,7 @@
 #include <stdlib.h>
 
 #include <algorithm>
+#include <utility>
 
 #include "bsr_internal.h"
 
@@ -69,6 +70,57 @@ __device__ inline int xcd_remap(int pid, int nblocks) {
   return x * base + min(x, rem) + local;
 }
 
+// Eight consecutive columns of output row m, accumulated in fp32: the statistics of a folded LayerNorm, bias,
+// positional embedding (with the row remap of the patch embedding), GELU with its stored pre-activation or
+// GELU', the residual, and the store (16 bytes of bf16, or 32 bytes of fp32).
+__device__ __forceinline__ void finish8(const GemmDesc& g, float (&v)[8], int m, int col, const float (&bias)[8],
+                                        const float (&cs)[8], const float2* st) {
+  if (st) {
+    const float2 ms = *st;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) v[j] = ms.y * fmaf(-ms.x, cs[j], v[j]);
+  }
+#pragma unroll
+  for (int j = 0; j < 8; ++j) v[j] += bias[j];
+  int64_t row = m;
+  if (g.remap_np > 0) {
+    row = (int64_t)m + m / g.remap_np + 1;
+    const float* pr = g.pos + (int64_t)(m % g.remap_np + 1) * g.N + col;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) v[j] += pr[j];
+  }
+  const int64_t off = row * g.ldc + col;
+  if (g.act == ACT_GELU) {
+    if (g.aux) {
+      bf16x8 u;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) u[j] = (bf16)v[j];
+      *(bf16x8*)((bf16*)g.aux + off) = u;
+    }
+#pragma unroll
+    for (int j = 0; j < 8; ++j) v[j] = gelu_f(v[j]);
+  } else if (g.act == ACT_GELU_BWD) {
+    const bf16x8 u = *(const bf16x8*)((const bf16*)g.aux + off);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) v[j] *= gelu_grad_f((float)u[j]);
+  }
+  if (g.out_f32) {
+    float* c = (float*)g.C + off;
+    *(float4*)c = make_float4(v[0], v[1], v[2], v[3]);
+    *(float4*)(c + 4) = make_float4(v[4], v[5], v[6], v[7]);
+  } else {
+    if (g.res) {
+      const bf16x8 rr = *(const bf16x8*)((const bf16*)g.res + off);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) v[j] += (float)rr[j];
+    }
+    bf16x8 o;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) o[j] = (bf16)v[j];
+    *(bf16x8*)((bf16*)g.C + off) = o;
+  }
+}
+
 // Epilogue of one wave tile.  The fp32 accumulators (element r of a 32x32 tile sits at row
 // 8*(r/4) + 4*(lane/32) + r%4, column lane%32) go through a per-wave LDS patch, 32 rows at a time,
 // and come back row-major so that each lane owns 8 consecutive columns of one row: bias, GELU,
@@ -109,50 +161,7 @@ __device__ __forceinline__ void epilogue(const GemmDesc& g, f32x16 (&acc)[MI][NI
       const float4 p0 = *(const float4*)(patch + lr * LDP + my_chunk * 8);
       const float4 p1 = *(const float4*)(patch + lr * LDP + my_chunk * 8 + 4);
       v[0] = p0.x; v[1] = p0.y; v[2] = p0.z; v[3] = p0.w; v[4] = p1.x; v[5] = p1.y; v[6] = p1.z; v[7] = p1.w;
-      if (rowstat) {
-        const float2 st = rowstat[mi * 32 + lr];
-#pragma unroll
-        for (int j = 0; j < 8; ++j) v[j] = st.y * fmaf(-st.x, cs[j], v[j]);
-      }
-#pragma unroll
-      for (int j = 0; j < 8; ++j) v[j] += bias[j];
-      int64_t row = m;
-      if (g.remap_np > 0) {
-        row = (int64_t)m + m / g.remap_np + 1;
-        const float* pr = g.pos + (int64_t)(m % g.remap_np + 1) * g.N + col;
-#pragma unroll
-        for (int j = 0; j < 8; ++j) v[j] += pr[j];
-      }
-      const int64_t off = row * g.ldc + col;
-      if (g.act == ACT_GELU) {
-        if (g.aux) {
-          bf16x8 u;
-#pragma unroll
-          for (int j = 0; j < 8; ++j) u[j] = (bf16)v[j];
-          *(bf16x8*)((bf16*)g.aux + off) = u;
-        }
-#pragma unroll
-        for (int j = 0; j < 8; ++j) v[j] = gelu_f(v[j]);
-      } else if (g.act == ACT_GELU_BWD) {
-        const bf16x8 u = *(const bf16x8*)((const bf16*)g.aux + off);
-#pragma unroll
-        for (int j = 0; j < 8; ++j) v[j] *= gelu_grad_f((float)u[j]);
-      }
-      if (g.out_f32) {
-        float* c = (float*)g.C + off;
-        *(float4*)c = make_float4(v[0], v[1], v[2], v[3]);
-        *(float4*)(c + 4) = make_float4(v[4], v[5], v[6], v[7]);
-      } else {
-        if (g.res) {
-          const bf16x8 rr = *(const bf16x8*)((const bf16*)g.res + off);
-#pragma unroll
-          for (int j = 0; j < 8; ++j) v[j] += (float)rr[j];
-        }
-        bf16x8 o;
-#pragma unroll
-        for (int j = 0; j < 8; ++j) o[j] = (bf16)v[j];
-        *(bf16x8*)((bf16*)g.C + off) = o;
-      }
+      finish8(g, v, m, col, bias, cs, rowstat ? rowstat + mi * 32 + lr : nullptr);
     }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
@@ -432,6 +441,281 @@ void launch_nt(const GemmDesc& g, hipStream_t s) {
   else if (g.K % BK == 0) gemm_nt_kernel<BM, BN, WM, WN, false, PF><<<tiles, WM * WN * 64, lds, s>>>(g, TnArgs());
   else gemm_nt_kernel<BM, BN, WM, WN, true, PF><<<tiles, WM * WN * 64, lds, s>>>(g, TnArgs());
 }
+
+// ------------------------------------------------------------------------------------------ NT, operands straight into LDS
+// The same product for K a multiple of 64, built around three facts measured on gfx950: LDS takes writes from
+// registers at only 64 - 72 bytes per clock, a wavefront that is alone on its SIMD has nobody to hide its waits,
+// and under matrix load the clock is set by power.  So (1) the operand tiles go from global memory straight into
+// LDS with global_load_lds_dwordx4 (lane l of a wavefront writes 16 bytes at M0 + 16 l: one instruction fills 8 tile
+// rows of 8 chunks, and the chunk swizzle of the LDS tile is applied to the global address a lane reads), which
+// costs no registers and no LDS-write instructions; (2) NST stages of (BM + BN) x 64 and ONE barrier per k-tile:
+// at the barrier every wavefront has finished reading k-tile kt and its own part of k-tile kt + 1 has landed
+// (s_waitcnt vmcnt counts such a load when its data is in LDS), so behind the barrier k-tile kt + NST can go into
+// the stage of k-tile kt; (3) the order of the k-loop is written out, every MFMA followed by at most one fragment
+// read or a few loads, and pinned with scheduling barriers (the compiler's own order bunches the reads in front
+// of the MFMAs and waits for them).  Wave tiles are at least 64 x 64 (128 x 64 in the 256 x 256 shape): per MFMA
+// a wavefront reads 0.75 - 1 KB of fragments instead of the 1.5 KB of a 64 x 32 wave tile.
+// The MFMA operands are swapped (weight rows first), so an accumulator holds the TRANSPOSED 32 x 32 output tile:
+// a lane owns one output row and four runs of four consecutive columns.  That lets the epilogue round to bf16
+// before the tile goes through LDS whenever nothing has to be added in fp32 afterwards (8-byte LDS writes of four
+// bf16 instead of sixteen 4-byte writes per tile), and use 16-byte LDS writes otherwise.
+template <int N> __device__ __forceinline__ void wait_vmcnt() {
+  __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | (0x7 << 4) | (0xF << 8));
+}
+__device__ __forceinline__ void wait_lgkmcnt0() { __builtin_amdgcn_s_waitcnt(0xF | (0x3 << 14) | (0x7 << 4)); }
+template <class F, int... I> __device__ __forceinline__ void sfor_impl(F&& f, std::integer_sequence<int, I...>) { (f(IC<I>{}), ...); }
+template <int N, class F> __device__ __forceinline__ void sfor(F&& f) { sfor_impl(f, std::make_integer_sequence<int, N>{}); }
+#define BSR_SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
+#define BSR_GLOBAL_PTR(p) ((const void __attribute__((address_space(1)))*)(p))
+#define BSR_LDS_VOID(p) ((void __attribute__((address_space(3)))*)(p))
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+
+// Epilogue of one wave tile whose accumulators hold transposed output tiles: element r of acc[mi][ni] is output
+// row mi*32 + lane%32, column ni*32 + 8*(r/4) + 4*(lane/32) + r%4.  32 rows at a time go through a per-wave LDS
+// patch and come back with a lane owning 8 consecutive columns of a row (16-byte global stores).
+template <int MI, int NI>
+__device__ __forceinline__ void epilogue_t(const GemmDesc& g, f32x16 (&acc)[MI][NI], int row0, int col0, int lane,
+                                           unsigned char* patch) {
+  constexpr int TN = NI * 32;
+  constexpr int CPR = TN / 8, RPP = 64 / CPR;       // 8-column chunks per row, rows per pass of the wave
+  constexpr int NPASS = (32 + RPP - 1) / RPP;       // (with 12 chunks per row 60 lanes work and the last pass is partial)
+  const int lm = lane & 31, lh = lane >> 5;
+  const int my_chunk = lane % CPR, my_row = lane / CPR;
+  const int col = col0 + my_chunk * 8;
+  const bool col_ok = col < g.N && my_row < RPP;    // N is a multiple of 8 on this path
+  // nothing to add after the transposition: round first, move half the bytes
+  const bool direct = !g.out_f32 && !g.res && g.remap_np == 0 && g.act != ACT_GELU_BWD;
+  if (direct) {
+    constexpr int LDB = TN * 2 + 16;                // bytes per patch row
+    f32x4 bq[NI][4];                                // bias of the columns this lane holds
+#pragma unroll
+    for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+      for (int rg = 0; rg < 4; ++rg) {
+        const int c = col0 + ni * 32 + 8 * rg + 4 * lh;
+        bq[ni][rg] = (g.bias && c < g.N) ? *(const f32x4*)(g.bias + c) : f32x4{0.f, 0.f, 0.f, 0.f};
+      }
+    const int npass = (g.act == ACT_GELU && g.aux) ? 2 : 1;    // the pre-activation leaves first
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi) {
+      for (int pass = 0; pass < npass; ++pass) {
+        const bool act_now = g.act == ACT_GELU && pass == npass - 1;
+        bf16* dst = (bf16*)((pass == 0 && npass == 2) ? g.aux : g.C);
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+          for (int rg = 0; rg < 4; ++rg) {
+            bf16x4 o;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              float v = acc[mi][ni][4 * rg + e] + bq[ni][rg][e];
+              if (act_now) v = gelu_f(v);
+              o[e] = (bf16)v;
+            }
+            *(bf16x4*)(patch + lm * LDB + (ni * 32 + 8 * rg + 4 * lh) * 2) = o;
+          }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int p = 0; p < NPASS; ++p) {
+          const int lr = p * RPP + my_row;
+          const int m = row0 + mi * 32 + lr;
+          if (lr >= 32 || m >= g.M || !col_ok) continue;
+          *(bf16x8*)(dst + (int64_t)m * g.ldc + col) = *(const bf16x8*)(patch + lr * LDB + my_chunk * 16);
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+      }
+    }
+    return;
+  }
+  constexpr int LDF = TN * 4 + 16;
+  float bias[8], cs[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) { bias[j] = (g.bias && col_ok) ? g.bias[col + j] : 0.f; cs[j] = 0.f; }
+#pragma unroll
+  for (int mi = 0; mi < MI; ++mi) {
+#pragma unroll
+    for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+      for (int rg = 0; rg < 4; ++rg)
+        *(f32x4*)(patch + lm * LDF + (ni * 32 + 8 * rg + 4 * lh) * 4) =
+            f32x4{acc[mi][ni][4 * rg], acc[mi][ni][4 * rg + 1], acc[mi][ni][4 * rg + 2], acc[mi][ni][4 * rg + 3]};
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int p = 0; p < NPASS; ++p) {
+      const int lr = p * RPP + my_row;
+      const int m = row0 + mi * 32 + lr;
+      if (lr >= 32 || m >= g.M || !col_ok) continue;
+      const f32x4 p0 = *(const f32x4*)(patch + lr * LDF + my_chunk * 32);
+      const f32x4 p1 = *(const f32x4*)(patch + lr * LDF + my_chunk * 32 + 16);
+      float v[8] = {p0[0], p0[1], p0[2], p0[3], p1[0], p1[1], p1[2], p1[3]};
+      finish8(g, v, m, col, bias, cs, nullptr);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+  }
+}
+
+// (a shape whose stages take at most half of the 160 KB is held to the registers that let two workgroups share a CU)
+template <int BM, int BN, int WM, int WN, int NST>
+__global__ __launch_bounds__(WM * WN * 64, (NST * (BM + BN) * 128 <= 80 * 1024 && WM * WN <= 4) ? 2 : 1)
+void gemm_ntd_kernel(GemmDesc g) {
+  constexpr int NT = WM * WN * 64;
+  constexpr int TM = BM / WM, TN = BN / WN, MI = TM / 32, NI = TN / 32, NMF = MI * NI, NFR = MI + NI;
+  constexpr int RPI = NT / 8;                       // tile rows one load instruction of the workgroup fills
+  constexpr int AL = BM / RPI, BL = BN / RPI;       // load instructions per thread and k-tile
+  constexpr int LPT = AL + BL;
+  constexpr int STAGE = (BM + BN) * 128;            // bytes of a stage: rows of 8 chunks of 16 bytes, A rows first
+  static_assert(BM % RPI == 0 && BN % RPI == 0 && RPI % 16 == 0, "a load instruction covers whole groups of 16 rows");
+  static_assert(NST >= 2 && NST <= 4 && (NST - 1) * LPT <= 60, "vmcnt has 6 bits");
+  static_assert(NMF >= NFR && NMF <= 16 && MI >= 1 && NI >= 1, "");
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave / WN, wn = wave % WN;
+  const int ntn = (g.N + BN - 1) / BN;
+  const int tile = xcd_remap(blockIdx.x, (int)gridDim.x);
+  const int m0 = (tile / ntn) * BM, n0 = (tile % ntn) * BN;
+  const bf16* __restrict__ A = (const bf16*)g.A;
+  const bf16* __restrict__ Bt = (const bf16*)g.B;
+
+  // loader: thread t of load instruction i brings chunk kc of tile row i*RPI + t/8 to LDS slot (row, t%8); rows
+  // past M (or N) repeat the last valid row: they only feed accumulators that are never stored
+  const int lrow = tid >> 3;
+  const int kc = (tid & 7) ^ swz(lrow);
+  unsigned off[LPT];
+#pragma unroll
+  for (int i = 0; i < AL; ++i) off[i] = (unsigned)min(m0 + i * RPI + lrow, g.M - 1) * (unsigned)g.a_rs + kc * 8;
+#pragma unroll
+  for (int i = 0; i < BL; ++i) off[AL + i] = (unsigned)min(n0 + i * RPI + lrow, g.N - 1) * (unsigned)g.b_cs + kc * 8;
+  auto issue1 = [&](auto I, int kt, int st) __attribute__((always_inline)) {
+    constexpr int i = decltype(I)::value;
+    const bf16* src = (i < AL ? A : Bt) + (size_t)kt * 64;
+    unsigned char* dst = smem + st * STAGE + wave * 1024 + (i < AL ? i * RPI * 128 : BM * 128 + (i - AL) * RPI * 128);
+    __builtin_amdgcn_global_load_lds(BSR_GLOBAL_PTR(src + off[i]), BSR_LDS_VOID(dst), 16, 0, 0);
+  };
+
+  f32x16 acc[MI][NI];
+#pragma unroll
+  for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+    for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.f;
+
+  // fragments: read order A0, B0 .. B(NI-1), A1 .. A(MI-1), so that the first MFMAs of a k-step can start early
+  const int lr = lane & 31, lh = lane >> 5, sw = swz(lr);
+  int offr[NFR];
+  bf16x8 fr[2][NFR];
+#pragma unroll
+  for (int j = 0; j < NFR; ++j) {
+    const bool isA = j == 0 || j > NI;
+    const int idx = j == 0 ? 0 : (j <= NI ? j - 1 : j - NI);
+    offr[j] = isA ? (wm * TM + idx * 32 + lr) * 128 : BM * 128 + (wn * TN + idx * 32 + lr) * 128;
+  }
+  auto rd1 = [&](auto SET, auto J, int st, int ks) __attribute__((always_inline)) {
+    constexpr int set = decltype(SET)::value, j = decltype(J)::value;
+    fr[set][j] = *(const bf16x8*)(smem + st * STAGE + (((ks * 2 + lh) ^ sw) << 4) + offr[j]);
+  };
+  auto mf1 = [&](auto SET, auto J) __attribute__((always_inline)) {
+    constexpr int set = decltype(SET)::value, j = decltype(J)::value, mi = j / NI, ni = j % NI;
+    constexpr int ja = mi == 0 ? 0 : NI + mi, jb = 1 + ni;
+    acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[set][jb], fr[set][ja], acc[mi][ni], 0, 0, 0);
+  };
+  // one k-step: MFMAs on fragment set SET; the fragments of (stage st, k-step ks) go into the other set
+  auto kstep = [&](auto SET, int st, int ks) __attribute__((always_inline)) {
+    constexpr int set = decltype(SET)::value;
+    sfor<NMF>([&](auto J) __attribute__((always_inline)) {
+      constexpr int j = decltype(J)::value;
+      mf1(IC<set>{}, J);
+      if constexpr (j < NFR) rd1(IC<set ^ 1>{}, J, st, ks);
+      BSR_SCHED_FENCE();
+    });
+  };
+  // The last k-step of k-tile kt (fragments in set 1) with the barrier.  VMW >= 0: loads that may stay in flight
+  // at the barrier (steady state, k-tile kt + NST is issued behind it); VMW < 0: tail, nothing is issued and the
+  // count follows from rem, the number of k-tiles after this one (after the last one barrier and reads are idle).
+  auto klast = [&](auto VMW, int kt, int st, int stn, int rem) __attribute__((always_inline)) {
+    constexpr int vmw = decltype(VMW)::value;
+    constexpr int PRE = NMF >= 16 ? 4 : (NMF >= 8 ? 2 : 1);       // MFMAs in front of the barrier
+    constexpr int POST = NMF - PRE;
+    constexpr int RPP = (NFR + POST - 1) / POST, LPP = (LPT + POST - 1) / POST;
+    sfor<PRE>([&](auto J) __attribute__((always_inline)) { mf1(IC<1>{}, J); BSR_SCHED_FENCE(); });
+    wait_lgkmcnt0();
+    if constexpr (vmw >= 0) wait_vmcnt<vmw>();
+    else if (rem >= 3) wait_vmcnt<2 * LPT>();
+    else if (rem == 2) wait_vmcnt<LPT>();
+    else wait_vmcnt<0>();
+    __builtin_amdgcn_s_barrier();
+    BSR_SCHED_FENCE();
+    sfor<POST>([&](auto P) __attribute__((always_inline)) {
+      constexpr int p = decltype(P)::value;
+      mf1(IC<1>{}, IC<PRE + p>{});
+      sfor<RPP>([&](auto R) __attribute__((always_inline)) {
+        constexpr int r = p * RPP + decltype(R)::value;
+        if constexpr (r < NFR) rd1(IC<0>{}, IC<r>{}, stn, 0);
+      });
+      if constexpr (vmw >= 0)
+        sfor<LPP>([&](auto L) __attribute__((always_inline)) {
+          constexpr int l = p * LPP + decltype(L)::value;
+          if constexpr (l < LPT) issue1(IC<l>{}, kt + NST, st);
+        });
+      BSR_SCHED_FENCE();
+    });
+  };
+
+  const int nk = g.K / BK;
+  // prologue: every stage filled (k-tiles 0 .. NST-1), k-tile 0 landed
+#pragma unroll
+  for (int j = 0; j < NST; ++j)
+    if (j < nk) sfor<LPT>([&](auto I) __attribute__((always_inline)) { issue1(I, j, j); });
+  {
+    const int fl = min(nk, NST) - 1;            // k-tiles that may stay in flight
+    if (fl >= 3) wait_vmcnt<3 * LPT>(); else if (fl == 2) wait_vmcnt<2 * LPT>(); else if (fl == 1) wait_vmcnt<LPT>(); else wait_vmcnt<0>();
+  }
+  __builtin_amdgcn_s_barrier();
+  sfor<NFR>([&](auto J) __attribute__((always_inline)) { rd1(IC<0>{}, J, 0, 0); });
+  int st = 0, kt = 0;
+  for (; kt + NST < nk; ++kt) {          // steady state
+    const int stn = (st + 1 == NST) ? 0 : st + 1;
+    kstep(IC<0>{}, st, 1);
+    kstep(IC<1>{}, st, 2);
+    kstep(IC<0>{}, st, 3);
+    klast(IC<(NST - 2) * LPT>{}, kt, st, stn, 0);
+    st = stn;
+  }
+  for (; kt < nk; ++kt) {                // the last NST k-tiles: nothing left to issue
+    const int stn = (st + 1 == NST) ? 0 : st + 1;
+    kstep(IC<0>{}, st, 1);
+    kstep(IC<1>{}, st, 2);
+    kstep(IC<0>{}, st, 3);
+    klast(IC<-1>{}, kt, st, stn, nk - 1 - kt);
+    st = stn;
+  }
+  // every wavefront is past the last barrier, i.e. has read its last fragments: the stages are free
+  epilogue_t<MI, NI>(g, acc, m0 + wm * TM, n0 + wn * TN, lane, smem + wave * (32 * (TN * 4 + 16)));
+}
+
+template <int BM, int BN, int WM, int WN, int NST>
+void launch_ntd(const GemmDesc& g, hipStream_t s) {
+  static bool attr_set = false;
+  constexpr size_t lds_tiles = (size_t)NST * (BM + BN) * 128;
+  constexpr size_t lds_patch = (size_t)WM * WN * 32 * ((BN / WN) * 4 + 16);
+  static_assert(lds_patch <= lds_tiles, "the epilogue patches live in the stage buffers");
+  auto kern = gemm_ntd_kernel<BM, BN, WM, WN, NST>;
+  if (!attr_set) {
+    (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_tiles);
+    attr_set = true;
+  }
+  const int tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
+  kern<<<tiles, WM * WN * 64, lds_tiles, s>>>(g);
+}
+// what the direct-to-LDS kernels take: whole k-tiles, one weight matrix, no folded LayerNorm
+bool is_ntd(const GemmDesc& g) { return g.K % BK == 0 && !g.grp_off && !g.ln_colsum; }
 
 // ------------------------------------------------------------------------------------------ TN
 // Weight gradient dW[Mo,No] = sum_t X[t,Mo]^T dY[t,No] (Eq. 4): both operands have the contraction
@@ -835,7 +1119,20 @@ static const NtShape kNtShapes[] = {
     // with deeper register prefetch (id = PF * 1000000 + shape)
     {3128064, 128, 64, -1.f, 0.f},      {3064128, 64, 128, -1.f, 0.f},     {2192128, 192, 128, -1.f, 0.f},
     {2256128, 256, 128, -1.f, 0.f},     {2128128, 128, 128, -1.f, 0.f},
+    // operands straight into LDS (id = 7000000 + shape; K a multiple of 64, one weight matrix, no folded LayerNorm:
+    // a launch outside that takes the model's shape instead)
+    {7256256, 256, 256, -1.f, 0.f},     {7320256, 320, 256, -1.f, 0.f},    {7192256, 192, 256, -1.f, 0.f},
+    {7256192, 256, 192, -1.f, 0.f},     {7256128, 256, 128, -1.f, 0.f},    {7128256, 128, 256, -1.f, 0.f},
+    {7192128, 192, 128, -1.f, 0.f},     {7128128, 128, 128, -1.f, 0.f},
 };
+// stages of the direct-to-LDS shapes (0: not one of them)
+static int ntd_stages(int id) {
+  switch (id) {
+    case 7256256: case 7320256: case 7192256: case 7256192: case 7192128: case 7128128: return 2;
+    case 7256128: case 7128256: return 3;
+    default: return 0;
+  }
+}
 
 int gemm_nt_model_tile(int M, int N, int K) {
   int pick = 0;
@@ -847,6 +1144,10 @@ int gemm_nt_model_tile(int M, int N, int K) {
     if (!pick || us < best) { pick = t.id; best = us; }
   }
   return pick;
+}
+size_t gemm_nt_tile_lds_bytes(int id) {
+  const int bm = id % 1000000 / 1000, bn = id % 1000, nst = ntd_stages(id);
+  return (size_t)(nst ? nst : 2) * (bm + bn) * BK * sizeof(bf16);
 }
 int gemm_nt_tile_count() { return (int)(sizeof(kNtShapes) / sizeof(kNtShapes[0])); }
 int gemm_nt_tile_id(int i) { return kNtShapes[i].id; }
@@ -865,8 +1166,16 @@ void gemm_mfma(const GemmDesc& g, float* splitk_ws, size_t splitk_ws_floats, hip
   }
   static const int forced = [] { const char* e = getenv("BSR_NT_TILE"); return e ? atoi(e) : 0; }();
   int pick = g.grp_off ? 128128 : (tile ? tile : forced);     // groups are a few hundred rows: small tiles
-  if (!pick) pick = gemm_nt_model_tile(g.M, g.N, g.K);
+  if (!pick || (ntd_stages(pick) && !is_ntd(g))) pick = gemm_nt_model_tile(g.M, g.N, g.K);
   switch (pick) {
+    case 7256256: launch_ntd<256, 256, 2, 4, 2>(g, s); break;
+    case 7320256: launch_ntd<320, 256, 2, 4, 2>(g, s); break;
+    case 7192256: launch_ntd<192, 256, 2, 4, 2>(g, s); break;
+    case 7256192: launch_ntd<256, 192, 4, 2, 2>(g, s); break;
+    case 7256128: launch_ntd<256, 128, 4, 2, 3>(g, s); break;
+    case 7128256: launch_ntd<128, 256, 2, 4, 3>(g, s); break;
+    case 7192128: launch_ntd<192, 128, 2, 2, 2>(g, s); break;
+    case 7128128: launch_ntd<128, 128, 2, 2, 2>(g, s); break;
     case 256256: launch_nt<256, 256, 2, 4>(g, s); break;
     case 256128: launch_nt<256, 128, 4, 4>(g, s); break;
     case 192128: launch_nt<192, 128, 2, 4>(g, s); break;
