@@ -1160,10 +1160,7 @@ static int32_t optimizer_step(bsr_ctx* c, const bsr_params* grads, const bsr_par
 // worse than that, too.)  So the choice is one shape for all launches, among the shapes that leave room for a
 // second workgroup on a CU (two tile buffers of at most 80 KB; the shape id is [prefetch depth] BM BN in
 // decimal), and what is timed is a whole side-by-side pass.
-static bool shares_a_cu(int tile_id) {
-  const int bm = tile_id % 1000000 / 1000, bn = tile_id % 1000;
-  return (size_t)2 * (bm + bn) * 64 * sizeof(bf16) <= 80 * 1024;
-}
+static bool shares_a_cu(int tile_id) { return gemm_nt_tile_lds_bytes(tile_id) <= 80 * 1024; }
 
 static int32_t autotune_overlapped(bsr_ctx* c, const void* input, const int32_t* labels, int32_t B, void* x_frozen,
                                    void* x_side, float* loss_out, const bsr_params* grads, int32_t* launches_out,

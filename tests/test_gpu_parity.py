@@ -465,6 +465,31 @@ def test_headline_workload_full_size(hip, orc32):
         assert len(set(free["kept_idx"][0][b]) & set(ref["kept_idx"][0][b])) >= 130
 
 
+# ------------------------------------------------------------------ batch 128: the shape sweep of the ablations
+
+@pytest.mark.parametrize("keep,trainable,kk", [(0.7, 4, [137, 95, 66]), (1.0, 12, [196, 196, 196]), (0.5, 2, [98, 49, 24])])
+def test_batch_128_sweep_points(hip, orc32, keep, trainable, kk):
+    """ViT-B/16 at batch 128 (the batch of Tables 3, 4, 7, 8), three corners of the sweep keep ratio x number of
+    trained blocks: 25 216 token rows take other paths than batch 32 does (other tile shapes and tails, longer
+    split-K, no frozen prefix at all when every block is trained).  Forced indices; every logit and gradient."""
+    cfg = S.get_config("c3_vit_b", batch=128, keep_ratio=keep, first_trainable=12 - trainable)
+    p = S.make_params(cfg)
+    x, y = S.make_inputs(cfg)
+    ref = orc32.step(cfg, p, x, y)
+    got = hip.run_hip_step(cfg, p, x, y, forced_idx=ref["kept_idx"])
+    assert got["keep_k"] == kk
+    assert hip.rel(got["logits"], ref["logits"]) < TOL_BF16
+    assert abs(got["loss"] - ref["loss"]) < TOL_BF16 * abs(ref["loss"])
+    assert set(got["grads"]) == set(ref["grads"])
+    for n, g in ref["grads"].items():
+        assert hip.rel(got["grads"][n], g) < TOL_BF16, n
+    if trainable < 12:
+        assert hip.rel(got["x_trainable"], ref["x_trainable"]) < TOL_BF16
+    del got, ref
+    import torch
+    torch.cuda.empty_cache()
+
+
 # ------------------------------------------------------------------ interleaved trainable layout
 
 def test_interleaved_layout_fp32(hip, orc64):
