@@ -356,6 +356,22 @@ int32_t bsr_linear_wgrad(const void* x, const void* dy, int32_t M, int32_t in, i
                          float* db, float* workspace, size_t workspace_floats, int32_t* used_mfma, void* stream);
 
 /*
+ * bsr_linear_wgrad for callers that cannot allocate device memory and have no workspace to hand over (code under
+ * HIP graph capture, serving loops, harnesses that forbid hipMalloc): the same kernels and the same result, with
+ * the split-K partial sums in an array that is part of the library itself (24 MiB of device memory on every GPU
+ * the library runs on, held until the process ends).  The call allocates nothing and frees nothing.
+ *   Limit: 2 * (in + 1) * out <= 6 Mi floats (two partial copies of dw and db; every matrix of ViT-B fits);
+ *          beyond it the call returns BSR_ERR_INVALID_ARG and launches nothing.
+ *   All calls on one GPU share that array and it keeps the last call's contents (no call needs it cleared: every
+ *   partial sum that is read was written by the same call): calls that overlap on one GPU, on different streams
+ *   or from different threads, race.  The first call on a device looks the array's address up
+ *   (hipGetSymbolAddress); make that call outside a graph capture.
+ * Errors: INVALID_ARG, HIP.
+ */
+int32_t bsr_linear_wgrad_static(const void* x, const void* dy, int32_t M, int32_t in, int32_t out, float* dw,
+                                float* db, int32_t* used_mfma, void* stream);
+
+/*
  * LayerNorm followed by a linear layer (the LN -> qkv and LN -> fc1 pairs of the pre-norm block, Sec. 3.1),
  * as the frozen prefix runs them in bf16: the LayerNorm is folded into the product,
  *   LN(x) W + b = rstd (x W' - mean c) + b',   W' = diag(gamma) W,   c = column sums of W',   b' = b + beta W,

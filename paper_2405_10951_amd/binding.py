@@ -111,6 +111,9 @@ def load_library():
     lib.bsr_linear_wgrad.restype = C.c_int32
     lib.bsr_linear_wgrad.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
                                      C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
+    lib.bsr_linear_wgrad_static.restype = C.c_int32
+    lib.bsr_linear_wgrad_static.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
+                                            C.c_void_p, C.c_void_p, C.c_void_p]
     lib.bsr_attention_forward.restype = C.c_int32
     lib.bsr_attention_forward.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
                                           C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
@@ -272,6 +275,20 @@ def bsr_linear_wgrad(x, dy, dw=None, workspace=None, db=None):
     _check(load_library().bsr_linear_wgrad(_dp(x), _dp(dy), M, kin, out, _dp(dw), _dp(db), _dp(workspace),
                                            C.c_size_t(0 if workspace is None else workspace.numel()),
                                            C.byref(used), _cur_stream(x)))
+    return dw, used.value
+
+
+def bsr_linear_wgrad_static(x, dy, dw=None, db=None):
+    """bsr_linear_wgrad with the split-K partial sums in the library's built-in scratch array: the call itself
+    allocates nothing (dw and db, when not given, are allocated here, in the binding)."""
+    import torch
+    M, kin = x.shape
+    out = dy.shape[1]
+    if dw is None:
+        dw = torch.empty((kin, out), dtype=torch.float32, device=x.device)
+    used = C.c_int32(-1)
+    _check(load_library().bsr_linear_wgrad_static(_dp(x), _dp(dy), M, kin, out, _dp(dw), _dp(db), C.byref(used),
+                                                  _cur_stream(x)))
     return dw, used.value
 
 

@@ -7,6 +7,7 @@
 #include <string.h>
 
 #include <algorithm>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -704,6 +705,36 @@ int check_params(const bsr_config& cf, const bsr_params* p, int first_block, boo
   }
   if (cf.num_classes > 0) { NEED(p->lnf_g, "lnf_g"); NEED(p->lnf_b, "lnf_b"); NEED(p->w_head, "w_head"); NEED(p->b_head, "b_head"); }
 #undef NEED
+  return BSR_OK;
+}
+
+// Scratch of bsr_linear_wgrad_static: the split-K partial sums of one weight gradient, in device memory that
+// belongs to the library's code object (every GPU the library runs on holds its own copy until the process ends).
+constexpr size_t STATIC_SCRATCH_FLOATS = (size_t)6 << 20;          // 24 MiB
+static __device__ __align__(256) float scratch[STATIC_SCRATCH_FLOATS];
+constexpr int STATIC_SCRATCH_MAX_DEVICES = 64;
+static float* g_scratch_ptr[STATIC_SCRATCH_MAX_DEVICES] = {};      // device address of `scratch`, per device
+static std::mutex g_scratch_mutex;
+
+// Device address of the array on the current device (looked up once per device, with that device current).
+// The array's name is only a host-side handle; kernels and copies get this pointer.
+static int static_scratch(float** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= STATIC_SCRATCH_MAX_DEVICES) {
+    (void)hipGetLastError();
+    return fail(nullptr, BSR_ERR_HIP, "bsr_linear_wgrad_static: no current device (or more than %d devices)", STATIC_SCRATCH_MAX_DEVICES);
+  }
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !p) {
+      (void)hipGetLastError();
+      return fail(nullptr, BSR_ERR_HIP, "bsr_linear_wgrad_static: hipGetSymbolAddress: %s", hipGetErrorString(e));
+    }
+    g_scratch_ptr[dev] = (float*)p;
+  }
+  *out = g_scratch_ptr[dev];
   return BSR_OK;
 }
 
@@ -1547,6 +1578,24 @@ int32_t bsr_linear_wgrad(const void* x, const void* dy, int32_t M, int32_t in, i
     colsum(dy, M, out, out, false, workspace, db, (hipStream_t)stream);
   }
   return run_layer(g, used_mfma, stream, "bsr_linear_wgrad", workspace, workspace_floats);
+}
+
+int32_t bsr_linear_wgrad_static(const void* x, const void* dy, int32_t M, int32_t in, int32_t out, float* dw, float* db,
+                                int32_t* used_mfma, void* stream) {
+  if (!aligned16(x) || !aligned16(dy) || !aligned16(dw) || M < 1 || in < 1 || out < 1)
+    return fail(nullptr, BSR_ERR_INVALID_ARG, "bsr_linear_wgrad_static: bad argument");
+  // the smallest split (two partial copies of dw and of db) has to fit, and so do the column-sum partials of a
+  // shape the MFMA kernel does not take: larger layers are refused rather than run without their scratch
+  const size_t need = (size_t)2 * ((size_t)in + 1) * (size_t)out;
+  if (need > STATIC_SCRATCH_FLOATS || colsum_partial_floats(M, out) > STATIC_SCRATCH_FLOATS)
+    return fail(nullptr, BSR_ERR_INVALID_ARG,
+                "bsr_linear_wgrad_static: a layer of %d x %d needs %zu floats of scratch, the built-in array holds %zu "
+                "(2 (in + 1) out must not exceed it)", in, out, need, STATIC_SCRATCH_FLOATS);
+  float* ws = nullptr;
+  const int rc = static_scratch(&ws);
+  if (rc != BSR_OK) return rc;
+  // every partial sum that is read has been written by this call: nothing in the array has to start at zero
+  return bsr_linear_wgrad(x, dy, M, in, out, dw, db, ws, STATIC_SCRATCH_FLOATS, used_mfma, stream);
 }
 
 int32_t bsr_attention_forward(const void* qkv, int32_t B, int32_t T, int32_t H, int32_t d, void* out,
