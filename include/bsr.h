@@ -8,10 +8,14 @@
  *   - Plain C.  Every function returns a bsr status (0 = BSR_OK, negative = error); nothing throws
  *     or aborts.  bsr_last_error() gives a text for the last failure on a context.
  *   - "device" pointers are HIP device memory owned by the caller; "host" pointers are ordinary
- *     host memory.  The library never allocates or frees device memory and never synchronises the
- *     device: all kernels are enqueued on the `stream` argument (a hipStream_t passed as void*;
- *     NULL is the default stream) and the call returns.  The only thing the library owns is the
- *     small host-side context, released by bsr_destroy().
+ *     host memory.  The library never allocates or frees device memory.  The calls of a step
+ *     (bsr_forward_frozen, bsr_select_tokens, bsr_train_blocks_fwd_bwd, bsr_sgd_step, bsr_adamw_step,
+ *     bsr_pipeline_step), bsr_init and the single-layer calls never wait for the device: all kernels are
+ *     enqueued on the `stream` argument (a hipStream_t passed as void*; NULL is the default stream)
+ *     and the call returns.  Three set-up / measurement calls DO block until their streams have
+ *     drained, because they read event times: bsr_autotune, bsr_autotune_overlapped and
+ *     bsr_profile_end.  The library owns the small host-side context and the HIP events it creates
+ *     for those three calls and for bsr_pipeline_step, all released by bsr_destroy().
  *   - Device pointers must be 16-byte aligned.  A NULL or misaligned required pointer gives
  *     BSR_ERR_INVALID_ARG before anything is launched.
  *   - Activations ("act" below) have the configured compute dtype: bf16 (2 bytes) or fp32.
@@ -95,6 +99,11 @@ typedef struct {
    * of the following blocks: the next drop location ranks it with the others, so the schedule becomes
    * n -> K + 1 patch tokens per drop.  0: dropped tokens are discarded. */
   int32_t fuse_dropped;
+  /* 1 (bf16 only): a LayerNorm of the frozen prefix whose output feeds one dense product only is not run as a
+   * kernel of its own; the qkv / fc1 product behind it reads the residual stream and applies the row statistics
+   * itself (see bsr_ln_linear_fold).  Same result up to rounding; saves launches, costs time inside the products.
+   * 0: every LayerNorm is its own kernel. */
+  int32_t fold_frozen_layernorm;
 } bsr_config;
 
 /* Tables of device pointers, one per tensor (fp32).  The same struct describes parameters,

@@ -34,7 +34,7 @@ class bsr_config(C.Structure):
                 ("n_experts", C.c_int32), ("moe_top_k", C.c_int32), ("n_moe", C.c_int32),
                 ("moe_blocks", C.c_int32 * MAX_BLOCKS),
                 ("n_trainable", C.c_int32), ("trainable_blocks", C.c_int32 * MAX_BLOCKS),
-                ("fuse_dropped", C.c_int32)]
+                ("fuse_dropped", C.c_int32), ("fold_frozen_layernorm", C.c_int32)]
 
 
 class bsr_block_params(C.Structure):
@@ -155,6 +155,7 @@ def make_config(cfg: dict, max_batch: int, keep_k=None) -> bsr_config:
     c.n_experts = int(cfg.get("n_experts", 0))
     c.moe_top_k = int(cfg.get("moe_top_k", 0))
     c.fuse_dropped = int(bool(cfg.get("fuse_dropped", 0)))
+    c.fold_frozen_layernorm = int(bool(cfg.get("fold_frozen_layernorm", 0)))
     tb = list(cfg.get("trainable_blocks") or [])
     c.n_trainable = len(tb)
     for i, b in enumerate(tb):

@@ -73,7 +73,8 @@ struct Buffers {
   SavedBlock sv[BSR_MAX_BLOCKS] = {};
   MoeBuf moe = {};                      // frozen mixture blocks share this one
   char *moe_u = nullptr;                // their GELU outputs [M*K, F]
-  char *moe_dy = nullptr, *moe_dxg = nullptr, *moe_dlog = nullptr;   // backward scratch
+  char *moe_dy = nullptr, *moe_dxg = nullptr;   // backward scratch
+  float* moe_rw_partial = nullptr;              // chunk sums of the router weight gradient
   char *dxa = nullptr, *dxb = nullptr, *dgu = nullptr, *dh = nullptr, *dqkv = nullptr;
   float *delta = nullptr, *partial = nullptr, *splitk = nullptr;
   float *ln_partial = nullptr;          // one slot per LayerNorm of the trained blocks (deferred dgamma / dbeta sums)
@@ -123,6 +124,7 @@ struct bsr_ctx {
   float eps;
   char* ws;
   size_t ws_bytes;
+  int deferred = BSR_OK;                     // an error met by a helper that cannot return it (see defer_fail)
   const int32_t* forced_experts = nullptr;   // bsr_moe_routing_io
   int32_t* experts_out = nullptr;
   float* router_logits_out = nullptr;
@@ -143,8 +145,25 @@ int fail(bsr_ctx* c, int code, const char* fmt, ...) {
 
 bool aligned16(const void* p) { return p && (((uintptr_t)p) & 15) == 0; }
 
+// An error found inside a launch helper that returns nothing (a product that no kernel takes): the launch is
+// skipped, the text is kept, and the entry point that is running returns the code from check_hip instead of
+// BSR_OK (what it enqueued after the skipped launch read a tensor nobody wrote).
+void defer_fail(bsr_ctx* c, int code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(c->err, sizeof(c->err), fmt, ap);
+  va_end(ap);
+  snprintf(g_err, sizeof(g_err), "%s", c->err);
+  if (c->deferred == BSR_OK) c->deferred = code;
+}
+
 int check_hip(bsr_ctx* c, const char* where) {
   hipError_t e = hipGetLastError();
+  if (c && c->deferred != BSR_OK) {
+    const int code = c->deferred;
+    c->deferred = BSR_OK;
+    return code;                     // (the text is already in place)
+  }
   if (e != hipSuccess) return fail(c, BSR_ERR_HIP, "%s: %s", where, hipGetErrorString(e));
   return BSR_OK;
 }
@@ -232,13 +251,14 @@ int make_schedule(const bsr_config* c, Schedule* s, char* why, size_t whyn) {
       if (s->moe[l]) rows += s->Tm[l];
     }
   }
-  // A LayerNorm of the frozen prefix is folded when its output goes into a dense product only (after a
-  // token drop the LayerNorm kernel also does the gather; a mixture block routes on the normalised tokens),
-  // and only for contexts of up to 8192 token rows: the fold trades a launch (a fixed cost) for 8 - 15 % more
-  // time in the product (measured: 1.5 % faster step at 6304 rows, 2.8 % slower at 25216).
-  static const int fold_env = [] { const char* e = getenv("BSR_LN_FOLD"); return e ? atoi(e) : -1; }();   // 0 / 1 force it
-  const bool fold = fold_env >= 0 ? fold_env != 0 : (int64_t)c->max_batch * s->T0 <= 8192;
-  if (c->dtype == BSR_BF16 && c->dim % 64 == 0 && fold)
+  // A LayerNorm of the frozen prefix can be folded when its output goes into a dense product only (after a
+  // token drop the LayerNorm kernel also does the gather; a mixture block routes on the normalised tokens).
+  // The fold trades launches (a fixed cost) for 8 - 15 % more time in the products that carry it, which run in
+  // the register-staged kernel: it is the caller's choice (measured on ViT-B/16: 1.5 % faster step at 6304
+  // token rows before the direct-to-LDS products existed, 1 % slower with them; 2.8 % slower at 25216 rows).
+  if (c->fold_frozen_layernorm != 0 && c->fold_frozen_layernorm != 1) BAD("fold_frozen_layernorm must be 0 or 1");
+  if (c->fold_frozen_layernorm && c->dtype != BSR_BF16) BAD("fold_frozen_layernorm needs dtype bf16");
+  if (c->fold_frozen_layernorm && c->dim % 64 == 0)
     for (int l = 0; l < s->ft && l < c->depth; ++l) {
       s->fold1[l] = true;
       s->fold2[l] = s->drop_of[l] < 0 && !s->moe[l];
@@ -367,7 +387,7 @@ size_t carve(const bsr_config& c, const Schedule& s, char* base, Buffers* out, b
   if (train_moe) {
     b.moe_dy = w.take<char>(B * Tmax * KE * D * E);
     b.moe_dxg = w.take<char>(B * Tmax * KE * D * E);
-    b.moe_dlog = w.take<char>(B * Tmax * ((NE + 7) / 8 * 8) * 2);
+    b.moe_rw_partial = w.take<float>(moe_router_wgrad_partial_floats((int)D, (int)NE));
   }
   b.dh = w.take<char>(B * Tmax * D * E);
   b.dqkv = w.take<char>(B * Tmax * 3 * D * E);
@@ -481,7 +501,7 @@ void tile_done(bsr_ctx* c, TileChoice& ch, hipStream_t s) {
 
 void gemm(bsr_ctx* c, const GemmDesc& g, hipStream_t s) {
   if (g.ln_colsum && (g.K % 64 || g.grp_off || !gemm_mfma_supported(g))) {
-    fail(c, BSR_ERR_BAD_CONFIG, "folded LayerNorm on a product of %d x %d x %d that cannot carry it", g.M, g.N, g.K);
+    defer_fail(c, BSR_ERR_BAD_CONFIG, "folded LayerNorm on a product of %d x %d x %d that cannot carry it", g.M, g.N, g.K);
     return;
   }
   ProfScope ps(c, BSR_PROF_GEMM, 2.0 * g.M * g.N * g.K, s);
@@ -490,7 +510,7 @@ void gemm(bsr_ctx* c, const GemmDesc& g, hipStream_t s) {
     gemm_mfma(g, c->b.splitk, c->b.splitk_floats, s, ch.tile, &c->tn_chain);
     tile_done(c, ch, s);
   }
-  else if (g.grp_off) fail(c, BSR_ERR_BAD_CONFIG, "grouped GEMM %d x %d x %d is not an MFMA shape", g.M, g.N, g.K);
+  else if (g.grp_off) defer_fail(c, BSR_ERR_BAD_CONFIG, "grouped GEMM %d x %d x %d is not an MFMA shape", g.M, g.N, g.K);
   else gemm_generic(g, s);
 }
 
@@ -571,7 +591,7 @@ void moe_ffn_backward(bsr_ctx* c, int l, const void* dx, int M2, SavedBlock& v, 
   const Shadow& sh = b.sh[l];
   MoeBuf& m = v.moe;
   const int R = M2 * K;
-  moe_combine_bwd(dx, m.y, m.pos, m.experts, m.gates, M2, D, E, K, b.moe_dy, m.dsel, b.moe_dlog, s);
+  moe_combine_bwd(dx, m.y, m.pos, m.experts, m.gates, M2, D, E, K, b.moe_dy, m.dsel, s);
   GemmDesc d1 = dgrad_desc(c, b.moe_dy, R, F, D, nullptr, sh.s_fc2, b.dgu);      // du = (dy W2^T) * GELU'(u)
   d1.act = ACT_GELU_BWD; d1.aux = v.u;
   d1.grp_off = m.off; d1.groups = E; d1.b_gs = (int64_t)D * F;
@@ -592,7 +612,8 @@ void moe_ffn_backward(bsr_ctx* c, int l, const void* dx, int M2, SavedBlock& v, 
     gemm(c, w1, s);
   }
   moe_unpermute_bwd(b.moe_dxg, m.pos, m.experts, m.dsel, (const float*)w.w_router, M2, D, E, K, dh, s);
-  if (train) gemm(c, wgrad_desc(c, v.h2, b.moe_dlog, M2, D, E, gw.w_router), s);  // dW_r = h^T dlogits
+  if (train)   // dW_r = h^T dlogits, the logit gradients in fp32
+    moe_router_wgrad(v.h2, m.experts, m.dsel, M2, D, E, K, b.moe_rw_partial, (float*)gw.w_router, s);
 }
 
 void attention_fwd(bsr_ctx* c, const void* qkv, int B, int T, void* out, float* lse, float* clsp,
@@ -1292,9 +1313,6 @@ static int32_t autotune_overlapped(bsr_ctx* c, const void* input, const int32_t*
       launches += (int)sites[k];
     }
     t.batch = B;
-    const char* venv = getenv("BSR_TUNE_VERBOSE");
-    if (venv && venv[0] == '1')
-      fprintf(stderr, "bsr_autotune_overlapped: shape %d (%.3f ms per pipelined pass of six)\n", gemm_nt_tile_id(both), best);
   }
   for (TuneRec& r : t.recs) {
     (void)hipEventDestroy(r.start);
@@ -1335,8 +1353,6 @@ static int32_t autotune(bsr_ctx* c, const void* input, const int32_t* labels, in
   t.cand = -1;
   const bool synced = hipStreamSynchronize(s) == hipSuccess;
   int launches = 0;
-  const char* venv = getenv("BSR_TUNE_VERBOSE");
-  const bool verbose = venv && venv[0] == '1';
   if (rc == BSR_OK && synced) {
     size_t sites[2] = {0, 0};
     for (const TuneRec& r : t.recs) sites[r.kind] = std::max(sites[r.kind], r.site + 1);
@@ -1358,11 +1374,6 @@ static int32_t autotune(bsr_ctx* c, const void* input, const int32_t* labels, in
           if (best[i * n + j] >= 0.f && (arg < 0 || best[i * n + j] < best[i * n + arg])) arg = j;
         t.pick[k][i].tile = arg < 0 ? 0 : gemm_nt_tile_id(arg);
         ++launches;
-        if (verbose) {                 // the measured microseconds of every shape, for inspection
-          fprintf(stderr, "bsr_autotune call %d launch %zu M=%d N=%d K=%d:", k, i, t.pick[k][i].M, t.pick[k][i].N, t.pick[k][i].K);
-          for (int j = 0; j < n; ++j) fprintf(stderr, " %d=%.1f", gemm_nt_tile_id(j), best[i * n + j] * 1e3f);
-          fprintf(stderr, " -> %d\n", t.pick[k][i].tile);
-        }
       }
     }
     t.batch = B;

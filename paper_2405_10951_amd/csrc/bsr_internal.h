@@ -189,10 +189,15 @@ void moe_gather_rows(const void* x, const int32_t* src, int64_t rows, int D, voi
 void moe_combine(const void* y, const int32_t* pos, const float* gates, const void* res, int64_t M, int D, int K,
                  void* x_out, hipStream_t s);
 // backward of moe_combine w.r.t. y and the gates: dy[pos[t,s],:] = gates[t,s] * dx[t,:];
-// dgate_s = <dx[t], y[pos[t,s]]>; dsel[t,s] = gates_s (dgate_s - sum_j gates_j dgate_j) (fp32) and the same
-// values scattered into dlogits[t, experts[t,s]] (bf16 [M,E], zero elsewhere)
+// dgate_s = <dx[t], y[pos[t,s]]>; dsel[t,s] = gates_s (dgate_s - sum_j gates_j dgate_j) (fp32): the gradient at
+// the K selected router logits of token t (the other logits get none)
 void moe_combine_bwd(const void* dx, const void* y, const int32_t* pos, const int32_t* experts, const float* gates,
-                     int64_t M, int D, int E, int K, void* dy, float* dsel, void* dlogits, hipStream_t s);
+                     int64_t M, int D, int E, int K, void* dy, float* dsel, hipStream_t s);
+// dW_r[D,E] (fp32) = h^T dlogits with dlogits[t, experts[t,s]] = dsel[t,s] kept in fp32; partial: scratch of
+// moe_router_wgrad_partial_floats(D, E) floats; sums in a fixed order
+size_t moe_router_wgrad_partial_floats(int D, int E);
+void moe_router_wgrad(const void* h, const int32_t* experts, const float* dsel, int64_t M, int D, int E, int K,
+                      float* partial, float* dw, hipStream_t s);
 // dh[t,:] = sum_s dxg[pos[t,s],:] + sum_s dsel[t,s] * w_router[:, experts[t,s]]
 void moe_unpermute_bwd(const void* dxg, const int32_t* pos, const int32_t* experts, const float* dsel,
                        const float* w_router, int64_t M, int D, int E, int K, void* dh, hipStream_t s);

@@ -505,7 +505,9 @@ __global__ __launch_bounds__(256) void topk_select_kernel(float* __restrict__ sc
     } else {
       v = scores[(int64_t)b * n + j];
     }
-    sc[j] = v;
+    // a NaN score (a diverged step) compares false with everything: ranked as it stands it would be "ahead of
+    // nobody and behind nobody" and more than k tokens would be kept.  It ranks last instead (the order stays total).
+    sc[j] = (v == v) ? v : -INFINITY;
   }
   __syncthreads();
   int base = 0;
@@ -527,7 +529,8 @@ __global__ __launch_bounds__(256) void topk_select_kernel(float* __restrict__ sc
     __syncthreads();
     int before = base;
     for (int v = 0; v < w; ++v) before += wave_count[v];
-    if (keep) idx[(int64_t)b * k + before + __popcll(mask & ((1ull << lane) - 1ull))] = j;
+    const int slot = before + __popcll(mask & ((1ull << lane) - 1ull));
+    if (keep && slot < k) idx[(int64_t)b * k + slot] = j;
     base += wave_count[0] + wave_count[1] + wave_count[2] + wave_count[3];
     __syncthreads();
   }

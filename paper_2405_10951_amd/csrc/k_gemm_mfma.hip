@@ -13,8 +13,6 @@
 // matrix cores.  Workgroups are renumbered so that each XCD (the hardware deals consecutive
 // workgroup ids round-robin over 8 XCDs) works on a contiguous range of tiles and its L2 sees whole
 // operand panels.
-#include <stdlib.h>
-
 #include <algorithm>
 #include <utility>
 
@@ -1007,11 +1005,8 @@ TnPlan plan_tn(const GemmDesc& g, float* ws, size_t ws_floats, TnChain* chain) {
   const size_t mn = (size_t)g.M * g.N;
   const size_t per_split = mn + (g.bsum ? (size_t)g.N : 0);   // partial dW, then partial column sums
   if (ws && mn % 4 == 0) {
-    static const int forced_target = [] { const char* e = getenv("BSR_TN_TARGET"); return e ? atoi(e) : 0; }();
-    const int target = forced_target > 0 ? forced_target : (nk >= 96 ? 512 : 384);
+    const int target = nk >= 96 ? 512 : 384;
     splits = std::max(1, std::min({target / tiles, nk / 4, (int)(ws_floats / per_split), 16}));
-    static const int forced = [] { const char* e = getenv("BSR_TN_SPLITS"); return e ? atoi(e) : 0; }();
-    if (forced > 0) splits = std::max(1, std::min({forced, nk, (int)(ws_floats / per_split)}));
   }
   p.kt_per = (nk + splits - 1) / splits;
   splits = (nk + p.kt_per - 1) / p.kt_per;
@@ -1164,8 +1159,7 @@ void gemm_mfma(const GemmDesc& g, float* splitk_ws, size_t splitk_ws_floats, hip
     launch_tn(g, splitk_ws, splitk_ws_floats, s, chain);
     return;
   }
-  static const int forced = [] { const char* e = getenv("BSR_NT_TILE"); return e ? atoi(e) : 0; }();
-  int pick = g.grp_off ? 128128 : (tile ? tile : forced);     // groups are a few hundred rows: small tiles
+  int pick = g.grp_off ? 128128 : tile;     // groups are a few hundred rows: small tiles
   if (!pick || (ntd_stages(pick) && !is_ntd(g))) pick = gemm_nt_model_tile(g.M, g.N, g.K);
   switch (pick) {
     case 7256256: launch_ntd<256, 256, 2, 4, 2>(g, s); break;
@@ -1201,11 +1195,9 @@ void gemm_mfma(const GemmDesc& g, float* splitk_ws, size_t splitk_ws_floats, hip
 // behind the input-gradient tiles), otherwise as two.
 void gemm_mfma_pair(const GemmDesc& nt, const GemmDesc& tn, float* splitk_ws, size_t splitk_ws_floats, hipStream_t s,
                     int tile, TnChain* chain) {
-  static const int forced = [] { const char* e = getenv("BSR_NT_TILE"); return e ? atoi(e) : 0; }();
-  static const bool no_fuse = [] { const char* e = getenv("BSR_NO_PAIR_FUSION"); return e && e[0] == '1'; }();
-  int pick = tile ? tile : forced;
+  int pick = tile;
   if (!pick) pick = gemm_nt_model_tile(nt.M, nt.N, nt.K);
-  const bool can = !no_fuse && is_nt(nt) && is_tn(tn) && !nt.grp_off && !tn.grp_off && nt.K % BK == 0;
+  const bool can = is_nt(nt) && is_tn(tn) && !nt.grp_off && !tn.grp_off && nt.K % BK == 0;
   if (can) {
     switch (pick) {
       case 128064: { const TnPlan p = plan_tn(tn, splitk_ws, splitk_ws_floats, chain); launch_nt_fused<128, 64, 4, 2, 1>(nt, p, s); if (!chain && p.mine.splits > 0) launch_reduce(p.mine, s); return; }

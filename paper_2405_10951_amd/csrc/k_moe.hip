@@ -168,8 +168,7 @@ __global__ __launch_bounds__(256) void moe_combine_bwd_kernel(const bf16* __rest
                                                               const int32_t* __restrict__ pos,
                                                               const int32_t* __restrict__ experts,
                                                               const float* __restrict__ gates, int64_t M, int D, int E,
-                                                              int K, bf16* __restrict__ dy, float* __restrict__ dsel,
-                                                              bf16* __restrict__ dlogits) {
+                                                              int K, bf16* __restrict__ dy, float* __restrict__ dsel) {
   const int lane = threadIdx.x % WAVE;
   const int64_t t = (int64_t)blockIdx.x * 4 + threadIdx.x / WAVE;
   if (t >= M) return;
@@ -201,16 +200,47 @@ __global__ __launch_bounds__(256) void moe_combine_bwd_kernel(const bf16* __rest
     dgate[q] = wave_sum(dgate[q]);
     if (q < K) mix = fmaf(gates[t * K + q], dgate[q], mix);
   }
-  // dlogits row: zero, then the K selected entries (lane e owns column e; E <= 32)
-  float mine = 0.f;
+  // gradient at the K selected logits (softmax over the selected ones); it stays in fp32
 #pragma unroll
   for (int q = 0; q < MOE_MAX_TOPK; ++q)
-    if (q < K) {
-      const float d = gates[t * K + q] * (dgate[q] - mix);
-      if (lane == 0) dsel[t * K + q] = d;
-      if (experts[t * K + q] == lane) mine = d;
+    if (q < K && lane == 0) dsel[t * K + q] = gates[t * K + q] * (dgate[q] - mix);
+}
+
+// Router weight gradient dW_r[d, e] = sum_t h[t, d] dlogit[t, e], where row t of dlogit is zero except for
+// dsel[t, s] at column experts[t, s]: all in fp32 (the operand h is the stored bf16 LayerNorm output), so that
+// the router sees the same gradient precision as the classification head.  Workgroup (x, y): 64 columns d,
+// token chunk y; its four wavefronts take every fourth token of the chunk and keep [E][64] sums in LDS, which
+// are then added in wavefront order; the chunk sums go to partial[y][d][e] and a second launch adds the chunks
+// in ascending order (no atomics: the result does not depend on timing).
+constexpr int ROUTER_WGRAD_CHUNKS = 32;
+__global__ __launch_bounds__(256) void moe_router_wgrad_kernel(const bf16* __restrict__ h, const int32_t* __restrict__ experts,
+                                                               const float* __restrict__ dsel, int64_t M, int D, int E, int K,
+                                                               float* __restrict__ partial) {
+  __shared__ float acc[4][MOE_MAX_EXPERTS][WAVE];
+  const int lane = threadIdx.x % WAVE, wave = threadIdx.x / WAVE;
+  const int d = blockIdx.x * WAVE + lane;
+  for (int e = 0; e < E; ++e) acc[wave][e][lane] = 0.f;
+  const int64_t per = (M + gridDim.y - 1) / gridDim.y;
+  const int64_t t0 = (int64_t)blockIdx.y * per, t1 = min(M, t0 + per);
+  for (int64_t t = t0 + wave; t < t1; t += 4) {
+    const float hv = d < D ? (float)h[t * D + d] : 0.f;
+    for (int s = 0; s < K; ++s) {
+      const int e = min(max(experts[t * K + s], 0), E - 1);      // (uniform over the wavefront)
+      acc[wave][e][lane] = fmaf(hv, dsel[t * K + s], acc[wave][e][lane]);
     }
-  if (lane < E) dlogits[t * E + lane] = (bf16)mine;
+  }
+  __syncthreads();
+  if (d < D)
+    for (int e = wave; e < E; e += 4)
+      partial[((int64_t)blockIdx.y * D + d) * E + e] = ((acc[0][e][lane] + acc[1][e][lane]) + acc[2][e][lane]) + acc[3][e][lane];
+}
+__global__ __launch_bounds__(256) void moe_router_wgrad_sum_kernel(const float* __restrict__ partial, int n, int chunks,
+                                                                   float* __restrict__ dw) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  float v = partial[i];
+  for (int c = 1; c < chunks; ++c) v += partial[(int64_t)c * n + i];
+  dw[i] = v;
 }
 
 __global__ __launch_bounds__(256) void moe_unpermute_bwd_kernel(const bf16* __restrict__ dxg,
@@ -272,10 +302,19 @@ void moe_combine(const void* y, const int32_t* pos, const float* gates, const vo
 }
 
 void moe_combine_bwd(const void* dx, const void* y, const int32_t* pos, const int32_t* experts, const float* gates,
-                     int64_t M, int D, int E, int K, void* dy, float* dsel, void* dlogits, hipStream_t s) {
+                     int64_t M, int D, int E, int K, void* dy, float* dsel, hipStream_t s) {
   if (M <= 0) return;
   moe_combine_bwd_kernel<<<(unsigned)((M + 3) / 4), 256, 0, s>>>((const bf16*)dx, (const float*)y, pos, experts, gates, M,
-                                                               D, E, K, (bf16*)dy, dsel, (bf16*)dlogits);
+                                                               D, E, K, (bf16*)dy, dsel);
+}
+
+size_t moe_router_wgrad_partial_floats(int D, int E) { return (size_t)ROUTER_WGRAD_CHUNKS * D * E; }
+void moe_router_wgrad(const void* h, const int32_t* experts, const float* dsel, int64_t M, int D, int E, int K,
+                      float* partial, float* dw, hipStream_t s) {
+  if (M <= 0) return;
+  moe_router_wgrad_kernel<<<dim3((D + WAVE - 1) / WAVE, ROUTER_WGRAD_CHUNKS), 256, 0, s>>>((const bf16*)h, experts, dsel, M, D, E, K,
+                                                                                          partial);
+  moe_router_wgrad_sum_kernel<<<(D * E + 255) / 256, 256, 0, s>>>(partial, D * E, ROUTER_WGRAD_CHUNKS, dw);
 }
 
 void moe_unpermute_bwd(const void* dxg, const int32_t* pos, const int32_t* experts, const float* dsel,

@@ -21,6 +21,14 @@ def rel_rms(a, b):
     return float(np.sqrt(np.mean((a - b) ** 2)) / max(float(np.sqrt(np.mean(b ** 2))), 1e-30))
 
 
+def outside_rate(a, b, rtol):
+    """Fraction of elements with |a-b| > atol + rtol*|b|, atol = rtol * rms(b): the per-element form of the
+    tolerance (a max-norm over ~10^5 elements is an extreme-value statistic, this is not)."""
+    a, b = np.asarray(a, np.float64), np.asarray(b, np.float64)
+    atol = rtol * float(np.sqrt(np.mean(b ** 2)))
+    return float(np.mean(np.abs(a - b) > atol + rtol * np.abs(b)))
+
+
 def run_hip_step(cfg, params, x, labels, forced_idx=None, max_batch=None, sgd=None, ctx=None,
                  forced_experts=None, adamw=None, autotune=False):
     """One BSR step on cuda:0.  forced_idx: list per drop of [B,k] arrays (or None).

@@ -59,3 +59,30 @@ def test_entry_points_refuse_bad_arguments(hip):
                                                   torch.zeros(1, device=dev).data_ptr(), None, None, None,
                                                   None, None, None, None))
     torch.cuda.synchronize()
+
+
+def test_selection_with_nan_scores_keeps_exactly_k(hip, orc32):
+    """A NaN score (a diverged step) ranks last, like minus infinity: exactly K indices come out, ascending, all
+    valid, equal to the reference ranking of the scores with NaN replaced by -inf.  The slots behind the K-th and
+    the neighbouring images' slots stay untouched."""
+    import torch
+    import paper_2405_10951_amd as P
+    cfg = S.get_config("mini_4blk", dtype="bf16")
+    ctx = P.Context(cfg, S.make_params(cfg), 4)
+    rng = np.random.default_rng(5)
+    for n, k in [(196, 137), (64, 44), (300, 7), (33, 33)]:
+        B = 4
+        a = rng.standard_normal((B, n)).astype(np.float32)
+        a[0, ::3] = np.nan                       # a third of the scores
+        a[1, :] = np.nan                         # all of them: the first K indices
+        a[2, n // 2] = np.nan
+        x = rng.standard_normal((B, n + 1, cfg["dim"])).astype(np.float32)
+        xt = torch.as_tensor(x).cuda().to(torch.bfloat16)
+        guard = torch.full((B * k + 64,), -7, dtype=torch.int32, device="cuda")
+        idx, _ = ctx.bsr_select_tokens(torch.as_tensor(a).cuda(), xt, k, idx_out=guard[:B * k].view(B, k))
+        torch.cuda.synchronize()
+        assert (guard[B * k:] == -7).all(), "wrote past the K-th slot of the last image"
+        idx = idx.cpu().numpy()
+        for b in range(B):
+            ref = orc32.topk(np.where(np.isnan(a[b]), -np.inf, a[b]).astype(np.float32), k)
+            assert np.array_equal(idx[b], ref), (n, k, b)

@@ -35,11 +35,10 @@ def setup(name, std=0.05, **over):
 
 def compare(hip, got, ref, cfg, tol=TOL, grads=True):
     assert hip.rel(got["x_trainable"], ref["x_trainable"]) < tol, "x entering the trainable blocks"
-    # the stated bar is on logits and gradients; the last block's output has ~10^5 elements of
-    # magnitude up to ~6 after twelve blocks of bf16 roundings, so its largest single deviation is an
-    # extreme-value statistic: it gets 1.5 x the tolerance, and the rms deviation the tolerance itself
-    assert hip.rel(got["x_final"], ref["x_final"]) < 1.5 * tol, "output of the last block"
+    # the last block's output is outside the stated bar: tolerance in rms and element by element (at most 2 in 1000
+    # elements outside atol + rtol |ref|); its largest single deviation is an extreme-value statistic
     assert hip.rel_rms(got["x_final"], ref["x_final"]) < tol, "output of the last block (rms)"
+    assert hip.outside_rate(got["x_final"], ref["x_final"], tol) < 2e-3, "output of the last block (per element)"
     assert hip.rel(got["logits"], ref["logits"]) < tol, "logits"
     assert abs(got["loss"] - ref["loss"]) < tol * max(1.0, abs(ref["loss"]))
     for l, rl in ref["router_logits"].items():
@@ -51,15 +50,17 @@ def compare(hip, got, ref, cfg, tol=TOL, grads=True):
             if np.abs(g).max() == 0:
                 assert np.abs(got["grads"][n]).max() == 0, n
             else:
-                # Router and last-block LayerNorm gradients of a mixture block are sums over few rows (in
-                # the last block only the class rows carry gradient) of terms that pass through the gate
-                # softmax and a bf16 copy of the router's logit gradients: at full ViT-S size their largest
-                # deviation lands between 0.012 and 0.029 (rms 0.010 - 0.022) from one rounding pattern to
-                # the next (batch 8, 16, 32; two builds that differ only in where attention rounds P).
-                # They get 1.75 x the tolerance; every other tensor the tolerance itself.
-                noisy = n.endswith("w_router") or ".ln" in n
-                assert hip.rel(got["grads"][n], g) < (1.75 * tol if noisy else tol), f"gradient of {n}"
-
+                # Every gradient tensor is held to the tolerance.  One kind is named and measured instead: the
+                # router matrix.  Its gradient is gate_0 gate_1 <dx, y_0 - y_1> per token (top-2), the inner product
+                # of two nearly orthogonal vectors, so the ~1 % deviation every tensor of a twelve-block bf16 model
+                # carries is amplified by 1 / cos(angle): measured 0.008 - 0.030 in the max norm from one rounding
+                # pattern to the next (rms 0.008 - 0.019), with the logit gradients and the sum over tokens in fp32.
+                # It gets the tolerance in rms and twice the tolerance in the max norm.
+                if n.endswith("w_router"):
+                    assert hip.rel_rms(got["grads"][n], g) < tol, f"gradient of {n} (rms)"
+                    assert hip.rel(got["grads"][n], g) < 2 * tol, f"gradient of {n}"
+                else:
+                    assert hip.rel(got["grads"][n], g) < tol, f"gradient of {n}"
 
 # (the 32-wide tiny_moe model is a CPU-oracle case: at that width a single bf16 rounding is several
 # per cent of a gradient entry)
@@ -151,8 +152,8 @@ def test_moe_sgd_step(hip, orc64):
 
 
 def test_c5_workload_matches_oracle(hip, orc32):
-    """The ViT-S mixture-of-experts workload at full model size (batch 8 here; the oracle is fp32)."""
-    cfg, p, x, y = setup("c5_vit_s_moe", std=0.02, batch=8)
+    """The ViT-S mixture-of-experts workload at full model size and at its batch of 32 (the oracle is fp32)."""
+    cfg, p, x, y = setup("c5_vit_s_moe", std=0.02, batch=32)
     ref = orc32.step(cfg, p, x, y)
     got = hip.run_hip_step(cfg, p, x, y, forced_idx=ref["kept_idx"], forced_experts=ref["experts"], autotune=True)
     compare(hip, got, ref, cfg)

@@ -41,11 +41,12 @@ def check_step(hip, orc, cfg, params, x, y, tol, free_running, gap=1e-5, grad_fl
     if free_running and not all_match:
         return got, ref, False          # later tensors legitimately differ after a near-tie flip
     assert hip.rel(got["x_trainable"], ref["x_trainable"]) < tol, "x entering the trainable blocks"
-    # the stated bar is on logits and gradients; the last block's output has ~10^5 elements of
-    # magnitude up to ~6 after twelve blocks of bf16 roundings, so its largest single deviation is an
-    # extreme-value statistic: it gets 1.5 x the tolerance, and the rms deviation the tolerance itself
-    assert hip.rel(got["x_final"], ref["x_final"]) < 1.5 * tol, "output of the last block"
+    # The stated bar is on logits and gradients.  The last block's output (~10^5 - 10^6 elements up to |7| after
+    # twelve blocks of bf16 roundings, rms deviation 0.5 - 0.9 % of its rms) is held to the tolerance in rms and
+    # element by element: at most 2 in 1000 elements outside atol + rtol |ref| (atol = rtol * rms(ref)); its single
+    # largest deviation is an extreme-value statistic of that many draws and is not asserted.
     assert hip.rel_rms(got["x_final"], ref["x_final"]) < tol, "output of the last block (rms)"
+    assert hip.outside_rate(got["x_final"], ref["x_final"], tol) < 2e-3, "output of the last block (per element)"
     if cfg["num_classes"]:
         assert hip.rel(got["logits"], ref["logits"]) < tol, "logits"
     assert abs(got["loss"] - ref["loss"]) < tol * max(1.0, abs(ref["loss"]))
@@ -463,6 +464,18 @@ def test_headline_workload_full_size(hip, orc32):
     for b in range(32):
         assert np.array_equal(free["kept_idx"][0][b], orc32.topk(free["scores"][0][b], 137))
         assert len(set(free["kept_idx"][0][b]) & set(ref["kept_idx"][0][b])) >= 130
+
+
+def test_frozen_layernorm_fold_option(hip, orc64):
+    """fold_frozen_layernorm = 1: the LayerNorms of the frozen prefix ride inside the qkv / fc1 products.  Same step
+    within the tolerance (forced indices), and the same x entering the trainable blocks as without the option up
+    to the rounding of one LayerNorm output."""
+    cfg, p, x, y = bf16_setup("c2_deit_s", batch=4, fold_frozen_layernorm=1)
+    got, ref, ok = check_step(hip, orc64, cfg, p, x, y, TOL_BF16, free_running=False)
+    assert ok
+    plain = hip.run_hip_step(dict(cfg, fold_frozen_layernorm=0), p, x, y, forced_idx=ref["kept_idx"])
+    assert not np.array_equal(plain["x_trainable"], got["x_trainable"]), "the option changed nothing: was it used?"
+    assert hip.rel(plain["x_trainable"], got["x_trainable"]) < TOL_BF16
 
 
 # ------------------------------------------------------------------ batch 128: the shape sweep of the ablations
