@@ -84,19 +84,22 @@ def time_steps(ctx, cfg, batch, steps, warmup, profile_steps=0, autotune=True, p
         wall = time.perf_counter() - t0
         return dict(wall_s=wall, ms_per_step=1e3 * wall / steps, ms_per_step_events=e0.elapsed_time(e1) / steps)
 
-    seq = timed(run_sequential)
-    prof = None
-    if profile_steps:          # per-launch event brackets, one step after the other (a launch alone on the GPU)
+    def bracketed(run):        # per-launch event brackets of the GEMM / attention launches over profile_steps steps
         ctx.bsr_profile_begin()
-        run_sequential(profile_steps)
+        run(profile_steps)
+        torch.cuda.synchronize()
         prof = ctx.bsr_profile_end()
-        prof = {k: (v[0] / profile_steps, v[1] / profile_steps, v[2] // profile_steps) for k, v in prof.items()}
+        return {k: (v[0] / profile_steps, v[1] / profile_steps, v[2] // profile_steps) for k, v in prof.items()}
+
+    seq = timed(run_sequential)
+    prof_seq = bracketed(run_sequential) if profile_steps else None
     has_prefix = (cfg.get("trainable_blocks") or [cfg["first_trainable"]])[0] > 0
-    best, tuned_overlapped, tiles = seq, None, "chosen launch by launch, each timed alone"
+    best, tuned_overlapped, tiles, prof_best = seq, None, "chosen launch by launch, each timed alone", prof_seq
     if pipeline and has_prefix:
         piped = timed(run_pipelined)                   # with the tile shapes chosen above
         if piped["ms_per_step"] < best["ms_per_step"]:
             best = piped
+            prof_best = bracketed(run_pipelined) if profile_steps else None
         if autotune:           # tile shapes chosen again, now with the two parts of the step side by side
             torch.cuda.synchronize()
             with torch.cuda.stream(s_frozen):
@@ -105,12 +108,15 @@ def time_steps(ctx, cfg, batch, steps, warmup, profile_steps=0, autotune=True, p
             piped2 = timed(run_pipelined)
             if piped2["ms_per_step"] < best["ms_per_step"]:
                 best, tiles = piped2, "one shape for every launch, chosen by timing the two parts side by side"
-    return dict(best, pipelined=best is not seq, tiles=tiles, sequential=seq, loss=float(loss[0].item()), prof=prof,
-                tuned=tuned, tuned_overlapped=tuned_overlapped)
+                prof_best = bracketed(run_pipelined) if profile_steps else None
+    return dict(best, pipelined=best is not seq, tiles=tiles, sequential=seq, loss=float(loss[0].item()), prof=prof_best,
+                prof_sequential=prof_seq, tuned=tuned, tuned_overlapped=tuned_overlapped)
 
 
-def cpu_baseline(cfg, sample_batch):
-    """The oracle as it stands (float build, OpenMP), one full step on a bounded sample."""
+def cpu_baseline(cfg, sample_batch, one_thread=True):
+    """The oracle as it stands (float build, OpenMP over images), one full step of the same workload on all host
+    cores, and once more on a single thread (in a child process: the thread count is fixed when OpenMP starts)."""
+    import subprocess
     import bsr_synth as S
     from oracle import Oracle
     orc = Oracle("f32")
@@ -120,15 +126,30 @@ def cpu_baseline(cfg, sample_batch):
     r = orc.step(cfg, p, x, y)
     dt = time.perf_counter() - t0
     cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
-    return dict(value=sample_batch / dt, unit="images/sec", cores=cores, kind="oracle",
-                sample=f"one full step (frozen forward, selection, trainable fwd+bwd) of the same "
-                       f"workload on {sample_batch} of the {cfg['batch']} images, fp32 C oracle with "
-                       f"OpenMP, {dt:.1f} s", loss=r["loss"])
+    out = dict(value=sample_batch / dt, unit="images/sec", cores=cores, kind="oracle",
+               sample=f"one full step (frozen forward, selection, trainable fwd+bwd) of the same workload on "
+                      f"{sample_batch} of the {cfg['batch']} images, fp32 C oracle with OpenMP, {dt:.1f} s", loss=r["loss"])
+    if one_thread:
+        code = ("import sys, time, json; sys.path.insert(0, %r); import bsr_synth as S; from oracle import Oracle\n"
+                "cfg = json.loads(sys.argv[1]); n = int(sys.argv[2]); orc = Oracle('f32'); p = S.make_params(cfg)\n"
+                "x, y = S.make_inputs(cfg, batch=n); t0 = time.perf_counter(); orc.step(cfg, p, x, y)\n"
+                "print(time.perf_counter() - t0)" % ROOT)
+        n1 = sample_batch                           # (about 20 s for the 32 images of the headline workload)
+        env = dict(os.environ, OMP_NUM_THREADS="1")
+        try:
+            res = subprocess.run([sys.executable, "-c", code, json.dumps(cfg), str(n1)], env=env, capture_output=True,
+                                 text=True, timeout=300)
+            dt1 = float(res.stdout.strip().splitlines()[-1])
+            out["one_thread"] = dict(value=n1 / dt1, unit="images/sec", cores=1,
+                                     sample=f"the same step on {n1} images, one thread, {dt1:.1f} s")
+        except Exception as e:      # noqa: BLE001  (the baseline is context, never a reason to lose the line)
+            out["one_thread"] = dict(value=None, error=str(e)[:200])
+    return out
 
 
-def recorded_traffic():
-    """HBM bytes per GEMM launch from the committed rocprofv3 counter runs (profiles/gemm_traffic.json),
-    or None when there is no record or the GEMM source has changed since it was taken."""
+def recorded_traffic(workload, batch):
+    """HBM bytes per GEMM launch from the committed rocprofv3 counter runs (profiles/gemm_traffic.json), or None
+    when there is no record for this workload and batch or the GEMM source has changed since it was taken."""
     import hashlib
     rec = os.path.join(ROOT, "profiles", "gemm_traffic.json")
     src = os.path.join(ROOT, "paper_2405_10951_amd", "csrc", "k_gemm_mfma.hip")
@@ -136,11 +157,34 @@ def recorded_traffic():
         with open(rec) as f:
             d = json.load(f)
         with open(src, "rb") as f:
-            if hashlib.sha256(f.read()).hexdigest() != d["kernel_source_sha256"]:
-                return None
-        return d["hbm_bytes_per_launch"]
+            sha = hashlib.sha256(f.read()).hexdigest()
+        e = d.get("records", {}).get(f"{workload}/batch{batch}")
+        if not e or e.get("kernel_source_sha256") != sha:
+            return None
+        return e["hbm_bytes_per_launch"]
     except (OSError, KeyError, ValueError):
         return None
+
+
+def sweep_c4(P, S, step_flops_of, steps, warmup):
+    """The shape sweep of the ablation tables at batch 128: keep ratio x number of trained blocks, one step after
+    the other on one stream (with every block trained there is no frozen prefix to run ahead)."""
+    import torch
+    points = []
+    for keep in (1.0, 0.7, 0.5):
+        for trainable in (12, 4, 2):
+            cfg = S.get_config("c3_vit_b", batch=128, keep_ratio=keep, first_trainable=12 - trainable)
+            ctx = build_context(cfg, 128)
+            r = time_steps(ctx, cfg, 128, steps, warmup, profile_steps=min(steps, 3), autotune=True, pipeline=False)
+            fl = step_flops_of(cfg, ctx, 128)
+            gemm_ms, gemm_flops, _ = r["prof"]["gemm"]
+            points.append({"keep_ratio": keep, "trainable_blocks": trainable, "ms_per_step": r["ms_per_step"],
+                           "images_per_sec": 128 * steps / r["wall_s"], "step_gflop": fl["total"] / 1e9,
+                           "step_pct_of_bf16_mfma_peak": 100.0 * fl["total"] / (r["ms_per_step"] * 1e-3) / (PEAK_BF16_TFLOPS * 1e12),
+                           "gemm_tflops_event_bracketed": gemm_flops / (gemm_ms * 1e-3) / 1e12})
+            del ctx
+            torch.cuda.empty_cache()
+    return points
 
 
 def main():
@@ -157,7 +201,9 @@ def main():
     ap.add_argument("--no-compare", action="store_true", help="skip the keep-1.0 / full-fine-tuning legs")
     ap.add_argument("--no-pipeline", action="store_true",
                     help="time the steps one after the other only (no overlap of the next batch's frozen forward)")
-    ap.add_argument("--cpu-sample", type=int, default=16)
+    ap.add_argument("--cpu-sample", type=int, default=None, help="images of the cpu_baseline leg (default: the whole batch)")
+    ap.add_argument("--no-sweep", action="store_true", help="skip the batch-128 sweep keep ratio x trained blocks")
+    ap.add_argument("--sweep-steps", type=int, default=5)
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 256 MiB device copy (reference for the HBM byte counters)")
     args = ap.parse_args()
@@ -180,10 +226,10 @@ def main():
     batch = args.batch or cfg["batch"]
     cfg["batch"] = batch
 
-    def flops_of(c, ctx):
+    def flops_of(c, ctx, nb=None):
         pd = c["in_chans"] * c["patch_size"] ** 2
         return step_flops(c["dim"], c["mlp_hidden"], c["num_classes"], pd, ctx.tokens_attn[0] - 1,
-                          ctx.tokens_attn, ctx.tokens_mlp, c["first_trainable"], batch,
+                          ctx.tokens_attn, ctx.tokens_mlp, c["first_trainable"], nb or batch,
                           moe_blocks=tuple(c.get("moe_blocks", ())), n_experts=c.get("n_experts", 0),
                           moe_top_k=c.get("moe_top_k", 0), trainable_blocks=c.get("trainable_blocks"))
 
@@ -192,10 +238,19 @@ def main():
                    autotune=not args.no_autotune, pipeline=not args.no_pipeline)
     fl = flops_of(cfg, ctx)
     ips = batch * args.steps / r["wall_s"]
-    gemm_ms, gemm_flops, gemm_n = r["prof"]["gemm"]
     bf16 = cfg["dtype"] == "bf16"
     peak = PEAK_BF16_TFLOPS if bf16 else PEAK_FP32_TFLOPS
-    achieved = gemm_flops / (gemm_ms * 1e-3) / 1e12
+
+    def roof(prof, schedule):
+        """The GEMM launches of a step as one kernel class: flops launched / summed launch durations (HIP events
+        recorded by the library around every launch, on the stream it is launched on)."""
+        gemm_ms, gemm_flops, gemm_n = prof["gemm"]
+        achieved = gemm_flops / (gemm_ms * 1e-3) / 1e12
+        return {"bound": "mfma", "kernel": "GEMM launches of the step (forward, dgrad, wgrad)", "schedule": schedule,
+                "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak, "traffic": None,
+                "launches_per_step": gemm_n, "ms_per_step": gemm_ms, "gflop_per_step": gemm_flops / 1e9}
+
+    sched_best = "pipelined (two streams)" if r["pipelined"] else "sequential (one stream)"
     out = {
         "metric": "BSR train images/sec, ViT-B/16 bs32 on 1 MI355X; % bf16 MFMA peak",
         "value": ips, "unit": "images/sec", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -222,13 +277,15 @@ def main():
         "tile_autotune": None if r["tuned"] is None else {"launches": r["tuned"][0], "differ_from_cost_model": r["tuned"][1]},
         "tile_autotune_overlapped": None if r["tuned_overlapped"] is None else
         {"launches": r["tuned_overlapped"][0], "differ_from_cost_model": r["tuned_overlapped"][1]},
-        "roofline": {"bound": "mfma", "kernel": "GEMM launches of the step (forward, dgrad, wgrad)",
-                     "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak,
-                     "traffic": None, "launches_per_step": gemm_n, "ms_per_step": gemm_ms,
-                     "gflop_per_step": gemm_flops / 1e9},
+        # the roofline of the schedule that produced `value`; beside it the same figure for one step after the
+        # other on one stream, where a launch has the GPU to itself (side by side, launches stretch each other)
+        "roofline": roof(r["prof"], sched_best),
+        "roofline_sequential": roof(r["prof_sequential"], "sequential (one stream)"),
         "kernel_classes_ms_per_step": {k: v[0] for k, v in r["prof"].items()},
     }
-    out["roofline"]["traffic"] = recorded_traffic()
+    out["roofline_sequential"]["traffic"] = recorded_traffic(args.workload, batch)
+    if not r["pipelined"]:
+        out["roofline"]["traffic"] = out["roofline_sequential"]["traffic"]
     if args.calibrate_copy:
         a = torch.empty(64 << 20, dtype=torch.float32, device="cuda").normal_()
         b = torch.empty_like(a)
@@ -249,8 +306,11 @@ def main():
             out[key + "_algorithmic"] = flops_of(c2, ctx2)["total"] / fl["total"]
             del ctx2
             torch.cuda.empty_cache()
+    if not args.no_sweep and args.workload == "c3_vit_b" and batch == 32:
+        out["sweep"] = {"workload": "c3_vit_b at batch 128, keep ratio x trained blocks (suffix), sequential schedule",
+                        "points": sweep_c4(P, S, flops_of, args.sweep_steps, 2)}
     if not args.no_cpu:
-        out["cpu_baseline"] = cpu_baseline(cfg, min(args.cpu_sample, batch))
+        out["cpu_baseline"] = cpu_baseline(cfg, min(args.cpu_sample or batch, batch))
     print(json.dumps(out))
 
 

@@ -69,8 +69,8 @@ typedef struct {
   int32_t keep_k[BSR_MAX_BLOCKS];           /* patch tokens kept at each drop (CLS is kept on top).
                                                If all entries are 0 they are derived from
                                                keep_ratio as floor(keep_ratio * n + 1e-9) on the
-                                               current patch count n (Sec. 4.1: "K determined by
-                                               the token drop rate"; keep_ratio = 1 - drop rate)   */
+                                               current patch count n (Sec. 4.1: K follows from the
+                                               drop rate; keep_ratio = 1 - drop rate)              */
   float keep_ratio;                         /* 0 < r <= 1; only read when keep_k is all 0          */
   int32_t first_trainable_block;            /* blocks [first, depth), the final LayerNorm and the
                                                head are trained; blocks before it are frozen and
@@ -92,7 +92,7 @@ typedef struct {
    * the gradient / momentum tables may be NULL. */
   int32_t n_trainable;
   int32_t trainable_blocks[BSR_MAX_BLOCKS]; /* strictly ascending block indices                    */
-  /* Sec. 4.1: "the unimportant ones are fused and passed onto the subsequent FFN layer".  1: a drop
+  /* Sec. 4.1 merges the tokens ranked unimportant into one token for the FFN that follows.  1: a drop
    * location that drops at least one token appends one more token after the kept ones, the
    * importance-weighted average of the dropped tokens (weights = their scores divided by the sum of
    * the dropped scores; constants of the backward pass, like the kept indices).  It is a patch token
@@ -271,6 +271,18 @@ int32_t bsr_autotune(bsr_ctx* ctx, const void* input, const int32_t* labels, int
 int32_t bsr_autotune_overlapped(bsr_ctx* ctx, const void* input, const int32_t* labels, int32_t B, void* x_frozen,
                                 void* x_side, float* loss_out, const bsr_params* grads, int32_t* launches_out,
                                 int32_t* changed_out, void* stream, void* side_stream);
+
+/*
+ * The tile choices a context holds after bsr_autotune / bsr_autotune_overlapped, for inspection and reports (host
+ * only).  part 0: the launches of bsr_forward_frozen in launch order, part 1: those of bsr_train_blocks_fwd_bwd
+ * (a backward launch carries the input gradient named here and, fused with it, the weight gradient of its layer).
+ *   rows, out, in  the product: rows x in times in x out      tile  shape id (see bsr_gemm_tile_shapes)
+ *   microseconds   what bsr_autotune measured for that shape at that launch (0 after bsr_autotune_overlapped,
+ *                  which times whole passes)
+ * Returns the number of launches of that part (0 without a choice or with bad arguments); writes at most max.
+ */
+typedef struct { int32_t rows, out, in, tile; float microseconds; } bsr_tile_choice;
+int32_t bsr_tile_choices(const bsr_ctx* ctx, int32_t part, bsr_tile_choice* choices_out, int32_t max);
 
 /*
  * Routing of the mixture-of-experts blocks (Sec. 5.3), for tests and inspection.  Per token the K

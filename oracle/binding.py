@@ -48,6 +48,17 @@ def build_oracle(force: bool = False) -> None:
         subprocess.run(cmd, check=True)
 
 
+def build_oracle_sanitized(out_dir: str) -> None:
+    """Both precisions with gcc's AddressSanitizer and UndefinedBehaviorSanitizer, into out_dir (load them with
+    gcc's libasan and libubsan preloaded)."""
+    os.makedirs(out_dir, exist_ok=True)
+    for prec, real in (("f64", "double"), ("f32", "float")):
+        cmd = ["gcc", "-O1", "-g", "-fno-omit-frame-pointer", "-fsanitize=address,undefined", "-march=x86-64-v3",
+               "-fopenmp", "-fPIC", "-shared", "-std=c11", f"-DREAL={real}", "-o",
+               os.path.join(out_dir, f"libbsr_oracle_{prec}.so"), _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+
+
 class _Config(C.Structure):
     _fields_ = [("image_size", C.c_int32), ("patch_size", C.c_int32), ("in_chans", C.c_int32),
                 ("tokens_in", C.c_int32), ("dim", C.c_int32), ("heads", C.c_int32),

@@ -37,6 +37,11 @@ class bsr_config(C.Structure):
                 ("fuse_dropped", C.c_int32), ("fold_frozen_layernorm", C.c_int32)]
 
 
+class bsr_tile_choice(C.Structure):
+    _fields_ = [("rows", C.c_int32), ("out", C.c_int32), ("in_", C.c_int32), ("tile", C.c_int32),
+                ("microseconds", C.c_float)]
+
+
 class bsr_block_params(C.Structure):
     _fields_ = [(f, C.c_void_p) for f in BLOCK_FIELDS] + [("w_router", C.c_void_p)]
 
@@ -90,6 +95,8 @@ def load_library():
                                    C.c_float, C.c_float, C.c_int32, C.c_void_p]
     lib.bsr_autotune.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
                                  C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.bsr_tile_choices.restype = C.c_int32
+    lib.bsr_tile_choices.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_int32]
     lib.bsr_autotune_overlapped.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
                                             C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
     lib.bsr_pipeline_step.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p,
@@ -446,6 +453,13 @@ class Context:
         self._chk(self.lib.bsr_autotune(self.ctx, _dp(inp), _dp(labels), C.c_int32(inp.shape[0]), _dp(x_frozen),
                                         _dp(loss_out), C.byref(gs), C.byref(n), C.byref(ch), self._stream()))
         return int(n.value), int(ch.value)
+
+    def bsr_tile_choices(self, part: int):
+        """[(rows, out, in, tile, microseconds)] of the launches of part 0 (frozen prefix) or 1 (trainable part)."""
+        n = self.lib.bsr_tile_choices(self.ctx, part, None, 0)
+        buf = (bsr_tile_choice * max(n, 1))()
+        self.lib.bsr_tile_choices(self.ctx, part, buf, n)
+        return [(b.rows, b.out, b.in_, b.tile, b.microseconds) for b in buf[:n]]
 
     def bsr_pipeline_step(self, inp_next, x_next, x_cur, labels_cur, loss_out, grads: dict, momenta: dict | None, lr: float,
                           momentum: float, weight_decay: float, stream_frozen, stream_train):

@@ -93,7 +93,7 @@ struct ProfRec {
 
 // Tile choice per NT GEMM launch, measured on the context's own launches (bsr_autotune).  A launch is
 // identified by the entry point it belongs to and its position in that call's launch order.
-struct TunePick { int M, N, K, tile; };
+struct TunePick { int M, N, K, tile; float us; };   // us: the chosen shape's measured time (0: not measured)
 struct TuneRec { int kind, cand; size_t site; int M, N, K; hipEvent_t start, stop; };
 struct Tune {
   int batch = 0;                       // the picks hold for this batch size (0: none)
@@ -1303,7 +1303,7 @@ static int32_t autotune_overlapped(bsr_ctx* c, const void* input, const int32_t*
     size_t sites[2] = {0, 0};
     for (const TuneRec& r : t.recs) sites[r.kind] = std::max(sites[r.kind], r.site + 1);
     for (int k = 0; k < 2; ++k) {
-      t.pick[k].assign(sites[k], TunePick{0, 0, 0, 0});
+      t.pick[k].assign(sites[k], TunePick{0, 0, 0, 0, 0.f});
       for (const TuneRec& r : t.recs) {
         if (r.kind != k) continue;
         TunePick& p = t.pick[k][r.site];
@@ -1358,7 +1358,7 @@ static int32_t autotune(bsr_ctx* c, const void* input, const int32_t* labels, in
     for (const TuneRec& r : t.recs) sites[r.kind] = std::max(sites[r.kind], r.site + 1);
     for (int k = 0; k < 2; ++k) {
       std::vector<float> best(sites[k] * n, -1.f);          // min over the rounds, per (site, shape)
-      t.pick[k].assign(sites[k], TunePick{0, 0, 0, 0});
+      t.pick[k].assign(sites[k], TunePick{0, 0, 0, 0, 0.f});
       for (const TuneRec& r : t.recs) {
         if (r.kind != k) continue;
         float ms = 0.f;
@@ -1373,6 +1373,7 @@ static int32_t autotune(bsr_ctx* c, const void* input, const int32_t* labels, in
         for (int j = 0; j < n; ++j)
           if (best[i * n + j] >= 0.f && (arg < 0 || best[i * n + j] < best[i * n + arg])) arg = j;
         t.pick[k][i].tile = arg < 0 ? 0 : gemm_nt_tile_id(arg);
+        t.pick[k][i].us = arg < 0 ? 0.f : best[i * n + arg] * 1e3f;
         ++launches;
       }
     }
@@ -1401,6 +1402,15 @@ int32_t bsr_autotune(bsr_ctx* c, const void* input, const int32_t* labels, int32
                      void* stream) {
   if (!c) return fail(nullptr, BSR_ERR_INVALID_ARG, "ctx is NULL");
   return autotune(c, input, labels, B, x_frozen, loss_out, grads, launches_out, changed_out, stream);
+}
+
+int32_t bsr_tile_choices(const bsr_ctx* c, int32_t part, bsr_tile_choice* out, int32_t max) {
+  if (!c || part < 0 || part > 1) return 0;
+  const std::vector<TunePick>& v = c->tune.pick[part];
+  for (size_t i = 0; out && i < v.size() && (int32_t)i < max; ++i) {
+    out[i].rows = v[i].M; out[i].out = v[i].N; out[i].in = v[i].K; out[i].tile = v[i].tile; out[i].microseconds = v[i].us;
+  }
+  return (int32_t)v.size();
 }
 
 int32_t bsr_autotune_overlapped(bsr_ctx* c, const void* input, const int32_t* labels, int32_t B, void* x_frozen,

@@ -1,7 +1,7 @@
 """Turn two rocprofv3 --pmc runs of bench.py (FETCH_SIZE, then WRITE_SIZE; both with
 --calibrate-copy) into the HBM bytes per GEMM launch that bench.py reports as roofline.traffic.
 
-    python -m paper_2405_10951_amd.traffic <fetch_counter_collection.csv> <write_counter_collection.csv> [steps]
+    python -m paper_2405_10951_amd.traffic <fetch_counter_collection.csv> <write_counter_collection.csv> [steps] [workload/batchN]
 
 Only the GEMM launches of the last `steps` steps count (default 7 = 1 warm-up + 3 timed + 3 bracketed steps
 of `bench.py --steps 3 --warmup 1`): the tile-tuning passes before them launch other tile shapes.
@@ -33,12 +33,12 @@ def per_kernel(path: str, counter: str, last_steps: int):
     rows.sort()
     starts = [i for i, r in enumerate(rows) if "patchify" in r[1]]
     first = starts[-last_steps] if 0 < last_steps <= len(starts) else 0
-    gemm = [v for _, n, v in rows[first:] if "gemm_nt_kernel" in n or "gemm_tn_kernel" in n]
+    gemm = [v for _, n, v in rows[first:] if "gemm_nt_kernel" in n or "gemm_ntd_kernel" in n or "gemm_tn_kernel" in n]
     copy = [v for _, n, v in rows if "copybuffer" in n.lower()]    # the runtime's plain device-to-device copy kernel
     return gemm, copy
 
 
-def main(fetch_csv: str, write_csv: str, last_steps: int = 7) -> None:
+def main(fetch_csv: str, write_csv: str, last_steps: int = 7, key: str = "c3_vit_b/batch32") -> None:
     gf, cf = per_kernel(fetch_csv, "FETCH_SIZE", last_steps)
     gw, cw = per_kernel(write_csv, "WRITE_SIZE", last_steps)
     if not (gf and gw and cf and cw):
@@ -56,10 +56,19 @@ def main(fetch_csv: str, write_csv: str, last_steps: int = 7) -> None:
            "bytes_per_counter_unit_fetch": scale_f, "bytes_per_counter_unit_write": scale_w,
            "kernel_source_sha256": sha}
     out = os.path.join(ROOT, "profiles", "gemm_traffic.json")
+    try:
+        with open(out) as f:
+            allrec = json.load(f)
+        if "records" not in allrec:
+            allrec = {"records": {}}
+    except (OSError, ValueError):
+        allrec = {"records": {}}
+    allrec["records"][key] = rec          # one record per workload and batch: bench.py looks its own up
     with open(out, "w") as f:
-        json.dump(rec, f, indent=1)
+        json.dump(allrec, f, indent=1)
     print(json.dumps(rec))
 
 
 if __name__ == "__main__":
-    main(sys.argv[1], sys.argv[2], int(sys.argv[3]) if len(sys.argv) > 3 else 7)
+    main(sys.argv[1], sys.argv[2], int(sys.argv[3]) if len(sys.argv) > 3 else 7,
+         sys.argv[4] if len(sys.argv) > 4 else "c3_vit_b/batch32")

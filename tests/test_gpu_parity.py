@@ -466,6 +466,78 @@ def test_headline_workload_full_size(hip, orc32):
         assert len(set(free["kept_idx"][0][b]) & set(ref["kept_idx"][0][b])) >= 130
 
 
+def test_headline_workload_through_the_timed_path(hip, orc32):
+    """The schedule bench.py times, at its size: ViT-B/16, batch 32 (Table 1's setting), tile shapes chosen by
+    bsr_autotune_overlapped, then bsr_pipeline_step over two batches A and B with the SGD step of Sec. 5 (lr 1e-3,
+    momentum 0.9, weight decay 1e-4) between them.  The loss and every gradient of the step on B, computed from
+    the weights the step on A updated, against the oracle taking the same two steps.  The oracle is given the kept
+    indices the GPU chose (free-running there; at K = 0.7 n the oracle's own k-th and (k+1)-th scores lie closer
+    than bf16 resolves), read from the same two steps made one after the other on a second context, whose
+    results the pipelined ones must equal bit for bit."""
+    import torch
+    import paper_2405_10951_amd as P
+    cfg = S.get_config("c3_vit_b")
+    batch = cfg["batch"]
+    p = S.make_params(cfg)
+    dev = torch.device("cuda:0")
+    data = [S.make_inputs(cfg, seed=sd) for sd in (11, 12)]
+    dd = [(torch.as_tensor(x).to(dev).to(torch.bfloat16).contiguous(), torch.as_tensor(y, dtype=torch.int32).to(dev))
+          for x, y in data]
+    hyp = dict(lr=1e-3, momentum=0.9, weight_decay=1e-4)
+
+    # one step after the other, with the kept indices and the logits read out
+    ctx_s = P.Context(cfg, p, batch)
+    mom_s = {n: torch.zeros_like(t) for n, t in ctx_s.new_grads().items()}
+    seq_a = hip.run_hip_step(cfg, p, *data[0], ctx=ctx_s, sgd=dict(momenta=mom_s, **hyp))
+    seq_b = hip.run_hip_step(cfg, p, *data[1], ctx=ctx_s, sgd=dict(momenta=mom_s, **hyp))
+
+    # the timed path
+    ctx = P.Context(cfg, p, batch)
+    grads = ctx.new_grads()
+    mom = {n: torch.zeros_like(g) for n, g in grads.items()}
+    xf = [torch.empty((batch, ctx.T_f, cfg["dim"]), dtype=torch.bfloat16, device=dev) for _ in range(2)]
+    losses = torch.zeros((3, 4), dtype=torch.float32, device=dev)
+    cur = torch.cuda.current_stream()
+    sa, sb = torch.cuda.Stream(), torch.cuda.Stream()
+    launches, _ = ctx.bsr_autotune_overlapped(dd[0][0], dd[0][1], xf[0], xf[1], losses[2], ctx.new_grads(), sa)
+    assert launches == 65
+    torch.cuda.synchronize()
+    sa.wait_stream(cur); sb.wait_stream(cur)
+    args = dict(grads=grads, momenta=mom, stream_frozen=sa, stream_train=sb, **hyp)
+    ctx.bsr_pipeline_step(dd[0][0], xf[0], None, None, losses[0], **args)
+    ctx.bsr_pipeline_step(dd[1][0], xf[1], xf[0], dd[0][1], losses[0], **args)
+    ctx.bsr_pipeline_step(None, None, xf[1], dd[1][1], losses[1], **args)
+    cur.wait_stream(sa); cur.wait_stream(sb)
+    torch.cuda.synchronize()
+    got_loss = losses[:2, 0].cpu().numpy()
+    got_grads = {n: g.cpu().numpy() for n, g in grads.items()}
+    assert got_loss[0] == np.float32(seq_a["loss"]) and got_loss[1] == np.float32(seq_b["loss"])
+    for n, g in got_grads.items():
+        assert np.array_equal(g, seq_b["grads"][n]), n
+    for n in ctx.trainable_names:
+        assert np.array_equal(ctx.params[n].cpu().numpy(), seq_b["new_params"][n]), n
+
+    # the oracle: step on A, the update, step on B
+    ref_a = orc32.step(cfg, p, *data[0], forced_idx=seq_a["kept_idx"])
+    p_ref, m_ref = dict(p), {n: np.zeros_like(g) for n, g in ref_a["grads"].items()}
+
+    def update(ref):
+        for n, g in ref["grads"].items():
+            w, m = orc32.sgd(p_ref[n], g, m_ref[n], hyp["lr"], hyp["momentum"], hyp["weight_decay"])
+            p_ref[n], m_ref[n] = w.reshape(p[n].shape), m.reshape(p[n].shape)
+
+    update(ref_a)
+    ref_b = orc32.step(cfg, p_ref, *data[1], forced_idx=seq_b["kept_idx"])
+    update(ref_b)
+    assert abs(got_loss[0] - ref_a["loss"]) < TOL_BF16 * abs(ref_a["loss"])
+    assert abs(got_loss[1] - ref_b["loss"]) < TOL_BF16 * abs(ref_b["loss"])
+    assert hip.rel(seq_b["logits"], ref_b["logits"]) < TOL_BF16
+    for n, g in ref_b["grads"].items():
+        assert hip.rel(got_grads[n], g) < TOL_BF16, n
+    for n in ctx.trainable_names:
+        assert hip.rel(seq_b["new_params"][n], p_ref[n]) < TOL_BF16, n
+
+
 def test_frozen_layernorm_fold_option(hip, orc64):
     """fold_frozen_layernorm = 1: the LayerNorms of the frozen prefix ride inside the qkv / fc1 products.  Same step
     within the tolerance (forced indices), and the same x entering the trainable blocks as without the option up
