@@ -783,7 +783,11 @@ __device__ __forceinline__ void tn_body(GemmDesc g, float* partial, float* bpart
   const int ntn = (g.N + BN - 1) / BN;
   const int ntiles = gx;
   const int tile = xcd_remap(bx, ntiles);
-  const int m0 = (tile / ntn) * BM, n0 = (tile % ntn) * BN;
+  // an XCD's contiguous range of tiles runs along the side with fewer tiles first, so that it spans that side
+  // and its L2 fetches the longer operand's token rows once instead of once per XCD
+  const int ntm = (g.M + BM - 1) / BM;
+  const bool mfast = ntm < ntn;
+  const int m0 = (mfast ? tile % ntm : tile / ntn) * BM, n0 = (mfast ? tile / ntm : tile % ntn) * BN;
   if (g.grp_off) {
     // grouped form: by is the group; the contraction runs over its token rows only
     const int e = by, r0 = g.grp_off[e], r1 = g.grp_off[e + 1];

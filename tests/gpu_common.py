@@ -15,6 +15,13 @@ def rel(a, b):
     return float(np.max(np.abs(a - b)) / max(float(np.max(np.abs(b))), 1e-30))
 
 
+def bf16_rne(a):
+    """fp32 -> the nearest bf16 value (ties to even), as fp32: what a bf16 copy of a weight matrix holds."""
+    u = np.ascontiguousarray(a, np.float32).view(np.uint32).astype(np.uint64)
+    r = ((u + 0x7FFF + ((u >> 16) & 1)) & 0xFFFF0000).astype(np.uint32)
+    return r.view(np.float32).reshape(np.shape(a))
+
+
 def rel_rms(a, b):
     """rms(a-b) / rms(b)"""
     a, b = np.asarray(a, np.float64), np.asarray(b, np.float64)

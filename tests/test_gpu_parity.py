@@ -473,7 +473,13 @@ def test_headline_workload_through_the_timed_path(hip, orc32):
     the weights the step on A updated, against the oracle taking the same two steps.  The oracle is given the kept
     indices the GPU chose (free-running there; at K = 0.7 n the oracle's own k-th and (k+1)-th scores lie closer
     than bf16 resolves), read from the same two steps made one after the other on a second context, whose
-    results the pipelined ones must equal bit for bit."""
+    results the pipelined ones must equal bit for bit.
+    The matrix cores multiply bf16 copies of the fp32 master matrices.  The synthetic weights are bf16 values, and
+    at this learning rate the first update moves a matrix element by about a tenth of a bf16 step, so the copies
+    after the update still hold the old values: that part of the update reaches the forward pass only once it has
+    accumulated in the master weights (the head, LayerNorms and biases are read in fp32 and move at once).  This
+    belongs to the arithmetic type, so the oracle's step on B runs at the updated matrices rounded to bf16 too;
+    with unrounded matrices its logits move by 3.7 % through the update and differ from the GPU's by 2.1 %."""
     import torch
     import paper_2405_10951_amd as P
     cfg = S.get_config("c3_vit_b")
@@ -527,7 +533,9 @@ def test_headline_workload_through_the_timed_path(hip, orc32):
             p_ref[n], m_ref[n] = w.reshape(p[n].shape), m.reshape(p[n].shape)
 
     update(ref_a)
-    ref_b = orc32.step(cfg, p_ref, *data[1], forced_idx=seq_b["kept_idx"])
+    p_b = {n: hip.bf16_rne(w) if n.rsplit(".", 1)[-1] in ("w_qkv", "w_proj", "w_fc1", "w_fc2") else w
+           for n, w in p_ref.items()}
+    ref_b = orc32.step(cfg, p_b, *data[1], forced_idx=seq_b["kept_idx"])
     update(ref_b)
     assert abs(got_loss[0] - ref_a["loss"]) < TOL_BF16 * abs(ref_a["loss"])
     assert abs(got_loss[1] - ref_b["loss"]) < TOL_BF16 * abs(ref_b["loss"])
