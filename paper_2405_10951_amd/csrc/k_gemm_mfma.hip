@@ -1163,7 +1163,9 @@ void gemm_mfma(const GemmDesc& g, float* splitk_ws, size_t splitk_ws_floats, hip
     launch_tn(g, splitk_ws, splitk_ws_floats, s, chain);
     return;
   }
-  int pick = g.grp_off ? 128128 : tile;     // groups are a few hundred rows: small tiles
+  // groups are a few hundred rows and each ends in a partial row tile: 128-row tiles, 64-row ones where a group
+  // averages under four of those (the last tile of a 268-row group is 9 % full at 128 rows, 19 % at 64)
+  int pick = g.grp_off ? (g.M < 512 * g.groups ? 64128 : 128128) : tile;
   if (!pick || (ntd_stages(pick) && !is_ntd(g))) pick = gemm_nt_model_tile(g.M, g.N, g.K);
   switch (pick) {
     case 7256256: launch_ntd<256, 256, 2, 4, 2>(g, s); break;
