@@ -560,7 +560,7 @@ __device__ __forceinline__ void epilogue_t(const GemmDesc& g, f32x16 (&acc)[MI][
 
 // (a shape whose stages take at most half of the 160 KB is held to the registers that let two workgroups share a CU)
 template <int BM, int BN, int WM, int WN, int NST>
-__global__ __launch_bounds__(WM * WN * 64, (NST * (BM + BN) * 128 <= 80 * 1024) ? 2 : 1)
+__global__ __launch_bounds__(WM * WN * 64, (NST * (BM + BN) * 128 <= 80 * 1024 && WM * WN <= 4) ? 2 : 1)
 void gemm_ntd_kernel(GemmDesc g) {
   constexpr int NT = WM * WN * 64;
   constexpr int TM = BM / WM, TN = BN / WN, MI = TM / 32, NI = TN / 32, NMF = MI * NI, NFR = MI + NI;
@@ -570,8 +570,7 @@ void gemm_ntd_kernel(GemmDesc g) {
   constexpr int STAGE = (BM + BN) * 128;            // bytes of a stage: rows of 8 chunks of 16 bytes, A rows first
   static_assert(BM % RPI == 0 && BN % RPI == 0 && RPI % 16 == 0, "a load instruction covers whole groups of 16 rows");
   static_assert(NST >= 2 && NST <= 4 && (NST - 1) * LPT <= 60, "vmcnt has 6 bits");
-  static_assert(NMF <= 16 && MI >= 1 && NI >= 1, "");
-  constexpr int RPS = (NFR + NMF - 1) / NMF;        // fragment reads behind each MFMA of a k-step
+  static_assert(NMF >= NFR && NMF <= 16 && MI >= 1 && NI >= 1, "");
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -631,10 +630,7 @@ void gemm_ntd_kernel(GemmDesc g) {
     sfor<NMF>([&](auto J) __attribute__((always_inline)) {
       constexpr int j = decltype(J)::value;
       mf1(IC<set>{}, J);
-      sfor<RPS>([&](auto R) __attribute__((always_inline)) {
-        constexpr int r = j * RPS + decltype(R)::value;
-        if constexpr (r < NFR) rd1(IC<set ^ 1>{}, IC<r>{}, st, ks);
-      });
+      if constexpr (j < NFR) rd1(IC<set ^ 1>{}, J, st, ks);
       BSR_SCHED_FENCE();
     });
   };
@@ -643,7 +639,7 @@ void gemm_ntd_kernel(GemmDesc g) {
   // count follows from rem, the number of k-tiles after this one (after the last one barrier and reads are idle).
   auto klast = [&](auto VMW, int kt, int st, int stn, int rem) __attribute__((always_inline)) {
     constexpr int vmw = decltype(VMW)::value;
-    constexpr int PRE = NMF >= 16 ? 4 : (NMF >= 8 ? 2 : (NMF >= 2 ? 1 : 0));       // MFMAs in front of the barrier
+    constexpr int PRE = NMF >= 16 ? 4 : (NMF >= 8 ? 2 : 1);       // MFMAs in front of the barrier
     constexpr int POST = NMF - PRE;
     constexpr int RPP = (NFR + POST - 1) / POST, LPP = (LPT + POST - 1) / POST;
     sfor<PRE>([&](auto J) __attribute__((always_inline)) { mf1(IC<1>{}, J); BSR_SCHED_FENCE(); });
@@ -1127,14 +1123,11 @@ static const NtShape kNtShapes[] = {
     {7256256, 256, 256, -1.f, 0.f},     {7320256, 320, 256, -1.f, 0.f},    {7192256, 192, 256, -1.f, 0.f},
     {7256192, 256, 192, -1.f, 0.f},     {7256128, 256, 128, -1.f, 0.f},    {7128256, 128, 256, -1.f, 0.f},
     {7192128, 192, 128, -1.f, 0.f},     {7128128, 128, 128, -1.f, 0.f},
-    // the same with eight wavefronts on the small tiles (id = 9000000 + shape): two workgroups, sixteen wavefronts per CU
-    {9192128, 192, 128, -1.f, 0.f},     {9128128, 128, 128, -1.f, 0.f},    {9128064, 128, 64, -1.f, 0.f},
 };
 // stages of the direct-to-LDS shapes (0: not one of them)
 static int ntd_stages(int id) {
   switch (id) {
     case 7256256: case 7320256: case 7192256: case 7256192: case 7192128: case 7128128: return 2;
-    case 9192128: case 9128128: case 9128064: return 2;
     case 7256128: case 7128256: return 3;
     default: return 0;
   }
@@ -1176,9 +1169,6 @@ void gemm_mfma(const GemmDesc& g, float* splitk_ws, size_t splitk_ws_floats, hip
   if (!pick || (ntd_stages(pick) && !is_ntd(g))) pick = gemm_nt_model_tile(g.M, g.N, g.K);
   switch (pick) {
     case 7256256: launch_ntd<256, 256, 2, 4, 2>(g, s); break;
-    case 9192128: launch_ntd<192, 128, 2, 4, 2>(g, s); break;
-    case 9128128: launch_ntd<128, 128, 2, 4, 2>(g, s); break;
-    case 9128064: launch_ntd<128, 64, 4, 2, 2>(g, s); break;
     case 7320256: launch_ntd<320, 256, 2, 4, 2>(g, s); break;
     case 7192256: launch_ntd<192, 256, 2, 4, 2>(g, s); break;
     case 7256192: launch_ntd<256, 192, 4, 2, 2>(g, s); break;
