@@ -91,8 +91,27 @@ def time_steps(ctx, cfg, batch, steps, warmup, profile_steps=0, autotune=True, p
         prof = ctx.bsr_profile_end()
         return {k: (v[0] / profile_steps, v[1] / profile_steps, v[2] // profile_steps) for k, v in prof.items()}
 
+    def per_call(n):           # the three calls of a sequential step apart, and the spread of the step time
+        ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(n)]
+        for e in ev:
+            e[0].record()
+            ctx.bsr_forward_frozen(xin, x_out=x_f[0])
+            e[1].record()
+            ctx.bsr_train_blocks_fwd_bwd(x_f[0], lab, grads, loss_out=loss)
+            e[2].record()
+            ctx.bsr_sgd_step(grads, mom, lr=1e-3, momentum=0.9, weight_decay=1e-4)
+            e[3].record()
+        torch.cuda.synchronize()
+        parts = [[e[i].elapsed_time(e[i + 1]) for e in ev] for i in range(3)]
+        whole = sorted(ev[i][0].elapsed_time(ev[i + 1][0]) for i in range(n - 1))    # start to start
+        med = lambda v: sorted(v)[len(v) // 2]
+        return {"bsr_forward_frozen_ms": med(parts[0]), "bsr_train_blocks_fwd_bwd_ms": med(parts[1]),
+                "bsr_sgd_step_ms": med(parts[2]), "step_ms_median": whole[len(whole) // 2], "step_ms_min": whole[0],
+                "steps": n, "note": "HIP events between the calls of sequential steps, medians; taken after the timed region"}
+
     seq = timed(run_sequential)
     prof_seq = bracketed(run_sequential) if profile_steps else None
+    calls = per_call(max(steps // 2, 10))
     has_prefix = (cfg.get("trainable_blocks") or [cfg["first_trainable"]])[0] > 0
     best, tuned_overlapped, tiles, prof_best = seq, None, "chosen launch by launch, each timed alone", prof_seq
     if pipeline and has_prefix:
@@ -109,7 +128,7 @@ def time_steps(ctx, cfg, batch, steps, warmup, profile_steps=0, autotune=True, p
             if piped2["ms_per_step"] < best["ms_per_step"]:
                 best, tiles = piped2, "one shape for every launch, chosen by timing the two parts side by side"
                 prof_best = bracketed(run_pipelined) if profile_steps else None
-    return dict(best, pipelined=best is not seq, tiles=tiles, sequential=seq, loss=float(loss[0].item()), prof=prof_best,
+    return dict(best, pipelined=best is not seq, tiles=tiles, sequential=seq, calls=calls, loss=float(loss[0].item()), prof=prof_best,
                 prof_sequential=prof_seq, tuned=tuned, tuned_overlapped=tuned_overlapped)
 
 
@@ -273,6 +292,7 @@ def main():
         "tile_shapes": r["tiles"],
         "ms_per_step_sequential": r["sequential"]["ms_per_step"],
         "images_per_sec_sequential": batch * args.steps / r["sequential"]["wall_s"],
+        "calls_sequential": r["calls"],
         "loss": r["loss"],
         "tile_autotune": None if r["tuned"] is None else {"launches": r["tuned"][0], "differ_from_cost_model": r["tuned"][1]},
         "tile_autotune_overlapped": None if r["tuned_overlapped"] is None else
