@@ -361,6 +361,9 @@ int32_t bsr_adamw_step(bsr_ctx* ctx, const bsr_params* grads, const bsr_params* 
  *   res   [M,out], may be NULL: added last      y     [M,out]
  * bsr_linear_dgrad (Eq. 2): dx[M,in] = dy[M,out] . W^T, optionally times GELU'(u) element-wise.
  *   w_s   bf16 copy of W stored [in,out]        u     [M,in], may be NULL
+ * tile (both): 0, or the id of a block-tile shape (bsr_gemm_tile_shapes) the MFMA kernel is to use; a shape that
+ *   cannot take the product (a direct-to-LDS shape when `in` / `out` to contract over is not a multiple of 64)
+ *   gives way to the default.  Every shape gives the same bits.  An unknown id: INVALID_ARG.
  * bsr_linear_wgrad (Eq. 4): dw[in,out] (fp32) = x[M,in]^T . dy[M,out], summed over all M rows.
  *   db         fp32 [out], may be NULL: the bias gradient, db[o] = sum over rows of dy[:,o], from the
  *              same launch when the MFMA kernel takes the shape (otherwise it needs the workspace)
@@ -370,9 +373,9 @@ int32_t bsr_adamw_step(bsr_ctx* ctx, const bsr_params* grads, const bsr_params* 
  */
 int32_t bsr_linear_forward(const void* x, int32_t M, int32_t in, int32_t out, const void* w_t,
                            const float* bias, int32_t act, void* u_out, const void* res, void* y,
-                           int32_t* used_mfma, void* stream);
+                           int32_t tile, int32_t* used_mfma, void* stream);
 int32_t bsr_linear_dgrad(const void* dy, int32_t M, int32_t in, int32_t out, const void* w_s,
-                         const void* u, void* dx, int32_t* used_mfma, void* stream);
+                         const void* u, void* dx, int32_t tile, int32_t* used_mfma, void* stream);
 int32_t bsr_linear_wgrad(const void* x, const void* dy, int32_t M, int32_t in, int32_t out, float* dw,
                          float* db, float* workspace, size_t workspace_floats, int32_t* used_mfma, void* stream);
 

@@ -103,7 +103,7 @@ def load_library():
                                       C.c_void_p, C.c_void_p, C.c_float, C.c_float, C.c_float, C.c_void_p, C.c_void_p]
     lib.bsr_linear_forward.restype = C.c_int32
     lib.bsr_linear_forward.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
-                                       C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+                                       C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]
     lib.bsr_gemm_tile_shapes.restype = C.c_int32
     lib.bsr_gemm_tile_shapes.argtypes = [C.c_void_p, C.c_int32]
     lib.bsr_ln_linear_fold.restype = C.c_int32
@@ -114,7 +114,7 @@ def load_library():
                                           C.c_float, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p]
     lib.bsr_linear_dgrad.restype = C.c_int32
     lib.bsr_linear_dgrad.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
-                                     C.c_void_p, C.c_void_p, C.c_void_p]
+                                     C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]
     lib.bsr_linear_wgrad.restype = C.c_int32
     lib.bsr_linear_wgrad.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
                                      C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
@@ -212,8 +212,8 @@ def _cur_stream(t):
     return C.c_void_p(torch.cuda.current_stream(t.device).cuda_stream)
 
 
-def bsr_linear_forward(x, w_t, bias=None, act=0, u_out=None, res=None, y=None):
-    """x [M,in] bf16, w_t [out,in] bf16 -> (y [M,out] bf16, used_mfma)."""
+def bsr_linear_forward(x, w_t, bias=None, act=0, u_out=None, res=None, y=None, tile=0):
+    """x [M,in] bf16, w_t [out,in] bf16 -> (y [M,out] bf16, used_mfma).  tile: 0 or a block-tile shape id."""
     import torch
     M, kin = x.shape
     out = w_t.shape[0]
@@ -221,7 +221,7 @@ def bsr_linear_forward(x, w_t, bias=None, act=0, u_out=None, res=None, y=None):
         y = torch.empty((M, out), dtype=torch.bfloat16, device=x.device)
     used = C.c_int32(-1)
     _check(load_library().bsr_linear_forward(_dp(x), M, kin, out, _dp(w_t), _dp(bias), act, _dp(u_out),
-                                             _dp(res), _dp(y), C.byref(used), _cur_stream(x)))
+                                             _dp(res), _dp(y), tile, C.byref(used), _cur_stream(x)))
     return y, used.value
 
 
@@ -258,15 +258,15 @@ def bsr_ln_linear_forward(x, w_folded, colsum, bias_folded, eps=1e-6, act=0, til
     return y
 
 
-def bsr_linear_dgrad(dy, w_s, u=None, dx=None):
-    """dy [M,out] bf16, w_s [in,out] bf16 -> (dx [M,in] bf16, used_mfma)."""
+def bsr_linear_dgrad(dy, w_s, u=None, dx=None, tile=0):
+    """dy [M,out] bf16, w_s [in,out] bf16 -> (dx [M,in] bf16, used_mfma).  tile: 0 or a block-tile shape id."""
     import torch
     M, out = dy.shape
     kin = w_s.shape[0]
     if dx is None:
         dx = torch.empty((M, kin), dtype=torch.bfloat16, device=dy.device)
     used = C.c_int32(-1)
-    _check(load_library().bsr_linear_dgrad(_dp(dy), M, kin, out, _dp(w_s), _dp(u), _dp(dx), C.byref(used),
+    _check(load_library().bsr_linear_dgrad(_dp(dy), M, kin, out, _dp(w_s), _dp(u), _dp(dx), tile, C.byref(used),
                                            _cur_stream(dy)))
     return dx, used.value
 

@@ -1515,26 +1515,33 @@ int32_t bsr_adamw_step(bsr_ctx* c, const bsr_params* grads, const bsr_params* ex
   return optimizer_step(c, grads, exp_avg, exp_avg_sq, o, (hipStream_t)stream, "bsr_adamw_step");
 }
 
+static bool known_tile(int tile) {
+  bool known = tile == 0;
+  for (int i = 0; i < gemm_nt_tile_count(); ++i) known |= gemm_nt_tile_id(i) == tile;
+  return known;
+}
+
 static int32_t run_layer(const GemmDesc& g, int32_t* used_mfma, void* stream, const char* where,
-                         float* ws = nullptr, size_t ws_floats = 0) {
+                         float* ws = nullptr, size_t ws_floats = 0, int tile = 0) {
   const bool mfma = gemm_mfma_supported(g);
   if (used_mfma) *used_mfma = mfma ? 1 : 0;
-  if (mfma) gemm_mfma(g, ws, ws_floats, (hipStream_t)stream);
+  if (mfma) gemm_mfma(g, ws, ws_floats, (hipStream_t)stream, tile);
   else gemm_generic(g, (hipStream_t)stream);
   return check_hip(nullptr, where);
 }
 
 int32_t bsr_linear_forward(const void* x, int32_t M, int32_t in, int32_t out, const void* w_t,
                            const float* bias, int32_t act, void* u_out, const void* res, void* y,
-                           int32_t* used_mfma, void* stream) {
+                           int32_t tile, int32_t* used_mfma, void* stream) {
   if (!aligned16(x) || !aligned16(w_t) || !aligned16(y) || M < 1 || in < 1 || out < 1 || (act != 0 && act != 1) ||
       (bias && !aligned16(bias)) || (u_out && !aligned16(u_out)) || (res && !aligned16(res)))
     return fail(nullptr, BSR_ERR_INVALID_ARG, "bsr_linear_forward: bad argument");
+  if (!known_tile(tile)) return fail(nullptr, BSR_ERR_INVALID_ARG, "bsr_linear_forward: %d is not a tile shape id", tile);
   GemmDesc g;
   g.A = x; g.a_rs = in; g.a_cs = 1; g.B = w_t; g.b_rs = 1; g.b_cs = in;
   g.C = y; g.ldc = out; g.M = M; g.N = out; g.K = in;
   g.bias = bias; g.act = act ? ACT_GELU : ACT_NONE; g.aux = act ? u_out : nullptr; g.res = res;
-  return run_layer(g, used_mfma, stream, "bsr_linear_forward");
+  return run_layer(g, used_mfma, stream, "bsr_linear_forward", nullptr, 0, tile);
 }
 
 int32_t bsr_gemm_tile_shapes(int32_t* ids, int32_t max) {
@@ -1558,9 +1565,7 @@ int32_t bsr_ln_linear_forward(const void* x, int32_t M, int32_t in, int32_t out,
   if (!aligned16(x) || !aligned16(w_folded) || !aligned16(colsum) || !aligned16(bias_folded) || !aligned16(y) || M < 1 ||
       in < 64 || in % 64 || out < 8 || out % 8 || (act != 0 && act != 1))
     return fail(nullptr, BSR_ERR_INVALID_ARG, "bsr_ln_linear_forward: bad argument");
-  bool known = tile == 0;
-  for (int i = 0; i < gemm_nt_tile_count(); ++i) known |= gemm_nt_tile_id(i) == tile;
-  if (!known) return fail(nullptr, BSR_ERR_INVALID_ARG, "bsr_ln_linear_forward: %d is not a tile shape id", tile);
+  if (!known_tile(tile)) return fail(nullptr, BSR_ERR_INVALID_ARG, "bsr_ln_linear_forward: %d is not a tile shape id", tile);
   GemmDesc g;
   g.A = x; g.a_rs = in; g.a_cs = 1; g.B = w_folded; g.b_rs = 1; g.b_cs = in;
   g.C = y; g.ldc = out; g.M = M; g.N = out; g.K = in;
@@ -1572,14 +1577,15 @@ int32_t bsr_ln_linear_forward(const void* x, int32_t M, int32_t in, int32_t out,
 }
 
 int32_t bsr_linear_dgrad(const void* dy, int32_t M, int32_t in, int32_t out, const void* w_s,
-                         const void* u, void* dx, int32_t* used_mfma, void* stream) {
+                         const void* u, void* dx, int32_t tile, int32_t* used_mfma, void* stream) {
   if (!aligned16(dy) || !aligned16(w_s) || !aligned16(dx) || M < 1 || in < 1 || out < 1)
     return fail(nullptr, BSR_ERR_INVALID_ARG, "bsr_linear_dgrad: bad argument");
+  if (!known_tile(tile)) return fail(nullptr, BSR_ERR_INVALID_ARG, "bsr_linear_dgrad: %d is not a tile shape id", tile);
   GemmDesc g;
   g.A = dy; g.a_rs = out; g.a_cs = 1; g.B = w_s; g.b_rs = 1; g.b_cs = out;
   g.C = dx; g.ldc = in; g.M = M; g.N = in; g.K = out;
   if (u) { g.act = ACT_GELU_BWD; g.aux = const_cast<void*>(u); }
-  return run_layer(g, used_mfma, stream, "bsr_linear_dgrad");
+  return run_layer(g, used_mfma, stream, "bsr_linear_dgrad", nullptr, 0, tile);
 }
 
 int32_t bsr_linear_wgrad(const void* x, const void* dy, int32_t M, int32_t in, int32_t out, float* dw,

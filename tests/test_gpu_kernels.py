@@ -66,6 +66,46 @@ def test_linear_forward(env, orc64, M, kin, out):
     assert_close(r.float().cpu().numpy()[rows], ref + res[rows], "residual")
 
 
+@pytest.mark.parametrize("M,kin,out", [(700, 256, 392), (300, 448, 392), (2144, 768, 768), (1000, 64, 3072), (333, 1536, 264),
+                                       (257, 128, 8), (65, 192, 576)])
+def test_every_tile_shape_gives_the_same_bits(env, orc64, M, kin, out):
+    """Both kernel families, every block-tile shape, every epilogue form (bias; GELU with the stored pre-activation;
+    residual; GELU' of a stored tensor in the input-gradient product of Eq. 2), on products whose rows and columns end
+    inside a tile and whose contraction is 1 .. 24 k-tiles: the same bits as the default shape, which is checked
+    against the oracle."""
+    torch, P = env
+    rng = np.random.default_rng(M * 3 + kin + out)
+    x = bf16_np(rng, (M, kin)); w = bf16_np(rng, (kin, out), 0.05); b = rng.standard_normal(out).astype(np.float32)
+    res = bf16_np(rng, (M, out)); aux = bf16_np(rng, (M, out))
+    xt = to_dev(torch, x, torch.bfloat16)
+    wt = to_dev(torch, np.ascontiguousarray(w.T), torch.bfloat16)
+    bt = to_dev(torch, b); rt = to_dev(torch, res, torch.bfloat16); at = to_dev(torch, aux, torch.bfloat16)
+    bits = lambda t: t.view(torch.int16).cpu().numpy().copy()
+
+    def forms(tile):
+        y, used = P.bsr_linear_forward(xt, wt, bt, tile=tile)
+        u = torch.full((M, out), -7.0, dtype=torch.bfloat16, device="cuda")
+        g, _ = P.bsr_linear_forward(xt, wt, bt, act=1, u_out=u, tile=tile)
+        r, _ = P.bsr_linear_forward(xt, wt, bt, res=rt, tile=tile)
+        # the same product seen as an input gradient: dy = x, W stored [in', out'] = w_t, times GELU'(aux)
+        d, _ = P.bsr_linear_dgrad(xt, wt, u=at, tile=tile)
+        torch.cuda.synchronize()
+        assert used == 1
+        return [bits(t) for t in (y, u, g, r, d)]
+
+    base = forms(0)
+    ref = orc64.linear(x, w, b)
+    assert_close(torch.from_numpy(base[0]).view(torch.bfloat16).float().numpy(), ref, "linear")
+    assert_close(torch.from_numpy(base[3]).view(torch.bfloat16).float().numpy(), ref + res, "residual")
+    assert_close(torch.from_numpy(base[4]).view(torch.bfloat16).float().numpy(),
+                 orc64.gelu_bwd(orc64.linear_dgrad(x, np.ascontiguousarray(w.T)), aux), "dgrad * GELU'")
+    for tile in P.bsr_gemm_tile_shapes():
+        for name, a, c in zip(("plain", "pre-activation", "gelu", "residual", "dgrad"), base, forms(tile)):
+            assert np.array_equal(a, c), f"tile shape {tile}, {name}: {int(np.sum(a != c))} of {a.size} elements differ"
+    with pytest.raises(P.BsrError):
+        P.bsr_linear_forward(xt, wt, bt, tile=4242)
+
+
 LN_SHAPES = [(6304, 768, 2304), (4416, 768, 3072), (2144, 768, 2304), (333, 128, 72), (1, 64, 8), (130, 768, 136)]
 
 
