@@ -310,7 +310,7 @@ def main():
         # side by side a launch's bracket also holds the time it waits for, and shares the CUs with, the other stream's
         # launches, and the brackets of the two streams overlap: their sum exceeds the step.  The same flops over the
         # step's own wall time is what the matrix cores did for this class at the very least.
-        over_wall = out["roofline"]["gflop_per_step"] / r["ms_per_step"] / 1e3
+        over_wall = out["roofline"]["gflop_per_step"] / r["ms_per_step"]          # GFLOP / ms = TFLOP/s
         out["roofline"]["achieved_over_step_wall"] = over_wall
         out["roofline"]["frac_over_step_wall"] = over_wall / peak
     if args.calibrate_copy:
