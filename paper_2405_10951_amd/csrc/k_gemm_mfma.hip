@@ -56,6 +56,9 @@ __device__ inline float gelu_grad_f(float u) {
 }
 
 template <int V> struct IC { static constexpr int value = V; };   // compile-time flag for generic lambdas
+// f(IC<0>{}), ..., f(IC<N-1>{}): a loop whose index is a compile-time constant in the body
+template <class F, int... I> __device__ __forceinline__ void sfor_impl(F&& f, std::integer_sequence<int, I...>) { (f(IC<I>{}), ...); }
+template <int N, class F> __device__ __forceinline__ void sfor(F&& f) { sfor_impl(f, std::make_integer_sequence<int, N>{}); }
 
 // LDS chunk swizzle: 16 consecutive rows reading the same logical 16-byte chunk hit 16 different
 // (row parity, chunk position) pairs, i.e. all 64 banks once; 8 consecutive rows hit 8 positions.
@@ -141,16 +144,22 @@ __device__ __forceinline__ void epilogue(const GemmDesc& g, f32x16 (&acc)[MI][NI
   float cs[8];
 #pragma unroll
   for (int j = 0; j < 8; ++j) cs[j] = (rowstat && col_ok) ? g.ln_colsum[col + j] : 0.f;
-#pragma unroll
+  // (row blocks and passes are loops, the accumulators of block mi picked by a switch: written out, this code was
+  // most of the kernel, and a launch that follows another kernel fetches its code anew)
+#pragma nounroll
   for (int mi = 0; mi < MI; ++mi) {
+    sfor<MI>([&](auto I) __attribute__((always_inline)) {
+      constexpr int i = decltype(I)::value;
+      if (mi != i) return;
 #pragma unroll
-    for (int ni = 0; ni < NI; ++ni)
+      for (int ni = 0; ni < NI; ++ni)
 #pragma unroll
-      for (int r = 0; r < 16; ++r)
-        patch[(8 * (r >> 2) + 4 * lh + (r & 3)) * LDP + ni * 32 + lc] = acc[mi][ni][r];
+        for (int r = 0; r < 16; ++r)
+          patch[(8 * (r >> 2) + 4 * lh + (r & 3)) * LDP + ni * 32 + lc] = acc[i][ni][r];
+    });
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
-#pragma unroll
+#pragma nounroll
     for (int pass = 0; pass < 32 / RPI; ++pass) {
       const int lr = pass * RPI + my_row;
       const int m = row0 + mi * 32 + lr;
@@ -461,8 +470,6 @@ template <int N> __device__ __forceinline__ void wait_vmcnt() {
   __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | (0x7 << 4) | (0xF << 8));
 }
 __device__ __forceinline__ void wait_lgkmcnt0() { __builtin_amdgcn_s_waitcnt(0xF | (0x3 << 14) | (0x7 << 4)); }
-template <class F, int... I> __device__ __forceinline__ void sfor_impl(F&& f, std::integer_sequence<int, I...>) { (f(IC<I>{}), ...); }
-template <int N, class F> __device__ __forceinline__ void sfor(F&& f) { sfor_impl(f, std::make_integer_sequence<int, N>{}); }
 #define BSR_SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
 #define BSR_GLOBAL_PTR(p) ((const void __attribute__((address_space(1)))*)(p))
 #define BSR_LDS_VOID(p) ((void __attribute__((address_space(3)))*)(p))
@@ -473,6 +480,10 @@ typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 // Epilogue of one wave tile whose accumulators hold transposed output tiles: element r of acc[mi][ni] is output
 // row mi*32 + lane%32, column ni*32 + 8*(r/4) + 4*(lane/32) + r%4.  32 rows at a time go through a per-wave LDS
 // patch and come back with a lane owning 8 consecutive columns of a row (16-byte global stores).
+// The code is kept short on purpose: a launch that follows another kernel fetches its code anew, and a version of
+// this epilogue with every row block and pass written out (13 700 of the kernel's 14 400 instructions) cost a
+// launch about 3 us.  So the row blocks are a loop (the accumulators of block mi are picked by a switch, which
+// is all that has to be written out per block) and so are the passes: the finishing code exists once.
 template <int MI, int NI>
 __device__ __forceinline__ void epilogue_t(const GemmDesc& g, f32x16 (&acc)[MI][NI], int row0, int col0, int lane,
                                            unsigned char* patch) {
@@ -483,8 +494,8 @@ __device__ __forceinline__ void epilogue_t(const GemmDesc& g, f32x16 (&acc)[MI][
   const int my_chunk = lane % CPR, my_row = lane / CPR;
   const int col = col0 + my_chunk * 8;
   const bool col_ok = col < g.N && my_row < RPP;    // N is a multiple of 8 on this path
-  // nothing to add after the transposition: round first, move half the bytes
-  const bool direct = !g.out_f32 && !g.res && g.remap_np == 0 && g.act != ACT_GELU_BWD;
+  // nothing but the bias to add: round first, move half the bytes
+  const bool direct = !g.out_f32 && !g.res && g.remap_np == 0 && g.act == ACT_NONE;
   if (direct) {
     constexpr int LDB = TN * 2 + 16;                // bytes per patch row
     f32x4 bq[NI][4];                                // bias of the columns this lane holds
@@ -495,37 +506,33 @@ __device__ __forceinline__ void epilogue_t(const GemmDesc& g, f32x16 (&acc)[MI][
         const int c = col0 + ni * 32 + 8 * rg + 4 * lh;
         bq[ni][rg] = (g.bias && c < g.N) ? *(const f32x4*)(g.bias + c) : f32x4{0.f, 0.f, 0.f, 0.f};
       }
-    const int npass = (g.act == ACT_GELU && g.aux) ? 2 : 1;    // the pre-activation leaves first
-#pragma unroll
+    bf16* dst = (bf16*)g.C;
+#pragma nounroll
     for (int mi = 0; mi < MI; ++mi) {
-      for (int pass = 0; pass < npass; ++pass) {
-        const bool act_now = g.act == ACT_GELU && pass == npass - 1;
-        bf16* dst = (bf16*)((pass == 0 && npass == 2) ? g.aux : g.C);
+      sfor<MI>([&](auto I) __attribute__((always_inline)) {
+        constexpr int i = decltype(I)::value;
+        if (mi != i) return;
 #pragma unroll
         for (int ni = 0; ni < NI; ++ni)
 #pragma unroll
           for (int rg = 0; rg < 4; ++rg) {
             bf16x4 o;
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-              float v = acc[mi][ni][4 * rg + e] + bq[ni][rg][e];
-              if (act_now) v = gelu_f(v);
-              o[e] = (bf16)v;
-            }
+            for (int e = 0; e < 4; ++e) o[e] = (bf16)(acc[i][ni][4 * rg + e] + bq[ni][rg][e]);
             *(bf16x4*)(patch + lm * LDB + (ni * 32 + 8 * rg + 4 * lh) * 2) = o;
           }
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-#pragma unroll
-        for (int p = 0; p < NPASS; ++p) {
-          const int lr = p * RPP + my_row;
-          const int m = row0 + mi * 32 + lr;
-          if (lr >= 32 || m >= g.M || !col_ok) continue;
-          *(bf16x8*)(dst + (int64_t)m * g.ldc + col) = *(const bf16x8*)(patch + lr * LDB + my_chunk * 16);
-        }
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
+      });
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+#pragma nounroll
+      for (int p = 0; p < NPASS; ++p) {
+        const int lr = p * RPP + my_row;
+        const int m = row0 + mi * 32 + lr;
+        if (lr >= 32 || m >= g.M || !col_ok) continue;
+        *(bf16x8*)(dst + (int64_t)m * g.ldc + col) = *(const bf16x8*)(patch + lr * LDB + my_chunk * 16);
       }
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
     }
     return;
   }
@@ -533,17 +540,21 @@ __device__ __forceinline__ void epilogue_t(const GemmDesc& g, f32x16 (&acc)[MI][
   float bias[8], cs[8];
 #pragma unroll
   for (int j = 0; j < 8; ++j) { bias[j] = (g.bias && col_ok) ? g.bias[col + j] : 0.f; cs[j] = 0.f; }
-#pragma unroll
+#pragma nounroll
   for (int mi = 0; mi < MI; ++mi) {
+    sfor<MI>([&](auto I) __attribute__((always_inline)) {
+      constexpr int i = decltype(I)::value;
+      if (mi != i) return;
 #pragma unroll
-    for (int ni = 0; ni < NI; ++ni)
+      for (int ni = 0; ni < NI; ++ni)
 #pragma unroll
-      for (int rg = 0; rg < 4; ++rg)
-        *(f32x4*)(patch + lm * LDF + (ni * 32 + 8 * rg + 4 * lh) * 4) =
-            f32x4{acc[mi][ni][4 * rg], acc[mi][ni][4 * rg + 1], acc[mi][ni][4 * rg + 2], acc[mi][ni][4 * rg + 3]};
+        for (int rg = 0; rg < 4; ++rg)
+          *(f32x4*)(patch + lm * LDF + (ni * 32 + 8 * rg + 4 * lh) * 4) =
+              f32x4{acc[i][ni][4 * rg], acc[i][ni][4 * rg + 1], acc[i][ni][4 * rg + 2], acc[i][ni][4 * rg + 3]};
+    });
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
-#pragma unroll
+#pragma nounroll
     for (int p = 0; p < NPASS; ++p) {
       const int lr = p * RPP + my_row;
       const int m = row0 + mi * 32 + lr;
