@@ -223,6 +223,8 @@ def main():
     ap.add_argument("--cpu-sample", type=int, default=None, help="images of the cpu_baseline leg (default: the whole batch)")
     ap.add_argument("--no-sweep", action="store_true", help="skip the batch-128 sweep keep ratio x trained blocks")
     ap.add_argument("--sweep-steps", type=int, default=5)
+    ap.add_argument("--fold-frozen-layernorm", action="store_true",
+                    help="bsr_config.fold_frozen_layernorm = 1: the frozen prefix's LayerNorms ride inside the qkv / fc1 products")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 256 MiB device copy (reference for the HBM byte counters)")
     args = ap.parse_args()
@@ -242,6 +244,8 @@ def main():
         cfg["keep_ratio"] = args.keep_ratio
     if args.trainable is not None:
         cfg["first_trainable"] = cfg["depth"] - args.trainable
+    if args.fold_frozen_layernorm:
+        cfg["fold_frozen_layernorm"] = 1
     batch = args.batch or cfg["batch"]
     cfg["batch"] = batch
 
