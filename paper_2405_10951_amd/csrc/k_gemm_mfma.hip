@@ -498,17 +498,17 @@ __device__ __forceinline__ void epilogue_t(const GemmDesc& g, f32x16 (&acc)[MI][
   const bool direct = !g.out_f32 && !g.res && g.remap_np == 0 && g.act == ACT_NONE;
   if (direct) {
     constexpr int LDB = TN * 2 + 16;                // bytes per patch row
-    f32x4 bq[NI][4];                                // bias of the columns this lane holds
-#pragma unroll
-    for (int ni = 0; ni < NI; ++ni)
-#pragma unroll
-      for (int rg = 0; rg < 4; ++rg) {
-        const int c = col0 + ni * 32 + 8 * rg + 4 * lh;
-        bq[ni][rg] = (g.bias && c < g.N) ? *(const f32x4*)(g.bias + c) : f32x4{0.f, 0.f, 0.f, 0.f};
-      }
     bf16* dst = (bf16*)g.C;
 #pragma nounroll
     for (int mi = 0; mi < MI; ++mi) {
+      f32x4 bq[NI][4];                              // bias of the columns this lane holds (read per row block: the
+#pragma unroll                                      // accumulators leave no registers to keep it in)
+      for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+        for (int rg = 0; rg < 4; ++rg) {
+          const int c = col0 + ni * 32 + 8 * rg + 4 * lh;
+          bq[ni][rg] = (g.bias && c < g.N) ? *(const f32x4*)(g.bias + c) : f32x4{0.f, 0.f, 0.f, 0.f};
+        }
       sfor<MI>([&](auto I) __attribute__((always_inline)) {
         constexpr int i = decltype(I)::value;
         if (mi != i) return;
