@@ -222,6 +222,9 @@ def main():
                     help="time the steps one after the other only (no overlap of the next batch's frozen forward)")
     ap.add_argument("--cpu-sample", type=int, default=None, help="images of the cpu_baseline leg (default: the whole batch)")
     ap.add_argument("--no-sweep", action="store_true", help="skip the batch-128 sweep keep ratio x trained blocks")
+    ap.add_argument("--sweep", choices=["c4", "none"], default=None,
+                    help="c4: the batch-128 sweep keep ratio {1.0, 0.7, 0.5} x trained blocks {12, 4, 2} under the `sweep` key "
+                         "(the default on the headline workload at batch 32; with this flag on any ViT-B run); none: skip it")
     ap.add_argument("--sweep-steps", type=int, default=5)
     ap.add_argument("--fold-frozen-layernorm", action="store_true",
                     help="bsr_config.fold_frozen_layernorm = 1: the frozen prefix's LayerNorms ride inside the qkv / fc1 products")
@@ -337,7 +340,8 @@ def main():
             out[key + "_algorithmic"] = flops_of(c2, ctx2)["total"] / fl["total"]
             del ctx2
             torch.cuda.empty_cache()
-    if not args.no_sweep and args.workload == "c3_vit_b" and batch == 32:
+    want_sweep = args.sweep == "c4" or (args.sweep is None and not args.no_sweep and batch == 32)
+    if want_sweep and args.workload == "c3_vit_b":
         out["sweep"] = {"workload": "c3_vit_b at batch 128, keep ratio x trained blocks (suffix), sequential schedule",
                         "points": sweep_c4(P, S, flops_of, args.sweep_steps, 2)}
     if not args.no_cpu:
